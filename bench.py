@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused VQ hot path on one MI355X.
+
+Headline workload (N = 1 GPU): Llama-7B-shaped decode VQ-gemv, bs = 1, one 2^16 x 8 fp16
+codebook per matrix, uint16 codes, fp16 per-channel scale.  One "step" is one decode token's
+worth of linear layers of the whole 32-block stack: 224 vq_gemv launches (4 x (4096,4096),
+2 x (11008,4096), 1 x (4096,11008) per block), every matrix with its own codes and codebook
+(1.5 GiB + 224 MiB, far beyond the 256 MB last-level cache, so every launch streams from HBM).
+All inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is effective bandwidth: algorithmic bytes (codes + codebook
+once + x + scale + y) per step divided by the step time.  Secondary objects report the
+per-shape gemv times, the prefill VQ-gemm (M = 2048) against the fp16 MFMA peak and the
+VQ-attn decode against HBM, each timed outside the headline region.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
+MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix-core peak, vendor figure
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32, help="decoder blocks in the gemv stack")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    ap.add_argument("--skip-secondary", action="store_true", help="only the headline gemv stack")
+    ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2503_02236_amd as vq
+    from paper_2503_02236_amd import workloads as wl
+    from paper_2503_02236_amd.binding import _stream
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    lib = vq.lib()
+    only = set(s for s in args.only.split(",") if s)
+
+    def want(section):
+        return not only or section in only
+
+    def timed(fn, iters, warm):
+        """Average ms per call of fn() over `iters` back-to-back calls, HIP events on the launch stream."""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    class GemvCall:
+        """Pre-marshalled vq_gemv call (descriptor built once, so the loop is launch-bound only)."""
+        def __init__(self, wd, x, y):
+            self.keep = (wd, x, y)
+            self.desc = wd.desc()
+            self.ref = ctypes.byref(self.desc)
+            self.x, self.y, self.bs = x.data_ptr(), y.data_ptr(), x.shape[0]
+
+        def __call__(self):
+            st = lib.vq_gemv(self.ref, self.x, self.bs, self.y, None, 0, _stream())
+            if st != 0:
+                raise vq.VQError(st, "vq_gemv")
+
+    result = {}
+    t_setup = time.time()
+
+    # ------------------------------------------------------------------ headline: C2 gemv stack
+    if want("gemv"):
+        L = args.layers
+        x_by_k = {K: torch.from_numpy(wl.make_activations(1, K, wl.seed_for(2, K))).to(dev) for K in (4096, 11008)}
+        calls, eff_bytes, per_shape = [], 0, {0: [], 1: [], 2: []}
+        host_block0 = []
+        for layer in range(L):
+            for slot, si in enumerate(wl.LLAMA7B_BLOCK):
+                N, K = wl.LLAMA7B_SHAPES[si]
+                w = wl.make_weight(N, K, 8, 16, 1, 65536, 0.02, wl.seed_for(2, layer * 7 + slot))
+                wd = vq.weight_to_device(w, dev)
+                y = torch.empty((1, N), dtype=torch.float16, device=dev)
+                c = GemvCall(wd, x_by_k[K], y)
+                calls.append(c)
+                per_shape[si].append(c)
+                eff_bytes += w.effective_bytes(1)
+                if layer == 0:
+                    host_block0.append(w)
+        torch.cuda.synchronize()
+
+        def step():
+            for c in calls:
+                c()
+
+        graph = None
+        if not args.no_graph:
+            step()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    step()
+            run_step = graph.replay
+        else:
+            run_step = step
+
+        for _ in range(args.warmup):
+            run_step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            run_step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_step = e0.elapsed_time(e1) / args.steps
+        gbps = eff_bytes / (ms_step * 1e-3) / 1e9
+
+        # per-shape cold times (eager, rotating over every matrix of that shape)
+        shape_us = {}
+        for si, cs in per_shape.items():
+            def loop(cs=cs):
+                for c in cs:
+                    c()
+            ms = timed(loop, 5, 1)
+            N, K = wl.LLAMA7B_SHAPES[si]
+            b = cs[0].keep[0]
+            bytes_one = (b.codes.numel() * 2 + b.codebooks.numel() * 2 + K * 2 + N * 2 + N * 2)
+            us = ms * 1e3 / len(cs)
+            shape_us["%dx%d" % (N, K)] = {"us": round(us, 3), "GBps": round(bytes_one / us / 1e3, 1),
+                                          "pct_hbm_peak": round(100 * bytes_one / us / 1e3 / HBM_PEAK_GBPS, 2)}
+        # warm (cache-resident) figure for the smallest shape, for context
+        warm_ms = timed(per_shape[0][0], 200, 20)
+        shape_us["4096x4096_warm_us"] = round(warm_ms * 1e3, 3)
+
+        n_launch = len(calls)
+        result.update({
+            "metric": "VQ-GEMV bs=1 effective HBM bandwidth, Llama-7B shapes, 2^16x8 codebook",
+            "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f16xf16->f32", "data": "synthetic",
+            "config": {"workload": "C2: Llama-7B decode VQ-gemv bs=1, %d blocks x 7 matrices, VQ<8,16,1> uint16 codes, "
+                                   "fp16 scale" % L,
+                       "launches_per_step": n_launch, "effective_bytes_per_step": eff_bytes,
+                       "timing": "hip-graph replay" if graph is not None else "eager launches"},
+            "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
+            "gemv_per_shape_cold": shape_us,
+            "roofline": {"bound": "hbm", "kernel": "gemv_rows_kernel<uint16,8,1>",
+                         "achieved": round(gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                         "bytes_per_launch": eff_bytes // n_launch,
+                         "avg_launch_us": round(ms_step * 1e3 / n_launch, 3)},
+        })
+
+        # ---- CPU oracle baseline on a bounded sample: one decoder block (7 matrices), bs = 1
+        if not args.skip_cpu:
+            import oracle
+            xs = {K: x_by_k[K].cpu().numpy() for K in x_by_k}
+            oracle.gemv(host_block0[0].codes, host_block0[0].codebooks, host_block0[0].scale, xs[host_block0[0].K])
+            reps = 3
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                for w in host_block0:
+                    oracle.gemv(w.codes, w.codebooks, w.scale, xs[w.K])
+            dt = (time.perf_counter() - t0) / reps
+            blk_bytes = sum(w.effective_bytes(1) for w in host_block0)
+            result["cpu_baseline"] = {"value": round(blk_bytes / dt / 1e9, 3), "unit": "GB/s",
+                                      "cores": oracle.threads(), "kind": "oracle",
+                                      "sample": "one decoder block (7 of the %d matrices), mean of %d runs, %.1f ms"
+                                                % (n_launch, reps, dt * 1e3)}
+        del calls, per_shape, graph
+        torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ secondary: C4 prefill gemm
+    if want("gemm") and not args.skip_secondary:
+        gemm = {}
+        X = torch.from_numpy(wl.make_activations(2048, 4096, wl.seed_for(4, 0))).to(dev)
+        for N in (4096, 11008):
+            for v in (8, 4):
+                wd = vq.weight_to_device(wl.config4_layer(N, v), dev)
+                Y = torch.empty((2048, N), dtype=torch.float16, device=dev)
+                fn = lambda: vq.vq_gemm(wd, X, Y=Y)
+                ms = timed(fn, 10, 2)
+                tf = 2.0 * 2048 * N * 4096 / (ms * 1e-3) / 1e12
+                gemm["N%d_v%d" % (N, v)] = {"us": round(ms * 1e3, 2), "TFLOPs": round(tf, 1),
+                                            "pct_mfma_fp16_peak": round(100 * tf / MFMA_FP16_PEAK_TFLOPS, 2)}
+                del wd, Y
+        result["gemm_prefill_M2048_K4096"] = gemm
+
+    # ------------------------------------------------------------------ secondary: C5 attention decode
+    if want("attn") and not args.skip_secondary:
+        kv = wl.config5_kv()
+        ring = [vq.kv_to_device(kv, dev) for _ in range(3)]     # 3 x 128 MiB of codes: beyond the last-level cache
+        q = torch.from_numpy(kv.q).to(dev)
+        out = torch.empty_like(q)
+        wsz = vq.vq_attn_decode_workspace(ring[0])
+        ws = torch.empty(max(wsz, 16), dtype=torch.uint8, device=dev)
+        sm = 1.0 / np.sqrt(128.0)
+
+        def attn_loop():
+            for kd in ring:
+                vq.vq_attn_decode(kd, q, sm, out=out, ws=ws)
+        ms = timed(attn_loop, 10, 2) / len(ring)
+        b = kv.effective_bytes()
+        result["attn_decode_B16_H32_T4096"] = {"us": round(ms * 1e3, 2), "GBps": round(b / ms / 1e6, 1),
+                                               "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2)}
+        del ring
+        torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ secondary: C3 additive gemv
+    if want("add") and not args.skip_secondary:
+        add = {}
+        for si in (0, 1, 2):
+            N, K = wl.LLAMA7B_SHAPES[si]
+            n_copies = 48 if si == 0 else 24
+            wds = [vq.weight_to_device(wl.config3_layer(si, layer), dev) for layer in range(n_copies)]
+            for bs in (1, 4, 16):
+                x = torch.from_numpy(wl.make_activations(bs, K, wl.seed_for(3, bs))).to(dev)
+                y = torch.empty((bs, N), dtype=torch.float16, device=dev)
+
+                cs = [GemvCall(wd, x, y) for wd in wds]
+
+                def loop(cs=cs):
+                    for c in cs:
+                        c()
+                ms = timed(loop, 3, 1) / len(wds)
+                b = wds[0].codes.numel() + wds[0].codebooks.numel() * 2 + N * 2 + bs * (K + N) * 2
+                add["%dx%d_bs%d" % (N, K, bs)] = {"us": round(ms * 1e3, 2),
+                                                   "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2)}
+            del wds
+            torch.cuda.empty_cache()
+        result["gemv_additive_2x256x8"] = add
+
+    result["setup_plus_run_s"] = round(time.time() - t_setup, 1)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

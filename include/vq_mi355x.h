@@ -1,0 +1,149 @@
+/*
+ * vq_mi355x.h -- C ABI of libvqmi: matrix products on AMD MI355X (gfx950) whose
+ * weight or KV-cache operand is stored as vector-quantization (VQ) codes, with
+ * the codebook lookup fused into the contraction.
+ *
+ * Method: VQ-LLM (arXiv 2503.02236).  The operand format is the paper's
+ * VQ<vector size, log2 #entries, residuals> (Sec. II-A, Tbl. I): a tensor is
+ * cut into sub-vectors of `v` elements, each replaced by `R` indices ("codes"),
+ * one per residual codebook; the value is the element-wise sum of the R looked-up
+ * entries (Sec. II-A, dequantization).  The three operations are the kernels the
+ * paper names VQ-gemv, VQ-gemm and VQ-attn (Sec. III-C, Sec. VI-C Alg. 2).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; descriptor
+ *     structs are HOST memory, read during the call only.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     are asynchronous on that stream; the library never synchronizes, never
+ *     allocates and never frees device memory.  Scratch comes in through `ws`.
+ *   - Return value: VQ_OK (0) or a negative vq_status.  Arguments are validated
+ *     on the host before anything is launched; a failed call launches nothing.
+ *   - Data pointers must be 16-byte aligned (VQ_ERR_ALIGN otherwise).
+ *   - Codes >= n_entries are a precondition violation and are not checked on
+ *     the device (with n_entries = 2^code_bits every code is valid).
+ *   - Arithmetic: fp16 inputs, fp32 accumulation, fp16 round-to-nearest-even
+ *     outputs; reductions are order-deterministic (no floating-point atomics),
+ *     so repeated calls give bit-identical results.
+ */
+#ifndef VQ_MI355X_H
+#define VQ_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum vq_status {
+    VQ_OK = 0,
+    VQ_ERR_NULL = -1,        /* a required pointer is NULL */
+    VQ_ERR_SHAPE = -2,       /* K % v, bs / M range, D % v, cb_groups, negative sizes */
+    VQ_ERR_UNSUPPORTED = -3, /* v / code_bits / n_entries / n_codebooks combination */
+    VQ_ERR_ALIGN = -4,       /* a data pointer is not 16-byte aligned */
+    VQ_ERR_WORKSPACE = -5,   /* ws is NULL or smaller than the *_workspace() query */
+    VQ_ERR_LAUNCH = -6       /* the HIP runtime refused a launch (hipGetLastError) */
+} vq_status;
+
+/*
+ * A VQ-compressed weight matrix W[N][K] of a linear layer y = W x
+ * (N output features, K input features).  Sub-vectors lie along K, the
+ * reduction axis, so row n holds K/v sub-vectors.
+ *   W[n][j*v + i] = sum_{r < n_codebooks} codebooks[r][codes[n][j][r]][i]
+ * summed in fp32, r ascending (Sec. II-A; "Residual" of Tbl. I = n_codebooks).
+ */
+typedef struct vq_weight_t {
+    int N, K;              /* output / input features; K % v == 0 */
+    int v;                 /* vector size: 4 or 8 */
+    int code_bits;         /* storage width of one code: 8 (uint8) or 16 (uint16, little endian) */
+    int n_codebooks;       /* R >= 1 additive (residual) codebooks, R <= 4 */
+    int n_entries;         /* E entries per codebook, 1 <= E <= 2^code_bits */
+    const void *codes;     /* device, [N][K/v][R], r fastest */
+    const void *codebooks; /* device, fp16 [R][E][v] */
+    const void *scale;     /* device, fp16 [N] per output channel, or NULL (= 1) */
+} vq_weight_t;
+
+/*
+ * VQ-gemv (decode phase, Sec. III-C / Sec. VII "GeMV", batch sizes 1..16):
+ *   y[m][n] = scale[n] * sum_k W[n][k] * x[m][k],   m < bs
+ * x: device fp16 [bs][K]; y: device fp16 [bs][N]; 1 <= bs <= 16.
+ * ws: device scratch of at least vq_gemv_workspace(w, bs) bytes (may be NULL
+ * when that is 0).  Errors: NULL / SHAPE / UNSUPPORTED / ALIGN / WORKSPACE / LAUNCH.
+ */
+int vq_gemv(const vq_weight_t *w, const void *x, int bs, void *y,
+            void *ws, size_t ws_bytes, void *stream);
+size_t vq_gemv_workspace(const vq_weight_t *w, int bs);
+
+/*
+ * VQ-gemm (prefill phase, Sec. III-C / Sec. VII "GeMM"): Y = X W^T with the
+ * dequantized tile fed to the fp16 matrix cores, fp32 accumulation.
+ *   Y[m][n] = scale[n] * sum_k W[n][k] * X[m][k],   m < M
+ * X: device fp16 [M][K]; Y: device fp16 [M][N]; M >= 1.
+ */
+int vq_gemm(const vq_weight_t *w, const void *X, int M, void *Y,
+            void *ws, size_t ws_bytes, void *stream);
+size_t vq_gemm_workspace(const vq_weight_t *w, int M);
+
+/*
+ * A VQ-compressed KV cache of one layer (Sec. III-A setup: VQ<4,8,1> as in CQ-2,
+ * 32 heads x 128 channels).  Every token's K (and V) vector of D channels is cut
+ * into D/v sub-vectors, each stored as one uint8 code.
+ *   K[b][h][t][p*v + i] = k_codebooks[h][g(p)][k_codes[b][h][t][p]][i],
+ *   g(p) = p * cb_groups / (D/v)
+ * cb_groups = 1: one codebook per (head, K|V); cb_groups = D/v: one codebook per
+ * sub-space, the coupled-quantization layout whose codebook switches along the
+ * channel axis (Sec. III-B, Tbl. IV) -- any divisor of D/v is accepted.
+ */
+typedef struct vq_kv_t {
+    int B, H, D, T;          /* batch, heads, head dim, cache length (row stride of the code arrays) */
+    int v;                   /* sub-vector length: 2, 4 or 8; D % v == 0 */
+    int n_entries;           /* E <= 256 */
+    int cb_groups;           /* G codebooks per (head, side); divides D/v */
+    const void *k_codes;     /* device, uint8 [B][H][T][D/v] */
+    const void *v_codes;     /* device, uint8 [B][H][T][D/v] */
+    const void *k_codebooks; /* device, fp16 [H][G][E][v] */
+    const void *v_codebooks; /* device, fp16 [H][G][E][v] */
+    const int *seq_lens;     /* device, int32 [B], valid tokens per sequence (0..T), or NULL = T */
+} vq_kv_t;
+
+/*
+ * VQ-attn (decode attention over the VQ cache; Sec. II-B formula, one query per
+ * sequence and head, all cached tokens attended, no mask):
+ *   out[b][h] = softmax_t( sm_scale * q[b][h] . K[b][h][t] ) . V[b][h][t]
+ * q, out: device fp16 [B][H][D].  sm_scale is usually 1/sqrt(D).
+ * A sequence with seq_lens[b] == 0 yields zeros.
+ * ws: at least vq_attn_decode_workspace(kv) bytes (partial softmax statistics
+ * and accumulators of the token-range split, merged by log-sum-exp).
+ */
+int vq_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out,
+                   void *ws, size_t ws_bytes, void *stream);
+size_t vq_attn_decode_workspace(const vq_kv_t *kv);
+
+/*
+ * Test hooks: the dequantized operand itself (Sec. II-A), for bit-exact checks.
+ * vq_dequant: W[N][K], fp32 (out_fp32 = 1: the fp32 sum of the residual entries)
+ *             or fp16 (out_fp32 = 0: that sum rounded to nearest even).
+ * vq_kv_dequant: which = 0 -> K, 1 -> V; out fp16 [B][H][T][D] (entries verbatim).
+ */
+int vq_dequant(const vq_weight_t *w, void *W, int out_fp32, void *stream);
+int vq_kv_dequant(const vq_kv_t *kv, int which, void *out, void *stream);
+
+/*
+ * Measurement helpers (not part of the method): a plain streaming copy and a
+ * streaming read-reduce of `bytes` bytes (multiple of 16) with 128-bit accesses,
+ * used to calibrate HBM counters and the achievable-bandwidth ceiling.
+ * vq_probe_read writes one 16-byte checksum per workgroup into sink (>= 64 KiB).
+ */
+int vq_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+int vq_probe_read(const void *src, size_t bytes, void *sink, void *stream);
+
+/* Human-readable name of a status code (static storage). */
+const char *vq_status_str(int status);
+
+/* Library version, as 10000*major + 100*minor + patch. */
+int vq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VQ_MI355X_H */

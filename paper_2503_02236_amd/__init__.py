@@ -1,0 +1,13 @@
+"""MI355X-native fused vector-quantization kernels (VQ-gemv, VQ-gemm, VQ-attn decode).
+
+The product is ``libvqmi.so`` (hand-written gfx950 HIP kernels behind a C ABI declared in
+``include/vq_mi355x.h``); this package is its thin Python binding plus the seeded synthetic
+workload generators.  Import is cheap: the library is loaded on first use and its absence is
+an error, never a fallback.
+"""
+from . import workloads  # noqa: F401
+from .binding import (  # noqa: F401
+    LIB_PATH, VQError, VQKVDev, VQWeightDev, kv_to_device, lib, status_str, vq_attn_decode,
+    vq_attn_decode_workspace, vq_dequant, vq_gemm, vq_gemm_workspace, vq_gemv, vq_gemv_workspace,
+    vq_kv_dequant, vq_probe_copy, vq_probe_read, weight_to_device,
+)

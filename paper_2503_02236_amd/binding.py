@@ -1,0 +1,246 @@
+"""Thin ctypes binding over libvqmi.so (argument marshalling only).
+
+Every function here has the name and semantics of the C entry point it wraps
+(``include/vq_mi355x.h``); torch is used for device memory and the current HIP
+stream, nothing else.  There is no fallback: if the library has not been built
+or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libvqmi.so")
+
+
+class VQError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_str(status)} ({status})")
+
+
+class vq_weight_t(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int), ("K", ctypes.c_int), ("v", ctypes.c_int), ("code_bits", ctypes.c_int),
+                ("n_codebooks", ctypes.c_int), ("n_entries", ctypes.c_int),
+                ("codes", ctypes.c_void_p), ("codebooks", ctypes.c_void_p), ("scale", ctypes.c_void_p)]
+
+
+class vq_kv_t(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("D", ctypes.c_int), ("T", ctypes.c_int),
+                ("v", ctypes.c_int), ("n_entries", ctypes.c_int), ("cb_groups", ctypes.c_int),
+                ("k_codes", ctypes.c_void_p), ("v_codes", ctypes.c_void_p),
+                ("k_codebooks", ctypes.c_void_p), ("v_codebooks", ctypes.c_void_p),
+                ("seq_lens", ctypes.c_void_p)]
+
+
+_lib = None
+
+#: name -> (restype, argtypes); must list every symbol the header declares
+SYMBOLS = {
+    "vq_gemv": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                               ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "vq_gemv_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t), ctypes.c_int]),
+    "vq_gemm": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                               ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "vq_gemm_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t), ctypes.c_int]),
+    "vq_attn_decode": (ctypes.c_int, [ctypes.POINTER(vq_kv_t), ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
+                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "vq_attn_decode_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_kv_t)]),
+    "vq_dequant": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]),
+    "vq_kv_dequant": (ctypes.c_int, [ctypes.POINTER(vq_kv_t), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]),
+    "vq_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "vq_probe_read": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]),
+    "vq_status_str": (ctypes.c_char_p, [ctypes.c_int]),
+    "vq_version": (ctypes.c_int, []),
+}
+
+
+def lib() -> ctypes.CDLL:
+    """Load libvqmi.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_02236_amd.build` "
+                               "(or __graft_entry__.build()); there is no CPU or PyTorch fallback")
+        l = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().vq_status_str(int(status)).decode()
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return int(t.data_ptr())
+
+
+@dataclass
+class VQWeightDev:
+    """Device-resident VQ weight: codes [N][K/v][R] (uint8/uint16), codebooks fp16 [R][E][v], scale fp16 [N]."""
+    N: int
+    K: int
+    v: int
+    code_bits: int
+    codes: torch.Tensor
+    codebooks: torch.Tensor
+    scale: Optional[torch.Tensor]
+
+    def desc(self) -> vq_weight_t:
+        R, E, v = self.codebooks.shape
+        code_dt = torch.uint8 if self.code_bits == 8 else torch.uint16
+        return vq_weight_t(self.N, self.K, self.v, self.code_bits, R, E,
+                           _dev(self.codes, "codes", code_dt), _dev(self.codebooks, "codebooks", torch.float16),
+                           _dev(self.scale, "scale", torch.float16))
+
+
+@dataclass
+class VQKVDev:
+    """Device-resident VQ KV cache of one layer (uint8 codes [B][H][T][D/v], fp16 codebooks [H][G][E][v])."""
+    B: int
+    H: int
+    D: int
+    T: int
+    v: int
+    k_codes: torch.Tensor
+    v_codes: torch.Tensor
+    k_codebooks: torch.Tensor
+    v_codebooks: torch.Tensor
+    seq_lens: Optional[torch.Tensor] = None
+
+    def desc(self) -> vq_kv_t:
+        _, G, E, _ = self.k_codebooks.shape
+        return vq_kv_t(self.B, self.H, self.D, self.T, self.v, E, G,
+                       _dev(self.k_codes, "k_codes", torch.uint8), _dev(self.v_codes, "v_codes", torch.uint8),
+                       _dev(self.k_codebooks, "k_codebooks", torch.float16),
+                       _dev(self.v_codebooks, "v_codebooks", torch.float16),
+                       _dev(self.seq_lens, "seq_lens", torch.int32))
+
+
+def weight_to_device(w, device="cuda:0") -> VQWeightDev:
+    """Upload a host ``workloads.VQWeight`` (numpy) to the GPU."""
+    import numpy as np
+    codes = torch.from_numpy(w.codes.view(np.uint8 if w.code_bits == 8 else np.uint16)).to(device)
+    cb = torch.from_numpy(w.codebooks).to(device)
+    sc = None if w.scale is None else torch.from_numpy(w.scale).to(device)
+    return VQWeightDev(w.N, w.K, w.v, w.code_bits, codes, cb, sc)
+
+
+def kv_to_device(kv, device="cuda:0") -> VQKVDev:
+    """Upload a host ``workloads.VQKVCache`` (numpy) to the GPU."""
+    t = lambda a: None if a is None else torch.from_numpy(a).to(device)
+    return VQKVDev(kv.B, kv.H, kv.D, kv.T, kv.v, t(kv.k_codes), t(kv.v_codes), t(kv.k_codebooks),
+                   t(kv.v_codebooks), t(kv.seq_lens))
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise VQError(status, where)
+
+
+def _workspace(nbytes: int, device, ws: Optional[torch.Tensor]):
+    if ws is not None:
+        return ws, _dev(ws, "ws"), ws.numel() * ws.element_size()
+    if nbytes == 0:
+        return None, None, 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return ws, int(ws.data_ptr()), nbytes
+
+
+def vq_gemv_workspace(w: VQWeightDev, bs: int) -> int:
+    d = w.desc()
+    return int(lib().vq_gemv_workspace(ctypes.byref(d), bs))
+
+
+def vq_gemv(w: VQWeightDev, x: torch.Tensor, y: Optional[torch.Tensor] = None,
+            ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """y[bs][N] = scale * (x[bs][K] @ dequant(W)^T) on the current stream."""
+    bs = x.shape[0]
+    if y is None:
+        y = torch.empty((bs, w.N), dtype=torch.float16, device=x.device)
+    d = w.desc()
+    ws_t, ws_p, ws_n = _workspace(int(lib().vq_gemv_workspace(ctypes.byref(d), bs)), x.device, ws)
+    _check(lib().vq_gemv(ctypes.byref(d), _dev(x, "x", torch.float16), bs, _dev(y, "y", torch.float16),
+                         ws_p, ws_n, _stream()), "vq_gemv")
+    return y
+
+
+def vq_gemm_workspace(w: VQWeightDev, M: int) -> int:
+    d = w.desc()
+    return int(lib().vq_gemm_workspace(ctypes.byref(d), M))
+
+
+def vq_gemm(w: VQWeightDev, X: torch.Tensor, Y: Optional[torch.Tensor] = None,
+            ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y[M][N] = scale * (X[M][K] @ dequant(W)^T) on the current stream (matrix cores)."""
+    M = X.shape[0]
+    if Y is None:
+        Y = torch.empty((M, w.N), dtype=torch.float16, device=X.device)
+    d = w.desc()
+    ws_t, ws_p, ws_n = _workspace(int(lib().vq_gemm_workspace(ctypes.byref(d), M)), X.device, ws)
+    _check(lib().vq_gemm(ctypes.byref(d), _dev(X, "X", torch.float16), M, _dev(Y, "Y", torch.float16),
+                         ws_p, ws_n, _stream()), "vq_gemm")
+    return Y
+
+
+def vq_attn_decode_workspace(kv: VQKVDev) -> int:
+    d = kv.desc()
+    return int(lib().vq_attn_decode_workspace(ctypes.byref(d)))
+
+
+def vq_attn_decode(kv: VQKVDev, q: torch.Tensor, sm_scale: float, out: Optional[torch.Tensor] = None,
+                   ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out[B][H][D] = softmax(sm_scale * q K^T) V over the VQ cache, on the current stream."""
+    if out is None:
+        out = torch.empty_like(q)
+    d = kv.desc()
+    ws_t, ws_p, ws_n = _workspace(int(lib().vq_attn_decode_workspace(ctypes.byref(d))), q.device, ws)
+    _check(lib().vq_attn_decode(ctypes.byref(d), _dev(q, "q", torch.float16), float(sm_scale),
+                                _dev(out, "out", torch.float16), ws_p, ws_n, _stream()), "vq_attn_decode")
+    return out
+
+
+def vq_dequant(w: VQWeightDev, out_fp32: bool = True) -> torch.Tensor:
+    """Dense W[N][K] (fp32 sum of residual entries, or its fp16 rounding): test hook."""
+    W = torch.empty((w.N, w.K), dtype=torch.float32 if out_fp32 else torch.float16, device=w.codes.device)
+    d = w.desc()
+    _check(lib().vq_dequant(ctypes.byref(d), _dev(W, "W"), 1 if out_fp32 else 0, _stream()), "vq_dequant")
+    return W
+
+
+def vq_kv_dequant(kv: VQKVDev, which: int) -> torch.Tensor:
+    """Dense fp16 K (which=0) or V (which=1) [B][H][T][D]: test hook."""
+    out = torch.empty((kv.B, kv.H, kv.T, kv.D), dtype=torch.float16, device=kv.k_codes.device)
+    d = kv.desc()
+    _check(lib().vq_kv_dequant(ctypes.byref(d), which, _dev(out, "out"), _stream()), "vq_kv_dequant")
+    return out
+
+
+def vq_probe_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    n = src.numel() * src.element_size()
+    _check(lib().vq_probe_copy(_dev(dst, "dst"), _dev(src, "src"), n, _stream()), "vq_probe_copy")
+
+
+def vq_probe_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    n = src.numel() * src.element_size()
+    _check(lib().vq_probe_read(_dev(src, "src"), n, _dev(sink, "sink"), _stream()), "vq_probe_read")

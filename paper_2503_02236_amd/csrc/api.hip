@@ -1,0 +1,148 @@
+// C ABI of libvqmi: host-side argument validation and dispatch to the gfx950 kernels.
+// Operand format and operations: VQ-LLM (arXiv 2503.02236) Sec. II-A, II-B, III-C.
+#include "vq_common.h"
+
+namespace vq {
+
+int check_weight(const vq_weight_t *w) {
+    if (!w) return VQ_ERR_NULL;
+    if (!w->codes || !w->codebooks) return VQ_ERR_NULL;
+    if (w->N < 0 || w->K < 0) return VQ_ERR_SHAPE;
+    if (w->v != 4 && w->v != 8) return VQ_ERR_UNSUPPORTED;
+    if (w->code_bits != 8 && w->code_bits != 16) return VQ_ERR_UNSUPPORTED;
+    if (w->n_codebooks < 1 || w->n_codebooks > 4) return VQ_ERR_UNSUPPORTED;
+    if (w->n_entries < 1 || w->n_entries > (1 << w->code_bits)) return VQ_ERR_UNSUPPORTED;
+    if (w->K % w->v != 0) return VQ_ERR_SHAPE;
+    if (!aligned16(w->codes) || !aligned16(w->codebooks)) return VQ_ERR_ALIGN;
+    if (w->scale && !aligned16(w->scale)) return VQ_ERR_ALIGN;
+    return VQ_OK;
+}
+
+int check_kv(const vq_kv_t *kv) {
+    if (!kv) return VQ_ERR_NULL;
+    if (!kv->k_codes || !kv->v_codes || !kv->k_codebooks || !kv->v_codebooks) return VQ_ERR_NULL;
+    if (kv->B < 0 || kv->H < 0 || kv->T < 0 || kv->D <= 0) return VQ_ERR_SHAPE;
+    if (kv->v != 2 && kv->v != 4 && kv->v != 8) return VQ_ERR_UNSUPPORTED;
+    if (kv->n_entries < 1 || kv->n_entries > 256) return VQ_ERR_UNSUPPORTED;
+    if (kv->D % kv->v != 0) return VQ_ERR_SHAPE;
+    int P = kv->D / kv->v;
+    if (kv->cb_groups < 1 || P % kv->cb_groups != 0) return VQ_ERR_SHAPE;
+    if (kv->D > 256 || kv->D % 8 != 0) return VQ_ERR_UNSUPPORTED;
+    if (!aligned16(kv->k_codes) || !aligned16(kv->v_codes) || !aligned16(kv->k_codebooks) ||
+        !aligned16(kv->v_codebooks))
+        return VQ_ERR_ALIGN;
+    if (kv->seq_lens && (reinterpret_cast<uintptr_t>(kv->seq_lens) & 3u)) return VQ_ERR_ALIGN;
+    return VQ_OK;
+}
+
+}  // namespace vq
+
+using namespace vq;
+
+extern "C" {
+
+int vq_version(void) { return 100; }
+
+const char *vq_status_str(int status) {
+    switch (status) {
+        case VQ_OK: return "VQ_OK";
+        case VQ_ERR_NULL: return "VQ_ERR_NULL: required pointer is NULL";
+        case VQ_ERR_SHAPE: return "VQ_ERR_SHAPE: inconsistent or out-of-range sizes";
+        case VQ_ERR_UNSUPPORTED: return "VQ_ERR_UNSUPPORTED: VQ configuration not supported";
+        case VQ_ERR_ALIGN: return "VQ_ERR_ALIGN: data pointer not 16-byte aligned";
+        case VQ_ERR_WORKSPACE: return "VQ_ERR_WORKSPACE: workspace missing or too small";
+        case VQ_ERR_LAUNCH: return "VQ_ERR_LAUNCH: HIP launch failed";
+        default: return "unknown vq_status";
+    }
+}
+
+size_t vq_gemv_workspace(const vq_weight_t *w, int bs) {
+    if (check_weight(w) != VQ_OK || bs < 1 || bs > 16) return 0;
+    return gemv_workspace(w, bs);
+}
+
+int vq_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *ws, size_t ws_bytes, void *stream) {
+    int st = check_weight(w);
+    if (st != VQ_OK) return st;
+    if (!x || !y) return VQ_ERR_NULL;
+    if (bs < 1 || bs > 16) return VQ_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(y)) return VQ_ERR_ALIGN;
+    size_t need = gemv_workspace(w, bs);
+    if (need && (!ws || ws_bytes < need)) return VQ_ERR_WORKSPACE;
+    if (ws && !aligned16(ws)) return VQ_ERR_ALIGN;
+    if (w->N == 0) return VQ_OK;
+    return launch_gemv(w, x, bs, y, ws, static_cast<hipStream_t>(stream));
+}
+
+size_t vq_gemm_workspace(const vq_weight_t *w, int M) {
+    if (check_weight(w) != VQ_OK || M < 1) return 0;
+    return gemm_workspace(w, M);
+}
+
+int vq_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *ws, size_t ws_bytes, void *stream) {
+    int st = check_weight(w);
+    if (st != VQ_OK) return st;
+    if (!X || !Y) return VQ_ERR_NULL;
+    if (M < 1) return VQ_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Y)) return VQ_ERR_ALIGN;
+    size_t need = gemm_workspace(w, M);
+    if (need && (!ws || ws_bytes < need)) return VQ_ERR_WORKSPACE;
+    if (ws && !aligned16(ws)) return VQ_ERR_ALIGN;
+    if (w->N == 0) return VQ_OK;
+    return launch_gemm(w, X, M, Y, ws, static_cast<hipStream_t>(stream));
+}
+
+size_t vq_attn_decode_workspace(const vq_kv_t *kv) {
+    if (check_kv(kv) != VQ_OK) return 0;
+    return attn_decode_workspace(kv);
+}
+
+int vq_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, size_t ws_bytes,
+                   void *stream) {
+    int st = check_kv(kv);
+    if (st != VQ_OK) return st;
+    if (!q || !out) return VQ_ERR_NULL;
+    if (!aligned16(q) || !aligned16(out)) return VQ_ERR_ALIGN;
+    size_t need = attn_decode_workspace(kv);
+    if (need && (!ws || ws_bytes < need)) return VQ_ERR_WORKSPACE;
+    if (ws && !aligned16(ws)) return VQ_ERR_ALIGN;
+    if (kv->B == 0 || kv->H == 0) return VQ_OK;
+    return launch_attn_decode(kv, q, sm_scale, out, ws, static_cast<hipStream_t>(stream));
+}
+
+int vq_dequant(const vq_weight_t *w, void *W, int out_fp32, void *stream) {
+    int st = check_weight(w);
+    if (st != VQ_OK) return st;
+    if (!W) return VQ_ERR_NULL;
+    if (!aligned16(W)) return VQ_ERR_ALIGN;
+    if (w->N == 0 || w->K == 0) return VQ_OK;
+    return launch_dequant(w, W, out_fp32, static_cast<hipStream_t>(stream));
+}
+
+int vq_kv_dequant(const vq_kv_t *kv, int which, void *out, void *stream) {
+    int st = check_kv(kv);
+    if (st != VQ_OK) return st;
+    if (!out) return VQ_ERR_NULL;
+    if (which != 0 && which != 1) return VQ_ERR_SHAPE;
+    if (!aligned16(out)) return VQ_ERR_ALIGN;
+    if (kv->B == 0 || kv->H == 0 || kv->T == 0) return VQ_OK;
+    return launch_kv_dequant(kv, which, out, static_cast<hipStream_t>(stream));
+}
+
+int vq_probe_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src) return VQ_ERR_NULL;
+    if (bytes % 16 != 0) return VQ_ERR_SHAPE;
+    if (!aligned16(dst) || !aligned16(src)) return VQ_ERR_ALIGN;
+    if (bytes == 0) return VQ_OK;
+    return launch_probe_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
+}
+
+int vq_probe_read(const void *src, size_t bytes, void *sink, void *stream) {
+    if (!sink || !src) return VQ_ERR_NULL;
+    if (bytes % 16 != 0) return VQ_ERR_SHAPE;
+    if (!aligned16(sink) || !aligned16(src)) return VQ_ERR_ALIGN;
+    if (bytes == 0) return VQ_OK;
+    return launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,145 @@
+// Test-hook kernels: the dequantized operand itself (VQ-LLM Sec. II-A, dequantization:
+// look up one entry per residual codebook, add them element-wise, concatenate sub-vectors),
+// plus two streaming probes used to calibrate bandwidth measurements.
+#include "vq_common.h"
+
+namespace vq {
+
+// One thread per sub-vector: W[n][j*V .. j*V+V) = sum_r C_r[code[n][j][r]] (fp32, r ascending).
+template <typename CodeT, int V, bool OUT32>
+__global__ __launch_bounds__(256) void dequant_kernel(const CodeT *__restrict__ codes,
+                                                      const half_t *__restrict__ cb, void *__restrict__ out,
+                                                      long n_vec, int R, int E) {
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long stride = (long)gridDim.x * blockDim.x;
+    for (; i < n_vec; i += stride) {
+        float acc[V];
+        half_t first[V];
+        for (int r = 0; r < R; ++r) {
+            unsigned c = codes[i * R + r];
+            const half_t *e = cb + ((size_t)r * E + c) * V;
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                half_t h = e[k];
+                if (r == 0) {
+                    first[k] = h;
+                    acc[k] = (float)h;
+                } else {
+                    acc[k] += (float)h;
+                }
+            }
+        }
+        if (OUT32) {
+            float *o = reinterpret_cast<float *>(out) + i * V;
+#pragma unroll
+            for (int k = 0; k < V; ++k) o[k] = acc[k];
+        } else {
+            half_t *o = reinterpret_cast<half_t *>(out) + i * V;
+#pragma unroll
+            for (int k = 0; k < V; ++k) o[k] = (R == 1) ? first[k] : (half_t)acc[k];  // RNE
+        }
+    }
+}
+
+int launch_dequant(const vq_weight_t *w, void *W, int out_fp32, hipStream_t s) {
+    long n_vec = (long)w->N * (w->K / w->v);
+    int blocks = (int)((n_vec + 255) / 256 < 65536 ? (n_vec + 255) / 256 : 65536);
+#define VQ_DQ(CT, V)                                                                                            \
+    do {                                                                                                        \
+        if (out_fp32)                                                                                           \
+            dequant_kernel<CT, V, true><<<blocks, 256, 0, s>>>((const CT *)w->codes, (const half_t *)w->codebooks, W, \
+                                                               n_vec, w->n_codebooks, w->n_entries);            \
+        else                                                                                                    \
+            dequant_kernel<CT, V, false><<<blocks, 256, 0, s>>>((const CT *)w->codes, (const half_t *)w->codebooks, W, \
+                                                                n_vec, w->n_codebooks, w->n_entries);           \
+    } while (0)
+    if (w->code_bits == 8) {
+        if (w->v == 8) VQ_DQ(uint8_t, 8); else VQ_DQ(uint8_t, 4);
+    } else {
+        if (w->v == 8) VQ_DQ(uint16_t, 8); else VQ_DQ(uint16_t, 4);
+    }
+#undef VQ_DQ
+    return launch_status();
+}
+
+// One thread per (b, h, t, p): copies entry k/v_codebooks[h][g(p)][code] verbatim.
+__global__ __launch_bounds__(256) void kv_dequant_kernel(const uint8_t *__restrict__ codes,
+                                                         const uint16_t *__restrict__ cb,
+                                                         uint16_t *__restrict__ out, long n_vec, int H, int T,
+                                                         int P, int v, int E, int G) {
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long stride = (long)gridDim.x * blockDim.x;
+    for (; i < n_vec; i += stride) {
+        int p = (int)(i % P);
+        long bht = i / P;
+        int h = (int)((bht / T) % H);
+        int g = (int)(((long)p * G) / P);
+        const uint16_t *e = cb + (((size_t)h * G + g) * E + codes[i]) * v;
+        for (int k = 0; k < v; ++k) out[i * v + k] = e[k];
+    }
+}
+
+int launch_kv_dequant(const vq_kv_t *kv, int which, void *out, hipStream_t s) {
+    int P = kv->D / kv->v;
+    long n_vec = (long)kv->B * kv->H * kv->T * P;
+    int blocks = (int)((n_vec + 255) / 256 < 65536 ? (n_vec + 255) / 256 : 65536);
+    kv_dequant_kernel<<<blocks, 256, 0, s>>>((const uint8_t *)(which ? kv->v_codes : kv->k_codes),
+                                             (const uint16_t *)(which ? kv->v_codebooks : kv->k_codebooks),
+                                             (uint16_t *)out, n_vec, kv->H, kv->T, P, kv->v, kv->n_entries,
+                                             kv->cb_groups);
+    return launch_status();
+}
+
+// ---- measurement probes: 128-bit streaming copy / read-reduce -------------------------------
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
+                                                         size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict__ src, size_t n16,
+                                                         uint4 *__restrict__ sink) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint4 a = make_uint4(0, 0, 0, 0);
+    // four independent loads in flight per thread
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+        a.x ^= v0.x ^ v1.x ^ v2.x ^ v3.x;
+        a.y ^= v0.y ^ v1.y ^ v2.y ^ v3.y;
+        a.z ^= v0.z ^ v1.z ^ v2.z ^ v3.z;
+        a.w ^= v0.w ^ v1.w ^ v2.w ^ v3.w;
+    }
+    for (; i < n16; i += stride) {
+        uint4 v0 = src[i];
+        a.x ^= v0.x; a.y ^= v0.y; a.z ^= v0.z; a.w ^= v0.w;
+    }
+    // fold the block into one value so the loads cannot be removed
+    __shared__ uint4 red[256];
+    red[threadIdx.x] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint4 t = make_uint4(0, 0, 0, 0);
+        for (int k = 0; k < 256; ++k) { t.x ^= red[k].x; t.y ^= red[k].y; t.z ^= red[k].z; t.w ^= red[k].w; }
+        sink[blockIdx.x] = t;
+    }
+}
+
+int launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
+    size_t n16 = bytes / 16;
+    int blocks = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+    probe_copy_kernel<<<blocks, 256, 0, s>>>((uint4 *)dst, (const uint4 *)src, n16);
+    return launch_status();
+}
+
+int launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t s) {
+    size_t n16 = bytes / 16;
+    int blocks = (int)((n16 + 1023) / 1024 < 4096 ? (n16 + 1023) / 1024 : 4096);
+    if (blocks < 1) blocks = 1;
+    probe_read_kernel<<<blocks, 256, 0, s>>>((const uint4 *)src, n16, (uint4 *)sink);
+    return launch_status();
+}
+
+}  // namespace vq

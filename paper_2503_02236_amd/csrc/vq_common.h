@@ -1,0 +1,86 @@
+// Internal helpers shared by the gfx950 kernels of libvqmi (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "vq_mi355x.h"
+
+namespace vq {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// 16-byte value that can be viewed as codes, packed halves or dwords.
+union alignas(16) V16 {
+    uint4 u;
+    uint32_t w[4];
+    uint16_t h[8];
+    uint8_t b[16];
+    half2_t h2[4];
+    half8_t h8;
+};
+
+union alignas(8) V8 {
+    uint2 u;
+    uint32_t w[2];
+    uint16_t h[4];
+    half2_t h2[2];
+    half4_t h4;
+};
+
+__device__ __forceinline__ V16 ld16(const void *p) {
+    V16 r;
+    r.u = *reinterpret_cast<const uint4 *>(p);
+    return r;
+}
+__device__ __forceinline__ V8 ld8(const void *p) {
+    V8 r;
+    r.u = *reinterpret_cast<const uint2 *>(p);
+    return r;
+}
+
+// a.x*b.x + a.y*b.y + c with fp32 accumulation (v_dot2_f32_f16).
+__device__ __forceinline__ float dot2(half2_t a, half2_t b, float c) {
+    return __builtin_amdgcn_fdot2(a, b, c, false);
+}
+
+// Sum over the 64 lanes of a wavefront; every lane gets the total.
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+    return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, 64));
+    return x;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Host-side validation shared by the entry points (no HIP calls).
+int check_weight(const vq_weight_t *w);
+int check_kv(const vq_kv_t *kv);
+
+// Kernel launchers (defined next to their kernels).
+int launch_dequant(const vq_weight_t *w, void *W, int out_fp32, hipStream_t s);
+int launch_kv_dequant(const vq_kv_t *kv, int which, void *out, hipStream_t s);
+int launch_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *ws, hipStream_t s);
+size_t gemv_workspace(const vq_weight_t *w, int bs);
+int launch_gemv_generic(const vq_weight_t *w, const void *x, int bs, void *y, hipStream_t s);
+int launch_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *ws, hipStream_t s);
+size_t gemm_workspace(const vq_weight_t *w, int M);
+int launch_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, hipStream_t s);
+size_t attn_decode_workspace(const vq_kv_t *kv);
+int launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+int launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t s);
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_LAUNCH; }
+
+}  // namespace vq

@@ -1,0 +1,151 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every declared symbol,
+and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2503_02236_amd as vq
+from paper_2503_02236_amd.binding import SYMBOLS, vq_kv_t, vq_weight_t
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "vq_mi355x.h")
+
+VQ_ERR_NULL, VQ_ERR_SHAPE, VQ_ERR_UNSUPPORTED, VQ_ERR_ALIGN, VQ_ERR_WORKSPACE = -1, -2, -3, -4, -5
+P = 0x10000  # a 16-byte aligned fake device address; never dereferenced on the error paths
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vq_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_and_library_exports_the_same_symbols():
+    names = declared_functions()
+    assert {"vq_gemv", "vq_gemm", "vq_attn_decode", "vq_dequant", "vq_kv_dequant"} <= set(names)
+    lib = vq.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(SYMBOLS) == names       # the binding wraps exactly what the header declares
+
+
+def test_status_strings():
+    assert vq.status_str(0) == "VQ_OK"
+    for s in range(-6, 0):
+        assert vq.status_str(s).startswith("VQ_ERR_")
+    assert "unknown" in vq.status_str(-99)
+    assert vq.lib().vq_version() >= 100
+
+
+def weight(**kw):
+    d = dict(N=64, K=64, v=8, code_bits=8, n_codebooks=1, n_entries=256, codes=P, codebooks=P, scale=None)
+    d.update(kw)
+    return vq_weight_t(**d)
+
+
+def kvdesc(**kw):
+    d = dict(B=1, H=1, D=128, T=16, v=4, n_entries=256, cb_groups=1, k_codes=P, v_codes=P, k_codebooks=P,
+             v_codebooks=P, seq_lens=None)
+    d.update(kw)
+    return vq_kv_t(**d)
+
+
+def gemv(w, x=P, bs=1, y=P, ws=None, ws_bytes=0):
+    return vq.lib().vq_gemv(ctypes.byref(w), x, bs, y, ws, ws_bytes, None)
+
+
+def gemm(w, x=P, M=1, y=P):
+    return vq.lib().vq_gemm(ctypes.byref(w), x, M, y, None, 0, None)
+
+
+@pytest.mark.parametrize("w,want", [
+    (weight(codes=None), VQ_ERR_NULL),
+    (weight(codebooks=None), VQ_ERR_NULL),
+    (weight(v=3), VQ_ERR_UNSUPPORTED),
+    (weight(v=16), VQ_ERR_UNSUPPORTED),
+    (weight(code_bits=12), VQ_ERR_UNSUPPORTED),
+    (weight(n_codebooks=0), VQ_ERR_UNSUPPORTED),
+    (weight(n_codebooks=5), VQ_ERR_UNSUPPORTED),
+    (weight(n_entries=257), VQ_ERR_UNSUPPORTED),
+    (weight(n_entries=0), VQ_ERR_UNSUPPORTED),
+    (weight(K=60), VQ_ERR_SHAPE),
+    (weight(N=-1), VQ_ERR_SHAPE),
+    (weight(codes=P + 8), VQ_ERR_ALIGN),
+    (weight(codebooks=P + 2), VQ_ERR_ALIGN),
+    (weight(scale=P + 4), VQ_ERR_ALIGN),
+])
+def test_weight_descriptor_validation(w, want):
+    assert gemv(w) == want
+    assert gemm(w) == want
+    assert vq.lib().vq_dequant(ctypes.byref(w), P, 1, None) == want
+    assert vq.lib().vq_gemv_workspace(ctypes.byref(w), 1) == 0
+
+
+def test_gemv_gemm_argument_validation():
+    w = weight()
+    assert vq.lib().vq_gemv(None, P, 1, P, None, 0, None) == VQ_ERR_NULL
+    assert gemv(w, x=None) == VQ_ERR_NULL
+    assert gemv(w, y=None) == VQ_ERR_NULL
+    assert gemv(w, bs=0) == VQ_ERR_SHAPE
+    assert gemv(w, bs=17) == VQ_ERR_SHAPE
+    assert gemv(w, x=P + 2) == VQ_ERR_ALIGN
+    assert gemv(w, y=P + 6) == VQ_ERR_ALIGN
+    assert gemm(w, M=0) == VQ_ERR_SHAPE
+    assert gemm(w, x=None) == VQ_ERR_NULL
+    assert gemm(w, y=P + 2) == VQ_ERR_ALIGN
+    assert vq.lib().vq_dequant(ctypes.byref(w), None, 1, None) == VQ_ERR_NULL
+    # N == 0 is a valid empty problem: success without a launch
+    assert gemv(weight(N=0)) == 0
+    assert gemm(weight(N=0)) == 0
+
+
+@pytest.mark.parametrize("kv,want", [
+    (kvdesc(k_codes=None), VQ_ERR_NULL),
+    (kvdesc(v_codebooks=None), VQ_ERR_NULL),
+    (kvdesc(v=3), VQ_ERR_UNSUPPORTED),
+    (kvdesc(n_entries=512), VQ_ERR_UNSUPPORTED),
+    (kvdesc(D=126), VQ_ERR_SHAPE),
+    (kvdesc(cb_groups=3), VQ_ERR_SHAPE),
+    (kvdesc(cb_groups=0), VQ_ERR_SHAPE),
+    (kvdesc(T=-1), VQ_ERR_SHAPE),
+    (kvdesc(k_codes=P + 1), VQ_ERR_ALIGN),
+    (kvdesc(seq_lens=P + 2), VQ_ERR_ALIGN),
+])
+def test_kv_descriptor_validation(kv, want):
+    lib = vq.lib()
+    assert lib.vq_attn_decode(ctypes.byref(kv), P, 0.1, P, None, 0, None) == want
+    assert lib.vq_kv_dequant(ctypes.byref(kv), 0, P, None) == want
+    assert lib.vq_attn_decode_workspace(ctypes.byref(kv)) == 0
+
+
+def test_attention_argument_validation():
+    lib = vq.lib()
+    kv = kvdesc()
+    assert lib.vq_attn_decode(ctypes.byref(kv), None, 0.1, P, None, 0, None) == VQ_ERR_NULL
+    assert lib.vq_attn_decode(ctypes.byref(kv), P, 0.1, P + 8, None, 0, None) == VQ_ERR_ALIGN
+    assert lib.vq_kv_dequant(ctypes.byref(kv), 2, P, None) == VQ_ERR_SHAPE
+    big = kvdesc(T=100000, B=2, H=2)
+    need = lib.vq_attn_decode_workspace(ctypes.byref(big))
+    assert need > 0                                    # long caches are split and need partials
+    assert lib.vq_attn_decode(ctypes.byref(big), P, 0.1, P, None, 0, None) == VQ_ERR_WORKSPACE
+    assert lib.vq_attn_decode(ctypes.byref(big), P, 0.1, P, P, need - 1, None) == VQ_ERR_WORKSPACE
+    assert lib.vq_attn_decode(ctypes.byref(kvdesc(B=0)), P, 0.1, P, None, 0, None) == 0
+
+
+def test_probe_argument_validation():
+    lib = vq.lib()
+    assert lib.vq_probe_copy(None, P, 16, None) == VQ_ERR_NULL
+    assert lib.vq_probe_copy(P, P, 15, None) == VQ_ERR_SHAPE
+    assert lib.vq_probe_read(P + 4, 16, P, None) == VQ_ERR_ALIGN
+    assert lib.vq_probe_copy(P, P, 0, None) == 0
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    from paper_2503_02236_amd import workloads as wl
+    w, x = wl.config1_tiny()
+    wd = vq.VQWeightDev(w.N, w.K, w.v, w.code_bits, torch.from_numpy(w.codes), torch.from_numpy(w.codebooks), None)
+    with pytest.raises(ValueError):
+        vq.vq_gemv(wd, torch.from_numpy(x))

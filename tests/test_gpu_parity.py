@@ -1,0 +1,234 @@
+"""GPU parity: every entry point of libvqmi, called through the C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Bars: dequantized tiles bit-exact; products and attention within relative L2 <= 2e-3 and
+max-abs <= 1e-2 * RMS(oracle output) of the un-rounded fp64 oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_02236_amd as vq
+from paper_2503_02236_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 2e-3
+MAX_ABS_RMS = 1e-2
+
+
+def assert_close(got_t, want, what=""):
+    got = got_t.float().cpu().numpy().astype(np.float64)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.isfinite(got).all(), what
+    rel = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300)
+    rms = np.sqrt(np.mean(want ** 2))
+    mx = np.abs(got - want).max() / max(rms, 1e-300)
+    print(f"{what}: rel_l2={rel:.3e} max_abs/rms={mx:.3e}", flush=True)
+    assert rel <= REL_L2, (what, rel)
+    assert mx <= MAX_ABS_RMS, (what, mx)
+
+
+def dev_x(x, device):
+    return torch.from_numpy(x).to(device)
+
+
+# ---------------------------------------------------------------- dequantized tiles: bit exact
+
+@pytest.mark.parametrize("N,K,v,bits,R,E,sigma", [
+    (256, 256, 8, 8, 1, 256, 0.02),        # config 1
+    (96, 4096, 8, 16, 1, 65536, 0.02),     # config 2 codebook, a slab of rows
+    (80, 4096, 8, 8, 2, 256, 0.01),        # config 3: additive pair
+    (64, 1024, 4, 16, 1, 65536, 0.02),     # config 4b
+    (33, 72, 4, 8, 3, 100, 0.02),          # ragged everything, three residuals
+    (5, 40, 8, 16, 4, 1000, 1e-4),         # mostly subnormal entries
+])
+def test_dequant_tiles_bit_exact(gpu_device, N, K, v, bits, R, E, sigma):
+    w = wl.make_weight(N, K, v, bits, R, E, sigma, seed=7 + N + K)
+    wd = vq.weight_to_device(w, gpu_device)
+    want32 = oracle.dequant(w.codes, w.codebooks)
+    got32 = vq.vq_dequant(wd, out_fp32=True).cpu().numpy()
+    assert np.array_equal(got32.view(np.uint32), want32.view(np.uint32))
+    got16 = vq.vq_dequant(wd, out_fp32=False).cpu().numpy()
+    assert np.array_equal(got16.view(np.uint16), want32.astype(np.float16).view(np.uint16))
+    if R == 1:   # one codebook: the tile is the entry's fp16 bits verbatim
+        assert np.array_equal(got16.view(np.uint16), w.codebooks[0][w.codes[:, :, 0]].reshape(N, K).view(np.uint16))
+
+
+@pytest.mark.parametrize("G,v", [(1, 4), (32, 4), (4, 8), (64, 2)])
+def test_kv_dequant_bit_exact(gpu_device, G, v):
+    kv = wl.make_kv(2, 3, 128, 37, v, 256, G, seed=31 + G)
+    kd = vq.kv_to_device(kv, gpu_device)
+    for which, codes, cb in ((0, kv.k_codes, kv.k_codebooks), (1, kv.v_codes, kv.v_codebooks)):
+        got = vq.vq_kv_dequant(kd, which).cpu().numpy()
+        want = oracle.kv_dequant(codes, cb).astype(np.float16)
+        assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+
+
+# ---------------------------------------------------------------- VQ-gemv
+
+def run_gemv(w, x, device):
+    wd = vq.weight_to_device(w, device)
+    y = vq.vq_gemv(wd, dev_x(x, device))
+    torch.cuda.synchronize()
+    return y
+
+
+def test_gemv_config1_tiny(gpu_device):
+    w, x = wl.config1_tiny()
+    assert_close(run_gemv(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x), "C1")
+
+
+@pytest.mark.parametrize("shape_idx", [0, 1, 2])
+def test_gemv_config2_llama7b_full_size(gpu_device, shape_idx):
+    w = wl.config2_layer(shape_idx)
+    x = wl.make_activations(1, w.K, wl.seed_for(2, shape_idx))
+    assert_close(run_gemv(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x), f"C2[{shape_idx}]")
+
+
+@pytest.mark.parametrize("shape_idx,bs", [(0, 1), (0, 4), (0, 16), (1, 1), (1, 16), (2, 4), (2, 16)])
+def test_gemv_config3_additive_full_size(gpu_device, shape_idx, bs):
+    w = wl.config3_layer(shape_idx)
+    x = wl.make_activations(bs, w.K, wl.seed_for(3, shape_idx * 100 + bs))
+    assert_close(run_gemv(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x), f"C3[{shape_idx}] bs={bs}")
+
+
+@pytest.mark.parametrize("N,K,v,bits,R,E,bs,scale", [
+    (1, 64, 8, 16, 1, 65536, 1, True),       # a single row
+    (19, 4096, 8, 16, 1, 65536, 3, True),    # ragged row count, odd batch
+    (130, 11008, 8, 16, 1, 4096, 2, False),  # three K-ranges, last one partly filled
+    (77, 8192, 8, 16, 1, 65536, 5, True),    # two K-ranges
+    (50, 16384, 8, 16, 1, 65536, 1, True),   # four K-ranges
+    (45, 1024, 4, 16, 1, 65536, 7, True),    # v = 4
+    (45, 1024, 4, 8, 1, 256, 16, True),      # v = 4, uint8
+    (45, 2048, 4, 8, 2, 256, 4, True),       # v = 4 additive
+    (45, 2048, 8, 16, 2, 4096, 9, True),     # uint16 additive
+    (31, 72, 8, 8, 1, 256, 2, True),         # K not a multiple of the chunk: generic path
+    (31, 120, 4, 16, 3, 300, 16, False),     # three residuals: generic path
+    (9, 32768, 8, 16, 1, 65536, 1, True),    # very long rows: generic path
+])
+def test_gemv_shapes_and_edges(gpu_device, N, K, v, bits, R, E, bs, scale):
+    sigma = 0.02 / R
+    w = wl.make_weight(N, K, v, bits, R, E, sigma, seed=1000 + N + K + bs, with_scale=scale)
+    x = wl.make_activations(bs, K, seed=2000 + N + K)
+    assert_close(run_gemv(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x), f"{N}x{K} v{v} R{R} bs{bs}")
+
+
+def test_gemv_zipf_codes(gpu_device):
+    w = wl.config2_layer(0, zipf_s=1.0)
+    x = wl.make_activations(1, w.K, 5)
+    assert_close(run_gemv(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x), "C2 zipf")
+
+
+def test_gemv_is_deterministic_and_leaves_neighbours_alone(gpu_device):
+    w = wl.config2_layer(0)
+    wd = vq.weight_to_device(w, gpu_device)
+    x = dev_x(wl.make_activations(1, w.K, 3), gpu_device)
+    buf = torch.full((w.N + 64,), 7.0, dtype=torch.float16, device=gpu_device)
+    y = buf[32:32 + w.N].view(1, w.N)
+    vq.vq_gemv(wd, x, y=y)
+    first = y.clone()
+    for _ in range(3):
+        vq.vq_gemv(wd, x, y=y)
+        assert torch.equal(y, first)
+    assert (buf[:32] == 7).all() and (buf[32 + w.N:] == 7).all()
+
+
+# ---------------------------------------------------------------- VQ-gemm
+
+@pytest.mark.parametrize("M,N,K,v,scale", [
+    (96, 256, 512, 8, False),
+    (300, 200, 1024, 8, True),     # ragged M and N tiles
+    (257, 520, 256, 4, True),      # v = 4, ragged
+    (32, 64, 64, 8, False),        # one K block
+    (7, 40, 128, 8, True),         # small M: row-kernel path
+])
+def test_gemm_small_full_compare(gpu_device, M, N, K, v, scale):
+    w = wl.make_weight(N, K, v, 16, 1, 65536, 0.02, seed=4000 + M + N, with_scale=scale)
+    X = wl.make_activations(M, K, seed=4100 + M)
+    Y = vq.vq_gemm(vq.weight_to_device(w, gpu_device), dev_x(X, gpu_device))
+    torch.cuda.synchronize()
+    assert_close(Y, oracle.gemm(w.codes, w.codebooks, w.scale, X), f"gemm {M}x{N}x{K} v{v}")
+
+
+def test_gemm_other_formats_use_row_path(gpu_device):
+    w = wl.make_weight(70, 256, 8, 8, 2, 256, 0.01, seed=4500)
+    X = wl.make_activations(40, 256, seed=4501)
+    Y = vq.vq_gemm(vq.weight_to_device(w, gpu_device), dev_x(X, gpu_device))
+    assert_close(Y, oracle.gemm(w.codes, w.codebooks, w.scale, X), "gemm uint8 R=2")
+
+
+@pytest.mark.parametrize("N,v", [(4096, 8), (11008, 8), (4096, 4), (11008, 4)])
+def test_gemm_config4_full_size_sampled_columns(gpu_device, N, v):
+    w = wl.config4_layer(N, v)
+    X = wl.make_activations(2048, 4096, wl.seed_for(4, N + v))
+    Y = vq.vq_gemm(vq.weight_to_device(w, gpu_device), dev_x(X, gpu_device))
+    torch.cuda.synchronize()
+    r = np.random.Generator(np.random.PCG64(N + v))
+    rows = np.unique(np.concatenate([r.integers(0, N, size=44), [0, 31, 32, 255, 256, N - 1, N - 33]]))
+    want = oracle.gemm(w.codes, w.codebooks, w.scale, X, rows=rows)      # all 2048 tokens x sampled columns
+    assert_close(Y[:, torch.from_numpy(rows).to(gpu_device)], want, f"C4 N={N} v={v}")
+    assert torch.isfinite(Y.float()).all()
+
+
+def test_gemm_rows_match_gemv(gpu_device):
+    # the prefill product of a few tokens and the decode product of the same tokens agree to tolerance
+    w = wl.make_weight(256, 1024, 8, 16, 1, 65536, 0.02, seed=4600)
+    X = wl.make_activations(64, 1024, seed=4601)
+    wd = vq.weight_to_device(w, gpu_device)
+    Y = vq.vq_gemm(wd, dev_x(X, gpu_device)).float().cpu().numpy()
+    y = vq.vq_gemv(wd, dev_x(X[:16].copy(), gpu_device)).float().cpu().numpy()
+    assert np.linalg.norm(Y[:16] - y) / np.linalg.norm(y) < 1e-3
+
+
+# ---------------------------------------------------------------- VQ-attn decode
+
+def run_attn(kv, device, sm_scale):
+    kd = vq.kv_to_device(kv, device)
+    out = vq.vq_attn_decode(kd, dev_x(kv.q, device), sm_scale)
+    torch.cuda.synchronize()
+    return out
+
+
+def oracle_attn(kv, sm_scale):
+    return oracle.attn_decode(kv.k_codes, kv.v_codes, kv.k_codebooks, kv.v_codebooks, kv.q, sm_scale,
+                              seq_lens=kv.seq_lens)
+
+
+@pytest.mark.parametrize("B,H,T,v,G,ragged", [
+    (2, 3, 1, 4, 1, False),        # a single token: out = V[0]
+    (2, 3, 300, 4, 1, False),
+    (3, 2, 2048, 4, 1, True),      # exactly one token range, ragged lengths
+    (2, 2, 2049, 4, 1, False),     # one token spills into a second range
+    (2, 2, 5000, 4, 1, True),      # three ranges, ragged
+    (1, 2, 700, 4, 32, False),     # one codebook per sub-space (coupled-quantization layout)
+    (1, 2, 700, 4, 4, True),
+    (1, 2, 513, 8, 1, False),
+    (1, 2, 513, 8, 16, False),
+    (1, 2, 513, 2, 1, True),
+    (1, 2, 513, 2, 64, False),
+])
+def test_attn_small_full_compare(gpu_device, B, H, T, v, G, ragged):
+    kv = wl.make_kv(B, H, 128, T, v, 256, G, seed=5000 + T + G + v, ragged=ragged)
+    sm = 1.0 / np.sqrt(128.0)
+    assert_close(run_attn(kv, gpu_device, sm), oracle_attn(kv, sm), f"attn B{B} H{H} T{T} v{v} G{G}")
+
+
+def test_attn_zero_length_sequence_and_sharp_softmax(gpu_device):
+    kv = wl.make_kv(3, 2, 128, 600, 4, 256, 1, seed=5100)
+    kv.seq_lens = np.array([600, 0, 1], dtype=np.int32)
+    sm = 1.0                                  # un-scaled scores ~ N(0, 128): nearly one-hot softmax
+    out = run_attn(kv, gpu_device, sm)
+    want = oracle_attn(kv, sm)
+    assert (out[1] == 0).all()
+    assert_close(out, want, "attn len0 / sharp")
+
+
+def test_attn_config5_full_size(gpu_device):
+    kv = wl.config5_kv()
+    sm = 1.0 / np.sqrt(128.0)
+    out = run_attn(kv, gpu_device, sm)
+    assert_close(out, oracle_attn(kv, sm), "C5 full")
+    again = run_attn(kv, gpu_device, sm)
+    assert torch.equal(out, again)            # fixed-order reductions: bit-identical repeats
