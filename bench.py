@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     ap.add_argument("--skip-secondary", action="store_true", help="only the headline gemv stack")
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--canonical", action="store_true",
+                    help="headline gemv from the canonical code layout (L2 gathers) instead of the re-tiled codes")
     ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add")
     return ap.parse_args()
 
@@ -80,14 +82,16 @@ def main():
 
     class GemvCall:
         """Pre-marshalled vq_gemv call (descriptor built once, so the loop is launch-bound only)."""
-        def __init__(self, wd, x, y):
-            self.keep = (wd, x, y)
+        def __init__(self, wd, x, y, ws=None):
+            self.keep = (wd, x, y, ws)
             self.desc = wd.desc()
             self.ref = ctypes.byref(self.desc)
             self.x, self.y, self.bs = x.data_ptr(), y.data_ptr(), x.shape[0]
+            self.ws = None if ws is None else ws.data_ptr()
+            self.ws_bytes = 0 if ws is None else ws.numel()
 
         def __call__(self):
-            st = lib.vq_gemv(self.ref, self.x, self.bs, self.y, None, 0, _stream())
+            st = lib.vq_gemv(self.ref, self.x, self.bs, self.y, self.ws, self.ws_bytes, _stream())
             if st != 0:
                 raise vq.VQError(st, "vq_gemv")
 
@@ -100,13 +104,15 @@ def main():
         x_by_k = {K: torch.from_numpy(wl.make_activations(1, K, wl.seed_for(2, K))).to(dev) for K in (4096, 11008)}
         calls, eff_bytes, per_shape = [], 0, {0: [], 1: [], 2: []}
         host_block0 = []
+        packed = not args.canonical
+        ws = vq.new_workspace(32 * 11008 * 4, dev) if packed else None   # shared by all layers
         for layer in range(L):
             for slot, si in enumerate(wl.LLAMA7B_BLOCK):
                 N, K = wl.LLAMA7B_SHAPES[si]
                 w = wl.make_weight(N, K, 8, 16, 1, 65536, 0.02, wl.seed_for(2, layer * 7 + slot))
-                wd = vq.weight_to_device(w, dev)
+                wd = vq.weight_to_device(w, dev, prepack=packed, keep_codes=not packed)
                 y = torch.empty((1, N), dtype=torch.float16, device=dev)
-                c = GemvCall(wd, x_by_k[K], y)
+                c = GemvCall(wd, x_by_k[K], y, ws)
                 calls.append(c)
                 per_shape[si].append(c)
                 eff_bytes += w.effective_bytes(1)
@@ -152,7 +158,7 @@ def main():
             ms = timed(loop, 5, 1)
             N, K = wl.LLAMA7B_SHAPES[si]
             b = cs[0].keep[0]
-            bytes_one = (b.codes.numel() * 2 + b.codebooks.numel() * 2 + K * 2 + N * 2 + N * 2)
+            bytes_one = (N * (K // 8) * 2 + b.codebooks.numel() * 2 + K * 2 + N * 2 + N * 2)
             us = ms * 1e3 / len(cs)
             shape_us["%dx%d" % (N, K)] = {"us": round(us, 3), "GBps": round(bytes_one / us / 1e3, 1),
                                           "pct_hbm_peak": round(100 * bytes_one / us / 1e3 / HBM_PEAK_GBPS, 2)}
@@ -169,10 +175,12 @@ def main():
             "config": {"workload": "C2: Llama-7B decode VQ-gemv bs=1, %d blocks x 7 matrices, VQ<8,16,1> uint16 codes, "
                                    "fp16 scale" % L,
                        "launches_per_step": n_launch, "effective_bytes_per_step": eff_bytes,
+                       "code_layout": "re-tiled offline by vq_gemv_prepack (LDS codebook slices)" if packed
+                                      else "canonical [N][K/8] (entries gathered from L2)",
                        "timing": "hip-graph replay" if graph is not None else "eager launches"},
             "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
             "gemv_per_shape_cold": shape_us,
-            "roofline": {"bound": "hbm", "kernel": "gemv_rows_kernel<uint16,8,1>",
+            "roofline": {"bound": "hbm", "kernel": "gemv_packed_kernel" if packed else "gemv_rows_kernel<uint16,8,1>",
                          "achieved": round(gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                          "bytes_per_launch": eff_bytes // n_launch,

@@ -46,6 +46,28 @@ typedef enum vq_status {
 } vq_status;
 
 /*
+ * Kernel-private re-tiling of the codes of one weight matrix for the bs = 1 VQ-gemv
+ * (weights are quantized offline, Sec. II-C; the paper itself rewrites indices offline when
+ * it reorders codebook entries, Sec. V-B).  Produced on the HOST by vq_gemv_prepack(); the
+ * caller uploads `data` to the device and hands this struct back unchanged.
+ *
+ * Idea (codebook-centric dataflow, Sec. VI-A, taken to the entry level): the codebook is cut
+ * into S slices that fit LDS, rows into RB blocks; workgroup (slice, block) sees only the codes
+ * that point into its slice, stored as 24-bit "atoms" (entry index inside the slice, sub-vector
+ * position j, valid bit), one row per lane, rows of similar length grouped 64 at a time.  Partial
+ * sums of the S slices are added in a fixed order by a second kernel (Sec. VI-A "global reduction").
+ * Layout of `data`: see the format description in the source of vq_gemv_prepack.
+ */
+typedef struct vq_gemv_pack_t {
+    const void *data;         /* DEVICE pointer when passed to vq_gemv (HOST buffer while packing) */
+    uint64_t bytes;           /* size of data */
+    uint32_t S, RB;           /* codebook slices, row blocks; S * RB workgroups */
+    uint32_t rows_per_block;
+    uint32_t n_groups;        /* 64-row groups in total */
+    uint64_t wg_off, group_off, rowid_off, atom_off; /* byte offsets of the four tables in data */
+} vq_gemv_pack_t;
+
+/*
  * A VQ-compressed weight matrix W[N][K] of a linear layer y = W x
  * (N output features, K input features).  Sub-vectors lie along K, the
  * reduction axis, so row n holds K/v sub-vectors.
@@ -61,6 +83,7 @@ typedef struct vq_weight_t {
     const void *codes;     /* device, [N][K/v][R], r fastest */
     const void *codebooks; /* device, fp16 [R][E][v] */
     const void *scale;     /* device, fp16 [N] per output channel, or NULL (= 1) */
+    const vq_gemv_pack_t *gemv_pack; /* host pointer, optional: re-tiled codes for vq_gemv with bs = 1 */
 } vq_weight_t;
 
 /*
@@ -73,6 +96,22 @@ typedef struct vq_weight_t {
 int vq_gemv(const vq_weight_t *w, const void *x, int bs, void *y,
             void *ws, size_t ws_bytes, void *stream);
 size_t vq_gemv_workspace(const vq_weight_t *w, int bs);
+
+/*
+ * Offline re-tiling for vq_gemv (see vq_gemv_pack_t).  HOST function: w->codes is read from
+ * HOST memory here (codebooks / scale are not touched); no GPU is needed.
+ *   vq_gemv_prepack_bytes: size of the packed buffer for this matrix, 0 if the configuration
+ *     has no packed form (supported: v = 8, uint16 codes, one codebook, E a power of two
+ *     >= 4096, K / v <= 2047).
+ *   vq_gemv_prepack: writes the packed buffer into out_host (>= that size, 16-byte aligned)
+ *     and fills *pack (pack->data = out_host; replace it by the device copy's address before
+ *     passing the struct to vq_gemv).  Errors: NULL / UNSUPPORTED / WORKSPACE (buffer too small).
+ * With w->gemv_pack set and bs == 1, vq_gemv runs from the packed codes (w->codes may then be
+ * NULL) and needs the workspace vq_gemv_workspace() reports (S x N fp32 partial sums; calls that
+ * share one workspace must not overlap).
+ */
+size_t vq_gemv_prepack_bytes(const vq_weight_t *w_host);
+int vq_gemv_prepack(const vq_weight_t *w_host, void *out_host, size_t out_bytes, vq_gemv_pack_t *pack);
 
 /*
  * VQ-gemm (prefill phase, Sec. III-C / Sec. VII "GeMM"): Y = X W^T with the

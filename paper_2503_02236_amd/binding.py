@@ -24,10 +24,18 @@ class VQError(RuntimeError):
         super().__init__(f"{where}: {status_str(status)} ({status})")
 
 
+class vq_gemv_pack_t(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("bytes", ctypes.c_uint64), ("S", ctypes.c_uint32), ("RB", ctypes.c_uint32),
+                ("rows_per_block", ctypes.c_uint32), ("n_groups", ctypes.c_uint32),
+                ("wg_off", ctypes.c_uint64), ("group_off", ctypes.c_uint64), ("rowid_off", ctypes.c_uint64),
+                ("atom_off", ctypes.c_uint64)]
+
+
 class vq_weight_t(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int), ("K", ctypes.c_int), ("v", ctypes.c_int), ("code_bits", ctypes.c_int),
                 ("n_codebooks", ctypes.c_int), ("n_entries", ctypes.c_int),
-                ("codes", ctypes.c_void_p), ("codebooks", ctypes.c_void_p), ("scale", ctypes.c_void_p)]
+                ("codes", ctypes.c_void_p), ("codebooks", ctypes.c_void_p), ("scale", ctypes.c_void_p),
+                ("gemv_pack", ctypes.POINTER(vq_gemv_pack_t))]
 
 
 class vq_kv_t(ctypes.Structure):
@@ -45,6 +53,9 @@ SYMBOLS = {
     "vq_gemv": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "vq_gemv_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t), ctypes.c_int]),
+    "vq_gemv_prepack_bytes": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t)]),
+    "vq_gemv_prepack": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_size_t,
+                                       ctypes.POINTER(vq_gemv_pack_t)]),
     "vq_gemm": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "vq_gemm_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t), ctypes.c_int]),
@@ -102,16 +113,21 @@ class VQWeightDev:
     K: int
     v: int
     code_bits: int
-    codes: torch.Tensor
+    codes: Optional[torch.Tensor]
     codebooks: torch.Tensor
     scale: Optional[torch.Tensor]
+    pack_data: Optional[torch.Tensor] = None     # device copy of the vq_gemv_prepack buffer
+    pack: Optional[vq_gemv_pack_t] = None        # its descriptor (data already points at pack_data)
 
-    def desc(self) -> vq_weight_t:
+    def desc(self, use_pack: bool = True) -> vq_weight_t:
         R, E, v = self.codebooks.shape
         code_dt = torch.uint8 if self.code_bits == 8 else torch.uint16
-        return vq_weight_t(self.N, self.K, self.v, self.code_bits, R, E,
-                           _dev(self.codes, "codes", code_dt), _dev(self.codebooks, "codebooks", torch.float16),
-                           _dev(self.scale, "scale", torch.float16))
+        d = vq_weight_t(self.N, self.K, self.v, self.code_bits, R, E,
+                        _dev(self.codes, "codes", code_dt), _dev(self.codebooks, "codebooks", torch.float16),
+                        _dev(self.scale, "scale", torch.float16), None)
+        if use_pack and self.pack is not None:
+            d.gemv_pack = ctypes.pointer(self.pack)
+        return d
 
 
 @dataclass
@@ -137,13 +153,49 @@ class VQKVDev:
                        _dev(self.seq_lens, "seq_lens", torch.int32))
 
 
-def weight_to_device(w, device="cuda:0") -> VQWeightDev:
-    """Upload a host ``workloads.VQWeight`` (numpy) to the GPU."""
+def vq_gemv_prepack(w):
+    """Offline re-tiling of a host ``workloads.VQWeight`` for the bs = 1 gemv (host only, no GPU).
+
+    Returns (packed uint8 numpy buffer, vq_gemv_pack_t whose ``data`` points at that buffer), or
+    (None, None) if the configuration has no packed form.
+    """
     import numpy as np
-    codes = torch.from_numpy(w.codes.view(np.uint8 if w.code_bits == 8 else np.uint16)).to(device)
+    codes = np.ascontiguousarray(w.codes)
+    d = vq_weight_t(w.N, w.K, w.v, w.code_bits, int(w.codebooks.shape[0]), int(w.codebooks.shape[1]),
+                    codes.ctypes.data, None, None, None)
+    n = int(lib().vq_gemv_prepack_bytes(ctypes.byref(d)))
+    if n == 0:
+        return None, None
+    buf = np.empty(n + 16, dtype=np.uint8)
+    off = (-buf.ctypes.data) % 16
+    out = buf[off:off + n]
+    pack = vq_gemv_pack_t()
+    _check(lib().vq_gemv_prepack(ctypes.byref(d), out.ctypes.data, n, ctypes.byref(pack)), "vq_gemv_prepack")
+    return out, pack
+
+
+def weight_to_device(w, device="cuda:0", prepack: bool = False, keep_codes: bool = True) -> VQWeightDev:
+    """Upload a host ``workloads.VQWeight`` (numpy) to the GPU; ``prepack`` adds the re-tiled gemv codes."""
+    import numpy as np
+    codes = None
+    if keep_codes or not prepack:
+        codes = torch.from_numpy(w.codes.view(np.uint8 if w.code_bits == 8 else np.uint16)).to(device)
     cb = torch.from_numpy(w.codebooks).to(device)
     sc = None if w.scale is None else torch.from_numpy(w.scale).to(device)
-    return VQWeightDev(w.N, w.K, w.v, w.code_bits, codes, cb, sc)
+    wd = VQWeightDev(w.N, w.K, w.v, w.code_bits, codes, cb, sc)
+    if prepack:
+        buf, pack = vq_gemv_prepack(w)
+        if buf is None:
+            raise ValueError("this VQ configuration has no packed gemv form")
+        wd.pack_data = torch.from_numpy(buf).to(device)
+        pack.data = int(wd.pack_data.data_ptr())
+        wd.pack = pack
+    return wd
+
+
+def new_workspace(nbytes: int, device="cuda:0") -> torch.Tensor:
+    """Device scratch of at least ``nbytes`` bytes (contents need no initialisation)."""
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
 
 
 def kv_to_device(kv, device="cuda:0") -> VQKVDev:

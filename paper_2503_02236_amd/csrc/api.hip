@@ -4,16 +4,16 @@
 
 namespace vq {
 
-int check_weight(const vq_weight_t *w) {
+int check_weight(const vq_weight_t *w, bool need_codes) {
     if (!w) return VQ_ERR_NULL;
-    if (!w->codes || !w->codebooks) return VQ_ERR_NULL;
+    if ((need_codes && !w->codes) || !w->codebooks) return VQ_ERR_NULL;
     if (w->N < 0 || w->K < 0) return VQ_ERR_SHAPE;
     if (w->v != 4 && w->v != 8) return VQ_ERR_UNSUPPORTED;
     if (w->code_bits != 8 && w->code_bits != 16) return VQ_ERR_UNSUPPORTED;
     if (w->n_codebooks < 1 || w->n_codebooks > 4) return VQ_ERR_UNSUPPORTED;
     if (w->n_entries < 1 || w->n_entries > (1 << w->code_bits)) return VQ_ERR_UNSUPPORTED;
     if (w->K % w->v != 0) return VQ_ERR_SHAPE;
-    if (!aligned16(w->codes) || !aligned16(w->codebooks)) return VQ_ERR_ALIGN;
+    if ((w->codes && !aligned16(w->codes)) || !aligned16(w->codebooks)) return VQ_ERR_ALIGN;
     if (w->scale && !aligned16(w->scale)) return VQ_ERR_ALIGN;
     return VQ_OK;
 }
@@ -57,15 +57,21 @@ const char *vq_status_str(int status) {
 }
 
 size_t vq_gemv_workspace(const vq_weight_t *w, int bs) {
-    if (check_weight(w) != VQ_OK || bs < 1 || bs > 16) return 0;
+    if (!w || bs < 1 || bs > 16) return 0;
+    const bool packed = gemv_uses_pack(w, bs);
+    if (check_weight(w, !packed) != VQ_OK) return 0;
+    if (packed && check_pack(w) != VQ_OK) return 0;
     return gemv_workspace(w, bs);
 }
 
 int vq_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *ws, size_t ws_bytes, void *stream) {
-    int st = check_weight(w);
-    if (st != VQ_OK) return st;
-    if (!x || !y) return VQ_ERR_NULL;
+    if (!w) return VQ_ERR_NULL;
     if (bs < 1 || bs > 16) return VQ_ERR_SHAPE;
+    const bool packed = gemv_uses_pack(w, bs);
+    int st = check_weight(w, !packed);
+    if (st != VQ_OK) return st;
+    if (packed && (st = check_pack(w)) != VQ_OK) return st;
+    if (!x || !y) return VQ_ERR_NULL;
     if (!aligned16(x) || !aligned16(y)) return VQ_ERR_ALIGN;
     size_t need = gemv_workspace(w, bs);
     if (need && (!ws || ws_bytes < need)) return VQ_ERR_WORKSPACE;
@@ -75,12 +81,12 @@ int vq_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *ws, size
 }
 
 size_t vq_gemm_workspace(const vq_weight_t *w, int M) {
-    if (check_weight(w) != VQ_OK || M < 1) return 0;
+    if (check_weight(w, true) != VQ_OK || M < 1) return 0;
     return gemm_workspace(w, M);
 }
 
 int vq_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *ws, size_t ws_bytes, void *stream) {
-    int st = check_weight(w);
+    int st = check_weight(w, true);
     if (st != VQ_OK) return st;
     if (!X || !Y) return VQ_ERR_NULL;
     if (M < 1) return VQ_ERR_SHAPE;
@@ -111,7 +117,7 @@ int vq_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, 
 }
 
 int vq_dequant(const vq_weight_t *w, void *W, int out_fp32, void *stream) {
-    int st = check_weight(w);
+    int st = check_weight(w, true);
     if (st != VQ_OK) return st;
     if (!W) return VQ_ERR_NULL;
     if (!aligned16(W)) return VQ_ERR_ALIGN;

@@ -206,7 +206,7 @@ int launch_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *, hip
     // any other configuration: 16 tokens at a time through the generic row kernel
     for (int m = 0; m < M; m += 16) {
         int bs = M - m < 16 ? M - m : 16;
-        int st = launch_gemv(w, Xp + (size_t)m * w->K, bs, Yp + (size_t)m * w->N, nullptr, s);
+        int st = launch_gemv_rows(w, Xp + (size_t)m * w->K, bs, Yp + (size_t)m * w->N, s);
         if (st != VQ_OK) return st;
     }
     return VQ_OK;

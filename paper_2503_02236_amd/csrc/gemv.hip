@@ -233,7 +233,7 @@ __global__ void fill_zero_kernel(half_t *p, long n) {
     if (i < n) p[i] = (half_t)0.f;
 }
 
-size_t gemv_workspace(const vq_weight_t *, int) { return 0; }
+size_t gemv_workspace(const vq_weight_t *w, int bs) { return gemv_uses_pack(w, bs) ? gemv_packed_workspace(w) : 0; }
 
 namespace {
 
@@ -315,7 +315,13 @@ int dispatch(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream
 
 }  // namespace
 
-int launch_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *, hipStream_t s) {
+int launch_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *ws, hipStream_t s) {
+    if (gemv_uses_pack(w, bs) && w->K > 0) return launch_gemv_packed(w, x, y, ws, s);
+    return launch_gemv_rows(w, x, bs, y, s);
+}
+
+// From the canonical code layout (any batch size 1..16).
+int launch_gemv_rows(const vq_weight_t *w, const void *x, int bs, void *y, hipStream_t s) {
     const half_t *xp = (const half_t *)x;
     half_t *yp = (half_t *)y;
     if (w->K == 0) {  // empty reduction: y = 0 (a fill kernel, so the call can be graph-captured)

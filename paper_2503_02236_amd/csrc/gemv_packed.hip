@@ -1,0 +1,388 @@
+// bs = 1 VQ-gemv from re-tiled ("packed") codes: codebook slices in LDS, dense LDS gathers.
+//
+// Why: with a 2^16 x 8 fp16 codebook (1 MiB) the entries cannot live in LDS, and random
+// 16-byte gathers from L2 run at ~0.44 per clock per CU on MI355X (each one moves a
+// 128-byte line), an order of magnitude below what the HBM code stream could feed.  Random
+// 16-byte gathers from LDS run at ~5.5 per clock per CU.  So the product is partitioned
+// along the codebook itself -- the codebook-centric dataflow of VQ-LLM (arXiv 2503.02236)
+// Sec. VI-A pushed from "one codebook per block" to "one codebook slice per block":
+//   workgroup (s, rb) holds slice s (E/S entries) and the activation vector in LDS and
+//   processes, for the rows of block rb, exactly the codes that point into slice s.
+// Those codes are found offline (Sec. II-C: weights are quantized offline; Sec. V-B already
+// rewrites indices offline) by vq_gemv_prepack and stored as 24-bit atoms:
+//   bits 0..11  entry index inside the slice      bits 12..22  sub-vector position j
+//   bit 23      valid (padding atoms are 0)
+// One lane owns one row: it walks that row's atoms (j ascending), gathers entry and x_j from
+// LDS and accumulates privately, so there is no cross-lane reduction at all.  Rows of a block
+// are sorted by atom count and grouped 64 at a time, so the lanes of a wavefront run nearly the
+// same trip count.  The S partial sums of a row are added in slice order by a second small
+// kernel (Sec. VI-A "explicit global reduction"), which keeps the result bit-reproducible.
+//
+// Packed buffer (little endian, all offsets from the start of the buffer, 256-byte aligned):
+//   wg table     [S*RB]      { uint32 first_group, uint32 n_groups }   workgroup = s*RB + rb; every
+//                            workgroup has ceil(rows_per_block / 64) groups, so first_group = wg * n_groups
+//   group table  [n_groups]  { uint32 atom_block, uint32 n_steps }     atom_block in 768-byte units
+//   row ids      [n_groups][64] uint16   row inside the block, 0xFFFF = idle lane
+//   atoms        blocks of 768 bytes = 64 lanes x 12 bytes = 4 atoms per lane per step
+#include <algorithm>
+#include <cstring>
+#include <vector>
+
+#include "vq_common.h"
+
+namespace vq {
+
+constexpr int kPackLocalBits = 12;
+constexpr int kPackJBits = 11;
+constexpr uint32_t kPackValid = 1u << 23;
+
+struct PackPlan {
+    uint32_t S, RB, rows_per_block, slice_entries;
+};
+
+static bool pack_supported(const vq_weight_t *w) {
+    if (w->v != 8 || w->code_bits != 16 || w->n_codebooks != 1) return false;
+    int E = w->n_entries;
+    if (E < 4096 || (E & (E - 1)) != 0) return false;
+    if (w->K <= 0 || w->N <= 0 || w->K / 8 >= (1 << kPackJBits)) return false;
+    return true;
+}
+
+// S * RB = 256 workgroups, one per compute unit.  Slices of 2048 entries (32 KiB) unless that
+// would give a workgroup more than 16 row groups (one per wavefront): then 4096 entries.
+static PackPlan pack_plan(const vq_weight_t *w) {
+    PackPlan p;
+    p.slice_entries = 2048;
+    if ((uint64_t)w->N * ((uint32_t)w->n_entries / 2048) > 256u * 1024u) p.slice_entries = 4096;
+    p.S = (uint32_t)w->n_entries / p.slice_entries;
+    uint32_t rb = 256 / p.S;
+    uint32_t max_rb = ((uint32_t)w->N + 63) / 64;   // at least one full 64-row group per block
+    if (rb > max_rb) rb = max_rb;
+    if (rb < 1) rb = 1;
+    p.RB = rb;
+    p.rows_per_block = ((uint32_t)w->N + rb - 1) / rb;
+    return p;
+}
+
+static inline uint64_t align256(uint64_t x) { return (x + 255) & ~(uint64_t)255; }
+
+// One pass builds everything; `out` == nullptr only measures.
+static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pack_t *pack) {
+    const PackPlan p = pack_plan(w);
+    const int J = w->K / 8;
+    const uint16_t *codes = reinterpret_cast<const uint16_t *>(w->codes);
+    uint32_t lb = 0;  // log2(slice_entries)
+    while ((1u << lb) < p.slice_entries) ++lb;
+    const uint32_t nwg = p.S * p.RB;
+
+    // counts[rb][s][row_in_block]
+    std::vector<uint32_t> cnt((size_t)nwg * p.rows_per_block, 0);
+    for (int n = 0; n < w->N; ++n) {
+        uint32_t rb = (uint32_t)n / p.rows_per_block, ri = (uint32_t)n % p.rows_per_block;
+        const uint16_t *row = codes + (size_t)n * J;
+        for (int j = 0; j < J; ++j) cnt[((size_t)(row[j] >> lb) * p.RB + rb) * p.rows_per_block + ri]++;
+    }
+    // per workgroup: rows sorted by count (descending, ties by row), groups of 64
+    struct Group { uint32_t atom_block, n_steps; };
+    std::vector<uint32_t> wg_tab((size_t)nwg * 2);
+    std::vector<Group> groups;
+    std::vector<uint16_t> rowids;
+    std::vector<uint32_t> order(p.rows_per_block);
+    uint64_t atom_blocks = 0;
+    for (uint32_t wg = 0; wg < nwg; ++wg) {
+        uint32_t rb = wg % p.RB;
+        uint32_t rows_here = 0;
+        if ((uint64_t)rb * p.rows_per_block < (uint64_t)w->N)
+            rows_here = std::min<uint32_t>(p.rows_per_block, (uint32_t)w->N - rb * p.rows_per_block);
+        const uint32_t *c = &cnt[(size_t)wg * p.rows_per_block];
+        for (uint32_t i = 0; i < rows_here; ++i) order[i] = i;
+        std::stable_sort(order.begin(), order.begin() + rows_here, [&](uint32_t a, uint32_t b) { return c[a] > c[b]; });
+        wg_tab[2 * wg] = (uint32_t)groups.size();   // always wg * groups_per_wg: the kernel computes it
+        const uint32_t ng = (p.rows_per_block + 63) / 64;
+        wg_tab[2 * wg + 1] = ng;
+        for (uint32_t g = 0; g < ng; ++g) {
+            Group gr;
+            gr.atom_block = (uint32_t)atom_blocks;
+            gr.n_steps = g * 64 < rows_here ? (c[order[g * 64]] + 3) / 4 : 0;  // a group's first row is its longest
+            atom_blocks += gr.n_steps;
+            groups.push_back(gr);
+            for (uint32_t l = 0; l < 64; ++l) {
+                uint32_t i = g * 64 + l;
+                rowids.push_back(i < rows_here ? (uint16_t)order[i] : (uint16_t)0xFFFF);
+            }
+        }
+    }
+    const uint64_t wg_off = 0;
+    const uint64_t group_off = align256(wg_off + wg_tab.size() * 4);
+    const uint64_t rowid_off = align256(group_off + groups.size() * sizeof(Group));
+    const uint64_t atom_off = align256(rowid_off + rowids.size() * 2);
+    const uint64_t total = atom_off + atom_blocks * 768;
+    if (pack) {
+        pack->data = out;
+        pack->bytes = total;
+        pack->S = p.S;
+        pack->RB = p.RB;
+        pack->rows_per_block = p.rows_per_block;
+        pack->n_groups = (uint32_t)groups.size();
+        pack->wg_off = wg_off;
+        pack->group_off = group_off;
+        pack->rowid_off = rowid_off;
+        pack->atom_off = atom_off;
+    }
+    if (!out) return total;
+
+    std::memset(out, 0, (size_t)atom_off);
+    std::memcpy(out + wg_off, wg_tab.data(), wg_tab.size() * 4);
+    std::memcpy(out + group_off, groups.data(), groups.size() * sizeof(Group));
+    std::memcpy(out + rowid_off, rowids.data(), rowids.size() * 2);
+    unsigned char *atoms = out + atom_off;
+    std::memset(atoms, 0, (size_t)(atom_blocks * 768));
+    // fill: lane l of group g walks row rowids[g][l]; its k-th atom of slice s goes to step k/4, slot k%4
+    for (uint32_t wg = 0; wg < nwg; ++wg) {
+        uint32_t s = wg / p.RB, rb = wg % p.RB;
+        for (uint32_t g = 0; g < wg_tab[2 * wg + 1]; ++g) {
+            const Group &gr = groups[wg_tab[2 * wg] + g];
+            for (uint32_t l = 0; l < 64; ++l) {
+                uint16_t ri = rowids[((size_t)wg_tab[2 * wg] + g) * 64 + l];
+                if (ri == 0xFFFF) continue;
+                const uint16_t *row = codes + ((size_t)rb * p.rows_per_block + ri) * J;
+                uint32_t k = 0;
+                for (int j = 0; j < J; ++j) {
+                    if ((uint32_t)(row[j] >> lb) != s) continue;
+                    uint32_t atom = (row[j] & ((1u << lb) - 1)) | ((uint32_t)j << kPackLocalBits) | kPackValid;
+                    unsigned char *q = atoms + ((size_t)gr.atom_block + k / 4) * 768 + l * 12 + (k % 4) * 3;
+                    q[0] = (unsigned char)atom;
+                    q[1] = (unsigned char)(atom >> 8);
+                    q[2] = (unsigned char)(atom >> 16);
+                    ++k;
+                }
+            }
+        }
+    }
+    return total;
+}
+
+// ---------------------------------------------------------------------------------- kernel
+
+struct PackedArgs {
+    const unsigned char *data;
+    const half_t *cb, *scale, *x;
+    half_t *y;
+    float *partial;       // [S][N]
+    int N, J, S, RB, rows_per_block, slice_entries;
+    unsigned long long wg_off, group_off, rowid_off, atom_off;
+};
+
+constexpr int kPackMaxSlices = 32;  // 2^16 entries / 2048 per slice
+constexpr int kPackPrefetch = 12;  // 4-atom steps held in registers while the slice is being staged
+
+__device__ __forceinline__ float atom_dot(uint32_t atom, const unsigned char *slice, const unsigned char *xl, float acc) {
+    V16 e = *reinterpret_cast<const V16 *>(slice + ((atom & 0xfffu) << 4));
+    V16 xv = *reinterpret_cast<const V16 *>(xl + (((atom >> kPackLocalBits) & 0x7ffu) << 4));
+    float d = dot2(e.h2[0], xv.h2[0], 0.f);
+    d = dot2(e.h2[1], xv.h2[1], d);
+    d = dot2(e.h2[2], xv.h2[2], d);
+    d = dot2(e.h2[3], xv.h2[3], d);
+    return (atom & kPackValid) ? acc + d : acc;
+}
+
+struct Acc4 {
+    float a0, a1, a2, a3;
+};
+
+__device__ __forceinline__ void step_dot(uint32_t d0, uint32_t d1, uint32_t d2, const unsigned char *slice,
+                                         const unsigned char *xl, Acc4 &acc) {
+    acc.a0 = atom_dot(d0 & 0xffffffu, slice, xl, acc.a0);
+    acc.a1 = atom_dot(__builtin_amdgcn_alignbit(d1, d0, 24) & 0xffffffu, slice, xl, acc.a1);
+    acc.a2 = atom_dot(__builtin_amdgcn_alignbit(d2, d1, 16) & 0xffffffu, slice, xl, acc.a2);
+    acc.a3 = atom_dot(d2 >> 8, slice, xl, acc.a3);
+}
+
+// All global loads of a workgroup are issued before anything waits: the kernel is a chain of
+// memory latencies (tables -> atoms -> partials), not a bandwidth problem, at these sizes.
+__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *slice = smem;                                    // slice_entries * 16 bytes
+    unsigned char *xl = smem + (size_t)a.slice_entries * 16;        // J * 16 bytes
+    float *accbuf = reinterpret_cast<float *>(xl + (size_t)a.J * 16);  // one float per row of the block
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nthreads = blockDim.x, nwaves = nthreads >> 6;
+    const int wg = blockIdx.x, s = wg / a.RB, rb = wg % a.RB;
+    const uint2 *gtab = reinterpret_cast<const uint2 *>(a.data + a.group_off);
+    const uint16_t *rowids = reinterpret_cast<const uint16_t *>(a.data + a.rowid_off);
+    const unsigned char *atoms = a.data + a.atom_off + lane * 12;
+
+    // (1) codebook slice and x: issue every load first (up to 4 + 2 per thread in flight)
+    const uint4 *src = reinterpret_cast<const uint4 *>(a.cb) + (size_t)s * a.slice_entries;
+    const uint4 *xs = reinterpret_cast<const uint4 *>(a.x);
+    uint4 sv[4], xv[3];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int idx = tid + i * nthreads;
+        sv[i] = idx < a.slice_entries ? src[idx] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        int idx = tid + i * nthreads;
+        xv[i] = idx < a.J ? xs[idx] : make_uint4(0, 0, 0, 0);
+    }
+    // (2) this wavefront's first group: table entry, row ids, then its atoms
+    const uint32_t n_groups = (uint32_t)(a.rows_per_block + 63) / 64, first_group = (uint32_t)wg * n_groups;
+    uint2 gr = make_uint2(0, 0);
+    uint32_t ri = 0xFFFFu;
+    if ((uint32_t)wave < n_groups) {
+        gr = gtab[first_group + wave];
+        ri = rowids[((size_t)first_group + wave) * 64 + lane];
+    }
+    uint32_t q[kPackPrefetch][3];
+#pragma unroll
+    for (int st = 0; st < kPackPrefetch; ++st) {
+        if ((uint32_t)st < gr.y) {
+            const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768);
+            q[st][0] = p[0]; q[st][1] = p[1]; q[st][2] = p[2];
+        } else {
+            q[st][0] = q[st][1] = q[st][2] = 0;
+        }
+    }
+    // (3) LDS writes of the staged data (slices larger than 4 * nthreads entries take the slow loop)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int idx = tid + i * nthreads;
+        if (idx < a.slice_entries) reinterpret_cast<uint4 *>(slice)[idx] = sv[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        int idx = tid + i * nthreads;
+        if (idx < a.J) reinterpret_cast<uint4 *>(xl)[idx] = xv[i];
+    }
+    for (int idx = tid + 4 * nthreads; idx < a.slice_entries; idx += nthreads) reinterpret_cast<uint4 *>(slice)[idx] = src[idx];
+    for (int idx = tid + 3 * nthreads; idx < a.J; idx += nthreads) reinterpret_cast<uint4 *>(xl)[idx] = xs[idx];
+    __syncthreads();
+
+    // (4) gathers and dot products: lane = row; results go to LDS in natural row order
+    for (uint32_t g = wave; g < n_groups; g += nwaves) {
+        if (g != (uint32_t)wave) {  // later groups of this wavefront: load as we go
+            gr = gtab[first_group + g];
+            ri = rowids[((size_t)first_group + g) * 64 + lane];
+        }
+        Acc4 acc = {0.f, 0.f, 0.f, 0.f};
+        uint32_t st0 = 0;
+        if (g == (uint32_t)wave) {
+#pragma unroll
+            for (int st = 0; st < kPackPrefetch; ++st)
+                if ((uint32_t)st < gr.y) step_dot(q[st][0], q[st][1], q[st][2], slice, xl, acc);
+            st0 = kPackPrefetch;
+        }
+        for (uint32_t st = st0; st < gr.y; ++st) {
+            const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768);
+            step_dot(p[0], p[1], p[2], slice, xl, acc);
+        }
+        if (ri != 0xFFFFu) accbuf[ri] = (acc.a0 + acc.a1) + (acc.a2 + acc.a3);
+    }
+    __syncthreads();
+
+    // (5) this slice's partial sums, in natural row order (coalesced).  A second, tiny kernel adds the
+    // S partials of every row in slice order -- the "explicit global reduction" of Sec. VI-A.  It is a
+    // kernel of its own because device-wide synchronisation inside one kernel costs more here: an
+    // agent-scope fence writes back and invalidates a whole L2 per wavefront, and tickets taken with
+    // atomics on one address serialise at about 6 ns each across the eight compute dies.
+    for (uint32_t c = wave; c < n_groups; c += nwaves) {
+        const int r = (int)c * 64 + lane;
+        const int n = rb * a.rows_per_block + r;
+        if (r < a.rows_per_block && n < a.N) a.partial[(size_t)s * a.N + n] = accbuf[r];
+    }
+}
+
+// y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.
+__global__ __launch_bounds__(256) void gemv_packed_finalize_kernel(const float *__restrict__ partial,
+                                                                  const half_t *__restrict__ scale,
+                                                                  half_t *__restrict__ y, int N, int S) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    float v[kPackMaxSlices];
+#pragma unroll
+    for (int k = 0; k < kPackMaxSlices; ++k) v[k] = partial[(size_t)(k < S ? k : S - 1) * N + n];
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPackMaxSlices; ++k) sum += k < S ? v[k] : 0.f;
+    y[n] = (half_t)(sum * (scale ? (float)scale[n] : 1.f));
+}
+
+bool gemv_uses_pack(const vq_weight_t *w, int bs) {
+    return w->gemv_pack != nullptr && bs == 1 && pack_supported(w);
+}
+
+size_t gemv_packed_workspace(const vq_weight_t *w) {
+    return (size_t)w->gemv_pack->S * w->N * sizeof(float);
+}
+
+int check_pack(const vq_weight_t *w) {
+    const vq_gemv_pack_t *p = w->gemv_pack;
+    if (!p->data) return VQ_ERR_NULL;
+    if (!aligned16(p->data)) return VQ_ERR_ALIGN;
+    if (!pack_supported(w)) return VQ_ERR_UNSUPPORTED;
+    PackPlan plan = pack_plan(w);
+    if (p->S != plan.S || p->RB != plan.RB || p->rows_per_block != plan.rows_per_block) return VQ_ERR_SHAPE;
+    if (p->S > (uint32_t)kPackMaxSlices) return VQ_ERR_UNSUPPORTED;
+    if (p->atom_off > p->bytes || p->rowid_off > p->atom_off || p->group_off > p->rowid_off) return VQ_ERR_SHAPE;
+    return VQ_OK;
+}
+
+int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, hipStream_t s) {
+    const vq_gemv_pack_t *p = w->gemv_pack;
+    PackPlan plan = pack_plan(w);
+    PackedArgs a;
+    a.data = (const unsigned char *)p->data;
+    a.cb = (const half_t *)w->codebooks;
+    a.scale = (const half_t *)w->scale;
+    a.x = (const half_t *)x;
+    a.y = (half_t *)y;
+    a.partial = (float *)ws;
+    a.N = w->N;
+    a.J = w->K / 8;
+    a.S = (int)p->S;
+    a.RB = (int)p->RB;
+    a.rows_per_block = (int)p->rows_per_block;
+    a.slice_entries = (int)plan.slice_entries;
+    a.wg_off = p->wg_off;
+    a.group_off = p->group_off;
+    a.rowid_off = p->rowid_off;
+    a.atom_off = p->atom_off;
+    int groups_per_wg = (int)((p->rows_per_block + 63) / 64);
+    size_t lds = (size_t)plan.slice_entries * 16 + (size_t)a.J * 16 + (size_t)groups_per_wg * 64 * sizeof(float);
+    int waves = groups_per_wg < 16 ? groups_per_wg : 16;
+    if (waves < 8) waves = 8;   // at least 512 threads, so that slice and x are staged with every load in flight
+    static size_t attr_lds = 0;
+    if (lds > 64 * 1024 && lds > attr_lds) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_packed_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_lds = lds;
+    }
+    gemv_packed_kernel<<<(int)(p->S * p->RB), waves * 64, lds, s>>>(a);
+    gemv_packed_finalize_kernel<<<(a.N + 255) / 256, 256, 0, s>>>(a.partial, a.scale, a.y, a.N, a.S);
+    return launch_status();
+}
+
+}  // namespace vq
+
+using namespace vq;
+
+extern "C" {
+
+size_t vq_gemv_prepack_bytes(const vq_weight_t *w) {
+    if (!w || !w->codes || !pack_supported(w)) return 0;
+    return (size_t)pack_build(w, nullptr, nullptr);
+}
+
+int vq_gemv_prepack(const vq_weight_t *w, void *out_host, size_t out_bytes, vq_gemv_pack_t *pack) {
+    if (!w || !w->codes || !out_host || !pack) return VQ_ERR_NULL;
+    if (w->v != 8 && w->v != 4) return VQ_ERR_UNSUPPORTED;
+    if (!pack_supported(w)) return VQ_ERR_UNSUPPORTED;
+    if (!aligned16(out_host)) return VQ_ERR_ALIGN;
+    uint64_t need = pack_build(w, nullptr, nullptr);
+    if (out_bytes < need) return VQ_ERR_WORKSPACE;
+    pack_build(w, (unsigned char *)out_host, pack);
+    return VQ_OK;
+}
+
+}  // extern "C"

@@ -65,7 +65,11 @@ __device__ __forceinline__ float wave_max(float x) {
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Host-side validation shared by the entry points (no HIP calls).
-int check_weight(const vq_weight_t *w);
+int check_weight(const vq_weight_t *w, bool need_codes);
+int check_pack(const vq_weight_t *w);
+bool gemv_uses_pack(const vq_weight_t *w, int bs);
+size_t gemv_packed_workspace(const vq_weight_t *w);
+int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, hipStream_t s);
 int check_kv(const vq_kv_t *kv);
 
 // Kernel launchers (defined next to their kernels).
@@ -73,6 +77,7 @@ int launch_dequant(const vq_weight_t *w, void *W, int out_fp32, hipStream_t s);
 int launch_kv_dequant(const vq_kv_t *kv, int which, void *out, hipStream_t s);
 int launch_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *ws, hipStream_t s);
 size_t gemv_workspace(const vq_weight_t *w, int bs);
+int launch_gemv_rows(const vq_weight_t *w, const void *x, int bs, void *y, hipStream_t s);
 int launch_gemv_generic(const vq_weight_t *w, const void *x, int bs, void *y, hipStream_t s);
 int launch_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *ws, hipStream_t s);
 size_t gemm_workspace(const vq_weight_t *w, int M);

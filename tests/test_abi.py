@@ -40,7 +40,8 @@ def test_status_strings():
 
 
 def weight(**kw):
-    d = dict(N=64, K=64, v=8, code_bits=8, n_codebooks=1, n_entries=256, codes=P, codebooks=P, scale=None)
+    d = dict(N=64, K=64, v=8, code_bits=8, n_codebooks=1, n_entries=256, codes=P, codebooks=P, scale=None,
+             gemv_pack=None)
     d.update(kw)
     return vq_weight_t(**d)
 
@@ -132,6 +133,40 @@ def test_attention_argument_validation():
     assert lib.vq_attn_decode(ctypes.byref(big), P, 0.1, P, None, 0, None) == VQ_ERR_WORKSPACE
     assert lib.vq_attn_decode(ctypes.byref(big), P, 0.1, P, P, need - 1, None) == VQ_ERR_WORKSPACE
     assert lib.vq_attn_decode(ctypes.byref(kvdesc(B=0)), P, 0.1, P, None, 0, None) == 0
+
+
+def test_packed_gemv_validation():
+    import numpy as np
+    from paper_2503_02236_amd import workloads as wl
+    from paper_2503_02236_amd.binding import vq_gemv_pack_t
+    lib = vq.lib()
+    w = wl.make_weight(128, 512, 8, 16, 1, 65536, 0.02, seed=9)
+    buf, pack = vq.vq_gemv_prepack(w)
+    d = weight(N=128, K=512, code_bits=16, n_entries=65536, codes=None)
+    assert gemv(d) == VQ_ERR_NULL                                  # neither codes nor a pack
+    pack.data = P                                                  # pretend it was uploaded
+    d.gemv_pack = ctypes.pointer(pack)
+    need = lib.vq_gemv_workspace(ctypes.byref(d), 1)
+    assert need == pack.S * 128 * 4
+    assert gemv(d) == VQ_ERR_WORKSPACE
+    assert gemv(d, ws=P, ws_bytes=need - 1) == VQ_ERR_WORKSPACE
+    assert gemv(d, bs=2) == VQ_ERR_NULL                            # bs > 1 needs the canonical codes
+    other = weight(N=256, K=512, code_bits=16, n_entries=65536, codes=None)
+    other.gemv_pack = ctypes.pointer(pack)
+    assert gemv(other, ws=P, ws_bytes=1 << 30) == VQ_ERR_SHAPE     # pack built for another shape
+    pack.data = P + 4
+    assert gemv(d, ws=P, ws_bytes=need) == VQ_ERR_ALIGN
+    # the packer itself
+    out = np.empty(buf.size + 16, dtype=np.uint8)
+    hd = vq_weight_t(128, 512, 8, 16, 1, 65536, w.codes.ctypes.data, None, None, None)
+    pk = vq_gemv_pack_t()
+    assert lib.vq_gemv_prepack(ctypes.byref(hd), None, buf.size, ctypes.byref(pk)) == VQ_ERR_NULL
+    aligned = out.ctypes.data + (-out.ctypes.data) % 16
+    assert lib.vq_gemv_prepack(ctypes.byref(hd), aligned, buf.size - 1, ctypes.byref(pk)) == VQ_ERR_WORKSPACE
+    assert lib.vq_gemv_prepack(ctypes.byref(hd), aligned + 1, buf.size, ctypes.byref(pk)) == VQ_ERR_ALIGN
+    hd.v = 4
+    assert lib.vq_gemv_prepack(ctypes.byref(hd), aligned, buf.size, ctypes.byref(pk)) == VQ_ERR_UNSUPPORTED
+    assert lib.vq_gemv_prepack_bytes(ctypes.byref(hd)) == 0
 
 
 def test_probe_argument_validation():

@@ -135,6 +135,64 @@ def test_gemv_is_deterministic_and_leaves_neighbours_alone(gpu_device):
     assert (buf[:32] == 7).all() and (buf[32 + w.N:] == 7).all()
 
 
+# ---------------------------------------------------------------- VQ-gemv from re-tiled codes
+
+def run_gemv_packed(w, x, device, ws=None):
+    wd = vq.weight_to_device(w, device, prepack=True, keep_codes=False)
+    assert wd.codes is None                       # the packed path needs no canonical codes
+    y = vq.vq_gemv(wd, dev_x(x, device), ws=ws)
+    torch.cuda.synchronize()
+    return y
+
+
+@pytest.mark.parametrize("shape_idx", [0, 1, 2])
+def test_gemv_packed_config2_full_size(gpu_device, shape_idx):
+    w = wl.config2_layer(shape_idx)
+    x = wl.make_activations(1, w.K, wl.seed_for(2, shape_idx))
+    assert_close(run_gemv_packed(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x),
+                 f"C2 packed[{shape_idx}]")
+
+
+@pytest.mark.parametrize("N,K,E,scale,zipf", [
+    (1, 64, 65536, True, None),         # one row, one sub-vector block
+    (63, 1024, 65536, True, None),      # less than one 64-row group
+    (1000, 4096, 65536, False, None),   # ragged row blocks, no scale
+    (300, 2048, 4096, True, None),      # two slices only
+    (257, 16368, 8192, True, None),     # longest supported rows
+    (2048, 4096, 65536, True, 1.0),     # skewed codes: empty (row, slice) cells, uneven lengths
+])
+def test_gemv_packed_shapes_and_edges(gpu_device, N, K, E, scale, zipf):
+    w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=3000 + N + K, with_scale=scale, zipf_s=zipf)
+    x = wl.make_activations(1, K, seed=3100 + N)
+    assert_close(run_gemv_packed(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x),
+                 f"packed {N}x{K} E{E}")
+
+
+def test_gemv_packed_shared_workspace_determinism_and_canonical_agreement(gpu_device):
+    # three layers of different shapes share one workspace, called back to back, twice
+    ws_bytes, layers = 0, []
+    for si in (0, 1, 2):
+        w = wl.config2_layer(si, layer=5)
+        wd = vq.weight_to_device(w, gpu_device, prepack=True)
+        x = dev_x(wl.make_activations(1, w.K, 40 + si), gpu_device)
+        layers.append((w, wd, x))
+        ws_bytes = max(ws_bytes, vq.vq_gemv_workspace(wd, 1))
+    assert ws_bytes == max(32 * 4096 * 4, 16 * 11008 * 4)   # S x N fp32 partial sums
+    ws = vq.new_workspace(ws_bytes, gpu_device)
+    outs = [[vq.vq_gemv(wd, x, ws=ws).clone() for (_, wd, x) in layers] for _ in range(3)]
+    torch.cuda.synchronize()
+    for rep in outs[1:]:
+        for a, b in zip(outs[0], rep):
+            assert torch.equal(a, b)
+    for (w, wd, x), y in zip(layers, outs[0]):
+        assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x.cpu().numpy()), "packed shared ws")
+        # bs > 1 on the same descriptor takes the canonical-layout path and agrees
+        x2 = torch.cat([x, x], dim=0).contiguous()
+        y2 = vq.vq_gemv(wd, x2, ws=ws)
+        assert (y2[0].float() - y[0].float()).abs().max() <= 2e-2 * y.float().abs().max()
+        assert torch.equal(y2[0], y2[1])
+
+
 # ---------------------------------------------------------------- VQ-gemm
 
 @pytest.mark.parametrize("M,N,K,v,scale", [

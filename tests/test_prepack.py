@@ -1,0 +1,91 @@
+"""Host-side checks of vq_gemv_prepack (no GPU): the re-tiled buffer is decoded here, by a decoder
+written from the format description alone, and must reproduce the canonical codes exactly."""
+import time
+
+import numpy as np
+import pytest
+
+import paper_2503_02236_amd as vq
+from paper_2503_02236_amd import workloads as wl
+
+
+
+def decode(buf, pack, N, J, SLICE):
+    """Packed buffer -> codes[N][J] plus per-position hit counts, following the documented layout."""
+    S, RB, RPB = pack.S, pack.RB, pack.rows_per_block
+    wg = np.frombuffer(buf, dtype=np.uint32, count=2 * S * RB, offset=pack.wg_off).reshape(S * RB, 2)
+    groups = np.frombuffer(buf, dtype=np.uint32, count=2 * pack.n_groups, offset=pack.group_off).reshape(-1, 2)
+    rowids = np.frombuffer(buf, dtype=np.uint16, count=64 * pack.n_groups, offset=pack.rowid_off).reshape(-1, 64)
+    atoms = np.frombuffer(buf, dtype=np.uint8, offset=pack.atom_off)
+    codes = np.zeros((N, J), dtype=np.int64)
+    hits = np.zeros((N, J), dtype=np.int32)
+    for w in range(S * RB):
+        s, rb = divmod(w, RB)
+        first, ng = int(wg[w, 0]), int(wg[w, 1])
+        prev_len = None
+        for g in range(first, first + ng):
+            blk, steps = int(groups[g, 0]), int(groups[g, 1])
+            a = atoms[blk * 768:(blk + steps) * 768].reshape(steps, 64, 4, 3).astype(np.uint32)
+            val = a[..., 0] | (a[..., 1] << 8) | (a[..., 2] << 16)          # [steps][lane][4]
+            val = val.transpose(1, 0, 2).reshape(64, steps * 4)             # lane-major atom lists
+            for lane in range(64):
+                ri = int(rowids[g, lane])
+                lst = val[lane]
+                valid = (lst >> 23) & 1
+                n_valid = int(valid.sum())
+                assert (valid[:n_valid] == 1).all() and (lst[n_valid:] == 0).all()   # valid atoms first, padding is zero
+                if ri == 0xFFFF:
+                    assert n_valid == 0
+                    continue
+                if prev_len is not None:
+                    assert n_valid <= prev_len                               # rows sorted by length inside a workgroup
+                prev_len = n_valid
+                n = rb * RPB + ri
+                assert ri < RPB and n < N
+                js = (lst[:n_valid] >> 12) & 0x7FF
+                assert (np.diff(js.astype(np.int64)) > 0).all()                # ascending positions: fixed summation order
+                codes[n, js] = s * SLICE + (lst[:n_valid] & 0xFFF)
+                hits[n, js] += 1
+    return codes, hits
+
+
+@pytest.mark.parametrize("N,K,E,zipf", [
+    (200, 1024, 65536, None),
+    (64, 512, 4096, None),
+    (513, 2048, 65536, 1.0),       # skewed codes: some (row, slice) cells are empty, lengths vary a lot
+    (1, 64, 65536, None),
+    (70, 16368, 8192, None),       # longest supported rows (K/8 = 2046)
+    (9000, 64, 65536, None),       # many rows: 4096-entry slices, 16 x 16 workgroups
+])
+def test_prepack_round_trip(N, K, E, zipf):
+    w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=77 + N, zipf_s=zipf)
+    buf, pack = vq.vq_gemv_prepack(w)
+    assert buf is not None and pack.bytes == buf.size
+    assert pack.S in (E // 2048, E // 4096) and pack.S * pack.RB <= 256
+    codes, hits = decode(buf, pack, N, K // 8, E // pack.S)
+    assert (hits == 1).all()                       # every code appears exactly once
+    assert np.array_equal(codes, w.codes[:, :, 0].astype(np.int64))
+
+
+def test_prepack_is_deterministic_and_rejects_other_formats():
+    w = wl.make_weight(128, 512, 8, 16, 1, 65536, 0.02, seed=5)
+    b1, _ = vq.vq_gemv_prepack(w)
+    b2, _ = vq.vq_gemv_prepack(w)
+    assert np.array_equal(b1, b2)
+    for bad in (wl.make_weight(64, 512, 8, 8, 1, 256, 0.02, seed=6),       # uint8 codes
+                wl.make_weight(64, 512, 4, 16, 1, 65536, 0.02, seed=6),    # v = 4
+                wl.make_weight(64, 512, 8, 16, 2, 4096, 0.02, seed=6),     # two codebooks
+                wl.make_weight(64, 512, 8, 16, 1, 1000, 0.02, seed=6),     # E not a power of two
+                wl.make_weight(8, 16384, 8, 16, 1, 65536, 0.02, seed=6)):  # rows too long for the position field
+        assert vq.vq_gemv_prepack(bad) == (None, None)
+
+
+def test_prepack_llama_shape_size_and_speed():
+    w = wl.config2_layer(1)                        # (11008, 4096)
+    t0 = time.time()
+    buf, pack = vq.vq_gemv_prepack(w)
+    dt = time.time() - t0
+    ratio = buf.size / w.codes.nbytes
+    print(f"prepack 11008x4096: {dt:.2f} s, {buf.size / 2**20:.1f} MiB = {ratio:.3f} x canonical codes")
+    assert (pack.S, pack.RB) == (16, 16)               # 11008 rows: 4096-entry slices
+    assert 1.5 <= ratio < 1.85                     # 3 bytes per code plus padding to whole 4-atom steps
