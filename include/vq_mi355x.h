@@ -118,6 +118,9 @@ int vq_gemv_prepack(const vq_weight_t *w_host, void *out_host, size_t out_bytes,
  * dequantized tile fed to the fp16 matrix cores, fp32 accumulation.
  *   Y[m][n] = scale[n] * sum_k W[n][k] * X[m][k],   m < M
  * X: device fp16 [M][K]; Y: device fp16 [M][N]; M >= 1.
+ * ws: vq_gemm_workspace(w, M) bytes.  For M > 256 that is N*K*2: the weight is dequantized once per
+ * call into ws (fp16, the same bits vq_dequant returns) and multiplied by a dense matrix-core kernel;
+ * for smaller M the dequantization is fused into the matrix-core loop and no workspace is needed.
  */
 int vq_gemm(const vq_weight_t *w, const void *X, int M, void *Y,
             void *ws, size_t ws_bytes, void *stream);

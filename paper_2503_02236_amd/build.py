@@ -15,7 +15,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvqmi.so")
-SOURCES = ["api.hip", "dequant.hip", "gemv.hip", "gemv_packed.hip", "gemm.hip", "attn.hip"]
+SOURCES = ["api.hip", "dequant.hip", "gemv.hip", "gemv_packed.hip", "gemm.hip", "gemm_dense.hip", "attn.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are disabled for every kernel of this library
@@ -35,7 +35,7 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build(extra_flags=(), jobs: int = 6) -> str:
+def build(extra_flags=(), jobs: int = 7) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))

@@ -161,7 +161,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     }
 }
 
-size_t gemm_workspace(const vq_weight_t *, int) { return 0; }
+// Large M: dequantize once into the workspace (fp16 [N][K]) and run the dense matrix-core kernel.
+// Small M: one M tile would not reuse the dequantized weights, so the fused kernel gathers them directly.
+static bool gemm_two_stage(const vq_weight_t *w, int M) { return M > 256 && w->K > 0 && w->K % 64 == 0; }
+
+size_t gemm_workspace(const vq_weight_t *w, int M) {
+    return gemm_two_stage(w, M) ? (size_t)w->N * w->K * sizeof(half_t) : 0;
+}
 
 namespace {
 
@@ -193,9 +199,14 @@ int run_mfma(const vq_weight_t *w, const half_t *X, int M, half_t *Y, hipStream_
 
 }  // namespace
 
-int launch_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *, hipStream_t s) {
+int launch_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *ws, hipStream_t s) {
     const half_t *Xp = (const half_t *)X;
     half_t *Yp = (half_t *)Y;
+    if (gemm_two_stage(w, M)) {
+        int st = launch_dequant(w, ws, /*out_fp32=*/0, s);
+        if (st != VQ_OK) return st;
+        return launch_gemm_dense(Xp, (const half_t *)ws, (const half_t *)w->scale, Yp, M, w->N, w->K, s);
+    }
     // matrix-core path: uint16 codes, one codebook, K a multiple of the 64-wide block
     bool fast = w->code_bits == 16 && w->n_codebooks == 1 && w->K % kGemmBK == 0 && w->K > 0 && M >= 32 &&
                 ((size_t)w->K / w->v * 2) % 16 == 0;

@@ -81,6 +81,8 @@ int launch_gemv_rows(const vq_weight_t *w, const void *x, int bs, void *y, hipSt
 int launch_gemv_generic(const vq_weight_t *w, const void *x, int bs, void *y, hipStream_t s);
 int launch_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *ws, hipStream_t s);
 size_t gemm_workspace(const vq_weight_t *w, int M);
+int launch_gemm_dense(const half_t *A, const half_t *B, const half_t *scale, half_t *C, int M, int N, int K,
+                      hipStream_t s);
 int launch_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, hipStream_t s);
 size_t attn_decode_workspace(const vq_kv_t *kv);
 int launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s);

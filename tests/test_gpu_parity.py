@@ -217,6 +217,21 @@ def test_gemm_other_formats_use_row_path(gpu_device):
     assert_close(Y, oracle.gemm(w.codes, w.codebooks, w.scale, X), "gemm uint8 R=2")
 
 
+@pytest.mark.parametrize("M,N,K,v,bits,R,E", [
+    (300, 130, 256, 8, 8, 2, 256),      # additive uint8 pairs, ragged tiles
+    (513, 257, 192, 4, 16, 3, 500),     # three residual codebooks, v = 4
+    (1025, 64, 64, 8, 8, 1, 256),       # one K block, five M tiles
+])
+def test_gemm_large_m_any_format_two_stage(gpu_device, M, N, K, v, bits, R, E):
+    w = wl.make_weight(N, K, v, bits, R, E, 0.02 / R, seed=4700 + M)
+    X = wl.make_activations(M, K, seed=4701 + M)
+    wd = vq.weight_to_device(w, gpu_device)
+    assert vq.vq_gemm_workspace(wd, M) == N * K * 2
+    Y = vq.vq_gemm(wd, dev_x(X, gpu_device))
+    torch.cuda.synchronize()
+    assert_close(Y, oracle.gemm(w.codes, w.codebooks, w.scale, X), f"gemm two-stage {M}x{N}x{K} R{R}")
+
+
 @pytest.mark.parametrize("N,v", [(4096, 8), (11008, 8), (4096, 4), (11008, 4)])
 def test_gemm_config4_full_size_sampled_columns(gpu_device, N, v):
     w = wl.config4_layer(N, v)
