@@ -45,17 +45,30 @@ struct AttnArgs {
 };
 
 // Butterfly sum of acc[0..N) over the 64 lanes; afterwards lane l holds the totals of
-// elements 2l and 2l+1 in acc[0], acc[1].
+// elements 2l and 2l+1 in acc[0], acc[1].  In every step a lane keeps one half of its values and
+// adds the partner lane's copy of that half.  The two big steps (partner 32 and 16 lanes away)
+// use the gfx950 lane-swap instructions: one swap puts "mine" and "the partner's" of the kept
+// half side by side; the small steps go through ds_bpermute.
 template <int N>
 __device__ __forceinline__ void lanes_reduce_scatter(float (&acc)[N], int lane) {
     static_assert(N == 128, "written for 128 accumulators");
 #pragma unroll
-    for (int step = 0; step < 6; ++step) {
+    for (int i = 0; i < 64; ++i) {  // upper 32 lanes of lo <-> lower 32 lanes of hi
+        auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i]), __float_as_uint(acc[i + 64]), false, false);
+        acc[i] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {  // odd rows of 16 of lo <-> even rows of hi
+        auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(acc[i]), __float_as_uint(acc[i + 32]), false, false);
+        acc[i] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+#pragma unroll
+    for (int step = 2; step < 6; ++step) {
         const int m = 32 >> step;       // lane mask
         const int half = 64 >> step;    // elements kept
         const bool upper = (lane & m) != 0;
 #pragma unroll
-        for (int i = 0; i < 64; ++i) {
+        for (int i = 0; i < 16; ++i) {
             if (i < half) {
                 float lo = acc[i], hi = acc[i + half];
                 float send = upper ? lo : hi;
@@ -257,18 +270,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     float lsum = 0.f;          // per lane
     float m_run = -INFINITY;   // wave-uniform running maximum of the scores (log2 domain)
 
-    auto tile_step = [&](int it, V16 (&kc)[NC], V16 (&vc)[NC]) {
-        // ---- scores of the lane's NI tokens (two partial sums each to shorten the dependent chain)
+    // Gathered entries of the group being used and of the one in flight.  The lookups of a tile form
+    // one sequence of 2 NG groups (K side, then V side) that continues into the next tile, so the LDS
+    // queue never drains at the boundaries between the two sides or between tiles.
+    static_assert(NG % 2 == 0, "the double buffer must be back at slot 0 after each side");
+    entry_t e[2][GS];
+    gather(kA, 0, 0, e[0]);
+
+    // kn: K codes of the following tile (the other register buffer)
+    auto tile_step = [&](int it, V16 (&kc)[NC], V16 (&vc)[NC], const V16 (&kn)[NC]) {
+        // ---- scores of the lane's NI tokens (two partial sums each to shorten the dependent chain).
+        // Masked tokens get -inf through an additive bias: a select on the finished score would make
+        // the compiler branch around the arithmetic and pull every gather of the tile in front of it.
         float sc[NI], bias[NI];
 #pragma unroll
         for (int i = 0; i < NI; ++i) bias[i] = (t_lane + it * TILE + i * 256 < end) ? 0.f : -INFINITY;
         {
-            entry_t e[2][GS];
-            gather(kc, 0, 0, e[0]);
             float d0 = 0.f, d1 = 0.f;
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
-                if (g + 1 < NG) gather(kc, g + 1, 0, e[(g + 1) & 1]);
+                if (g + 1 < NG)
+                    gather(kc, g + 1, 0, e[(g + 1) & 1]);
+                else
+                    gather(vc, 0, v_off, e[0]);
                 __builtin_amdgcn_sched_barrier(0);  // keep the gathers of g+1 ahead of the arithmetic of g
 #pragma unroll
                 for (int j = 0; j < GS; ++j) {
@@ -292,8 +316,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
                 __builtin_amdgcn_sched_barrier(0);
                 if ((g + 1) * GS % P == 0) {  // last group of a sub-token
                     const int i = (g * GS) / P;
-                    // masked tokens get -inf through an additive bias: a select here would make the
-                    // compiler branch around the arithmetic and pull every gather of the tile in front
                     sc[i] = __builtin_fmaf(d0 + d1, a.scale2, bias[i]);
                     d0 = d1 = 0.f;
                 }
@@ -316,12 +338,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 
         // ---- acc += p_t * V[t]
         {
-            entry_t e[2][GS];
-            gather(vc, 0, v_off, e[0]);
             float p_t = 0.f;
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
-                if (g + 1 < NG) gather(vc, g + 1, v_off, e[(g + 1) & 1]);
+                if (g + 1 < NG)
+                    gather(vc, g + 1, v_off, e[(g + 1) & 1]);
+                else
+                    gather(kn, 0, 0, e[0]);  // first K group of the next tile
                 __builtin_amdgcn_sched_barrier(0);
                 if ((g * GS) % P == 0) {  // first group of a sub-token
                     const float s = sc[(g * GS) / P];
@@ -350,8 +373,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     };
 
     for (int it = 0; it < ntiles; it += 2) {
-        tile_step(it, kA, vA);
-        if (it + 1 < ntiles) tile_step(it + 1, kB, vB);
+        tile_step(it, kA, vA, kB);
+        if (it + 1 < ntiles) tile_step(it + 1, kB, vB, kA);
     }
 
     // ---- reduce over lanes, then over the four wavefronts (fixed order) ---------------------
