@@ -40,6 +40,12 @@ def parse():
     ap.add_argument("--canonical", action="store_true",
                     help="headline gemv from the canonical code layout (L2 gathers) instead of the re-tiled codes")
     ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="counter run (wrap in rocprofv3 --pmc FETCH_SIZE or WRITE_SIZE): three plain copies of "
+                         "known size as calibration, then one eager pass over the headline gemv stack; no timing")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "gemv_packed_c2_hbm_traffic.md"),
+                    help="summary written by paper_2503_02236_amd.profile_summary traffic; its "
+                         "'traffic_bytes_per_launch:' line fills roofline.traffic")
     return ap.parse_args()
 
 
@@ -95,8 +101,29 @@ def main():
             if st != 0:
                 raise vq.VQError(st, "vq_gemv")
 
+    def read_traffic(path):
+        """HBM bytes per vq_gemv launch from the committed counter summary (None if there is none)."""
+        try:
+            for line in open(path):
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+        except OSError:
+            pass
+        return None
+
     result = {}
     t_setup = time.time()
+
+    if args.pmc_probe:
+        nbytes = 256 << 20
+        src = torch.full((nbytes,), 3, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            vq.vq_probe_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+        only = {"gemv"}
 
     # ------------------------------------------------------------------ headline: C2 gemv stack
     if want("gemv"):
@@ -123,6 +150,13 @@ def main():
         def step():
             for c in calls:
                 c()
+
+        if args.pmc_probe:
+            step()
+            torch.cuda.synchronize()
+            print(json.dumps({"pmc_probe": True, "probe_copy_bytes": 256 << 20, "probe_copies": 3,
+                              "gemv_launches": len(calls), "effective_bytes": eff_bytes}), flush=True)
+            return
 
         graph = None
         if not args.no_graph:
@@ -182,7 +216,8 @@ def main():
             "gemv_per_shape_cold": shape_us,
             "roofline": {"bound": "hbm", "kernel": "gemv_packed_kernel" if packed else "gemv_rows_kernel<uint16,8,1>",
                          "achieved": round(gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                         "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                         "frac": round(gbps / HBM_PEAK_GBPS, 4),
+                         "traffic": read_traffic(args.traffic_file) if packed else None,
                          "bytes_per_launch": eff_bytes // n_launch,
                          "avg_launch_us": round(ms_step * 1e3 / n_launch, 3)},
         })

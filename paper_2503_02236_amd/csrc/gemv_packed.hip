@@ -206,25 +206,38 @@ __global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) {
     unsigned char *xl = smem + (size_t)a.slice_entries * 16;        // J * 16 bytes
     float *accbuf = reinterpret_cast<float *>(xl + (size_t)a.J * 16);  // one float per row of the block
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nthreads = blockDim.x, nwaves = nthreads >> 6;
-    const int wg = blockIdx.x, s = wg / a.RB, rb = wg % a.RB;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nwaves = blockDim.x >> 6;
+    // Workgroups are dealt round-robin to the 8 compute dies, each with its own L2.  All row blocks of
+    // one codebook slice run on the same die, so a slice is fetched from memory by one L2 only
+    // (otherwise every die pulls the whole 1 MiB codebook: 8 MiB per launch).
+    int s, rb;
+    if (a.S % 8 == 0) {
+        const int die = blockIdx.x & 7, local = blockIdx.x >> 3, per_die = a.S >> 3;
+        s = die * per_die + local % per_die;
+        rb = local / per_die;
+    } else {
+        s = blockIdx.x / a.RB;
+        rb = blockIdx.x % a.RB;
+    }
+    const int wg = s * a.RB + rb;  // index into the packed tables
     const uint2 *gtab = reinterpret_cast<const uint2 *>(a.data + a.group_off);
     const uint16_t *rowids = reinterpret_cast<const uint16_t *>(a.data + a.rowid_off);
     const unsigned char *atoms = a.data + a.atom_off + lane * 12;
 
-    // (1) codebook slice and x: issue every load first (up to 4 + 2 per thread in flight)
-    const uint4 *src = reinterpret_cast<const uint4 *>(a.cb) + (size_t)s * a.slice_entries;
-    const uint4 *xs = reinterpret_cast<const uint4 *>(a.x);
-    uint4 sv[4], xv[3];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int idx = tid + i * nthreads;
-        sv[i] = idx < a.slice_entries ? src[idx] : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        int idx = tid + i * nthreads;
-        xv[i] = idx < a.J ? xs[idx] : make_uint4(0, 0, 0, 0);
+    // (1) codebook slice and x go straight from global memory into LDS (no registers): one
+    //     wave-wide 1 KiB transfer per 64 entries, lane l's 16 bytes land at base + 16 l
+    {
+        typedef __attribute__((address_space(3))) void lds_void_t;
+        typedef const __attribute__((address_space(1))) void global_void_t;
+        const uint4 *src = reinterpret_cast<const uint4 *>(a.cb) + (size_t)s * a.slice_entries;
+        const uint4 *xs = reinterpret_cast<const uint4 *>(a.x);
+        for (int c = wave; c * 64 < a.slice_entries; c += nwaves)  // slices are multiples of 64 entries
+            __builtin_amdgcn_global_load_lds((global_void_t *)(src + c * 64 + lane), (lds_void_t *)(slice + c * 1024),
+                                             16, 0, 0);
+        for (int c = wave; c * 64 < a.J; c += nwaves)
+            if (c * 64 + lane < a.J)
+                __builtin_amdgcn_global_load_lds((global_void_t *)(xs + c * 64 + lane), (lds_void_t *)(xl + c * 1024),
+                                                 16, 0, 0);
     }
     // (2) this wavefront's first group: table entry, row ids, then its atoms
     const uint32_t n_groups = (uint32_t)(a.rows_per_block + 63) / 64, first_group = (uint32_t)wg * n_groups;
@@ -244,19 +257,9 @@ __global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) {
             q[st][0] = q[st][1] = q[st][2] = 0;
         }
     }
-    // (3) LDS writes of the staged data (slices larger than 4 * nthreads entries take the slow loop)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int idx = tid + i * nthreads;
-        if (idx < a.slice_entries) reinterpret_cast<uint4 *>(slice)[idx] = sv[i];
-    }
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        int idx = tid + i * nthreads;
-        if (idx < a.J) reinterpret_cast<uint4 *>(xl)[idx] = xv[i];
-    }
-    for (int idx = tid + 4 * nthreads; idx < a.slice_entries; idx += nthreads) reinterpret_cast<uint4 *>(slice)[idx] = src[idx];
-    for (int idx = tid + 3 * nthreads; idx < a.J; idx += nthreads) reinterpret_cast<uint4 *>(xl)[idx] = xs[idx];
+    // (3) everything this wavefront asked for has landed (the direct-to-LDS transfers count as vector
+    //     memory loads); after the barrier the slice and x of all wavefronts are visible
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     // (4) gathers and dot products: lane = row; results go to LDS in natural row order

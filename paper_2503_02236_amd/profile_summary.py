@@ -1,0 +1,96 @@
+"""Turn rocprofv3 CSV output into the short text summaries kept under profiles/.
+
+  python -m paper_2503_02236_amd.profile_summary stats <kernel_stats.csv> <out.md> --cmd "<command>" [--note "..."]
+  python -m paper_2503_02236_amd.profile_summary traffic <fetch_counter_collection.csv> <write_counter_collection.csv>
+         <out.md> --cmd "<command>" [--copy-bytes N]
+
+`traffic` expects two counter runs of `bench.py --pmc-probe` (one with FETCH_SIZE, one with
+WRITE_SIZE; both counters are in KiB per dispatch).  The probe run starts with plain copies of
+a known size; the ratio counter / known bytes of those copies is the calibration factor every
+other reading is divided by.  The vq_gemv figure is the sum over the kernels of one call
+(main kernel + finalize), averaged over all calls of the pass.
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import subprocess
+
+
+def _short(name: str) -> str:
+    try:
+        name = subprocess.run(["c++filt", name], capture_output=True, text=True).stdout.strip() or name
+    except OSError:
+        pass
+    return name.split("(")[0][-90:]
+
+
+def stats(args):
+    rows = list(csv.DictReader(open(args.src)))
+    with open(args.out, "w") as f:
+        f.write("# rocprofv3 kernel-trace summary\n\ncommand: `%s`\n\n%s\n\n" % (args.cmd, args.note))
+        f.write("| kernel | calls | avg us | min us | max us | total ms | % |\n|---|---|---|---|---|---|---|\n")
+        for r in rows:
+            if float(r["Percentage"]) < 0.05:
+                continue
+            f.write("| %s | %s | %.2f | %.2f | %.2f | %.3f | %.2f |\n" % (
+                _short(r["Name"]), r["Calls"], float(r["AverageNs"]) / 1e3, float(r["MinNs"]) / 1e3,
+                float(r["MaxNs"]) / 1e3, float(r["TotalDurationNs"]) / 1e6, float(r["Percentage"])))
+
+
+def _per_kernel(path, counter):
+    agg = collections.defaultdict(list)
+    for r in csv.DictReader(open(path)):
+        if r["Counter_Name"] == counter:
+            agg[_short(r["Kernel_Name"])].append(float(r["Counter_Value"]) * 1024.0)  # KiB -> bytes
+    return agg
+
+
+def traffic(args):
+    fetch = _per_kernel(args.fetch, "FETCH_SIZE")
+    write = _per_kernel(args.write, "WRITE_SIZE")
+    copy_name = next(k for k in fetch if "probe_copy" in k)
+    f_cal = sum(fetch[copy_name]) / len(fetch[copy_name]) / args.copy_bytes
+    w_cal = sum(write[copy_name]) / len(write[copy_name]) / args.copy_bytes
+    main = next(k for k in fetch if "gemv_packed_kernel" in k)
+    fin = next(k for k in fetch if "gemv_packed_finalize" in k)
+    n = len(fetch[main])
+    rd = (sum(fetch[main]) + sum(fetch[fin])) / n / f_cal
+    wr = (sum(write[main]) + sum(write[fin])) / n / w_cal
+    with open(args.out, "w") as f:
+        f.write("# HBM traffic of vq_gemv on the C2 stack (rocprofv3 --pmc)\n\ncommands (one run per counter):\n`%s`\n\n"
+                % args.cmd)
+        f.write("Calibration on vq_probe_copy of %d bytes: FETCH_SIZE reads %.4f x, WRITE_SIZE %.4f x the known size.\n"
+                "Readings below are divided by these factors.\n\n" % (args.copy_bytes, f_cal, w_cal))
+        f.write("| kernel | dispatches | read bytes / dispatch | written bytes / dispatch |\n|---|---|---|---|\n")
+        for k in (main, fin):
+            f.write("| %s | %d | %.0f | %.0f |\n" % (k, len(fetch[k]), sum(fetch[k]) / len(fetch[k]) / f_cal,
+                                                    sum(write[k]) / len(write[k]) / w_cal))
+        f.write("\nper vq_gemv call (both kernels), average over %d calls of the 32-block stack:\n\n" % n)
+        f.write("read_bytes_per_launch: %.0f\nwritten_bytes_per_launch: %.0f\ntraffic_bytes_per_launch: %.0f\n"
+                % (rd, wr, rd + wr))
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="mode", required=True)
+    a = sub.add_parser("stats")
+    a.add_argument("src")
+    a.add_argument("out")
+    a.add_argument("--cmd", required=True)
+    a.add_argument("--note", default="")
+    a.set_defaults(fn=stats)
+    b = sub.add_parser("traffic")
+    b.add_argument("fetch")
+    b.add_argument("write")
+    b.add_argument("out")
+    b.add_argument("--cmd", required=True)
+    b.add_argument("--copy-bytes", type=int, default=256 << 20)
+    b.set_defaults(fn=traffic)
+    args = ap.parse_args()
+    args.fn(args)
+
+
+if __name__ == "__main__":
+    main()
