@@ -1,0 +1,219 @@
+// VQ-gemv for small batches (bs = 1..16) when the codebooks fit LDS, on the matrix cores of gfx950.
+// Operation: VQ-LLM (arXiv 2503.02236) Sec. III-C "VQ-gemv", batch sizes of Sec. VII (1..16);
+// residual codebooks summed as in Sec. II-A.
+//
+// Why matrix cores for a gemv: with a lane-per-code mapping on the vector ALU, every (row, token)
+// pair needs its own reduction over the 64 lanes, so the cost grows with bs (16 wave reductions per
+// row at bs = 16).  v_mfma_f32_16x16x32_f16 does that reduction itself: A = 16 weight rows x 32 k,
+// B = 32 k x 16 tokens, C = 16 x 16 fp32.  A lane's A operand is 8 consecutive k of one row, i.e.
+// exactly one dequantized v = 8 sub-vector (two for v = 4): gathered from the LDS codebook straight
+// into the operand registers (layout fusion, Sec. VI-B: no shuffle, no LDS round trip).  Batches
+// below 16 leave token columns zero; the gathers, not the MFMAs, bound the kernel.
+//
+// Mapping: one workgroup per 16 weight rows (256 workgroups at N = 4096).  Lane (r = lane % 16,
+// g = lane / 16) loads 16 (or 8) bytes of codes of row r: CPL consecutive sub-vector positions.  One
+// "iteration" of a wavefront therefore covers 4 * CPL positions of all 16 rows, with CPL / (8/v)
+// MFMAs; x operands for those positions come straight from global memory (L2-resident).
+// Iterations are dealt round-robin to the wavefronts (K = 4096, uint8 pairs: 16 iterations, one
+// per wavefront at N = 4096); the per-wavefront 16 x 16 partial tiles are added in wavefront order through LDS.
+#include "vq_common.h"
+
+namespace vq {
+
+typedef float float4v_t __attribute__((ext_vector_type(4)));
+
+struct GemvMfmaArgs {
+    const void *codes;
+    const half_t *cb, *scale, *x;
+    half_t *y;
+    int N, K, J, E, bs, nit;
+};
+
+// One code load per lane and iteration: 16 bytes, or 8 for single uint8 codes (16 positions would need
+// 16 x operands in registers).
+template <typename CodeT, int R>
+struct GemvMfmaShape {
+    static constexpr int LB = R * (int)sizeof(CodeT) == 1 ? 8 : 16;
+    static constexpr int CPL = LB / (R * (int)sizeof(CodeT));
+};
+
+template <typename CodeT, int V, int R>
+__global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
+    constexpr int LB = GemvMfmaShape<CodeT, R>::LB;     // bytes of codes per lane and iteration
+    constexpr int CPL = GemvMfmaShape<CodeT, R>::CPL;   // sub-vector positions per code load
+    constexpr int CPO = 8 / V;                          // codes per MFMA operand (8 consecutive k)
+    constexpr int MPI = CPL / CPO;                      // MFMAs per iteration
+    static_assert(CPL * R * sizeof(CodeT) == LB && MPI >= 1, "unsupported code width");
+    extern __shared__ __align__(16) unsigned char smem[];
+    half_t *cbl = reinterpret_cast<half_t *>(smem);                      // [R][E][V]
+    const int cb_bytes = R * a.E * V * 2;
+    float4v_t *red = reinterpret_cast<float4v_t *>(smem + ((cb_bytes + 15) & ~15));  // [waves][64]
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nwaves = blockDim.x >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const int n = min(n0 + r, a.N - 1);  // rows past the end are computed and dropped
+
+    // codes and x of this wavefront's first iteration are requested before the codebook is staged
+    const unsigned char *crow = reinterpret_cast<const unsigned char *>(a.codes) + (size_t)n * a.J * R * sizeof(CodeT);
+    auto load_iter = [&](int it, V16 &cd, half8_t (&xb)[MPI]) {
+        const int jbase = (it * 4 + g) * CPL;  // first position of this lane; J % CPL == 0
+        const bool valid = it < a.nit && jbase < a.J;
+        cd.u = make_uint4(0, 0, 0, 0);
+        if (valid) {
+            if (LB == 16) {
+                cd = ld16(crow + (size_t)jbase * R * sizeof(CodeT));
+            } else {
+                V8 c8 = ld8(crow + (size_t)jbase * R * sizeof(CodeT));
+                cd.w[0] = c8.w[0];
+                cd.w[1] = c8.w[1];
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < MPI; ++m) {
+            V16 xv;
+            xv.u = make_uint4(0, 0, 0, 0);
+            // lanes of a k-group are valid or invalid together, and a zero B operand cancels whatever
+            // A holds, so masking x is enough
+            if (valid && r < a.bs) xv = ld16(a.x + (size_t)r * a.K + (size_t)jbase * V + m * 8);
+            xb[m] = xv.h8;
+        }
+    };
+    V16 cd;
+    half8_t xb[MPI];
+    load_iter(wave, cd, xb);
+
+    for (int i = tid; i < cb_bytes / 16; i += blockDim.x)
+        reinterpret_cast<uint4 *>(cbl)[i] = reinterpret_cast<const uint4 *>(a.cb)[i];
+    __syncthreads();
+
+    float4v_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int it = wave; it < a.nit; it += nwaves) {
+        V16 cd_next;
+        half8_t xb_next[MPI];
+        load_iter(it + nwaves, cd_next, xb_next);
+#pragma unroll
+        for (int m = 0; m < MPI; ++m) {
+            V16 op;
+#pragma unroll
+            for (int h = 0; h < CPO; ++h) {
+                const int c = m * CPO + h;  // code position inside the 16-byte word
+#pragma unroll
+                for (int rr = 0; rr < R; ++rr) {
+                    const unsigned code = sizeof(CodeT) == 1 ? cd.b[c * R + rr] : cd.h[c * R + rr];
+                    const half_t *e = cbl + ((size_t)rr * a.E + code) * V;
+                    if (V == 8) {
+                        V16 ev = ld16(e);
+                        if (rr == 0) {
+                            op = ev;
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) op.h2[q] += ev.h2[q];
+                        }
+                    } else {
+                        V8 ev = ld8(e);
+                        if (rr == 0) {
+                            op.h2[2 * h] = ev.h2[0];
+                            op.h2[2 * h + 1] = ev.h2[1];
+                        } else {
+                            op.h2[2 * h] += ev.h2[0];
+                            op.h2[2 * h + 1] += ev.h2[1];
+                        }
+                    }
+                }
+            }
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(op.h8, xb[m], acc, 0, 0, 0);
+        }
+        cd = cd_next;
+#pragma unroll
+        for (int m = 0; m < MPI; ++m) xb[m] = xb_next[m];
+    }
+
+    // partial tiles -> LDS, summed in wavefront order by the first wavefront.
+    // C layout: lane holds token (lane % 16), rows 4 (lane / 16) + 0..3.
+    red[wave * 64 + lane] = acc;
+    __syncthreads();
+    if (wave == 0) {
+        float4v_t sum = red[lane];
+        for (int w = 1; w < nwaves; ++w) {
+            const float4v_t p = red[w * 64 + lane];
+            sum += p;
+        }
+        if (r < a.bs) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int nn = n0 + 4 * g + i;
+                if (nn < a.N) {
+                    const float sc = a.scale ? (float)a.scale[nn] : 1.f;
+                    a.y[(size_t)r * a.N + nn] = (half_t)(sum[i] * sc);
+                }
+            }
+        }
+    }
+}
+
+namespace {
+
+template <typename CodeT, int V, int R>
+int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s) {
+    constexpr int CPL = GemvMfmaShape<CodeT, R>::CPL;
+    GemvMfmaArgs a;
+    a.codes = w->codes;
+    a.cb = (const half_t *)w->codebooks;
+    a.scale = (const half_t *)w->scale;
+    a.x = x;
+    a.y = y;
+    a.N = w->N;
+    a.K = w->K;
+    a.J = w->K / V;
+    a.E = w->n_entries;
+    a.bs = bs;
+    a.nit = (a.J + 4 * CPL - 1) / (4 * CPL);
+    // wavefronts per workgroup: the chip holds 16 per CU (4096 in all); with more than 256 workgroups
+    // fewer, longer-running wavefronts keep every workgroup resident at once (measured on N = 11008:
+    // 4 wavefronts 11.5 us, 8: 13.3, 16: 16.5 at bs = 1)
+    const int n_wg = (a.N + 15) / 16;
+    int waves = 16;
+    while (waves > 4 && n_wg * waves > 4096) waves >>= 1;
+    if (waves > a.nit) waves = a.nit;
+    if (waves < 1) waves = 1;
+    const size_t cb_bytes = (size_t)R * a.E * V * 2;
+    const size_t lds = ((cb_bytes + 15) & ~(size_t)15) + (size_t)waves * 64 * sizeof(float4v_t);
+    gemv_mfma_kernel<CodeT, V, R><<<(a.N + 15) / 16, waves * 64, lds, s>>>(a);
+    return launch_status();
+}
+
+template <typename CodeT, int V>
+int by_r(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s) {
+    switch (w->n_codebooks) {
+        case 1: return run<CodeT, V, 1>(w, x, bs, y, s);
+        case 2: return run<CodeT, V, 2>(w, x, bs, y, s);
+        default: return run<CodeT, V, 4>(w, x, bs, y, s);
+    }
+}
+
+}  // namespace
+
+// Codebooks must fit the default LDS window next to the reduction buffer, and a row of codes must be
+// a whole number of 16-byte words made of whole sub-vector positions.
+bool gemv_mfma_supported(const vq_weight_t *w) {
+    const int R = w->n_codebooks, sz = w->code_bits / 8;
+    if (w->v != 8 && w->v != 4) return false;
+    if (R != 1 && R != 2 && R != 4) return false;
+    if (R * sz > 8) return false;
+    const int cpl = (R * sz == 1 ? 8 : 16) / (R * sz), cpo = 8 / w->v;
+    if (cpl < cpo) return false;
+    if (w->K <= 0 || (w->K / w->v) % cpl != 0) return false;
+    if ((size_t)R * w->n_entries * w->v * 2 > 48 * 1024) return false;
+    if ((R * w->n_entries * w->v * 2) % 16 != 0) return false;
+    return true;
+}
+
+int launch_gemv_mfma(const vq_weight_t *w, const void *x, int bs, void *y, hipStream_t s) {
+    const half_t *xp = (const half_t *)x;
+    half_t *yp = (half_t *)y;
+    if (w->code_bits == 8) return w->v == 8 ? by_r<uint8_t, 8>(w, xp, bs, yp, s) : by_r<uint8_t, 4>(w, xp, bs, yp, s);
+    return w->v == 8 ? by_r<uint16_t, 8>(w, xp, bs, yp, s) : by_r<uint16_t, 4>(w, xp, bs, yp, s);
+}
+
+}  // namespace vq

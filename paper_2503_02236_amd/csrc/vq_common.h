@@ -78,6 +78,8 @@ int launch_kv_dequant(const vq_kv_t *kv, int which, void *out, hipStream_t s);
 int launch_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *ws, hipStream_t s);
 size_t gemv_workspace(const vq_weight_t *w, int bs);
 int launch_gemv_rows(const vq_weight_t *w, const void *x, int bs, void *y, hipStream_t s);
+bool gemv_mfma_supported(const vq_weight_t *w);
+int launch_gemv_mfma(const vq_weight_t *w, const void *x, int bs, void *y, hipStream_t s);
 int launch_gemv_generic(const vq_weight_t *w, const void *x, int bs, void *y, hipStream_t s);
 int launch_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *ws, hipStream_t s);
 size_t gemm_workspace(const vq_weight_t *w, int M);
