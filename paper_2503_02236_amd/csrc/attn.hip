@@ -3,19 +3,26 @@
 // VQ<4,8,1>, 32 heads x 128 channels: Sec. III-A; token-parallel split with a merge of the
 // local softmax statistics: Sec. III-B (flash-decoding dataflow of Fig. 5).
 //
-// Mapping (wave64): one lane owns one token at a time.  It dequantizes the token's whole
-// K vector sub-vector by sub-vector and dots it with q (row-wise: no exchange needed,
-// Sec. III-B Fig. 6), and later dequantizes the token's V vector and adds p_t * V[t] into
-// its PRIVATE 128-float accumulator.  The column-wise accumulation over tokens that forces a
-// shared-memory round trip in the paper's baseline is thereby deferred to one butterfly
-// reduction over the 64 lanes at the very end, so dequantized values never travel through
-// LDS.  Codebooks live in LDS (2 KB each for one codebook per head and side).
+// Mapping (wave64): four lanes share a token.  Lane (tok = lane % 16, g = lane / 16) owns channels
+// [32 g, 32 g + 32) of token tok of the current 16-token step.
+//   K side: the scores come from the matrix cores.  v_mfma_f32_16x16x32_f16 takes, per lane, 8
+//   consecutive k of one column as its B operand: with k = channel and column = token that is
+//   8 / v dequantized sub-vectors of the lane's token, gathered from the LDS codebook straight into the
+//   operand registers (layout fusion, Sec. VI-B: no shuffle, no LDS round trip).  The A operand is q,
+//   the same in all 16 rows, so every accumulator row holds the score and each of a token's four
+//   lanes reads its token's score from its own registers.  Four MFMAs cover the 128 channels.
+//   V side: the lane dequantizes its 32 channels of the token's V vector and adds p_t * V[t] into 32
+//   PRIVATE fp32 accumulators.  The column-wise accumulation over tokens that forces a shared-memory
+//   round trip in the paper's baseline (Sec. III-B, Fig. 6) is deferred to one butterfly over the 16
+//   token lanes at the very end, so dequantized values never travel through LDS.
+// Only ~130 registers per lane are needed, so 16 wavefronts per CU hide the gather latency.
+// Codebooks live in LDS (2 KB each for one codebook per head and side).
 //
-// A workgroup streams over its token range in tiles of 32 codes per lane and side (1 token
-// for v = 4).  The codes of the next two tiles are in flight while a tile is processed (register
-// double buffers), so the HBM stream and the LDS gathers overlap.  Softmax is kept online
-// per wavefront: a wave-uniform running maximum; the accumulators are rescaled only when a
-// tile raises it (rare after the first tiles).
+// A workgroup streams over its token range in tiles of 16 code bytes per lane and side (32 tokens
+// per wavefront for v = 4).  The codes of the
+// next two tiles are in flight while a tile is processed (register double buffers), so the HBM stream
+// and the LDS gathers overlap.  Softmax is kept online per wavefront: a wave-uniform running
+// maximum; the accumulators are rescaled only when a tile raises it (rare after the first tiles).
 #include "vq_common.h"
 
 namespace vq {
@@ -24,12 +31,10 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kAttnMinTokens = 512;   // do not split token ranges below this
 constexpr int kAttnTargetWgs = 512;   // two workgroups per compute unit
 
-// tokens per lane per tile: 32 code bytes per lane and side (one token of 64 for v = 2)
-template <int V>
-struct AttnTile {
-    static constexpr int NI = V == 2 ? 1 : 32 / (128 / V);
-    static constexpr int TOKENS = 256 * NI;  // per workgroup and tile
-};
+constexpr int kAttnWaves = 8;   // wavefronts per workgroup
+// 16-token steps per wavefront and tile: 16 bytes of codes per lane, tile and side
+constexpr int attn_steps(int v) { return v / 2; }
+constexpr int attn_tile(int v) { return kAttnWaves * 16 * attn_steps(v); }  // tokens per workgroup and tile
 
 struct AttnArgs {
     const uint8_t *k_codes, *v_codes;
@@ -44,28 +49,14 @@ struct AttnArgs {
     float scale2;   // sm_scale * log2(e)
 };
 
-// Butterfly sum of acc[0..N) over the 64 lanes; afterwards lane l holds the totals of
-// elements 2l and 2l+1 in acc[0], acc[1].  In every step a lane keeps one half of its values and
-// adds the partner lane's copy of that half.  The two big steps (partner 32 and 16 lanes away)
-// use the gfx950 lane-swap instructions: one swap puts "mine" and "the partner's" of the kept
-// half side by side; the small steps go through ds_bpermute.
-template <int N>
-__device__ __forceinline__ void lanes_reduce_scatter(float (&acc)[N], int lane) {
-    static_assert(N == 128, "written for 128 accumulators");
+// Butterfly sum of acc[0..32) over the 16 lanes of a row (lanes that share lane / 16); afterwards
+// lane l holds the totals of elements 2 (l % 16) and 2 (l % 16) + 1 in acc[0], acc[1].  In every step
+// a lane keeps one half of its values and adds the partner lane's copy of that half.
+__device__ __forceinline__ void row_reduce_scatter(float (&acc)[32], int lane) {
 #pragma unroll
-    for (int i = 0; i < 64; ++i) {  // upper 32 lanes of lo <-> lower 32 lanes of hi
-        auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i]), __float_as_uint(acc[i + 64]), false, false);
-        acc[i] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-    }
-#pragma unroll
-    for (int i = 0; i < 32; ++i) {  // odd rows of 16 of lo <-> even rows of hi
-        auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(acc[i]), __float_as_uint(acc[i + 32]), false, false);
-        acc[i] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-    }
-#pragma unroll
-    for (int step = 2; step < 6; ++step) {
-        const int m = 32 >> step;       // lane mask
-        const int half = 64 >> step;    // elements kept
+    for (int step = 0; step < 4; ++step) {
+        const int m = 8 >> step;        // lane mask
+        const int half = 16 >> step;    // elements kept
         const bool upper = (lane & m) != 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -99,34 +90,22 @@ __device__ __forceinline__ float wave_max_uniform(float x) {
     return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
-// One codebook entry as it is held in registers, and its load from an LDS byte address.
-template <int V> struct AttnEntry;
-template <> struct AttnEntry<8> {
-    typedef V16 type;
-    static __device__ __forceinline__ type load(unsigned addr) {
+// Load of one codebook entry (v halves) from an LDS byte address into bytes [at, at + 2 v) of a
+// 64-byte register block.
+template <int V>
+__device__ __forceinline__ void lds_entry_into(V16 (&blk)[4], int at, unsigned addr) {
+    if constexpr (V == 8) {
         typedef unsigned raw_t __attribute__((ext_vector_type(4)));
         const raw_t r = *reinterpret_cast<const __attribute__((address_space(3))) raw_t *>((uintptr_t)addr);
-        type e;
-        e.w[0] = r.x; e.w[1] = r.y; e.w[2] = r.z; e.w[3] = r.w;
-        return e;
-    }
-};
-template <> struct AttnEntry<4> {
-    typedef V8 type;
-    static __device__ __forceinline__ type load(unsigned addr) {
+        blk[at / 16].w[0] = r.x; blk[at / 16].w[1] = r.y; blk[at / 16].w[2] = r.z; blk[at / 16].w[3] = r.w;
+    } else if constexpr (V == 4) {
         typedef unsigned raw_t __attribute__((ext_vector_type(2)));
         const raw_t r = *reinterpret_cast<const __attribute__((address_space(3))) raw_t *>((uintptr_t)addr);
-        type e;
-        e.w[0] = r.x; e.w[1] = r.y;
-        return e;
+        blk[at / 16].w[(at % 16) / 4] = r.x; blk[at / 16].w[(at % 16) / 4 + 1] = r.y;
+    } else {
+        blk[at / 16].w[(at % 16) / 4] = *reinterpret_cast<const __attribute__((address_space(3))) unsigned *>((uintptr_t)addr);
     }
-};
-template <> struct AttnEntry<2> {
-    typedef half2_t type;
-    static __device__ __forceinline__ type load(unsigned addr) {
-        return *reinterpret_cast<const __attribute__((address_space(3))) half2_t *>((uintptr_t)addr);
-    }
-};
+}
 
 // (byte B of w) << sh in one instruction (the compiler emits an extract and a shift-add)
 template <int B>
@@ -151,21 +130,18 @@ __device__ __forceinline__ unsigned byte_shl(unsigned w, unsigned sh) {
 // sits at LDS offset 0 and the V codebook at 4096, so an entry's address is (code * v * 2) plus a
 // constant that folds into the offset field of the LDS instruction.
 //
-// Inside a tile the 64 lookups of a side go in small groups: the LDS gathers of group g+1 are
-// issued before the arithmetic of group g, so that gathers (limited by LDS bank conflicts) and
-// vector arithmetic overlap inside one wavefront; only two wavefronts per SIMD fit the 128
-// private accumulators.
+// The lookups of a tile form one sequence of groups (per 16-token step: the lane's 32 K channels, later
+// its 32 V channels); the LDS gathers of group n+1 are issued before the arithmetic of group n, and the
+// sequence continues across the K/V boundary and into the next tile, so the LDS queue never drains.
 template <int V, bool ONE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_decode_kernel(AttnArgs a) {
+__global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void attn_decode_kernel(AttnArgs a) {
     constexpr int D = 128;
     constexpr int P = D / V;          // codes (bytes) per token and side
-    constexpr int NI = AttnTile<V>::NI;
-    constexpr int TILE = AttnTile<V>::TOKENS;
-    constexpr int GS = V == 8 ? 4 : 8;  // lookups per group (at most 16 registers of entries per group)
-    constexpr int NG = NI * P / GS;   // groups per tile and side
-    constexpr int NC = NI * P / 16;   // 16-byte code words per lane, tile and side
+    constexpr int CB = 32 / V;        // codes (bytes) per lane, step and side: the lane's 32 channels
+    constexpr int CW = (CB + 3) / 4;  // dwords holding them
+    constexpr int NS = attn_steps(V);
+    constexpr int TILE = attn_tile(V);
     constexpr unsigned SH = V == 8 ? 4 : V == 4 ? 3 : 2;  // log2 of the entry size in bytes
-    typedef typename AttnEntry<V>::type entry_t;
     extern __shared__ __align__(16) unsigned char smem[];
     // Entry addresses are formed as plain LDS byte offsets (shifted code + constant), which is only
     // right if the dynamic LDS block starts at LDS address 0: true for a kernel without static LDS.
@@ -173,25 +149,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     if ((unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem != 0u) return;
     const int cb_bytes = a.G * a.E * V * 2;        // per side
     const int v_off = ONE ? 4096 : cb_bytes;       // LDS offset of the V codebook
-    float *xw = reinterpret_cast<float *>(smem + 2 * (size_t)v_off);  // [4][D] + [4] + [4]
-    float *xw_m = xw + 4 * D, *xw_l = xw_m + 4;
+    float *xw = reinterpret_cast<float *>(smem + 2 * (size_t)v_off);  // [waves][D] + [waves] + [waves]
+    float *xw_m = xw + kAttnWaves * D, *xw_l = xw_m + kAttnWaves;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tok = lane & 15, g = lane >> 4;
     const int bh = blockIdx.x, split = blockIdx.y;
     const int b = bh / a.H, h = bh % a.H;
     const int len = a.seq_lens ? min(max(a.seq_lens[b], 0), a.T) : a.T;
     const int start = split * a.tc;
     const int end = min(len, start + a.tc);  // this workgroup attends tokens [start, end)
-
-    // query: uniform over the workgroup and never written by this kernel; read through the constant
-    // address space so that it is fetched with scalar loads and lives in scalar registers
-    half2_t qf[D / 2];
-    {
-        typedef const __attribute__((address_space(4))) half2_t const_half2_t;
-        const_half2_t *qp = (const_half2_t *)(uintptr_t)(a.q + (size_t)bh * D);
-#pragma unroll
-        for (int i = 0; i < D / 2; ++i) qf[i] = qp[i];
-    }
 
     if (start >= end) {  // nothing to attend in this token range (uniform over the workgroup)
         if (tid < D) {
@@ -211,16 +178,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 
     const int ntiles = (end - start + TILE - 1) / TILE;
     const size_t row0 = (size_t)bh * a.T;
-    const int t_lane = start + wave * 64 + lane;  // token of (tile it, sub-token i): + it*TILE + i*256
+    // token of (tile it, step s) for this lane: t_lane + it * TILE + s * 16
+    const int t_lane = start + wave * (16 * NS) + tok;
 
-    // codes of one tile and side -> registers; tokens past the end re-read the last valid token
-    auto load_codes = [&](const uint8_t *codes, int it, V16 (&buf)[NC]) {
+    // codes of one tile and side -> registers (the lane's CB bytes of each of its NS tokens); tokens
+    // past the end re-read the last valid token (their scores are masked)
+    auto load_codes = [&](const uint8_t *codes, int it, uint32_t (&buf)[NS][CW]) {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int t = min(t_lane + it * TILE + i * 256, end - 1);
-            const uint8_t *cp = codes + (row0 + t) * P;
+        for (int s = 0; s < NS; ++s) {
+            const int t = min(t_lane + it * TILE + s * 16, end - 1);
+            const uint8_t *cp = codes + (row0 + t) * P + g * CB;
+            if constexpr (CB == 4) {
+                buf[s][0] = *reinterpret_cast<const uint32_t *>(cp);
+            } else if constexpr (CB == 8) {
+                V8 c = ld8(cp);
+                buf[s][0] = c.w[0]; buf[s][1] = c.w[1];
+            } else {
+                V16 c = ld16(cp);
 #pragma unroll
-            for (int c = 0; c < P / 16; ++c) buf[i * (P / 16) + c] = ld16(cp + c * 16);
+                for (int i = 0; i < 4; ++i) buf[s][i] = c.w[i];
+            }
         }
     };
 
@@ -233,141 +210,97 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
         kst = ks[tid];
         vst = vs[tid];
     }
-    // 2. codes of the first two tiles
-    V16 kA[NC], vA[NC], kB[NC], vB[NC];
+    // 2. codes of the first two tiles, and q as the A operands of the four MFMAs: channels
+    //    32 g + 8 i .. + 7 (the same for every row of the operand)
+    uint32_t kA[NS][CW], vA[NS][CW], kB[NS][CW], vB[NS][CW];
     load_codes(a.k_codes, 0, kA);
     load_codes(a.v_codes, 0, vA);
     load_codes(a.k_codes, 1, kB);
     load_codes(a.v_codes, 1, vB);
+    half8_t qop[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qop[i] = ld16(a.q + (size_t)bh * D + 32 * g + 8 * i).h8;
     if (tid < n16) {
         reinterpret_cast<uint4 *>(smem)[tid] = kst;
         reinterpret_cast<uint4 *>(smem + v_off)[tid] = vst;
     }
-    for (int i = tid + 256; i < n16; i += 256) {  // codebooks larger than 4 KiB per side
+    for (int i = tid + kAttnWaves * 64; i < n16; i += kAttnWaves * 64) {  // codebooks larger than 8 KiB per side
         reinterpret_cast<uint4 *>(smem)[i] = ks[i];
         reinterpret_cast<uint4 *>(smem + v_off)[i] = vs[i];
     }
     __syncthreads();
 
     const unsigned sh = SH;
-    // gathers of group g (lookups GS g .. GS g + GS - 1 of the tile; lookup u = sub-token u / P, sub-vector u % P)
-    auto gather = [&](const V16 (&codes)[NC], int g, int base, entry_t (&e)[GS]) {
+    // gathers of one group: the CB entries of step s, into a 64-byte register block in channel order
+    auto gather = [&](const uint32_t (&codes)[NS][CW], int s, int base, V16 (&blk)[4]) {
 #pragma unroll
-        for (int j = 0; j < GS; ++j) {
-            const int u = g * GS + j, p = u % P;
-            const unsigned w = codes[u / 16].w[(u % 16) / 4];
-            unsigned off = (u % 4) == 0 ? byte_shl<0>(w, sh)
-                           : (u % 4) == 1 ? byte_shl<1>(w, sh)
-                           : (u % 4) == 2 ? byte_shl<2>(w, sh) : byte_shl<3>(w, sh);
-            if (!ONE) off += ((unsigned)(p >> a.pg_shift) * a.E) << SH;
-            e[j] = AttnEntry<V>::load((unsigned)base + off);
+        for (int c = 0; c < CB; ++c) {
+            const unsigned w = codes[s][c / 4];
+            unsigned off = (c % 4) == 0 ? byte_shl<0>(w, sh)
+                           : (c % 4) == 1 ? byte_shl<1>(w, sh)
+                           : (c % 4) == 2 ? byte_shl<2>(w, sh) : byte_shl<3>(w, sh);
+            if (!ONE) off += ((unsigned)((g * CB + c) >> a.pg_shift) * a.E) << SH;
+            lds_entry_into<V>(blk, c * V * 2, (unsigned)base + off);
         }
     };
 
-    float acc[D];
+    float acc[32];  // channels 32 g .. 32 g + 31 of sum_t p_t V[t]
 #pragma unroll
-    for (int d = 0; d < D; ++d) acc[d] = 0.f;
-    float lsum = 0.f;          // per lane
+    for (int d = 0; d < 32; ++d) acc[d] = 0.f;
+    float lsum = 0.f;          // per lane (every token is counted by its four lanes)
     float m_run = -INFINITY;   // wave-uniform running maximum of the scores (log2 domain)
 
-    // Gathered entries of the group being used and of the one in flight.  The lookups of a tile form
-    // one sequence of 2 NG groups (K side, then V side) that continues into the next tile, so the LDS
-    // queue never drains at the boundaries between the two sides or between tiles.
-    static_assert(NG % 2 == 0, "the double buffer must be back at slot 0 after each side");
-    entry_t e[2][GS];
-    gather(kA, 0, 0, e[0]);
+    V16 eb[2][4];  // entries of the group being used and of the one in flight
+    gather(kA, 0, 0, eb[0]);
 
     // kn: K codes of the following tile (the other register buffer)
-    auto tile_step = [&](int it, V16 (&kc)[NC], V16 (&vc)[NC], const V16 (&kn)[NC]) {
-        // ---- scores of the lane's NI tokens (two partial sums each to shorten the dependent chain).
-        // Masked tokens get -inf through an additive bias: a select on the finished score would make
-        // the compiler branch around the arithmetic and pull every gather of the tile in front of it.
-        float sc[NI], bias[NI];
+    auto tile_step = [&](int it, uint32_t (&kc)[NS][CW], uint32_t (&vc)[NS][CW], const uint32_t (&kn)[NS][CW]) {
+        // ---- scores.  Masked tokens get -inf through an additive bias (a select on the finished score
+        // would make the compiler branch around the arithmetic and move the gathers).
+        float sc[NS];
 #pragma unroll
-        for (int i = 0; i < NI; ++i) bias[i] = (t_lane + it * TILE + i * 256 < end) ? 0.f : -INFINITY;
-        {
-            float d0 = 0.f, d1 = 0.f;
+        for (int s = 0; s < NS; ++s) {
+            if (s + 1 < NS)
+                gather(kc, s + 1, 0, eb[(s + 1) & 1]);
+            else
+                gather(vc, 0, v_off, eb[NS & 1]);
+            __builtin_amdgcn_sched_barrier(0);  // keep the gathers of the next group ahead of this arithmetic
+            float4_t c4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                if (g + 1 < NG)
-                    gather(kc, g + 1, 0, e[(g + 1) & 1]);
-                else
-                    gather(vc, 0, v_off, e[0]);
-                __builtin_amdgcn_sched_barrier(0);  // keep the gathers of g+1 ahead of the arithmetic of g
-#pragma unroll
-                for (int j = 0; j < GS; ++j) {
-                    const int p = (g * GS + j) % P;
-                    const entry_t &ev = e[g & 1][j];
-                    if constexpr (V == 8) {
-                        d0 = dot2(ev.h2[0], qf[p * 4 + 0], d0);
-                        d1 = dot2(ev.h2[1], qf[p * 4 + 1], d1);
-                        d0 = dot2(ev.h2[2], qf[p * 4 + 2], d0);
-                        d1 = dot2(ev.h2[3], qf[p * 4 + 3], d1);
-                    } else if constexpr (V == 4) {
-                        d0 = dot2(ev.h2[0], qf[p * 2], d0);
-                        d1 = dot2(ev.h2[1], qf[p * 2 + 1], d1);
-                    } else {
-                        if (j & 1)
-                            d1 = dot2(ev, qf[p], d1);
-                        else
-                            d0 = dot2(ev, qf[p], d0);
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                if ((g + 1) * GS % P == 0) {  // last group of a sub-token
-                    const int i = (g * GS) / P;
-                    sc[i] = __builtin_fmaf(d0 + d1, a.scale2, bias[i]);
-                    d0 = d1 = 0.f;
-                }
-            }
+            for (int i = 0; i < 4; ++i) c4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[i], eb[s & 1][i].h8, c4, 0, 0, 0);
+            const float bias = (t_lane + it * TILE + s * 16 < end) ? 0.f : -INFINITY;
+            sc[s] = __builtin_fmaf(c4[0], a.scale2, bias);
+            __builtin_amdgcn_sched_barrier(0);
         }
         load_codes(a.k_codes, it + 2, kc);  // the K codes of this tile are used up
 
         // ---- online softmax: raise the wave's running maximum if needed (uniform branch)
         float tmax = sc[0];
 #pragma unroll
-        for (int i = 1; i < NI; ++i) tmax = fmaxf(tmax, sc[i]);
+        for (int s = 1; s < NS; ++s) tmax = fmaxf(tmax, sc[s]);
         tmax = wave_max_uniform(tmax);
         if (tmax > m_run) {
             const float f = __builtin_amdgcn_exp2f(m_run - tmax);  // 0 while nothing was accumulated
 #pragma unroll
-            for (int d = 0; d < D; ++d) acc[d] *= f;
+            for (int d = 0; d < 32; ++d) acc[d] *= f;
             lsum *= f;
             m_run = tmax;
         }
 
-        // ---- acc += p_t * V[t]
-        {
-            float p_t = 0.f;
+        // ---- acc += p_t * V[t] on the lane's 32 channels
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                if (g + 1 < NG)
-                    gather(vc, g + 1, v_off, e[(g + 1) & 1]);
-                else
-                    gather(kn, 0, 0, e[0]);  // first K group of the next tile
-                __builtin_amdgcn_sched_barrier(0);
-                if ((g * GS) % P == 0) {  // first group of a sub-token
-                    const float s = sc[(g * GS) / P];
-                    p_t = s == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s - m_run);
-                    lsum += p_t;
-                }
+        for (int s = 0; s < NS; ++s) {
+            if (s + 1 < NS)
+                gather(vc, s + 1, v_off, eb[(NS + s + 1) & 1]);
+            else
+                gather(kn, 0, 0, eb[0]);  // first K group of the next tile (2 NS is even)
+            __builtin_amdgcn_sched_barrier(0);
+            const float p_t = sc[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sc[s] - m_run);
+            lsum += p_t;
+            const V16 (&ev)[4] = eb[(NS + s) & 1];
 #pragma unroll
-                for (int j = 0; j < GS; ++j) {
-                    const int p = (g * GS + j) % P;
-                    const entry_t &ev = e[g & 1][j];
-                    if constexpr (V == 8) {
-#pragma unroll
-                        for (int k = 0; k < 8; ++k) acc[p * 8 + k] += p_t * (float)ev.h8[k];
-                    } else if constexpr (V == 4) {
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) acc[p * 4 + k] += p_t * (float)ev.h4[k];
-                    } else {
-                        acc[p * 2] += p_t * (float)ev[0];
-                        acc[p * 2 + 1] += p_t * (float)ev[1];
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int d = 0; d < 32; ++d) acc[d] += p_t * (float)ev[d / 8].h8[d % 8];
+            __builtin_amdgcn_sched_barrier(0);
         }
         load_codes(a.v_codes, it + 2, vc);
     };
@@ -377,21 +310,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
         if (it + 1 < ntiles) tile_step(it + 1, kB, vB, kA);
     }
 
-    // ---- reduce over lanes, then over the four wavefronts (fixed order) ---------------------
-    lanes_reduce_scatter<D>(acc, lane);
-    lsum = wave_sum(lsum);
-    xw[wave * D + 2 * lane] = acc[0];
-    xw[wave * D + 2 * lane + 1] = acc[1];
+    // ---- reduce over the 16 token lanes, then over the wavefronts (fixed order) -------------
+    row_reduce_scatter(acc, lane);
+    lsum = wave_sum(lsum) * 0.25f;  // four lanes per token
+    xw[wave * D + 32 * g + 2 * tok] = acc[0];
+    xw[wave * D + 32 * g + 2 * tok + 1] = acc[1];
     if (lane == 0) {
         xw_m[wave] = m_run;
         xw_l[wave] = lsum;
     }
     __syncthreads();
     if (tid < D) {
-        float M = fmaxf(fmaxf(xw_m[0], xw_m[1]), fmaxf(xw_m[2], xw_m[3]));
+        float M = xw_m[0];
+#pragma unroll
+        for (int w = 1; w < kAttnWaves; ++w) M = fmaxf(M, xw_m[w]);
         float L = 0.f, o = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < kAttnWaves; ++w) {
             float wgt = (xw_m[w] == -INFINITY) ? 0.f : exp2f(xw_m[w] - M);
             L += xw_l[w] * wgt;
             o += xw[w * D + tid] * wgt;
@@ -430,7 +365,7 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float *__restrict
 // Token-range split: enough workgroups to fill the chip (two per compute unit) when batch x heads
 // alone does not, ranges of at least kAttnMinTokens tokens, rounded to whole tiles.
 static void attn_split(const vq_kv_t *kv, int *S, int *tc) {
-    const int tile = kv->v == 8 ? AttnTile<8>::TOKENS : kv->v == 4 ? AttnTile<4>::TOKENS : AttnTile<2>::TOKENS;
+    const int tile = attn_tile(kv->v);
     const long long bh = (long long)kv->B * kv->H;
     long long want = bh > 0 ? (kAttnTargetWgs + bh - 1) / bh : 1;
     long long most = (kv->T + kAttnMinTokens - 1) / kAttnMinTokens;
@@ -454,14 +389,14 @@ size_t attn_decode_workspace(const vq_kv_t *kv) {
 template <int V, bool ONE>
 static int run_attn(const AttnArgs &a, hipStream_t s) {
     const size_t side = ONE ? 4096 : (size_t)a.G * a.E * V * sizeof(half_t);  // matches the kernel's layout
-    size_t lds = 2 * side + (4 * 128 + 8) * sizeof(float);
+    size_t lds = 2 * side + (size_t)kAttnWaves * (128 + 2) * sizeof(float);
     static size_t attr_lds = 0;
     if (lds > 64 * 1024 && lds > attr_lds) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_decode_kernel<V, ONE>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_lds = lds;
     }
-    attn_decode_kernel<V, ONE><<<dim3(a.B * a.H, a.S), 256, lds, s>>>(a);
+    attn_decode_kernel<V, ONE><<<dim3(a.B * a.H, a.S), kAttnWaves * 64, lds, s>>>(a);
     if (a.S > 1) attn_merge_kernel<<<a.B * a.H, 128, 0, s>>>(a.ws, a.out, a.S);
     return launch_status();
 }
