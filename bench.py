@@ -276,6 +276,19 @@ def main():
                                                "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2)}
         del ring
         torch.cuda.empty_cache()
+        # same shape with the coupled-quantization layout: 32 codebooks per head and side (64 KiB each)
+        kv = wl.config5_kv(G=32)
+        ring = [vq.kv_to_device(kv, dev) for _ in range(3)]
+
+        def attn_loop_cq():
+            for kd in ring:
+                vq.vq_attn_decode(kd, q, sm, out=out, ws=ws)
+        ms = timed(attn_loop_cq, 10, 2) / len(ring)
+        b = kv.effective_bytes()
+        result["attn_decode_B16_H32_T4096_cq32"] = {"us": round(ms * 1e3, 2), "GBps": round(b / ms / 1e6, 1),
+                                                    "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2)}
+        del ring
+        torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ secondary: C3 additive gemv
     if want("add") and not args.skip_secondary:

@@ -298,6 +298,15 @@ def test_attn_zero_length_sequence_and_sharp_softmax(gpu_device):
     assert_close(out, want, "attn len0 / sharp")
 
 
+def test_attn_config5_coupled_quantization_layout_full_size(gpu_device):
+    # the paper's CQ-2 layout (Sec. III-B, Tbl. IV): one codebook per 4-channel sub-space, 32 per head and
+    # side (64 KiB of K codebooks per head), at the full C5 shape
+    kv = wl.config5_kv(G=32)
+    sm = 1.0 / np.sqrt(128.0)
+    out = run_attn(kv, gpu_device, sm)
+    assert_close(out, oracle_attn(kv, sm), "C5 G=32 full")
+
+
 def test_attn_config5_full_size(gpu_device):
     kv = wl.config5_kv()
     sm = 1.0 / np.sqrt(128.0)
