@@ -3,8 +3,10 @@
 
 Headline workload (N = 1 GPU): Llama-7B-shaped decode VQ-gemv, bs = 1, one 2^16 x 8 fp16
 codebook per matrix, uint16 codes, fp16 per-channel scale.  One "step" is one decode token's
-worth of linear layers of the whole 32-block stack: 224 vq_gemv launches (4 x (4096,4096),
-2 x (11008,4096), 1 x (4096,11008) per block), every matrix with its own codes and codebook
+worth of linear layers of the whole 32-block stack: 224 matrices (4 x (4096,4096),
+2 x (11008,4096), 1 x (4096,11008) per block) in 128 launches -- the projections of a block that share
+their input go through vq_gemv_batch (query/key/value; gate/up), the other two through vq_gemv;
+`--no-batch` gives one vq_gemv per matrix -- every matrix with its own codes and codebook
 (1.5 GiB + 224 MiB, far beyond the 256 MB last-level cache, so every launch streams from HBM).
 All inputs are resident in HBM before the timed region.
 
@@ -39,6 +41,9 @@ def parse():
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--canonical", action="store_true",
                     help="headline gemv from the canonical code layout (L2 gathers) instead of the re-tiled codes")
+    ap.add_argument("--no-batch", action="store_true",
+                    help="one vq_gemv call per matrix (224 launches) instead of vq_gemv_batch for the projections of "
+                         "a block that share their input (query/key/value; gate/up)")
     ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter run (wrap in rocprofv3 --pmc FETCH_SIZE or WRITE_SIZE): three plain copies of "
@@ -129,22 +134,43 @@ def main():
     if want("gemv"):
         L = args.layers
         x_by_k = {K: torch.from_numpy(wl.make_activations(1, K, wl.seed_for(2, K))).to(dev) for K in (4096, 11008)}
-        calls, eff_bytes, per_shape = [], 0, {0: [], 1: [], 2: []}
+        calls, singles, eff_bytes, per_shape = [], [], 0, {0: [], 1: [], 2: []}
         host_block0 = []
         packed = not args.canonical
-        ws = vq.new_workspace(32 * 11008 * 4, dev) if packed else None   # shared by all layers
+        batched = packed and not args.no_batch
+        ws = vq.new_workspace(4 << 20, dev) if packed else None   # shared by all launches of the stream
+
+        class BatchCall:
+            """Pre-marshalled vq_gemv_batch call."""
+            def __init__(self, members):
+                self.b = vq.GemvBatch([m.keep[0] for m in members], [m.keep[1] for m in members],
+                                      [m.keep[2] for m in members])
+                assert self.b.workspace() <= ws.numel()
+
+            def __call__(self):
+                st = self.b.run(ws.data_ptr(), ws.numel())
+                if st != 0:
+                    raise vq.VQError(st, "vq_gemv_batch")
+
         for layer in range(L):
+            block = []
             for slot, si in enumerate(wl.LLAMA7B_BLOCK):
                 N, K = wl.LLAMA7B_SHAPES[si]
                 w = wl.make_weight(N, K, 8, 16, 1, 65536, 0.02, wl.seed_for(2, layer * 7 + slot))
                 wd = vq.weight_to_device(w, dev, prepack=packed, keep_codes=not packed)
                 y = torch.empty((1, N), dtype=torch.float16, device=dev)
                 c = GemvCall(wd, x_by_k[K], y, ws)
-                calls.append(c)
+                block.append(c)
+                singles.append(c)
                 per_shape[si].append(c)
                 eff_bytes += w.effective_bytes(1)
                 if layer == 0:
                     host_block0.append(w)
+            if batched:
+                # slots: 0-2 query/key/value (one input), 3 output, 4-5 gate/up (one input), 6 down
+                calls += [BatchCall(block[0:3]), block[3], BatchCall(block[4:6]), block[6]]
+            else:
+                calls += block
         torch.cuda.synchronize()
 
         def step():
@@ -208,16 +234,20 @@ def main():
             "dtype": "f16xf16->f32", "data": "synthetic",
             "config": {"workload": "C2: Llama-7B decode VQ-gemv bs=1, %d blocks x 7 matrices, VQ<8,16,1> uint16 codes, "
                                    "fp16 scale" % L,
-                       "launches_per_step": n_launch, "effective_bytes_per_step": eff_bytes,
+                       "launches_per_step": n_launch, "matrices_per_step": len(singles),
+                       "effective_bytes_per_step": eff_bytes,
+                       "calls": ("per block: vq_gemv_batch(q,k,v), vq_gemv(o), vq_gemv_batch(gate,up), vq_gemv(down)"
+                                 if batched else "one vq_gemv per matrix"),
                        "code_layout": "re-tiled offline by vq_gemv_prepack (LDS codebook slices)" if packed
                                       else "canonical [N][K/8] (entries gathered from L2)",
                        "timing": "hip-graph replay" if graph is not None else "eager launches"},
             "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
             "gemv_per_shape_cold": shape_us,
-            "roofline": {"bound": "hbm", "kernel": "gemv_packed_kernel" if packed else "gemv_rows_kernel<uint16,8,1>",
+            "roofline": {"bound": "hbm", "kernel": ("gemv_packed_batch_kernel / gemv_packed_kernel (+ finalize)" if batched else
+                                    "gemv_packed_kernel (+ finalize)" if packed else "gemv_rows_kernel<uint16,8,1>"),
                          "achieved": round(gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": round(gbps / HBM_PEAK_GBPS, 4),
-                         "traffic": read_traffic(args.traffic_file) if packed else None,
+                         "traffic": read_traffic(args.traffic_file) if batched else None,
                          "bytes_per_launch": eff_bytes // n_launch,
                          "avg_launch_us": round(ms_step * 1e3 / n_launch, 3)},
         })
@@ -237,8 +267,8 @@ def main():
             result["cpu_baseline"] = {"value": round(blk_bytes / dt / 1e9, 3), "unit": "GB/s",
                                       "cores": oracle.threads(), "kind": "oracle",
                                       "sample": "one decoder block (7 of the %d matrices), mean of %d runs, %.1f ms"
-                                                % (n_launch, reps, dt * 1e3)}
-        del calls, per_shape, graph
+                                                % (len(singles), reps, dt * 1e3)}
+        del calls, singles, per_shape, graph
         torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ secondary: C4 prefill gemm

@@ -114,6 +114,21 @@ size_t vq_gemv_prepack_bytes(const vq_weight_t *w_host);
 int vq_gemv_prepack(const vq_weight_t *w_host, void *out_host, size_t out_bytes, vq_gemv_pack_t *pack);
 
 /*
+ * Several independent bs = 1 VQ-gemv problems y_i = W_i x_i in one call (count <= VQ_GEMV_BATCH_MAX):
+ * the projections of a decoder block that do not depend on each other (query/key/value; gate/up).
+ * When every W_i carries re-tiled codes (gemv_pack) the whole batch is ONE launch of the codebook-centric
+ * kernel (Sec. VI-A) plus one launch of its global reduction, so the fixed latencies of a launch are paid
+ * once; any other mix is run as `count` vq_gemv calls.  Results are bit-identical to separate vq_gemv calls.
+ * w, x, y: HOST arrays of `count` pointers (x_i: device fp16 [K_i], y_i: device fp16 [N_i]; the x_i may
+ * be the same buffer).  ws: vq_gemv_batch_workspace(w, count) bytes.
+ * Errors: as vq_gemv; VQ_ERR_SHAPE for count outside 1..VQ_GEMV_BATCH_MAX.
+ */
+#define VQ_GEMV_BATCH_MAX 4
+int vq_gemv_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count,
+                  void *ws, size_t ws_bytes, void *stream);
+size_t vq_gemv_batch_workspace(const vq_weight_t *const *w, int count);
+
+/*
  * VQ-gemm (prefill phase, Sec. III-C / Sec. VII "GeMM"): Y = X W^T with the
  * dequantized tile fed to the fp16 matrix cores, fp32 accumulation.
  *   Y[m][n] = scale[n] * sum_k W[n][k] * X[m][k],   m < M

@@ -53,6 +53,10 @@ SYMBOLS = {
     "vq_gemv": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "vq_gemv_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t), ctypes.c_int]),
+    "vq_gemv_batch": (ctypes.c_int, [ctypes.POINTER(ctypes.POINTER(vq_weight_t)), ctypes.POINTER(ctypes.c_void_p),
+                                     ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p,
+                                     ctypes.c_size_t, ctypes.c_void_p]),
+    "vq_gemv_batch_workspace": (ctypes.c_size_t, [ctypes.POINTER(ctypes.POINTER(vq_weight_t)), ctypes.c_int]),
     "vq_gemv_prepack_bytes": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t)]),
     "vq_gemv_prepack": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_size_t,
                                        ctypes.POINTER(vq_gemv_pack_t)]),
@@ -235,6 +239,35 @@ def vq_gemv(w: VQWeightDev, x: torch.Tensor, y: Optional[torch.Tensor] = None,
     _check(lib().vq_gemv(ctypes.byref(d), _dev(x, "x", torch.float16), bs, _dev(y, "y", torch.float16),
                          ws_p, ws_n, _stream()), "vq_gemv")
     return y
+
+
+class GemvBatch:
+    """Marshalled arguments of one ``vq_gemv_batch`` call (host pointer arrays built once)."""
+
+    def __init__(self, ws_list, xs, ys):
+        n = len(ws_list)
+        self.keep = (list(ws_list), list(xs), list(ys))
+        self.descs = [w.desc() for w in ws_list]
+        self.w_arr = (ctypes.POINTER(vq_weight_t) * n)(*[ctypes.pointer(d) for d in self.descs])
+        self.x_arr = (ctypes.c_void_p * n)(*[_dev(x, "x", torch.float16) for x in xs])
+        self.y_arr = (ctypes.c_void_p * n)(*[_dev(y, "y", torch.float16) for y in ys])
+        self.count = n
+
+    def workspace(self) -> int:
+        return int(lib().vq_gemv_batch_workspace(self.w_arr, self.count))
+
+    def run(self, ws_ptr, ws_bytes) -> int:
+        return lib().vq_gemv_batch(self.w_arr, self.x_arr, self.y_arr, self.count, ws_ptr, ws_bytes, _stream())
+
+
+def vq_gemv_batch(ws_list, xs, ys=None, ws: Optional[torch.Tensor] = None):
+    """Independent bs = 1 problems y_i = scale_i * (W_i x_i) in one call; returns the list of y_i."""
+    if ys is None:
+        ys = [torch.empty((1, w.N), dtype=torch.float16, device=x.device) for w, x in zip(ws_list, xs)]
+    call = GemvBatch(ws_list, xs, ys)
+    ws_t, ws_p, ws_n = _workspace(call.workspace(), xs[0].device, ws)
+    _check(call.run(ws_p, ws_n), "vq_gemv_batch")
+    return ys
 
 
 def vq_gemm_workspace(w: VQWeightDev, M: int) -> int:

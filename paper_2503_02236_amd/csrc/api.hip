@@ -80,6 +80,58 @@ int vq_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *ws, size
     return launch_gemv(w, x, bs, y, ws, static_cast<hipStream_t>(stream));
 }
 
+// Every problem of the batch can run from re-tiled codes in one launch.
+static bool batch_all_packed(const vq_weight_t *const *w, int count) {
+    for (int i = 0; i < count; ++i)
+        if (!w[i] || !gemv_uses_pack(w[i], 1) || w[i]->K <= 0 || w[i]->N <= 0) return false;
+    return true;
+}
+
+static size_t batch_slot(const vq_weight_t *w) { return (gemv_workspace(w, 1) + 255) & ~(size_t)255; }
+
+size_t vq_gemv_batch_workspace(const vq_weight_t *const *w, int count) {
+    if (!w || count < 1 || count > VQ_GEMV_BATCH_MAX) return 0;
+    size_t total = 0;
+    for (int i = 0; i < count; ++i) {
+        if (!w[i]) return 0;
+        const bool packed = gemv_uses_pack(w[i], 1);
+        if (check_weight(w[i], !packed) != VQ_OK || (packed && check_pack(w[i]) != VQ_OK)) return 0;
+        total += batch_slot(w[i]);
+    }
+    return total;
+}
+
+int vq_gemv_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, void *ws,
+                  size_t ws_bytes, void *stream) {
+    if (!w || !x || !y) return VQ_ERR_NULL;
+    if (count < 1 || count > VQ_GEMV_BATCH_MAX) return VQ_ERR_SHAPE;
+    size_t need = 0;
+    for (int i = 0; i < count; ++i) {
+        if (!w[i]) return VQ_ERR_NULL;
+        const bool packed = gemv_uses_pack(w[i], 1);
+        int st = check_weight(w[i], !packed);
+        if (st != VQ_OK) return st;
+        if (packed && (st = check_pack(w[i])) != VQ_OK) return st;
+        if (!x[i] || !y[i]) return VQ_ERR_NULL;
+        if (!aligned16(x[i]) || !aligned16(y[i])) return VQ_ERR_ALIGN;
+        need += batch_slot(w[i]);
+    }
+    if (need && (!ws || ws_bytes < need)) return VQ_ERR_WORKSPACE;
+    if (ws && !aligned16(ws)) return VQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (batch_all_packed(w, count)) return launch_gemv_packed_batch(w, x, y, count, ws, s);
+    // any other mix: one launch per problem, each with its own slot of the workspace
+    size_t off = 0;
+    for (int i = 0; i < count; ++i) {
+        if (w[i]->N > 0) {
+            int st = launch_gemv(w[i], x[i], 1, y[i], (unsigned char *)ws + off, s);
+            if (st != VQ_OK) return st;
+        }
+        off += batch_slot(w[i]);
+    }
+    return VQ_OK;
+}
+
 size_t vq_gemm_workspace(const vq_weight_t *w, int M) {
     if (check_weight(w, true) != VQ_OK || M < 1) return 0;
     return gemm_workspace(w, M);

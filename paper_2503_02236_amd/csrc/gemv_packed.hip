@@ -174,7 +174,7 @@ struct PackedArgs {
 };
 
 constexpr int kPackMaxSlices = 32;  // 2^16 entries / 2048 per slice
-constexpr int kPackPrefetch = 12;  // 4-atom steps held in registers while the slice is being staged
+constexpr int kPackPrefetch = 10;  // 4-atom steps held in registers while the slice is being staged
 
 __device__ __forceinline__ float atom_dot(uint32_t atom, const unsigned char *slice, const unsigned char *xl, float acc) {
     V16 e = *reinterpret_cast<const V16 *>(slice + ((atom & 0xfffu) << 4));
@@ -200,7 +200,7 @@ __device__ __forceinline__ void step_dot(uint32_t d0, uint32_t d1, uint32_t d2, 
 
 // All global loads of a workgroup are issued before anything waits: the kernel is a chain of
 // memory latencies (tables -> atoms -> partials), not a bandwidth problem, at these sizes.
-__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) {
+__device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int bid) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *slice = smem;                                    // slice_entries * 16 bytes
     unsigned char *xl = smem + (size_t)a.slice_entries * 16;        // J * 16 bytes
@@ -212,12 +212,12 @@ __global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) {
     // (otherwise every die pulls the whole 1 MiB codebook: 8 MiB per launch).
     int s, rb;
     if (a.S % 8 == 0) {
-        const int die = blockIdx.x & 7, local = blockIdx.x >> 3, per_die = a.S >> 3;
+        const int die = bid & 7, local = bid >> 3, per_die = a.S >> 3;
         s = die * per_die + local % per_die;
         rb = local / per_die;
     } else {
-        s = blockIdx.x / a.RB;
-        rb = blockIdx.x % a.RB;
+        s = bid / a.RB;
+        rb = bid % a.RB;
     }
     const int wg = s * a.RB + rb;  // index into the packed tables
     const uint2 *gtab = reinterpret_cast<const uint2 *>(a.data + a.group_off);
@@ -296,10 +296,25 @@ __global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) {
     }
 }
 
+__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body(a, blockIdx.x); }
+
+// Several independent problems in one launch (blockIdx.y picks the problem): the fixed latencies of a
+// launch (ramp-up, first touches of tables and atoms, drain) are paid once for all of them, and
+// workgroups of different problems share a CU.
+constexpr int kPackMaxBatch = 4;
+struct PackedBatch {
+    PackedArgs a[kPackMaxBatch];
+};
+__global__ __launch_bounds__(1024) void gemv_packed_batch_kernel(PackedBatch b) {
+    const PackedArgs &a = b.a[blockIdx.y];
+    if ((int)blockIdx.x >= a.S * a.RB) return;
+    gemv_packed_body(a, blockIdx.x);
+}
+
 // y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.
-__global__ __launch_bounds__(256) void gemv_packed_finalize_kernel(const float *__restrict__ partial,
-                                                                  const half_t *__restrict__ scale,
-                                                                  half_t *__restrict__ y, int N, int S) {
+__device__ __forceinline__ void gemv_packed_finalize_body(const float *__restrict__ partial,
+                                                          const half_t *__restrict__ scale, half_t *__restrict__ y,
+                                                          int N, int S) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
     float v[kPackMaxSlices];
@@ -309,6 +324,15 @@ __global__ __launch_bounds__(256) void gemv_packed_finalize_kernel(const float *
 #pragma unroll
     for (int k = 0; k < kPackMaxSlices; ++k) sum += k < S ? v[k] : 0.f;
     y[n] = (half_t)(sum * (scale ? (float)scale[n] : 1.f));
+}
+__global__ __launch_bounds__(256) void gemv_packed_finalize_kernel(const float *__restrict__ partial,
+                                                                  const half_t *__restrict__ scale,
+                                                                  half_t *__restrict__ y, int N, int S) {
+    gemv_packed_finalize_body(partial, scale, y, N, S);
+}
+__global__ __launch_bounds__(256) void gemv_packed_finalize_batch_kernel(PackedBatch b) {
+    const PackedArgs &a = b.a[blockIdx.y];
+    gemv_packed_finalize_body(a.partial, a.scale, a.y, a.N, a.S);
 }
 
 bool gemv_uses_pack(const vq_weight_t *w, int bs) {
@@ -331,16 +355,25 @@ int check_pack(const vq_weight_t *w) {
     return VQ_OK;
 }
 
-int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, hipStream_t s) {
+namespace {
+
+struct PackedLaunch {
+    PackedArgs a;
+    int grid, waves;
+    size_t lds;
+};
+
+PackedLaunch packed_launch(const vq_weight_t *w, const void *x, void *y, void *partial) {
     const vq_gemv_pack_t *p = w->gemv_pack;
     PackPlan plan = pack_plan(w);
-    PackedArgs a;
+    PackedLaunch l;
+    PackedArgs &a = l.a;
     a.data = (const unsigned char *)p->data;
     a.cb = (const half_t *)w->codebooks;
     a.scale = (const half_t *)w->scale;
     a.x = (const half_t *)x;
     a.y = (half_t *)y;
-    a.partial = (float *)ws;
+    a.partial = (float *)partial;
     a.N = w->N;
     a.J = w->K / 8;
     a.S = (int)p->S;
@@ -352,17 +385,59 @@ int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, h
     a.rowid_off = p->rowid_off;
     a.atom_off = p->atom_off;
     int groups_per_wg = (int)((p->rows_per_block + 63) / 64);
-    size_t lds = (size_t)plan.slice_entries * 16 + (size_t)a.J * 16 + (size_t)groups_per_wg * 64 * sizeof(float);
-    int waves = groups_per_wg < 16 ? groups_per_wg : 16;
-    if (waves < 8) waves = 8;   // at least 512 threads, so that slice and x are staged with every load in flight
-    static size_t attr_lds = 0;
-    if (lds > 64 * 1024 && lds > attr_lds) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_packed_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_lds = lds;
+    l.lds = (size_t)plan.slice_entries * 16 + (size_t)a.J * 16 + (size_t)groups_per_wg * 64 * sizeof(float);
+    l.waves = groups_per_wg < 16 ? groups_per_wg : 16;
+    if (l.waves < 8) l.waves = 8;   // at least 512 threads, so that slice and x are staged with many loads in flight
+    l.grid = (int)(p->S * p->RB);
+    return l;
+}
+
+void packed_lds_attr(const void *kernel, size_t lds, size_t *set) {
+    if (lds > 64 * 1024 && lds > *set) {
+        (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        *set = lds;
     }
-    gemv_packed_kernel<<<(int)(p->S * p->RB), waves * 64, lds, s>>>(a);
-    gemv_packed_finalize_kernel<<<(a.N + 255) / 256, 256, 0, s>>>(a.partial, a.scale, a.y, a.N, a.S);
+}
+
+}  // namespace
+
+int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, hipStream_t s) {
+    PackedLaunch l = packed_launch(w, x, y, ws);
+    static size_t attr_lds = 0;
+    packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_kernel), l.lds, &attr_lds);
+    gemv_packed_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
+    gemv_packed_finalize_kernel<<<(l.a.N + 255) / 256, 256, 0, s>>>(l.a.partial, l.a.scale, l.a.y, l.a.N, l.a.S);
+    return launch_status();
+}
+
+// Partial sums of the problems of a batch lie back to back in the workspace, each 256-byte aligned.
+size_t gemv_packed_batch_workspace(const vq_weight_t *const *w, int count) {
+    size_t total = 0;
+    for (int i = 0; i < count; ++i) total += (gemv_packed_workspace(w[i]) + 255) & ~(size_t)255;
+    return total;
+}
+
+int launch_gemv_packed_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, void *ws,
+                             hipStream_t s) {
+    PackedBatch b;
+    int grid = 0, waves = 0, max_n = 0;
+    size_t lds = 0, off = 0;
+    for (int i = 0; i < kPackMaxBatch; ++i) {
+        const int k = i < count ? i : 0;  // unused slots repeat problem 0 (never launched: grid.y = count)
+        PackedLaunch l = packed_launch(w[k], x[k], y[k], (unsigned char *)ws + (i < count ? off : 0));
+        b.a[i] = l.a;
+        if (i < count) {
+            off += (gemv_packed_workspace(w[i]) + 255) & ~(size_t)255;
+            grid = l.grid > grid ? l.grid : grid;
+            waves = l.waves > waves ? l.waves : waves;
+            lds = l.lds > lds ? l.lds : lds;
+            max_n = l.a.N > max_n ? l.a.N : max_n;
+        }
+    }
+    static size_t attr_lds = 0;
+    packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_batch_kernel), lds, &attr_lds);
+    gemv_packed_batch_kernel<<<dim3(grid, count), waves * 64, lds, s>>>(b);
+    gemv_packed_finalize_batch_kernel<<<dim3((max_n + 255) / 256, count), 256, 0, s>>>(b);
     return launch_status();
 }
 

@@ -7,8 +7,8 @@
 `traffic` expects two counter runs of `bench.py --pmc-probe` (one with FETCH_SIZE, one with
 WRITE_SIZE; both counters are in KiB per dispatch).  The probe run starts with plain copies of
 a known size; the ratio counter / known bytes of those copies is the calibration factor every
-other reading is divided by.  The vq_gemv figure is the sum over the kernels of one call
-(main kernel + finalize), averaged over all calls of the pass.
+other reading is divided by.  The per-launch figure is the sum over all gemv kernels of the
+pass (main kernels + their reduction kernels) divided by the number of main-kernel dispatches.
 """
 from __future__ import annotations
 
@@ -53,21 +53,22 @@ def traffic(args):
     copy_name = next(k for k in fetch if "probe_copy" in k)
     f_cal = sum(fetch[copy_name]) / len(fetch[copy_name]) / args.copy_bytes
     w_cal = sum(write[copy_name]) / len(write[copy_name]) / args.copy_bytes
-    main = next(k for k in fetch if "gemv_packed_kernel" in k)
-    fin = next(k for k in fetch if "gemv_packed_finalize" in k)
-    n = len(fetch[main])
-    rd = (sum(fetch[main]) + sum(fetch[fin])) / n / f_cal
-    wr = (sum(write[main]) + sum(write[fin])) / n / w_cal
+    kernels = sorted(k for k in fetch if "gemv_packed" in k)
+    mains = [k for k in kernels if "finalize" not in k]         # one dispatch of these per launch of the stack
+    n = sum(len(fetch[k]) for k in mains)
+    rd = sum(sum(fetch[k]) for k in kernels) / n / f_cal
+    wr = sum(sum(write[k]) for k in kernels) / n / w_cal
     with open(args.out, "w") as f:
-        f.write("# HBM traffic of vq_gemv on the C2 stack (rocprofv3 --pmc)\n\ncommands (one run per counter):\n`%s`\n\n"
+        f.write("# HBM traffic of the vq_gemv launches of the C2 stack (rocprofv3 --pmc)\n\ncommands (one run per counter):\n`%s`\n\n"
                 % args.cmd)
         f.write("Calibration on vq_probe_copy of %d bytes: FETCH_SIZE reads %.4f x, WRITE_SIZE %.4f x the known size.\n"
                 "Readings below are divided by these factors.\n\n" % (args.copy_bytes, f_cal, w_cal))
         f.write("| kernel | dispatches | read bytes / dispatch | written bytes / dispatch |\n|---|---|---|---|\n")
-        for k in (main, fin):
+        for k in kernels:
             f.write("| %s | %d | %.0f | %.0f |\n" % (k, len(fetch[k]), sum(fetch[k]) / len(fetch[k]) / f_cal,
                                                     sum(write[k]) / len(write[k]) / w_cal))
-        f.write("\nper vq_gemv call (both kernels), average over %d calls of the 32-block stack:\n\n" % n)
+        f.write("\nper launch (a vq_gemv or vq_gemv_batch call: main kernel + its reduction kernel), average over the "
+                "%d launches of one pass over the 32-block stack:\n\n" % n)
         f.write("read_bytes_per_launch: %.0f\nwritten_bytes_per_launch: %.0f\ntraffic_bytes_per_launch: %.0f\n"
                 % (rd, wr, rd + wr))
 

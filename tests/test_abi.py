@@ -169,6 +169,29 @@ def test_packed_gemv_validation():
     assert lib.vq_gemv_prepack_bytes(ctypes.byref(hd)) == 0
 
 
+def test_gemv_batch_validation():
+    lib = vq.lib()
+    WP = ctypes.POINTER(vq_weight_t)
+    d = weight()
+    def batch(ws_list, xs, ys, count=None, ws=None, ws_bytes=0):
+        n = len(ws_list)
+        wa = (WP * n)(*[ctypes.pointer(w) if w is not None else WP() for w in ws_list])
+        xa = (ctypes.c_void_p * n)(*xs)
+        ya = (ctypes.c_void_p * n)(*ys)
+        return lib.vq_gemv_batch(wa, xa, ya, n if count is None else count, ws, ws_bytes, None)
+    assert lib.vq_gemv_batch(None, None, None, 1, None, 0, None) == VQ_ERR_NULL
+    assert batch([d], [P], [P], count=0) == VQ_ERR_SHAPE
+    assert batch([d] * 5, [P] * 5, [P] * 5) == VQ_ERR_SHAPE             # more than VQ_GEMV_BATCH_MAX
+    assert batch([d, None], [P, P], [P, P]) == VQ_ERR_NULL
+    assert batch([d, d], [P, None], [P, P]) == VQ_ERR_NULL
+    assert batch([d, d], [P, P], [P, P + 2]) == VQ_ERR_ALIGN
+    assert batch([d, weight(K=100)], [P, P], [P, P]) == VQ_ERR_SHAPE    # every member is validated
+    wa = (WP * 2)(ctypes.pointer(d), ctypes.pointer(d))
+    assert lib.vq_gemv_batch_workspace(wa, 2) == 0                      # canonical codes, LDS codebook: no scratch
+    assert lib.vq_gemv_batch_workspace(wa, 9) == 0
+    assert batch([weight(N=0)], [P], [P]) == 0                          # nothing to do, nothing launched
+
+
 def test_probe_argument_validation():
     lib = vq.lib()
     assert lib.vq_probe_copy(None, P, 16, None) == VQ_ERR_NULL

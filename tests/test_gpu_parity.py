@@ -168,6 +168,31 @@ def test_gemv_packed_shapes_and_edges(gpu_device, N, K, E, scale, zipf):
                  f"packed {N}x{K} E{E}")
 
 
+def test_gemv_batch_matches_single_calls_and_oracle(gpu_device):
+    # query/key/value-like: three matrices, one input; then a mixed batch (different K, one member without a
+    # pack, one with an LDS-sized codebook) that takes the one-launch-per-problem route
+    x = wl.make_activations(1, 1024, 31)
+    xd = dev_x(x, gpu_device)
+    ws3 = [wl.make_weight(N, 1024, 8, 16, 1, 65536, 0.02, seed=7300 + i) for i, N in enumerate((768, 768, 300))]
+    wds = [vq.weight_to_device(w, gpu_device, prepack=True, keep_codes=False) for w in ws3]
+    ys = vq.vq_gemv_batch(wds, [xd, xd, xd])
+    again = vq.vq_gemv_batch(wds, [xd, xd, xd])
+    torch.cuda.synchronize()
+    for w, wd, y, y2 in zip(ws3, wds, ys, again):
+        assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), "batch member")
+        assert torch.equal(y, vq.vq_gemv(wd, xd))          # same arithmetic as the single call
+        assert torch.equal(y, y2)
+    x2 = wl.make_activations(1, 512, 32)
+    x2d = dev_x(x2, gpu_device)
+    wa = wl.make_weight(200, 512, 8, 16, 1, 65536, 0.02, seed=7310)
+    wb = wl.make_weight(130, 512, 8, 8, 2, 256, 0.01, seed=7311)
+    mixed = [wds[0], vq.weight_to_device(wa, gpu_device), vq.weight_to_device(wb, gpu_device)]
+    ys = vq.vq_gemv_batch(mixed, [xd, x2d, x2d])
+    torch.cuda.synchronize()
+    for w, xx, y in zip((ws3[0], wa, wb), (x, x2, x2), ys):
+        assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, xx), "mixed batch member")
+
+
 def test_gemv_packed_shared_workspace_determinism_and_canonical_agreement(gpu_device):
     # three layers of different shapes share one workspace, called back to back, twice
     ws_bytes, layers = 0, []
