@@ -174,7 +174,8 @@ struct PackedArgs {
 };
 
 constexpr int kPackMaxSlices = 32;  // 2^16 entries / 2048 per slice
-constexpr int kPackPrefetch = 10;  // 4-atom steps held in registers while the slice is being staged
+constexpr int kPackPrefetch = 10;      // 4-atom steps fetched into registers while the slice is being staged
+constexpr int kPackPrefetchBatch = 4;  // batch kernel: a ring of 4 steps in flight (80 registers, three workgroups per CU)
 
 __device__ __forceinline__ float atom_dot(uint32_t atom, const unsigned char *slice, const unsigned char *xl, float acc) {
     V16 e = *reinterpret_cast<const V16 *>(slice + ((atom & 0xfffu) << 4));
@@ -200,6 +201,7 @@ __device__ __forceinline__ void step_dot(uint32_t d0, uint32_t d1, uint32_t d2, 
 
 // All global loads of a workgroup are issued before anything waits: the kernel is a chain of
 // memory latencies (tables -> atoms -> partials), not a bandwidth problem, at these sizes.
+template <int PF, bool RING>
 __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int bid) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *slice = smem;                                    // slice_entries * 16 bytes
@@ -247,9 +249,18 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int 
         gr = gtab[first_group + wave];
         ri = rowids[((size_t)first_group + wave) * 64 + lane];
     }
-    uint32_t q[kPackPrefetch][3];
+    // atoms of steps 0 .. PF-1 of that group into a ring of registers
+    uint32_t q[PF][3];
+    auto load_step = [&](uint32_t (&dst)[3], uint32_t first, uint32_t st, uint32_t steps) {
+        if (st < steps) {
+            const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)first + st) * 768);
+            dst[0] = p[0]; dst[1] = p[1]; dst[2] = p[2];
+        } else {
+            dst[0] = dst[1] = dst[2] = 0;
+        }
+    };
 #pragma unroll
-    for (int st = 0; st < kPackPrefetch; ++st) {
+    for (int st = 0; st < PF; ++st) {
         if ((uint32_t)st < gr.y) {
             const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768);
             q[st][0] = p[0]; q[st][1] = p[1]; q[st][2] = p[2];
@@ -264,21 +275,40 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int 
 
     // (4) gathers and dot products: lane = row; results go to LDS in natural row order
     for (uint32_t g = wave; g < n_groups; g += nwaves) {
-        if (g != (uint32_t)wave) {  // later groups of this wavefront: load as we go
+        if (g != (uint32_t)wave) {  // later groups of this wavefront (only when a block has more than 16 groups)
             gr = gtab[first_group + g];
             ri = rowids[((size_t)first_group + g) * 64 + lane];
+            if constexpr (RING) {
+#pragma unroll
+                for (int k = 0; k < PF; ++k) load_step(q[k], gr.x, k, gr.y);
+            }
         }
         Acc4 acc = {0.f, 0.f, 0.f, 0.f};
-        uint32_t st0 = 0;
-        if (g == (uint32_t)wave) {
+        if constexpr (RING) {
+            // the ring always holds the next PF steps: slot k is refilled with step st + PF as soon as
+            // step st has been taken out of it
+            for (uint32_t base = 0; base < gr.y; base += PF) {
 #pragma unroll
-            for (int st = 0; st < kPackPrefetch; ++st)
-                if ((uint32_t)st < gr.y) step_dot(q[st][0], q[st][1], q[st][2], slice, xl, acc);
-            st0 = kPackPrefetch;
-        }
-        for (uint32_t st = st0; st < gr.y; ++st) {
-            const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768);
-            step_dot(p[0], p[1], p[2], slice, xl, acc);
+                for (int k = 0; k < PF; ++k) {
+                    const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
+                    load_step(q[k], gr.x, base + k + PF, gr.y);
+                    if (base + k < gr.y) step_dot(d0, d1, d2, slice, xl, acc);
+                }
+            }
+        } else {
+            // the first PF steps of the wavefront's first group are in registers (the whole group for the
+            // shapes this was tuned on); everything else is loaded as it goes
+            uint32_t st0 = 0;
+            if (g == (uint32_t)wave) {
+#pragma unroll
+                for (int st = 0; st < PF; ++st)
+                    if ((uint32_t)st < gr.y) step_dot(q[st][0], q[st][1], q[st][2], slice, xl, acc);
+                st0 = PF;
+            }
+            for (uint32_t st = st0; st < gr.y; ++st) {
+                const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768);
+                step_dot(p[0], p[1], p[2], slice, xl, acc);
+            }
         }
         if (ri != 0xFFFFu) accbuf[ri] = (acc.a0 + acc.a1) + (acc.a2 + acc.a3);
     }
@@ -296,7 +326,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int 
     }
 }
 
-__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body(a, blockIdx.x); }
+__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body<kPackPrefetch, false>(a, blockIdx.x); }
 
 // Several independent problems in one launch (blockIdx.y picks the problem): the fixed latencies of a
 // launch (ramp-up, first touches of tables and atoms, drain) are paid once for all of them, and
@@ -305,10 +335,10 @@ constexpr int kPackMaxBatch = 4;
 struct PackedBatch {
     PackedArgs a[kPackMaxBatch];
 };
-__global__ __launch_bounds__(1024) void gemv_packed_batch_kernel(PackedBatch b) {
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void gemv_packed_batch_kernel(PackedBatch b) {
     const PackedArgs &a = b.a[blockIdx.y];
     if ((int)blockIdx.x >= a.S * a.RB) return;
-    gemv_packed_body(a, blockIdx.x);
+    gemv_packed_body<kPackPrefetchBatch, true>(a, blockIdx.x);
 }
 
 // y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.
