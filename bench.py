@@ -44,7 +44,7 @@ def parse():
     ap.add_argument("--no-batch", action="store_true",
                     help="one vq_gemv call per matrix (224 launches) instead of vq_gemv_batch for the projections of "
                          "a block that share their input (query/key/value; gate/up)")
-    ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add")
+    ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add,zipf")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter run (wrap in rocprofv3 --pmc FETCH_SIZE or WRITE_SIZE): three plain copies of "
                          "known size as calibration, then one eager pass over the headline gemv stack; no timing")
@@ -343,6 +343,38 @@ def main():
             del wds
             torch.cuda.empty_cache()
         result["gemv_additive_2x256x8"] = add
+
+    # ------------------------------------------------------------------ secondary: skewed code usage (Zipf, s = 1)
+    if want("zipf") and not args.skip_secondary:
+        zipf = {}
+        N, K = wl.LLAMA7B_SHAPES[0]
+        n_copies = 24
+        x = torch.from_numpy(wl.make_activations(1, K, wl.seed_for(2, K))).to(dev)
+        y = torch.empty((1, N), dtype=torch.float16, device=dev)
+        ws = vq.new_workspace(4 << 20, dev)
+        variants = {"canonical_entries_in_quantizer_order": [], "canonical_reordered_by_frequency": [],
+                    "packed_entries_in_quantizer_order": [], "packed_reordered_by_frequency": []}
+        hot_frac = 0.0
+        for layer in range(n_copies):
+            w = wl.shuffle_entries(wl.make_weight(N, K, 8, 16, 1, 65536, 0.02, wl.seed_for(6, layer), zipf_s=1.0),
+                                   seed=layer)
+            r = vq.vq_reorder_by_frequency(w)
+            hot_frac += float((r.codes < 4096).mean()) / n_copies
+            variants["canonical_entries_in_quantizer_order"].append(GemvCall(vq.weight_to_device(w, dev), x, y))
+            variants["canonical_reordered_by_frequency"].append(GemvCall(vq.weight_to_device(r, dev), x, y))
+            variants["packed_entries_in_quantizer_order"].append(
+                GemvCall(vq.weight_to_device(w, dev, prepack=True, keep_codes=False), x, y, ws))
+            variants["packed_reordered_by_frequency"].append(
+                GemvCall(vq.weight_to_device(r, dev, prepack=True, keep_codes=False), x, y, ws))
+        for name, cs in variants.items():
+            def loop(cs=cs):
+                for c in cs:
+                    c()
+            zipf[name + "_us"] = round(timed(loop, 5, 1) * 1e3 / n_copies, 2)
+        zipf["codes_served_by_the_4096_entry_lds_cache"] = round(hot_frac, 3)
+        result["gemv_zipf_s1_4096x4096"] = zipf
+        del variants
+        torch.cuda.empty_cache()
 
     result["setup_plus_run_s"] = round(time.time() - t_setup, 1)
     print(json.dumps(result), flush=True)

@@ -84,6 +84,8 @@ typedef struct vq_weight_t {
     const void *codebooks; /* device, fp16 [R][E][v] */
     const void *scale;     /* device, fp16 [N] per output channel, or NULL (= 1) */
     const vq_gemv_pack_t *gemv_pack; /* host pointer, optional: re-tiled codes for vq_gemv with bs = 1 */
+    int hot_entries;       /* 0, or (after vq_reorder_by_frequency) how many leading entries serve half of
+                              the codes: lets vq_gemv keep the hot front of a large codebook in LDS */
 } vq_weight_t;
 
 /*
@@ -112,6 +114,25 @@ size_t vq_gemv_workspace(const vq_weight_t *w, int bs);
  */
 size_t vq_gemv_prepack_bytes(const vq_weight_t *w_host);
 int vq_gemv_prepack(const vq_weight_t *w_host, void *out_host, size_t out_bytes, vq_gemv_pack_t *pack);
+
+/*
+ * Offline frequency reordering of the codebook entries of one weight (Sec. V-B: entries are used very
+ * unevenly; the hot ones belong at the front, where a kernel's on-chip cache of the first entries finds
+ * them).  HOST function, no GPU: w_host->codes and w_host->codebooks are HOST memory.  For every
+ * codebook r the entries are sorted by descending number of codes that point at them (ties keep their
+ * order) and the codes are rewritten to follow, so the dequantized weight is bit-identical.
+ *   codes_out_host:     same type and shape as w_host->codes (may be the same buffer)
+ *   codebooks_out_host: fp16 [R][E][v] (must NOT be w_host->codebooks)
+ *   hot_entries_out:    optional; the smallest n such that the first n entries of every codebook serve
+ *                       at least half of its codes (the paper sets its cache boundaries from the same
+ *                       offline histogram).  Put it into vq_weight_t.hot_entries of the reordered weight:
+ *                       when a single codebook is too large for LDS and hot_entries fits the on-chip
+ *                       cache (4096 entries of v = 8), vq_gemv on canonical codes keeps the front of the
+ *                       codebook in LDS and gathers only the rest from L2.  Results never depend on it.
+ * Errors: NULL / SHAPE (a code >= n_entries, or output aliasing the input codebooks) / UNSUPPORTED.
+ */
+int vq_reorder_by_frequency(const vq_weight_t *w_host, void *codes_out_host, void *codebooks_out_host,
+                            int *hot_entries_out);
 
 /*
  * Several independent bs = 1 VQ-gemv problems y_i = W_i x_i in one call (count <= VQ_GEMV_BATCH_MAX):

@@ -35,7 +35,7 @@ class vq_weight_t(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int), ("K", ctypes.c_int), ("v", ctypes.c_int), ("code_bits", ctypes.c_int),
                 ("n_codebooks", ctypes.c_int), ("n_entries", ctypes.c_int),
                 ("codes", ctypes.c_void_p), ("codebooks", ctypes.c_void_p), ("scale", ctypes.c_void_p),
-                ("gemv_pack", ctypes.POINTER(vq_gemv_pack_t))]
+                ("gemv_pack", ctypes.POINTER(vq_gemv_pack_t)), ("hot_entries", ctypes.c_int)]
 
 
 class vq_kv_t(ctypes.Structure):
@@ -53,6 +53,8 @@ SYMBOLS = {
     "vq_gemv": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "vq_gemv_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t), ctypes.c_int]),
+    "vq_reorder_by_frequency": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.POINTER(ctypes.c_int)]),
     "vq_gemv_batch": (ctypes.c_int, [ctypes.POINTER(ctypes.POINTER(vq_weight_t)), ctypes.POINTER(ctypes.c_void_p),
                                      ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p,
                                      ctypes.c_size_t, ctypes.c_void_p]),
@@ -122,13 +124,14 @@ class VQWeightDev:
     scale: Optional[torch.Tensor]
     pack_data: Optional[torch.Tensor] = None     # device copy of the vq_gemv_prepack buffer
     pack: Optional[vq_gemv_pack_t] = None        # its descriptor (data already points at pack_data)
+    hot_entries: int = 0                         # from vq_reorder_by_frequency (0: entries in no particular order)
 
     def desc(self, use_pack: bool = True) -> vq_weight_t:
         R, E, v = self.codebooks.shape
         code_dt = torch.uint8 if self.code_bits == 8 else torch.uint16
         d = vq_weight_t(self.N, self.K, self.v, self.code_bits, R, E,
                         _dev(self.codes, "codes", code_dt), _dev(self.codebooks, "codebooks", torch.float16),
-                        _dev(self.scale, "scale", torch.float16), None)
+                        _dev(self.scale, "scale", torch.float16), None, int(self.hot_entries))
         if use_pack and self.pack is not None:
             d.gemv_pack = ctypes.pointer(self.pack)
         return d
@@ -178,6 +181,26 @@ def vq_gemv_prepack(w):
     return out, pack
 
 
+def vq_reorder_by_frequency(w):
+    """Offline frequency reordering of a host ``workloads.VQWeight`` (host only, no GPU).
+
+    Returns a new VQWeight with the same dequantized values whose codebook entries are sorted by
+    descending use; its ``hot_entries`` is the number of leading entries that serve half of the codes.
+    """
+    import numpy as np
+    from .workloads import VQWeight
+    codes = np.ascontiguousarray(w.codes)
+    cb = np.ascontiguousarray(w.codebooks)
+    d = vq_weight_t(w.N, w.K, w.v, w.code_bits, int(cb.shape[0]), int(cb.shape[1]),
+                    codes.ctypes.data, cb.ctypes.data, None, None)
+    codes_out = np.empty_like(codes)
+    cb_out = np.empty_like(cb)
+    hot = ctypes.c_int(0)
+    _check(lib().vq_reorder_by_frequency(ctypes.byref(d), codes_out.ctypes.data, cb_out.ctypes.data,
+                                         ctypes.byref(hot)), "vq_reorder_by_frequency")
+    return VQWeight(w.N, w.K, w.v, w.code_bits, codes_out, cb_out, w.scale, hot_entries=int(hot.value))
+
+
 def weight_to_device(w, device="cuda:0", prepack: bool = False, keep_codes: bool = True) -> VQWeightDev:
     """Upload a host ``workloads.VQWeight`` (numpy) to the GPU; ``prepack`` adds the re-tiled gemv codes."""
     import numpy as np
@@ -186,7 +209,7 @@ def weight_to_device(w, device="cuda:0", prepack: bool = False, keep_codes: bool
         codes = torch.from_numpy(w.codes.view(np.uint8 if w.code_bits == 8 else np.uint16)).to(device)
     cb = torch.from_numpy(w.codebooks).to(device)
     sc = None if w.scale is None else torch.from_numpy(w.scale).to(device)
-    wd = VQWeightDev(w.N, w.K, w.v, w.code_bits, codes, cb, sc)
+    wd = VQWeightDev(w.N, w.K, w.v, w.code_bits, codes, cb, sc, hot_entries=int(getattr(w, "hot_entries", 0)))
     if prepack:
         buf, pack = vq_gemv_prepack(w)
         if buf is None:

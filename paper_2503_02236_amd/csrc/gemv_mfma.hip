@@ -27,6 +27,7 @@ struct GemvMfmaArgs {
     const half_t *cb, *scale, *x;
     half_t *y;
     int N, K, J, E, bs, nit;
+    int n_hot;  // entries of each codebook held in LDS (all of them unless HOT)
 };
 
 // One code load per lane and iteration: 16 bytes, or 8 for single uint8 codes (16 positions would need
@@ -37,7 +38,11 @@ struct GemvMfmaShape {
     static constexpr int CPL = LB / (R * (int)sizeof(CodeT));
 };
 
-template <typename CodeT, int V, int R>
+// HOT: the codebook does not fit LDS.  Its first n_hot entries are cached there and the rest is gathered
+// from global memory (L2): the shared-memory level of the hierarchical codebook cache of Sec. V-B.  It
+// pays off when the entries have been reordered by frequency (vq_reorder_by_frequency), so that most
+// codes are small; with uniformly used entries nearly every lookup takes the L2 path.
+template <typename CodeT, int V, int R, bool HOT>
 __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
     constexpr int LB = GemvMfmaShape<CodeT, R>::LB;     // bytes of codes per lane and iteration
     constexpr int CPL = GemvMfmaShape<CodeT, R>::CPL;   // sub-vector positions per code load
@@ -46,7 +51,7 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
     static_assert(CPL * R * sizeof(CodeT) == LB && MPI >= 1, "unsupported code width");
     extern __shared__ __align__(16) unsigned char smem[];
     half_t *cbl = reinterpret_cast<half_t *>(smem);                      // [R][E][V]
-    const int cb_bytes = R * a.E * V * 2;
+    const int cb_bytes = R * a.n_hot * V * 2;
     float4v_t *red = reinterpret_cast<float4v_t *>(smem + ((cb_bytes + 15) & ~15));  // [waves][64]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nwaves = blockDim.x >> 6;
@@ -83,6 +88,7 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
     half8_t xb[MPI];
     load_iter(wave, cd, xb);
 
+    // all codebooks, or (HOT, one codebook) its first n_hot entries
     for (int i = tid; i < cb_bytes / 16; i += blockDim.x)
         reinterpret_cast<uint4 *>(cbl)[i] = reinterpret_cast<const uint4 *>(a.cb)[i];
     __syncthreads();
@@ -101,9 +107,32 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
 #pragma unroll
                 for (int rr = 0; rr < R; ++rr) {
                     const unsigned code = sizeof(CodeT) == 1 ? cd.b[c * R + rr] : cd.h[c * R + rr];
-                    const half_t *e = cbl + ((size_t)rr * a.E + code) * V;
+                    // the entry: from the LDS copy, or (cold entry of a partly cached codebook) from L2.  The two
+                    // loads are kept apart by their address spaces, so neither becomes a generic-pointer load
+                    V16 ev;
+                    ev.u = make_uint4(0, 0, 0, 0);
+                    typedef unsigned raw4_t __attribute__((ext_vector_type(4)));
+                    typedef unsigned raw2_t __attribute__((ext_vector_type(2)));
+                    const half_t *le = cbl + ((size_t)rr * a.n_hot + code) * V;
+                    const half_t *ge = a.cb + ((size_t)rr * a.E + code) * V;
+                    if (!HOT || code < (unsigned)a.n_hot) {
+                        if (V == 8) {
+                            const raw4_t t = *(const __attribute__((address_space(3))) raw4_t *)le;
+                            ev.w[0] = t.x; ev.w[1] = t.y; ev.w[2] = t.z; ev.w[3] = t.w;
+                        } else {
+                            const raw2_t t = *(const __attribute__((address_space(3))) raw2_t *)le;
+                            ev.w[0] = t.x; ev.w[1] = t.y;
+                        }
+                    } else {
+                        if (V == 8) {
+                            const raw4_t t = *(const __attribute__((address_space(1))) raw4_t *)ge;
+                            ev.w[0] = t.x; ev.w[1] = t.y; ev.w[2] = t.z; ev.w[3] = t.w;
+                        } else {
+                            const raw2_t t = *(const __attribute__((address_space(1))) raw2_t *)ge;
+                            ev.w[0] = t.x; ev.w[1] = t.y;
+                        }
+                    }
                     if (V == 8) {
-                        V16 ev = ld16(e);
                         if (rr == 0) {
                             op = ev;
                         } else {
@@ -111,7 +140,6 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
                             for (int q = 0; q < 4; ++q) op.h2[q] += ev.h2[q];
                         }
                     } else {
-                        V8 ev = ld8(e);
                         if (rr == 0) {
                             op.h2[2 * h] = ev.h2[0];
                             op.h2[2 * h + 1] = ev.h2[1];
@@ -154,7 +182,10 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
 
 namespace {
 
-template <typename CodeT, int V, int R>
+constexpr size_t kGemvMfmaLdsCodebook = 48 * 1024;  // whole codebooks up to this size live in LDS
+constexpr int kGemvMfmaHotEntries8 = 4096;           // v = 8 entries of a larger codebook cached in LDS (64 KiB)
+
+template <typename CodeT, int V, int R, bool HOT>
 int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s) {
     constexpr int CPL = GemvMfmaShape<CodeT, R>::CPL;
     GemvMfmaArgs a;
@@ -177,25 +208,39 @@ int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s)
     while (waves > 4 && n_wg * waves > 4096) waves >>= 1;
     if (waves > a.nit) waves = a.nit;
     if (waves < 1) waves = 1;
-    const size_t cb_bytes = (size_t)R * a.E * V * 2;
+    // hot prefix: 64 KiB of entries with one workgroup per CU, 32 KiB when several share a CU
+    a.n_hot = a.E;
+    if (HOT) {
+        const int cap = (n_wg <= 256 ? 64 * 1024 : 32 * 1024) / (V * 2);
+        a.n_hot = a.E < cap ? a.E : cap;
+    }
+    const size_t cb_bytes = (size_t)R * a.n_hot * V * 2;
     const size_t lds = ((cb_bytes + 15) & ~(size_t)15) + (size_t)waves * 64 * sizeof(float4v_t);
-    gemv_mfma_kernel<CodeT, V, R><<<(a.N + 15) / 16, waves * 64, lds, s>>>(a);
+    static size_t attr_lds = 0;
+    if (lds > 64 * 1024 && lds > attr_lds) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_mfma_kernel<CodeT, V, R, HOT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_lds = lds;
+    }
+    gemv_mfma_kernel<CodeT, V, R, HOT><<<n_wg, waves * 64, lds, s>>>(a);
     return launch_status();
 }
 
 template <typename CodeT, int V>
 int by_r(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s) {
+    const bool hot = (size_t)w->n_codebooks * w->n_entries * w->v * 2 > kGemvMfmaLdsCodebook;
+    if (hot) return run<CodeT, V, 1, true>(w, x, bs, y, s);  // only single codebooks are cached partly
     switch (w->n_codebooks) {
-        case 1: return run<CodeT, V, 1>(w, x, bs, y, s);
-        case 2: return run<CodeT, V, 2>(w, x, bs, y, s);
-        default: return run<CodeT, V, 4>(w, x, bs, y, s);
+        case 1: return run<CodeT, V, 1, false>(w, x, bs, y, s);
+        case 2: return run<CodeT, V, 2, false>(w, x, bs, y, s);
+        default: return run<CodeT, V, 4, false>(w, x, bs, y, s);
     }
 }
 
 }  // namespace
 
-// Codebooks must fit the default LDS window next to the reduction buffer, and a row of codes must be
-// a whole number of 16-byte words made of whole sub-vector positions.
+// Codebooks must fit LDS next to the reduction buffer (a single larger codebook is cached partly), and a
+// row of codes must be a whole number of code words made of whole sub-vector positions.
 bool gemv_mfma_supported(const vq_weight_t *w) {
     const int R = w->n_codebooks, sz = w->code_bits / 8;
     if (w->v != 8 && w->v != 4) return false;
@@ -204,7 +249,10 @@ bool gemv_mfma_supported(const vq_weight_t *w) {
     const int cpl = (R * sz == 1 ? 8 : 16) / (R * sz), cpo = 8 / w->v;
     if (cpl < cpo) return false;
     if (w->K <= 0 || (w->K / w->v) % cpl != 0) return false;
-    if ((size_t)R * w->n_entries * w->v * 2 > 48 * 1024) return false;
+    if ((size_t)R * w->n_entries * w->v * 2 > kGemvMfmaLdsCodebook) {
+        // a single large codebook is cached partly, if the caller says that its front is hot enough
+        if (R != 1 || w->hot_entries <= 0 || w->hot_entries > kGemvMfmaHotEntries8 * 8 / w->v) return false;
+    }
     if ((R * w->n_entries * w->v * 2) % 16 != 0) return false;
     return true;
 }

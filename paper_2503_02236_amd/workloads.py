@@ -46,6 +46,7 @@ class VQWeight:
     codes: np.ndarray          # uint8/uint16 [N][K/v][R]
     codebooks: np.ndarray      # float16 [R][E][v]
     scale: Optional[np.ndarray]  # float16 [N] or None
+    hot_entries: int = 0       # set by the frequency reordering tool: leading entries that serve half of the codes
 
     @property
     def R(self) -> int:
@@ -88,6 +89,24 @@ def zipf_codes(rng: np.random.Generator, E: int, shape, s: float = 1.0) -> np.nd
     cdf = np.cumsum(p / p.sum())
     u = rng.random(size=shape)
     return np.minimum(np.searchsorted(cdf, u), E - 1)
+
+
+def shuffle_entries(w: "VQWeight", seed: int) -> "VQWeight":
+    """The same weight with every codebook's entries in a random order (codes rewritten to follow).
+
+    ``zipf_codes`` makes index 0 the hottest entry; a quantizer's codebook has no such order, so skewed
+    workloads are shuffled before anything that is supposed to find the hot entries sees them.
+    """
+    rng = _rng(seed ^ 0x5AFE)
+    codes = np.empty_like(w.codes)
+    cbs = np.empty_like(w.codebooks)
+    for r in range(w.R):
+        perm = rng.permutation(w.E)              # new position -> old entry
+        inv = np.empty(w.E, dtype=np.int64)
+        inv[perm] = np.arange(w.E)
+        cbs[r] = w.codebooks[r][perm]
+        codes[..., r] = inv[w.codes[..., r]].astype(w.codes.dtype)
+    return VQWeight(w.N, w.K, w.v, w.code_bits, codes, cbs, w.scale)
 
 
 def make_activations(M: int, K: int, seed: int) -> np.ndarray:

@@ -115,6 +115,20 @@ def test_gemv_shapes_and_edges(gpu_device, N, K, v, bits, R, E, bs, scale):
     assert_close(run_gemv(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x), f"{N}x{K} v{v} R{R} bs{bs}")
 
 
+@pytest.mark.parametrize("bs", [1, 5])
+def test_gemv_hot_entry_cache_on_reordered_zipf_codes(gpu_device, bs):
+    # skewed code usage, entries in arbitrary order, then sorted by use offline: the first entries are
+    # served from LDS, the rest from L2; both orders must give the oracle's result
+    w = wl.shuffle_entries(wl.make_weight(1000, 2048, 8, 16, 1, 65536, 0.02, seed=9100, zipf_s=1.0), seed=3)
+    r = vq.vq_reorder_by_frequency(w)
+    x = wl.make_activations(bs, 2048, 9101)
+    want = oracle.gemv(w.codes, w.codebooks, w.scale, x)
+    assert_close(run_gemv(w, x, gpu_device), want, "zipf shuffled")
+    assert_close(run_gemv(r, x, gpu_device), want, "zipf reordered")
+    assert 0 < r.hot_entries <= 4096                   # so the reordered weight takes the LDS-cached path
+    assert (r.codes < 4096).mean() > 0.6               # and the cache really serves most lookups
+
+
 def test_gemv_zipf_codes(gpu_device):
     w = wl.config2_layer(0, zipf_s=1.0)
     x = wl.make_activations(1, w.K, 5)
