@@ -131,7 +131,7 @@ __device__ __forceinline__ unsigned byte_shl(unsigned w, unsigned sh) {
 // constant that folds into the offset field of the LDS instruction.
 //
 // The lookups of a tile form one sequence of groups (per 16-token step: the lane's 32 K channels, later
-// its 32 V channels); the LDS gathers of group n+1 are issued before the arithmetic of group n, and the
+// its 32 V channels); the LDS gathers of group n+1 are written before the arithmetic of group n, and the
 // sequence continues across the K/V boundary and into the next tile, so the LDS queue never drains.
 template <int V, bool ONE>
 __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void attn_decode_kernel(AttnArgs a) {
@@ -264,13 +264,11 @@ __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu
                 gather(kc, s + 1, 0, eb[(s + 1) & 1]);
             else
                 gather(vc, 0, v_off, eb[NS & 1]);
-            __builtin_amdgcn_sched_barrier(0);  // keep the gathers of the next group ahead of this arithmetic
             float4_t c4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int i = 0; i < 4; ++i) c4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[i], eb[s & 1][i].h8, c4, 0, 0, 0);
             const float bias = (t_lane + it * TILE + s * 16 < end) ? 0.f : -INFINITY;
             sc[s] = __builtin_fmaf(c4[0], a.scale2, bias);
-            __builtin_amdgcn_sched_barrier(0);
         }
         load_codes(a.k_codes, it + 2, kc);  // the K codes of this tile are used up
 
@@ -294,13 +292,11 @@ __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu
                 gather(vc, s + 1, v_off, eb[(NS + s + 1) & 1]);
             else
                 gather(kn, 0, 0, eb[0]);  // first K group of the next tile (2 NS is even)
-            __builtin_amdgcn_sched_barrier(0);
             const float p_t = sc[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sc[s] - m_run);
             lsum += p_t;
             const V16 (&ev)[4] = eb[(NS + s) & 1];
 #pragma unroll
             for (int d = 0; d < 32; ++d) acc[d] += p_t * (float)ev[d / 8].h8[d % 8];
-            __builtin_amdgcn_sched_barrier(0);
         }
         load_codes(a.v_codes, it + 2, vc);
     };
