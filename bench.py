@@ -130,6 +130,24 @@ def main():
         del src, dst
         only = {"gemv"}
 
+    # ------------------------------------------------------------------ measured ceilings of this chip
+    # (second reference beside the vendor peaks): a plain 128-bit streaming read of 1 GiB, cold, and a
+    # register-resident fp16 MFMA loop
+    ceil_hbm = ceil_mfma = None
+    if not args.pmc_probe:
+        big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        big.fill_(1)
+        sink = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+        ms = timed(lambda: vq.vq_probe_read(big, sink), 10, 2)
+        ceil_hbm = big.numel() / ms / 1e6
+        del big
+        iters = 2000
+        ms = timed(lambda: vq.vq_probe_mfma(1024, iters, sink), 5, 1)
+        ceil_mfma = 1024 * 4 * iters * 8 * 32768.0 / (ms * 1e-3) / 1e12
+        result["measured_ceilings"] = {"hbm_stream_read_GBps": round(ceil_hbm, 1),
+                                       "mfma_fp16_register_loop_TFLOPs": round(ceil_mfma, 1)}
+        torch.cuda.empty_cache()
+
     # ------------------------------------------------------------------ headline: C2 gemv stack
     if want("gemv"):
         L = args.layers
@@ -242,6 +260,7 @@ def main():
                                       else "canonical [N][K/8] (entries gathered from L2)",
                        "timing": "hip-graph replay" if graph is not None else "eager launches"},
             "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
+            "pct_measured_stream_read": round(100 * gbps / ceil_hbm, 2),
             "gemv_per_shape_cold": shape_us,
             "roofline": {"bound": "hbm", "kernel": ("gemv_packed_batch_kernel / gemv_packed_kernel (+ finalize)" if batched else
                                     "gemv_packed_kernel (+ finalize)" if packed else "gemv_rows_kernel<uint16,8,1>"),
@@ -283,7 +302,8 @@ def main():
                 ms = timed(fn, 10, 2)
                 tf = 2.0 * 2048 * N * 4096 / (ms * 1e-3) / 1e12
                 gemm["N%d_v%d" % (N, v)] = {"us": round(ms * 1e3, 2), "TFLOPs": round(tf, 1),
-                                            "pct_mfma_fp16_peak": round(100 * tf / MFMA_FP16_PEAK_TFLOPS, 2)}
+                                            "pct_mfma_fp16_peak": round(100 * tf / MFMA_FP16_PEAK_TFLOPS, 2),
+                                            "pct_measured_mfma_loop": round(100 * tf / ceil_mfma, 2)}
                 del wd, Y
         result["gemm_prefill_M2048_K4096"] = gemm
 
@@ -303,7 +323,8 @@ def main():
         ms = timed(attn_loop, 10, 2) / len(ring)
         b = kv.effective_bytes()
         result["attn_decode_B16_H32_T4096"] = {"us": round(ms * 1e3, 2), "GBps": round(b / ms / 1e6, 1),
-                                               "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2)}
+                                               "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2),
+                                               "pct_measured_stream_read": round(100 * b / ms / 1e6 / ceil_hbm, 2)}
         del ring
         torch.cuda.empty_cache()
         # same shape with the coupled-quantization layout: 32 codebooks per head and side (64 KiB each)

@@ -214,6 +214,13 @@ int vq_kv_dequant(const vq_kv_t *kv, int which, void *out, void *stream);
  */
 int vq_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 int vq_probe_read(const void *src, size_t bytes, void *sink, void *stream);
+/*
+ * vq_probe_mfma: `workgroups` x 4 wavefronts, each running `iters` x 8 back-to-back register-resident
+ * v_mfma_f32_32x32x16_f16 (32768 flops each) with no memory traffic: the matrix-core rate this chip
+ * sustains, as the second reference beside the vendor peak.  sink: >= 16 device bytes (practically never
+ * written).
+ */
+int vq_probe_mfma(int workgroups, int iters, void *sink, void *stream);
 
 /* Human-readable name of a status code (static storage). */
 const char *vq_status_str(int status);

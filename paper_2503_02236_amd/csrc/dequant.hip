@@ -127,6 +127,35 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict
     }
 }
 
+// Register-resident matrix-core loop: 8 independent 32x32x16 fp16 MFMA accumulator chains per wavefront,
+// no memory traffic.  What the fp16 matrix cores sustain on this chip, for the second roofline fraction.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink) {
+    float16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    half8_t a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (half_t)(threadIdx.x * 0.001f);
+        b[i] = (half_t)(i * 0.01f);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t += acc[i][0];
+    if (t == 12345.f) sink[0] = t;  // keeps the loop alive; practically never stores
+}
+
+int launch_probe_mfma(int workgroups, int iters, void *sink, hipStream_t s) {
+    probe_mfma_kernel<<<workgroups, 256, 0, s>>>(iters, (float *)sink);
+    return launch_status();
+}
+
 int launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
     size_t n16 = bytes / 16;
     int blocks = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
