@@ -133,8 +133,13 @@ __device__ __forceinline__ unsigned byte_shl(unsigned w, unsigned sh) {
 // The lookups of a tile form one sequence of groups (per 16-token step: the lane's 32 K channels, later
 // its 32 V channels); the LDS gathers of group n+1 are written before the arithmetic of group n, and the
 // sequence continues across the K/V boundary and into the next tile, so the LDS queue never drains.
-template <int V, bool ONE>
-__global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void attn_decode_kernel(AttnArgs a) {
+//
+// SEQ: sequences per workgroup (1 or 2).  With 2, wavefronts 0-7 and 8-15 attend two batch entries of
+// the SAME head and share its codebooks in LDS: the layout with one codebook per sub-space needs 128 KiB
+// for them, so only one workgroup fits a CU, and this keeps 16 wavefronts on it and stages the
+// codebooks once per pair.
+template <int V, bool ONE, int SEQ>
+__global__ __launch_bounds__(kAttnWaves * 64 * SEQ) __attribute__((amdgpu_waves_per_eu(4, 4))) void attn_decode_kernel(AttnArgs a) {
     constexpr int D = 128;
     constexpr int P = D / V;          // codes (bytes) per token and side
     constexpr int CB = 32 / V;        // codes (bytes) per lane, step and side: the lane's 32 channels
@@ -149,34 +154,23 @@ __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu
     if ((unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem != 0u) return;
     const int cb_bytes = a.G * a.E * V * 2;        // per side
     const int v_off = ONE ? 4096 : cb_bytes;       // LDS offset of the V codebook
-    float *xw = reinterpret_cast<float *>(smem + 2 * (size_t)v_off);  // [waves][D] + [waves] + [waves]
-    float *xw_m = xw + kAttnWaves * D, *xw_l = xw_m + kAttnWaves;
-
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int seq = (tid >> 6) / kAttnWaves, wave = (tid >> 6) % kAttnWaves;  // sequence of the workgroup, wavefront in it
     const int tok = lane & 15, g = lane >> 4;
-    const int bh = blockIdx.x, split = blockIdx.y;
-    const int b = bh / a.H, h = bh % a.H;
-    const int len = a.seq_lens ? min(max(a.seq_lens[b], 0), a.T) : a.T;
+    const int h = blockIdx.x % a.H, split = blockIdx.y;
+    const int b = (blockIdx.x / a.H) * SEQ + seq;
+    const bool valid = b < a.B;                      // an odd batch leaves the last pair half empty
+    const int bh = (valid ? b : 0) * a.H + h;
+    float *xw = reinterpret_cast<float *>(smem + 2 * (size_t)v_off) + seq * (kAttnWaves * (D + 2));  // [waves][D] + [waves] + [waves]
+    float *xw_m = xw + kAttnWaves * D, *xw_l = xw_m + kAttnWaves;
+    const int len = !valid ? 0 : a.seq_lens ? min(max(a.seq_lens[b], 0), a.T) : a.T;
     const int start = split * a.tc;
-    const int end = min(len, start + a.tc);  // this workgroup attends tokens [start, end)
+    const int end = min(len, start + a.tc);  // this sequence attends tokens [start, end) here
+    // nothing to attend in this token range: the wavefronts still take part in the barriers and
+    // deliver an empty partial result (uniform over the wavefronts of a sequence)
+    const bool active = start < end;
 
-    if (start >= end) {  // nothing to attend in this token range (uniform over the workgroup)
-        if (tid < D) {
-            if (a.S == 1) {
-                a.out[(size_t)bh * D + tid] = (half_t)0.f;
-            } else {
-                float *wp = a.ws + ((size_t)bh * a.S + split) * (D + 2);
-                wp[tid] = 0.f;
-                if (tid == 0) {
-                    wp[D] = -INFINITY;
-                    wp[D + 1] = 0.f;
-                }
-            }
-        }
-        return;
-    }
-
-    const int ntiles = (end - start + TILE - 1) / TILE;
+    const int ntiles = active ? (end - start + TILE - 1) / TILE : 0;
     const size_t row0 = (size_t)bh * a.T;
     // token of (tile it, step s) for this lane: t_lane + it * TILE + s * 16
     const int t_lane = start + wave * (16 * NS) + tok;
@@ -212,19 +206,21 @@ __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu
     }
     // 2. codes of the first two tiles, and q as the A operands of the four MFMAs: channels
     //    32 g + 8 i .. + 7 (the same for every row of the operand)
-    uint32_t kA[NS][CW], vA[NS][CW], kB[NS][CW], vB[NS][CW];
-    load_codes(a.k_codes, 0, kA);
-    load_codes(a.v_codes, 0, vA);
-    load_codes(a.k_codes, 1, kB);
-    load_codes(a.v_codes, 1, vB);
-    half8_t qop[4];
+    uint32_t kA[NS][CW] = {}, vA[NS][CW] = {}, kB[NS][CW] = {}, vB[NS][CW] = {};
+    half8_t qop[4] = {};
+    if (active) {
+        load_codes(a.k_codes, 0, kA);
+        load_codes(a.v_codes, 0, vA);
+        load_codes(a.k_codes, 1, kB);
+        load_codes(a.v_codes, 1, vB);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) qop[i] = ld16(a.q + (size_t)bh * D + 32 * g + 8 * i).h8;
+        for (int i = 0; i < 4; ++i) qop[i] = ld16(a.q + (size_t)bh * D + 32 * g + 8 * i).h8;
+    }
     if (tid < n16) {
         reinterpret_cast<uint4 *>(smem)[tid] = kst;
         reinterpret_cast<uint4 *>(smem + v_off)[tid] = vst;
     }
-    for (int i = tid + kAttnWaves * 64; i < n16; i += kAttnWaves * 64) {  // codebooks larger than 8 KiB per side
+    for (int i = tid + (int)blockDim.x; i < n16; i += (int)blockDim.x) {  // larger codebooks
         reinterpret_cast<uint4 *>(smem)[i] = ks[i];
         reinterpret_cast<uint4 *>(smem + v_off)[i] = vs[i];
     }
@@ -251,7 +247,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu
     float m_run = -INFINITY;   // wave-uniform running maximum of the scores (log2 domain)
 
     V16 eb[2][4];  // entries of the group being used and of the one in flight
-    gather(kA, 0, 0, eb[0]);
+    gather(kA, 0, 0, eb[0]);  // (codes are zero when there is nothing to attend: entry 0, unused)
 
     // kn: K codes of the following tile (the other register buffer)
     auto tile_step = [&](int it, uint32_t (&kc)[NS][CW], uint32_t (&vc)[NS][CW], const uint32_t (&kn)[NS][CW]) {
@@ -316,7 +312,8 @@ __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu
         xw_l[wave] = lsum;
     }
     __syncthreads();
-    if (tid < D) {
+    if (valid && tid - seq * (kAttnWaves * 64) < D) {
+        const int d = tid - seq * (kAttnWaves * 64);
         float M = xw_m[0];
 #pragma unroll
         for (int w = 1; w < kAttnWaves; ++w) M = fmaxf(M, xw_m[w]);
@@ -325,14 +322,14 @@ __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu
         for (int w = 0; w < kAttnWaves; ++w) {
             float wgt = (xw_m[w] == -INFINITY) ? 0.f : exp2f(xw_m[w] - M);
             L += xw_l[w] * wgt;
-            o += xw[w * D + tid] * wgt;
+            o += xw[w * D + d] * wgt;
         }
         if (a.S == 1) {
-            a.out[(size_t)bh * D + tid] = (half_t)(L > 0.f ? o / L : 0.f);
+            a.out[(size_t)bh * D + d] = (half_t)(L > 0.f ? o / L : 0.f);
         } else {
             float *wp = a.ws + ((size_t)bh * a.S + split) * (D + 2);
-            wp[tid] = o;
-            if (tid == 0) {
+            wp[d] = o;
+            if (d == 0) {
                 wp[D] = M;
                 wp[D + 1] = L;
             }
@@ -382,19 +379,28 @@ size_t attn_decode_workspace(const vq_kv_t *kv) {
     return (size_t)kv->B * kv->H * S * (kv->D + 2) * sizeof(float);
 }
 
-template <int V, bool ONE>
-static int run_attn(const AttnArgs &a, hipStream_t s) {
+template <int V, bool ONE, int SEQ>
+static int run_attn_seq(const AttnArgs &a, hipStream_t s) {
     const size_t side = ONE ? 4096 : (size_t)a.G * a.E * V * sizeof(half_t);  // matches the kernel's layout
-    size_t lds = 2 * side + (size_t)kAttnWaves * (128 + 2) * sizeof(float);
+    size_t lds = 2 * side + (size_t)SEQ * kAttnWaves * (128 + 2) * sizeof(float);
     static size_t attr_lds = 0;
     if (lds > 64 * 1024 && lds > attr_lds) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_decode_kernel<V, ONE>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_decode_kernel<V, ONE, SEQ>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_lds = lds;
     }
-    attn_decode_kernel<V, ONE><<<dim3(a.B * a.H, a.S), kAttnWaves * 64, lds, s>>>(a);
+    const int groups = (a.B + SEQ - 1) / SEQ;
+    attn_decode_kernel<V, ONE, SEQ><<<dim3(groups * a.H, a.S), kAttnWaves * 64 * SEQ, lds, s>>>(a);
     if (a.S > 1) attn_merge_kernel<<<a.B * a.H, 128, 0, s>>>(a.ws, a.out, a.S);
     return launch_status();
+}
+
+template <int V, bool ONE>
+static int run_attn(const AttnArgs &a, hipStream_t s) {
+    // two sequences of a head per workgroup when the codebooks are so large that only one workgroup fits a CU
+    const size_t side = ONE ? 4096 : (size_t)a.G * a.E * V * sizeof(half_t);
+    if (!ONE && a.B >= 2 && 2 * (2 * side + 4200) > 160 * 1024) return run_attn_seq<V, false, 2>(a, s);
+    return run_attn_seq<V, ONE, 1>(a, s);
 }
 
 int launch_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, hipStream_t s) {

@@ -327,6 +327,17 @@ def test_attn_small_full_compare(gpu_device, B, H, T, v, G, ragged):
     assert_close(run_attn(kv, gpu_device, sm), oracle_attn(kv, sm), f"attn B{B} H{H} T{T} v{v} G{G}")
 
 
+def test_attn_two_sequences_per_workgroup_odd_batch_and_empty_sequences(gpu_device):
+    # 32 codebooks per head and side: pairs of batch entries share a workgroup; the batch is odd, one
+    # sequence is empty and one stops inside the first token range while its partner goes on
+    kv = wl.make_kv(5, 2, 128, 1300, 4, 256, 32, seed=5200)
+    kv.seq_lens = np.array([1300, 0, 37, 1300, 600], dtype=np.int32)
+    sm = 1.0 / np.sqrt(128.0)
+    out = run_attn(kv, gpu_device, sm)
+    assert (out[1] == 0).all()
+    assert_close(out, oracle_attn(kv, sm), "attn pairs")
+
+
 def test_attn_zero_length_sequence_and_sharp_softmax(gpu_device):
     kv = wl.make_kv(3, 2, 128, 600, 4, 256, 1, seed=5100)
     kv.seq_lens = np.array([600, 0, 1], dtype=np.int32)
