@@ -182,6 +182,19 @@ def test_gemv_packed_shapes_and_edges(gpu_device, N, K, E, scale, zipf):
                  f"packed {N}x{K} E{E}")
 
 
+def test_gemv_batch_config2_full_size(gpu_device):
+    # the launches bench.py times: query/key/value (3 x 4096x4096) and gate/up (2 x 11008x4096), re-tiled codes
+    for shape_idx, count in ((0, 3), (1, 2)):
+        ws = [wl.config2_layer(shape_idx, layer=10 + i) for i in range(count)]
+        x = wl.make_activations(1, ws[0].K, wl.seed_for(2, 700 + shape_idx))
+        xd = dev_x(x, gpu_device)
+        wds = [vq.weight_to_device(w, gpu_device, prepack=True, keep_codes=False) for w in ws]
+        ys = vq.vq_gemv_batch(wds, [xd] * count)
+        torch.cuda.synchronize()
+        for i, (w, y) in enumerate(zip(ws, ys)):
+            assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), f"C2 batch[{shape_idx}][{i}]")
+
+
 def test_gemv_batch_matches_single_calls_and_oracle(gpu_device):
     # query/key/value-like: three matrices, one input; then a mixed batch (different K, one member without a
     # pack, one with an LDS-sized codebook) that takes the one-launch-per-problem route
