@@ -48,9 +48,9 @@ def _load():
         lib.vq_oracle_half_to_float_array.argtypes = [c_void, c_void, ctypes.c_size_t]
         lib.vq_oracle_threads.restype = c_int
         lib.vq_oracle_dequant.restype = None
-        lib.vq_oracle_dequant.argtypes = [c_int] * 6 + [c_void] * 3
+        lib.vq_oracle_dequant.argtypes = [c_int] * 8 + [c_void] * 3
         lib.vq_oracle_gemm.restype = None
-        lib.vq_oracle_gemm.argtypes = [c_int] * 6 + [c_void] * 4 + [c_int, c_void, c_int, c_void]
+        lib.vq_oracle_gemm.argtypes = [c_int] * 8 + [c_void] * 4 + [c_int, c_void, c_int, c_void]
         lib.vq_oracle_kv_dequant.restype = None
         lib.vq_oracle_kv_dequant.argtypes = [c_int] * 7 + [c_void] * 3
         lib.vq_oracle_attn_decode.restype = None
@@ -83,10 +83,20 @@ def half_to_float(bits: np.ndarray) -> np.ndarray:
     return out
 
 
-def _check_weight(codes, codebooks, scale, N, K, v):
+def _check_weight(codes, codebooks, scale, N, K, v, cb_tile):
     if codes.dtype not in (np.uint8, np.uint16):
         raise TypeError("codes must be uint8 or uint16")
-    R, E, vv = codebooks.shape
+    if cb_tile is None:
+        if codebooks.ndim != 3:
+            raise ValueError("codebooks must be [R][E][v]")
+        tn = tk = 0
+    else:
+        tn, tk = int(cb_tile[0]), int(cb_tile[1])
+        if tn <= 0 or tk <= 0 or K % tk != 0 or tk % v != 0:
+            raise ValueError("codebook tile must be positive, divide K and hold whole sub-vectors")
+        if codebooks.ndim != 5 or codebooks.shape[:2] != (-(-N // tn), K // tk):
+            raise ValueError("per-tile codebooks must be [ceil(N/tile_n)][K/tile_k][R][E][v]")
+    R, E, vv = codebooks.shape[-3:]
     if vv != v or K % v != 0:
         raise ValueError("vector length mismatch")
     if codes.shape != (N, K // v, R):
@@ -95,33 +105,37 @@ def _check_weight(codes, codebooks, scale, N, K, v):
         raise ValueError("code out of range")
     if scale is not None and scale.shape != (N,):
         raise ValueError("scale shape")
-    return R, E
+    return R, E, tn, tk
 
 
-def dequant(codes: np.ndarray, codebooks: np.ndarray) -> np.ndarray:
-    """codes [N][K/v][R] + codebooks fp16 [R][E][v] -> dense fp32 W[N][K] (Sec. II-A)."""
+def dequant(codes: np.ndarray, codebooks: np.ndarray, cb_tile=None) -> np.ndarray:
+    """codes [N][K/v][R] + codebooks fp16 [R][E][v] -> dense fp32 W[N][K] (Sec. II-A).
+
+    ``cb_tile=(tile_n, tile_k)``: one set of codebooks per tile of W, codebooks
+    [ceil(N/tile_n)][K/tile_k][R][E][v] (Sec. III-B, Tbl. III).
+    """
     N, J, _ = codes.shape
-    v = codebooks.shape[2]
+    v = codebooks.shape[-1]
     K = J * v
-    R, E = _check_weight(codes, codebooks, None, N, K, v)
+    R, E, tn, tk = _check_weight(codes, codebooks, None, N, K, v, cb_tile)
     codes = np.ascontiguousarray(codes)
     cb = _f16_bits(codebooks, "codebooks")
     W = np.empty((N, K), dtype=np.float32)
-    _load().vq_oracle_dequant(N, K, v, codes.dtype.itemsize * 8, R, E, _ptr(codes), _ptr(cb), _ptr(W))
+    _load().vq_oracle_dequant(N, K, v, codes.dtype.itemsize * 8, R, E, tn, tk, _ptr(codes), _ptr(cb), _ptr(W))
     return W
 
 
 def gemm(codes: np.ndarray, codebooks: np.ndarray, scale: Optional[np.ndarray], x: np.ndarray,
-         rows: Optional[Sequence[int]] = None) -> np.ndarray:
+         rows: Optional[Sequence[int]] = None, cb_tile=None) -> np.ndarray:
     """Y[m][n] = scale[n] * sum_k W[n][k] x[m][k] in fp64; x fp16 [M][K].
 
     ``rows`` restricts the evaluation to those output channels (sampled parity at
-    full size); the result is then [M][len(rows)].
+    full size); the result is then [M][len(rows)].  ``cb_tile``: see :func:`dequant`.
     """
     N, J, _ = codes.shape
-    v = codebooks.shape[2]
+    v = codebooks.shape[-1]
     K = J * v
-    R, E = _check_weight(codes, codebooks, scale, N, K, v)
+    R, E, tn, tk = _check_weight(codes, codebooks, scale, N, K, v, cb_tile)
     if x.ndim != 2 or x.shape[1] != K:
         raise ValueError("x must be [M][K]")
     M = x.shape[0]
@@ -137,14 +151,14 @@ def gemm(codes: np.ndarray, codebooks: np.ndarray, scale: Optional[np.ndarray], 
             raise ValueError("rows out of range")
         NR = int(rows_a.size)
     Y = np.empty((M, NR), dtype=np.float64)
-    _load().vq_oracle_gemm(N, K, v, codes.dtype.itemsize * 8, R, E, _ptr(codes), _ptr(cb), _ptr(sc),
+    _load().vq_oracle_gemm(N, K, v, codes.dtype.itemsize * 8, R, E, tn, tk, _ptr(codes), _ptr(cb), _ptr(sc),
                            _ptr(xb), M, _ptr(rows_a), NR, _ptr(Y))
     return Y
 
 
-def gemv(codes, codebooks, scale, x, rows=None) -> np.ndarray:
+def gemv(codes, codebooks, scale, x, rows=None, cb_tile=None) -> np.ndarray:
     """Decode-phase product: same definition as :func:`gemm` with M = batch (1..16)."""
-    return gemm(codes, codebooks, scale, x, rows)
+    return gemm(codes, codebooks, scale, x, rows, cb_tile)
 
 
 def _check_kv(codes, codebooks, B, H, T, D):

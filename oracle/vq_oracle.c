@@ -33,7 +33,8 @@
  * Parity pins (tests/test_oracle_pins.py): hand-computed tiny cases, one-hot
  * codebooks (index sums), palette codebooks against a dense fp64 matmul,
  * linearity over residual codebooks and over the scale, GEMM rows against
- * separate GEMVs, entry-permutation invariance, closed-form attention cases
+ * separate GEMVs, entry-permutation invariance, per-tile codebooks against
+ * per-tensor results assembled tile by tile, closed-form attention cases
  * (T = 1, q = 0, one dominant key), dense fp64 softmax attention, split
  * invariance, and all 65536 fp16 bit patterns of the half -> float routine.
  */
@@ -89,12 +90,21 @@ static inline uint32_t read_code(const void *codes, int code_bits, size_t idx)
  * Sec. II-A: entry lookup per residual, element-wise accumulation over the
  * residuals (fp32, residual 0 first), concatenation over the K/v sub-spaces.
  * codes: [N][K/v][R]; codebooks: fp16 bits [R][E][v].
+ * Codebook scope (Sec. III-B and Tbl. III: some algorithms keep one set of
+ * codebooks per tensor, others one per tile of the weight, e.g. per (256, 256)
+ * tile): with tile_n, tile_k > 0 the codebooks are
+ * [ceil(N/tile_n)][K/tile_k][R][E][v] and element (n, k) uses the set of tile
+ * (n / tile_n, k / tile_k); tile_n = tile_k = 0 means one set for the tensor.
  */
-static void dequant_row(int n, int K, int v, int code_bits, int R, int E,
-                        const void *codes, const uint16_t *codebooks, float *row)
+static void dequant_row(int n, int K, int v, int code_bits, int R, int E, int tile_n, int tile_k,
+                        const void *codes, const uint16_t *codebooks_all, float *row)
 {
     int J = K / v;
+    int tiles_k = tile_k > 0 ? K / tile_k : 1;
     for (int j = 0; j < J; ++j) {
+        const uint16_t *codebooks = codebooks_all;
+        if (tile_n > 0)
+            codebooks += ((size_t)(n / tile_n) * tiles_k + (size_t)(j * v) / tile_k) * ((size_t)R * E * v);
         for (int i = 0; i < v; ++i) {
             float acc = 0.0f;
             for (int r = 0; r < R; ++r) {
@@ -108,12 +118,12 @@ static void dequant_row(int n, int K, int v, int code_bits, int R, int E,
 }
 
 /* Dense fp32 weight Wd[N][K] (the bit-exact tile reference). */
-void vq_oracle_dequant(int N, int K, int v, int code_bits, int R, int E,
+void vq_oracle_dequant(int N, int K, int v, int code_bits, int R, int E, int tile_n, int tile_k,
                        const void *codes, const uint16_t *codebooks, float *Wd)
 {
 #pragma omp parallel for schedule(static)
     for (int n = 0; n < N; ++n)
-        dequant_row(n, K, v, code_bits, R, E, codes, codebooks, Wd + (size_t)n * K);
+        dequant_row(n, K, v, code_bits, R, E, tile_n, tile_k, codes, codebooks, Wd + (size_t)n * K);
 }
 
 /*
@@ -123,7 +133,7 @@ void vq_oracle_dequant(int N, int K, int v, int code_bits, int R, int E,
  * Y is [M][n_rows] in that case, column order following `rows`.
  * scale: fp16 bits [N] or NULL.
  */
-void vq_oracle_gemm(int N, int K, int v, int code_bits, int R, int E,
+void vq_oracle_gemm(int N, int K, int v, int code_bits, int R, int E, int tile_n, int tile_k,
                     const void *codes, const uint16_t *codebooks, const uint16_t *scale,
                     const uint16_t *x, int M, const int *rows, int n_rows, double *Y)
 {
@@ -134,7 +144,7 @@ void vq_oracle_gemm(int N, int K, int v, int code_bits, int R, int E,
 #pragma omp for schedule(static)
         for (int r = 0; r < NR; ++r) {
             int n = rows ? rows[r] : r;
-            dequant_row(n, K, v, code_bits, R, E, codes, codebooks, row);
+            dequant_row(n, K, v, code_bits, R, E, tile_n, tile_k, codes, codebooks, row);
             double s = scale ? (double)vq_oracle_half_to_float(scale[n]) : 1.0;
             for (int m = 0; m < M; ++m) {
                 const uint16_t *xm = x + (size_t)m * K;

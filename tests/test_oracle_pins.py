@@ -318,3 +318,44 @@ def test_attention_g1_equals_replicated_group_codebooks():
     kvG["k_codebooks"] = np.repeat(kv["k_codebooks"], 4, axis=1)
     kvG["v_codebooks"] = np.repeat(kv["v_codebooks"], 4, axis=1)
     assert np.array_equal(out1, oracle.attn_decode(**kvG, sm_scale=0.25))
+
+
+# ---------------------------------------------------------------- per-tile codebooks (Sec. III-B, Tbl. III)
+
+def test_per_tile_codebooks_equal_per_tensor_results_assembled_tile_by_tile():
+    # Each (tile_n, tile_k) tile of W has its own codebooks.  Tile by tile this is the per-tensor case (pinned
+    # above) on the tile's codes, so the tiled dequantization must equal the blocks stitched together, and the
+    # product must equal a dense fp64 matmul of that stitched matrix.
+    rng = np.random.default_rng(77)
+    N, K, v, R, E, tn, tk = 20, 48, 4, 2, 16, 8, 16          # ragged last row tile (20 = 8 + 8 + 4)
+    TN, TK = -(-N // tn), K // tk
+    cbs = rng.integers(-8, 9, size=(TN, TK, R, E, v)).astype(np.float16)
+    codes = rng.integers(0, E, size=(N, K // v, R)).astype(np.uint8)
+    W = oracle.dequant(codes, cbs, cb_tile=(tn, tk))
+    want = np.empty((N, K), dtype=np.float32)
+    for a in range(TN):
+        for b in range(TK):
+            rows = slice(a * tn, min(N, (a + 1) * tn))
+            cols = slice(b * tk // v, (b + 1) * tk // v)
+            want[rows, b * tk:(b + 1) * tk] = oracle.dequant(np.ascontiguousarray(codes[rows, cols]), cbs[a, b])
+    assert W.tobytes() == want.tobytes()
+    x = rng.integers(-4, 5, size=(3, K)).astype(np.float16)
+    scale = rng.uniform(0.5, 1.5, size=N).astype(np.float16)
+    Y = oracle.gemm(codes, cbs, scale, x, cb_tile=(tn, tk))
+    dense = (x.astype(np.float64) @ want.astype(np.float64).T) * scale.astype(np.float64)[None, :]
+    np.testing.assert_allclose(Y, dense, rtol=1e-14, atol=0)
+
+
+def test_per_tile_codebooks_with_identical_tiles_reduce_to_one_codebook():
+    rng = np.random.default_rng(78)
+    N, K, v, R, E = 32, 64, 8, 1, 32
+    cb = rng.normal(0, 0.02, size=(R, E, v)).astype(np.float16)
+    codes = rng.integers(0, E, size=(N, K // v, R)).astype(np.uint8)
+    tiled = np.broadcast_to(cb, (2, 4, R, E, v)).copy()
+    assert oracle.dequant(codes, tiled, cb_tile=(16, 16)).tobytes() == oracle.dequant(codes, cb).tobytes()
+    # and a tile that differs changes exactly its block
+    tiled[1, 2] += np.float16(1.0)
+    d = oracle.dequant(codes, tiled, cb_tile=(16, 16)) - oracle.dequant(codes, cb)
+    mask = np.zeros((N, K), dtype=bool)
+    mask[16:32, 32:48] = True
+    assert (d[~mask] == 0).all() and (d[mask] != 0).all()
