@@ -73,6 +73,9 @@ typedef struct vq_gemv_pack_t {
  * reduction axis, so row n holds K/v sub-vectors.
  *   W[n][j*v + i] = sum_{r < n_codebooks} codebooks[r][codes[n][j][r]][i]
  * summed in fp32, r ascending (Sec. II-A; "Residual" of Tbl. I = n_codebooks).
+ * With per-tile codebooks (cb_tile_n, cb_tile_k > 0) `codebooks` above is the set of the tile that holds
+ * (n, j*v).  Re-tiled gemv codes (gemv_pack), hot_entries and the fused small-M matrix-core path of vq_gemm
+ * apply to per-tensor codebooks only.
  */
 typedef struct vq_weight_t {
     int N, K;              /* output / input features; K % v == 0 */
@@ -86,6 +89,12 @@ typedef struct vq_weight_t {
     const vq_gemv_pack_t *gemv_pack; /* host pointer, optional: re-tiled codes for vq_gemv with bs = 1 */
     int hot_entries;       /* 0, or (after vq_reorder_by_frequency) how many leading entries serve half of
                               the codes: lets vq_gemv keep the hot front of a large codebook in LDS */
+    int cb_tile_n, cb_tile_k; /* codebook scope (Sec. III-B, Tbl. III).  0, 0: one set of codebooks for the tensor.
+                              Otherwise one set per (cb_tile_n x cb_tile_k) tile of W (e.g. 256 x 256):
+                              codebooks are fp16 [ceil(N/cb_tile_n)][K/cb_tile_k][R][E][v] and element (n, k)
+                              uses set (n / cb_tile_n, k / cb_tile_k).  cb_tile_n % 16 == 0, cb_tile_k % 64 == 0,
+                              K % cb_tile_k == 0; all sets of one row of tiles must fit LDS together
+                              ((K / cb_tile_k) * R * E * v * 2 <= 128 KiB) */
 } vq_weight_t;
 
 /*

@@ -35,7 +35,8 @@ class vq_weight_t(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int), ("K", ctypes.c_int), ("v", ctypes.c_int), ("code_bits", ctypes.c_int),
                 ("n_codebooks", ctypes.c_int), ("n_entries", ctypes.c_int),
                 ("codes", ctypes.c_void_p), ("codebooks", ctypes.c_void_p), ("scale", ctypes.c_void_p),
-                ("gemv_pack", ctypes.POINTER(vq_gemv_pack_t)), ("hot_entries", ctypes.c_int)]
+                ("gemv_pack", ctypes.POINTER(vq_gemv_pack_t)), ("hot_entries", ctypes.c_int),
+                ("cb_tile_n", ctypes.c_int), ("cb_tile_k", ctypes.c_int)]
 
 
 class vq_kv_t(ctypes.Structure):
@@ -126,13 +127,15 @@ class VQWeightDev:
     pack_data: Optional[torch.Tensor] = None     # device copy of the vq_gemv_prepack buffer
     pack: Optional[vq_gemv_pack_t] = None        # its descriptor (data already points at pack_data)
     hot_entries: int = 0                         # from vq_reorder_by_frequency (0: entries in no particular order)
+    cb_tile: Optional[tuple] = None              # (tile_n, tile_k): codebooks [N/tile_n][K/tile_k][R][E][v]
 
     def desc(self, use_pack: bool = True) -> vq_weight_t:
-        R, E, v = self.codebooks.shape
+        R, E, v = self.codebooks.shape[-3:]
+        tn, tk = self.cb_tile if self.cb_tile else (0, 0)
         code_dt = torch.uint8 if self.code_bits == 8 else torch.uint16
         d = vq_weight_t(self.N, self.K, self.v, self.code_bits, R, E,
                         _dev(self.codes, "codes", code_dt), _dev(self.codebooks, "codebooks", torch.float16),
-                        _dev(self.scale, "scale", torch.float16), None, int(self.hot_entries))
+                        _dev(self.scale, "scale", torch.float16), None, int(self.hot_entries), int(tn), int(tk))
         if use_pack and self.pack is not None:
             d.gemv_pack = ctypes.pointer(self.pack)
         return d
@@ -210,7 +213,8 @@ def weight_to_device(w, device="cuda:0", prepack: bool = False, keep_codes: bool
         codes = torch.from_numpy(w.codes.view(np.uint8 if w.code_bits == 8 else np.uint16)).to(device)
     cb = torch.from_numpy(w.codebooks).to(device)
     sc = None if w.scale is None else torch.from_numpy(w.scale).to(device)
-    wd = VQWeightDev(w.N, w.K, w.v, w.code_bits, codes, cb, sc, hot_entries=int(getattr(w, "hot_entries", 0)))
+    wd = VQWeightDev(w.N, w.K, w.v, w.code_bits, codes, cb, sc, hot_entries=int(getattr(w, "hot_entries", 0)),
+                     cb_tile=getattr(w, "cb_tile", None))
     if prepack:
         buf, pack = vq_gemv_prepack(w)
         if buf is None:

@@ -13,6 +13,13 @@ int check_weight(const vq_weight_t *w, bool need_codes) {
     if (w->n_codebooks < 1 || w->n_codebooks > 4) return VQ_ERR_UNSUPPORTED;
     if (w->n_entries < 1 || w->n_entries > (1 << w->code_bits)) return VQ_ERR_UNSUPPORTED;
     if (w->K % w->v != 0) return VQ_ERR_SHAPE;
+    if (w->cb_tile_n != 0 || w->cb_tile_k != 0) {  // per-tile codebooks
+        if (w->cb_tile_n <= 0 || w->cb_tile_k <= 0) return VQ_ERR_SHAPE;
+        if (w->cb_tile_n % 16 != 0 || w->cb_tile_k % 64 != 0 || w->K % w->cb_tile_k != 0) return VQ_ERR_SHAPE;
+        if ((size_t)(w->K / w->cb_tile_k) * w->n_codebooks * w->n_entries * w->v * 2 > 128 * 1024)
+            return VQ_ERR_UNSUPPORTED;
+        if (w->gemv_pack) return VQ_ERR_UNSUPPORTED;
+    }
     if ((w->codes && !aligned16(w->codes)) || !aligned16(w->codebooks)) return VQ_ERR_ALIGN;
     if (w->scale && !aligned16(w->scale)) return VQ_ERR_ALIGN;
     return VQ_OK;

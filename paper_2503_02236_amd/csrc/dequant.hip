@@ -8,13 +8,17 @@ namespace vq {
 // One thread per sub-vector: W[n][j*V .. j*V+V) = sum_r C_r[code[n][j][r]] (fp32, r ascending).
 template <typename CodeT, int V, bool OUT32>
 __global__ __launch_bounds__(256) void dequant_kernel(const CodeT *__restrict__ codes,
-                                                      const half_t *__restrict__ cb, void *__restrict__ out,
-                                                      long n_vec, int R, int E) {
+                                                      const half_t *__restrict__ cb_all, void *__restrict__ out,
+                                                      long n_vec, int R, int E, int J, int tile_n, int tile_j,
+                                                      int tiles_k) {
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     long stride = (long)gridDim.x * blockDim.x;
     for (; i < n_vec; i += stride) {
         float acc[V];
         half_t first[V];
+        // per-tile codebooks (Sec. III-B, Tbl. III): the set of the tile that holds sub-vector (n, j)
+        const half_t *cb = cb_all;
+        if (tile_n > 0) cb += ((size_t)((i / J) / tile_n) * tiles_k + (size_t)((i % J) / tile_j)) * ((size_t)R * E * V);
         for (int r = 0; r < R; ++r) {
             unsigned c = codes[i * R + r];
             const half_t *e = cb + ((size_t)r * E + c) * V;
@@ -44,14 +48,16 @@ __global__ __launch_bounds__(256) void dequant_kernel(const CodeT *__restrict__ 
 int launch_dequant(const vq_weight_t *w, void *W, int out_fp32, hipStream_t s) {
     long n_vec = (long)w->N * (w->K / w->v);
     int blocks = (int)((n_vec + 255) / 256 < 65536 ? (n_vec + 255) / 256 : 65536);
+    const int J = w->K / w->v, tile_n = w->cb_tile_n, tile_j = tile_n > 0 ? w->cb_tile_k / w->v : 1,
+              tiles_k = tile_n > 0 ? w->K / w->cb_tile_k : 1;
 #define VQ_DQ(CT, V)                                                                                            \
     do {                                                                                                        \
         if (out_fp32)                                                                                           \
             dequant_kernel<CT, V, true><<<blocks, 256, 0, s>>>((const CT *)w->codes, (const half_t *)w->codebooks, W, \
-                                                               n_vec, w->n_codebooks, w->n_entries);            \
+                                                               n_vec, w->n_codebooks, w->n_entries, J, tile_n, tile_j, tiles_k); \
         else                                                                                                    \
             dequant_kernel<CT, V, false><<<blocks, 256, 0, s>>>((const CT *)w->codes, (const half_t *)w->codebooks, W, \
-                                                                n_vec, w->n_codebooks, w->n_entries);           \
+                                                                n_vec, w->n_codebooks, w->n_entries, J, tile_n, tile_j, tiles_k); \
     } while (0)
     if (w->code_bits == 8) {
         if (w->v == 8) VQ_DQ(uint8_t, 8); else VQ_DQ(uint8_t, 4);

@@ -208,7 +208,7 @@ int launch_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *ws, h
         return launch_gemm_dense(Xp, (const half_t *)ws, (const half_t *)w->scale, Yp, M, w->N, w->K, s);
     }
     // matrix-core path: uint16 codes, one codebook, K a multiple of the 64-wide block
-    bool fast = w->code_bits == 16 && w->n_codebooks == 1 && w->K % kGemmBK == 0 && w->K > 0 && M >= 32 &&
+    bool fast = w->cb_tile_n == 0 && w->code_bits == 16 && w->n_codebooks == 1 && w->K % kGemmBK == 0 && w->K > 0 && M >= 32 &&
                 ((size_t)w->K / w->v * 2) % 16 == 0;
     if (fast) {
         if (w->v == 8) return run_mfma<8, 8, 2>(w, Xp, M, Yp, s);

@@ -28,6 +28,8 @@ struct GemvMfmaArgs {
     half_t *y;
     int N, K, J, E, bs, nit;
     int n_hot;  // entries of each codebook held in LDS (all of them unless HOT)
+    // per-tile codebooks (Sec. III-B, Tbl. III): sets per row of tiles, sub-vector positions per tile, rows per tile
+    int tiles_k, tile_j, tile_n;
 };
 
 // One code load per lane and iteration: 16 bytes, or 8 for single uint8 codes (16 positions would need
@@ -51,7 +53,8 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
     static_assert(CPL * R * sizeof(CodeT) == LB && MPI >= 1, "unsupported code width");
     extern __shared__ __align__(16) unsigned char smem[];
     half_t *cbl = reinterpret_cast<half_t *>(smem);                      // [R][E][V]
-    const int cb_bytes = R * a.n_hot * V * 2;
+    const int set_halves = R * a.n_hot * V;          // one set of codebooks
+    const int cb_bytes = set_halves * 2 * a.tiles_k;  // every set of this workgroup's row of tiles
     float4v_t *red = reinterpret_cast<float4v_t *>(smem + ((cb_bytes + 15) & ~15));  // [waves][64]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nwaves = blockDim.x >> 6;
@@ -88,9 +91,11 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
     half8_t xb[MPI];
     load_iter(wave, cd, xb);
 
-    // all codebooks, or (HOT, one codebook) its first n_hot entries
+    // all codebooks (with per-tile codebooks: the sets of the tiles this workgroup's 16 rows cross), or (HOT,
+    // one codebook) its first n_hot entries
+    const half_t *cb_src = a.cb + (a.tile_n > 0 ? (size_t)(n0 / a.tile_n) * a.tiles_k * set_halves : 0);
     for (int i = tid; i < cb_bytes / 16; i += blockDim.x)
-        reinterpret_cast<uint4 *>(cbl)[i] = reinterpret_cast<const uint4 *>(a.cb)[i];
+        reinterpret_cast<uint4 *>(cbl)[i] = reinterpret_cast<const uint4 *>(cb_src)[i];
     __syncthreads();
 
     float4v_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -98,6 +103,9 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
         V16 cd_next;
         half8_t xb_next[MPI];
         load_iter(it + nwaves, cd_next, xb_next);
+        // codebook set of this lane's positions (a load never straddles two tiles)
+        // (lanes past the end of the row are clamped to the last set; their x operand is zero)
+        const half_t *cbt = cbl + (size_t)min(((it * 4 + g) * CPL) / a.tile_j, a.tiles_k - 1) * set_halves;
 #pragma unroll
         for (int m = 0; m < MPI; ++m) {
             V16 op;
@@ -113,7 +121,7 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
                     ev.u = make_uint4(0, 0, 0, 0);
                     typedef unsigned raw4_t __attribute__((ext_vector_type(4)));
                     typedef unsigned raw2_t __attribute__((ext_vector_type(2)));
-                    const half_t *le = cbl + ((size_t)rr * a.n_hot + code) * V;
+                    const half_t *le = cbt + ((size_t)rr * a.n_hot + code) * V;
                     const half_t *ge = a.cb + ((size_t)rr * a.E + code) * V;
                     if (!HOT || code < (unsigned)a.n_hot) {
                         if (V == 8) {
@@ -208,13 +216,16 @@ int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s)
     while (waves > 4 && n_wg * waves > 4096) waves >>= 1;
     if (waves > a.nit) waves = a.nit;
     if (waves < 1) waves = 1;
+    a.tile_n = w->cb_tile_n;
+    a.tiles_k = w->cb_tile_n > 0 ? w->K / w->cb_tile_k : 1;
+    a.tile_j = w->cb_tile_n > 0 ? w->cb_tile_k / V : (1 << 30);
     // hot prefix: 64 KiB of entries with one workgroup per CU, 32 KiB when several share a CU
     a.n_hot = a.E;
     if (HOT) {
         const int cap = (n_wg <= 256 ? 64 * 1024 : 32 * 1024) / (V * 2);
         a.n_hot = a.E < cap ? a.E : cap;
     }
-    const size_t cb_bytes = (size_t)R * a.n_hot * V * 2;
+    const size_t cb_bytes = (size_t)R * a.n_hot * V * 2 * a.tiles_k;
     const size_t lds = ((cb_bytes + 15) & ~(size_t)15) + (size_t)waves * 64 * sizeof(float4v_t);
     static size_t attr_lds = 0;
     if (lds > 64 * 1024 && lds > attr_lds) {
@@ -228,7 +239,7 @@ int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s)
 
 template <typename CodeT, int V>
 int by_r(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s) {
-    const bool hot = (size_t)w->n_codebooks * w->n_entries * w->v * 2 > kGemvMfmaLdsCodebook;
+    const bool hot = w->cb_tile_n == 0 && (size_t)w->n_codebooks * w->n_entries * w->v * 2 > kGemvMfmaLdsCodebook;
     if (hot) return run<CodeT, V, 1, true>(w, x, bs, y, s);  // only single codebooks are cached partly
     switch (w->n_codebooks) {
         case 1: return run<CodeT, V, 1, false>(w, x, bs, y, s);
@@ -249,7 +260,9 @@ bool gemv_mfma_supported(const vq_weight_t *w) {
     const int cpl = (R * sz == 1 ? 8 : 16) / (R * sz), cpo = 8 / w->v;
     if (cpl < cpo) return false;
     if (w->K <= 0 || (w->K / w->v) % cpl != 0) return false;
-    if ((size_t)R * w->n_entries * w->v * 2 > kGemvMfmaLdsCodebook) {
+    if (w->cb_tile_n > 0) {
+        // per-tile codebooks: the sets of one row of tiles live in LDS together (size checked with the descriptor)
+    } else if ((size_t)R * w->n_entries * w->v * 2 > kGemvMfmaLdsCodebook) {
         // a single large codebook is cached partly, if the caller says that its front is hot enough
         if (R != 1 || w->hot_entries <= 0 || w->hot_entries > kGemvMfmaHotEntries8 * 8 / w->v) return false;
     }

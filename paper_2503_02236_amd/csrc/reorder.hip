@@ -54,6 +54,7 @@ extern "C" int vq_reorder_by_frequency(const vq_weight_t *w_host, void *codes_ou
     int st = check_weight(w_host, true);
     if (st == VQ_ERR_ALIGN) st = VQ_OK;  // host buffers need no 16-byte alignment
     if (st != VQ_OK) return st;
+    if (w_host->cb_tile_n != 0) return VQ_ERR_UNSUPPORTED;  // per-tensor codebooks only
     if (codebooks_out_host == w_host->codebooks) return VQ_ERR_SHAPE;  // entries move: not in place
     if (w_host->N == 0 || w_host->K == 0) {
         std::memcpy(codebooks_out_host, w_host->codebooks, (size_t)w_host->n_codebooks * w_host->n_entries * w_host->v * 2);

@@ -47,14 +47,15 @@ class VQWeight:
     codebooks: np.ndarray      # float16 [R][E][v]
     scale: Optional[np.ndarray]  # float16 [N] or None
     hot_entries: int = 0       # set by the frequency reordering tool: leading entries that serve half of the codes
+    cb_tile: Optional[tuple] = None  # (tile_n, tile_k): codebooks are [ceil(N/tile_n)][K/tile_k][R][E][v]
 
     @property
     def R(self) -> int:
-        return int(self.codebooks.shape[0])
+        return int(self.codebooks.shape[-3])
 
     @property
     def E(self) -> int:
-        return int(self.codebooks.shape[1])
+        return int(self.codebooks.shape[-2])
 
     def effective_bytes(self, bs: int = 1) -> int:
         """Algorithmic bytes of one product: codes + codebook once + x + scale + y."""
@@ -65,8 +66,11 @@ class VQWeight:
 
 
 def make_weight(N: int, K: int, v: int, code_bits: int, R: int, E: int, sigma: float, seed: int,
-                with_scale: bool = True, zipf_s: Optional[float] = None) -> VQWeight:
-    """Uniform (or Zipf-skewed) codes, N(0, sigma) codebooks, U(0.5, 1.5) per-channel scale."""
+                with_scale: bool = True, zipf_s: Optional[float] = None,
+                cb_tile: Optional[tuple] = None) -> VQWeight:
+    """Uniform (or Zipf-skewed) codes, N(0, sigma) codebooks, U(0.5, 1.5) per-channel scale.
+
+    ``cb_tile=(tile_n, tile_k)`` draws one set of codebooks per tile of W (per-tile codebook scope)."""
     if K % v:
         raise ValueError("K must be a multiple of v")
     if E > (1 << code_bits):
@@ -78,9 +82,10 @@ def make_weight(N: int, K: int, v: int, code_bits: int, R: int, E: int, sigma: f
         codes = rng.integers(0, E, size=shape, dtype=dt)
     else:
         codes = zipf_codes(rng, E, shape, zipf_s).astype(dt)
-    codebooks = rng.normal(0.0, sigma, size=(R, E, v)).astype(np.float16)
+    cb_shape = (R, E, v) if cb_tile is None else (-(-N // cb_tile[0]), K // cb_tile[1], R, E, v)
+    codebooks = rng.normal(0.0, sigma, size=cb_shape).astype(np.float16)
     scale = rng.uniform(0.5, 1.5, size=(N,)).astype(np.float16) if with_scale else None
-    return VQWeight(N, K, v, code_bits, codes, codebooks, scale)
+    return VQWeight(N, K, v, code_bits, codes, codebooks, scale, cb_tile=cb_tile)
 
 
 def zipf_codes(rng: np.random.Generator, E: int, shape, s: float = 1.0) -> np.ndarray:
@@ -171,6 +176,13 @@ def config2_layer(shape_idx: int, layer: int = 0, zipf_s: Optional[float] = None
     """Llama-7B decode layer, one 2^16 x 8 codebook N(0,0.02), uint16 codes, fp16 scale."""
     N, K = LLAMA7B_SHAPES[shape_idx]
     return make_weight(N, K, 8, 16, 1, 65536, 0.02, seed_for(2, layer * 3 + shape_idx), zipf_s=zipf_s)
+
+
+def gptvq_like_layer(shape_idx: int, layer: int = 0) -> VQWeight:
+    """Per-tile codebook scope as in the paper's GPTVQ-2 row (Tbl. III): VQ<4,8,1>, one 256-entry codebook per
+    (256, 256) tile of the weight, Llama-7B shapes."""
+    N, K = LLAMA7B_SHAPES[shape_idx]
+    return make_weight(N, K, 4, 8, 1, 256, 0.02, seed_for(7, layer * 3 + shape_idx), cb_tile=(256, 256))
 
 
 def config3_layer(shape_idx: int, layer: int = 0) -> VQWeight:

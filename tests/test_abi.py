@@ -169,6 +169,14 @@ def test_packed_gemv_validation():
     assert lib.vq_gemv_prepack_bytes(ctypes.byref(hd)) == 0
 
 
+def test_per_tile_codebook_descriptor_validation():
+    assert gemv(weight(K=256, cb_tile_n=32, cb_tile_k=0)) == VQ_ERR_SHAPE    # both or neither
+    assert gemv(weight(K=256, cb_tile_n=24, cb_tile_k=64)) == VQ_ERR_SHAPE   # rows per tile: multiple of 16
+    assert gemv(weight(K=256, cb_tile_n=32, cb_tile_k=32)) == VQ_ERR_SHAPE   # columns per tile: multiple of 64
+    assert gemv(weight(K=320, cb_tile_n=32, cb_tile_k=128)) == VQ_ERR_SHAPE  # K not a whole number of tiles
+    assert gemv(weight(K=64 * 600, cb_tile_n=32, cb_tile_k=64)) == VQ_ERR_UNSUPPORTED  # 600 sets of 4 KiB > LDS
+
+
 def test_gemv_batch_validation():
     lib = vq.lib()
     WP = ctypes.POINTER(vq_weight_t)

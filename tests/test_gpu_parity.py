@@ -377,3 +377,47 @@ def test_attn_config5_full_size(gpu_device):
     assert_close(out, oracle_attn(kv, sm), "C5 full")
     again = run_attn(kv, gpu_device, sm)
     assert torch.equal(out, again)            # fixed-order reductions: bit-identical repeats
+
+
+# ---------------------------------------------------------------- per-tile codebooks (Sec. III-B, Tbl. III)
+
+def run_dequant_tiled(w, device, fp32):
+    wd = vq.weight_to_device(w, device)
+    out = vq.vq_dequant(wd, out_fp32=fp32)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("N,K,v,bits,R,E,tile", [
+    (512, 512, 4, 8, 1, 256, (256, 256)),     # the paper's per-tile row: VQ<4,8,1>, (256, 256) tiles
+    (300, 384, 8, 8, 2, 64, (64, 128)),       # ragged last row tile, residual codebooks
+    (96, 256, 8, 16, 1, 1024, (32, 64)),      # uint16 codes
+])
+def test_per_tile_codebooks_dequant_and_gemv(gpu_device, N, K, v, bits, R, E, tile):
+    w = wl.make_weight(N, K, v, bits, R, E, 0.02, seed=8100 + N, cb_tile=tile)
+    want32 = oracle.dequant(w.codes, w.codebooks, cb_tile=tile)
+    got32 = run_dequant_tiled(w, gpu_device, True).cpu().numpy()
+    assert got32.tobytes() == want32.tobytes()                              # bit-exact fp32 tiles
+    got16 = run_dequant_tiled(w, gpu_device, False).cpu().numpy()
+    assert got16.tobytes() == want32.astype(np.float16).tobytes()          # and their fp16 rounding
+    for bs in (1, 7, 16):
+        x = wl.make_activations(bs, K, 8200 + bs)
+        assert_close(run_gemv(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x, cb_tile=tile),
+                     f"tiled gemv bs{bs}")
+
+
+def test_per_tile_codebooks_full_size_gemv_and_gemm(gpu_device):
+    w = wl.gptvq_like_layer(1)                                              # 11008 x 4096, 43 x 16 tiles
+    x = wl.make_activations(1, w.K, 8300)
+    assert_close(run_gemv(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x, cb_tile=w.cb_tile),
+                 "tiled gemv full")
+    X = wl.make_activations(300, w.K, 8301)                                 # two-stage prefill path (M > 256)
+    rows = np.arange(0, w.N, 97)
+    wd = vq.weight_to_device(w, gpu_device)
+    Y = vq.vq_gemm(wd, dev_x(X, gpu_device))
+    torch.cuda.synchronize()
+    want = oracle.gemm(w.codes, w.codebooks, w.scale, X, rows=rows, cb_tile=w.cb_tile)
+    assert_close(Y[:, torch.from_numpy(rows).to(gpu_device)], want, "tiled gemm")
+    Ys = vq.vq_gemm(wd, dev_x(X[:40], gpu_device))                          # small M: goes through the gemv kernels
+    torch.cuda.synchronize()
+    assert_close(Ys[:, torch.from_numpy(rows).to(gpu_device)], want[:40], "tiled gemm small M")
