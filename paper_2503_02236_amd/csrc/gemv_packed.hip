@@ -49,11 +49,15 @@ static bool pack_supported(const vq_weight_t *w) {
 }
 
 // S * RB = 256 workgroups, one per compute unit.  Slices of 2048 entries (32 KiB) unless that
-// would give a workgroup more than 16 row groups (one per wavefront): then 4096 entries.
+// would give a workgroup more than 16 row groups (one per wavefront): then 4096 entries.  Long rows
+// (K > 8192) take 1024-entry slices: the atom list of a (row, slice) cell is K/8 / S long, and a short
+// list is what keeps every step of a wavefront in its register prefetch (measured on 4096 x 11008:
+// 18.2 -> 14.6 us; on K = 4096 the doubled partial-sum traffic costs more than it saves).
 static PackPlan pack_plan(const vq_weight_t *w) {
     PackPlan p;
     p.slice_entries = 2048;
     if ((uint64_t)w->N * ((uint32_t)w->n_entries / 2048) > 256u * 1024u) p.slice_entries = 4096;
+    else if (w->K / 8 > 1024 && w->n_entries >= 65536) p.slice_entries = 1024;
     p.S = (uint32_t)w->n_entries / p.slice_entries;
     uint32_t rb = 256 / p.S;
     uint32_t max_rb = ((uint32_t)w->N + 63) / 64;   // at least one full 64-row group per block
@@ -173,7 +177,7 @@ struct PackedArgs {
     unsigned long long wg_off, group_off, rowid_off, atom_off;
 };
 
-constexpr int kPackMaxSlices = 32;  // 2^16 entries / 2048 per slice
+constexpr int kPackMaxSlices = 64;  // 2^16 entries / 1024 per slice
 constexpr int kPackPrefetch = 10;      // 4-atom steps fetched into registers while the slice is being staged
 constexpr int kPackPrefetchBatch = 4;  // batch kernel: a ring of 4 steps in flight (80 registers, three workgroups per CU)
 
@@ -341,28 +345,36 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
     gemv_packed_body<kPackPrefetchBatch, true>(a, blockIdx.x);
 }
 
-// y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.
+// y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.  MAXS loads are issued unconditionally
+// (slices past S re-read the last one) so that none of them waits behind a branch.
+template <int MAXS>
 __device__ __forceinline__ void gemv_packed_finalize_body(const float *__restrict__ partial,
                                                           const half_t *__restrict__ scale, half_t *__restrict__ y,
                                                           int N, int S) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
-    float v[kPackMaxSlices];
+    float v[MAXS];
 #pragma unroll
-    for (int k = 0; k < kPackMaxSlices; ++k) v[k] = partial[(size_t)(k < S ? k : S - 1) * N + n];
+    for (int k = 0; k < MAXS; ++k) v[k] = partial[(size_t)(k < S ? k : S - 1) * N + n];
     float sum = 0.f;
 #pragma unroll
-    for (int k = 0; k < kPackMaxSlices; ++k) sum += k < S ? v[k] : 0.f;
+    for (int k = 0; k < MAXS; ++k) sum += k < S ? v[k] : 0.f;
     y[n] = (half_t)(sum * (scale ? (float)scale[n] : 1.f));
 }
 __global__ __launch_bounds__(256) void gemv_packed_finalize_kernel(const float *__restrict__ partial,
                                                                   const half_t *__restrict__ scale,
                                                                   half_t *__restrict__ y, int N, int S) {
-    gemv_packed_finalize_body(partial, scale, y, N, S);
+    if (S <= 32)
+        gemv_packed_finalize_body<32>(partial, scale, y, N, S);
+    else
+        gemv_packed_finalize_body<kPackMaxSlices>(partial, scale, y, N, S);
 }
 __global__ __launch_bounds__(256) void gemv_packed_finalize_batch_kernel(PackedBatch b) {
     const PackedArgs &a = b.a[blockIdx.y];
-    gemv_packed_finalize_body(a.partial, a.scale, a.y, a.N, a.S);
+    if (a.S <= 32)
+        gemv_packed_finalize_body<32>(a.partial, a.scale, a.y, a.N, a.S);
+    else
+        gemv_packed_finalize_body<kPackMaxSlices>(a.partial, a.scale, a.y, a.N, a.S);
 }
 
 bool gemv_uses_pack(const vq_weight_t *w, int bs) {
