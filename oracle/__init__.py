@@ -49,6 +49,8 @@ def _load():
         lib.vq_oracle_threads.restype = c_int
         lib.vq_oracle_dequant.restype = None
         lib.vq_oracle_dequant.argtypes = [c_int] * 8 + [c_void] * 3
+        lib.vq_oracle_unpack12.restype = None
+        lib.vq_oracle_unpack12.argtypes = [c_void, ctypes.c_size_t, c_void]
         lib.vq_oracle_gemm.restype = None
         lib.vq_oracle_gemm.argtypes = [c_int] * 8 + [c_void] * 4 + [c_int, c_void, c_int, c_void]
         lib.vq_oracle_kv_dequant.restype = None
@@ -83,9 +85,43 @@ def half_to_float(bits: np.ndarray) -> np.ndarray:
     return out
 
 
+def unpack12(packed: np.ndarray, n_codes: int) -> np.ndarray:
+    """The first n_codes 12-bit codes of a packed byte string (through the C reader, for tests)."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8).ravel()
+    if packed.size * 2 < n_codes * 3:
+        raise ValueError("packed buffer too short")
+    out = np.empty(n_codes, dtype=np.uint32)
+    _load().vq_oracle_unpack12(_ptr(packed), n_codes, _ptr(out))
+    return out
+
+
+class Packed12:
+    """12-bit codes: ``data`` is the packed uint8 string of the logical array [N][K/v][R] (row-major)."""
+
+    def __init__(self, data: np.ndarray, shape):
+        self.data = np.ascontiguousarray(data, dtype=np.uint8).ravel()
+        self.shape = tuple(int(x) for x in shape)
+        n = self.shape[0] * self.shape[1] * self.shape[2]
+        if n % 2 or self.data.size != n * 3 // 2:
+            raise ValueError("packed size does not match the logical shape")
+        self.dtype = np.dtype(np.uint8)
+        self.size = n
+
+    def max(self):
+        return int(unpack12(self.data, self.size).max()) if self.size else 0
+
+
+def _code_bits(codes) -> int:
+    return 12 if isinstance(codes, Packed12) else codes.dtype.itemsize * 8
+
+
+def _code_buf(codes):
+    return codes.data if isinstance(codes, Packed12) else np.ascontiguousarray(codes)
+
+
 def _check_weight(codes, codebooks, scale, N, K, v, cb_tile):
-    if codes.dtype not in (np.uint8, np.uint16):
-        raise TypeError("codes must be uint8 or uint16")
+    if not isinstance(codes, Packed12) and codes.dtype not in (np.uint8, np.uint16):
+        raise TypeError("codes must be uint8, uint16 or Packed12")
     if cb_tile is None:
         if codebooks.ndim != 3:
             raise ValueError("codebooks must be [R][E][v]")
@@ -118,10 +154,10 @@ def dequant(codes: np.ndarray, codebooks: np.ndarray, cb_tile=None) -> np.ndarra
     v = codebooks.shape[-1]
     K = J * v
     R, E, tn, tk = _check_weight(codes, codebooks, None, N, K, v, cb_tile)
-    codes = np.ascontiguousarray(codes)
+    bits, codes = _code_bits(codes), _code_buf(codes)
     cb = _f16_bits(codebooks, "codebooks")
     W = np.empty((N, K), dtype=np.float32)
-    _load().vq_oracle_dequant(N, K, v, codes.dtype.itemsize * 8, R, E, tn, tk, _ptr(codes), _ptr(cb), _ptr(W))
+    _load().vq_oracle_dequant(N, K, v, bits, R, E, tn, tk, _ptr(codes), _ptr(cb), _ptr(W))
     return W
 
 
@@ -139,7 +175,7 @@ def gemm(codes: np.ndarray, codebooks: np.ndarray, scale: Optional[np.ndarray], 
     if x.ndim != 2 or x.shape[1] != K:
         raise ValueError("x must be [M][K]")
     M = x.shape[0]
-    codes = np.ascontiguousarray(codes)
+    bits, codes = _code_bits(codes), _code_buf(codes)
     cb = _f16_bits(codebooks, "codebooks")
     sc = None if scale is None else _f16_bits(scale, "scale")
     xb = _f16_bits(x, "x")
@@ -151,7 +187,7 @@ def gemm(codes: np.ndarray, codebooks: np.ndarray, scale: Optional[np.ndarray], 
             raise ValueError("rows out of range")
         NR = int(rows_a.size)
     Y = np.empty((M, NR), dtype=np.float64)
-    _load().vq_oracle_gemm(N, K, v, codes.dtype.itemsize * 8, R, E, tn, tk, _ptr(codes), _ptr(cb), _ptr(sc),
+    _load().vq_oracle_gemm(N, K, v, bits, R, E, tn, tk, _ptr(codes), _ptr(cb), _ptr(sc),
                            _ptr(xb), M, _ptr(rows_a), NR, _ptr(Y))
     return Y
 

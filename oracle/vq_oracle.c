@@ -20,7 +20,8 @@
  *
  * Readings where the paper is silent (also listed in the design notes):
  *   - sub-vectors lie along the input-feature (reduction) axis K of W[N][K];
- *   - codes are stored [N][K/v][R], residual index fastest, as uint8/uint16;
+ *   - codes are stored [N][K/v][R], residual index fastest, as uint8/uint16,
+ *     or as a packed 12-bit string in the same order (layout at read_code);
  *   - residual entries are summed in fp32, residual 0 first;
  *   - an optional per-output-channel scale multiplies the accumulated sum;
  *   - all T cached tokens come from the VQ cache; seq_lens[b] may shorten T.
@@ -79,10 +80,31 @@ int vq_oracle_threads(void)
 #endif
 }
 
+/*
+ * Code number idx of the tensor.  8 and 16 bits: one uint8 / uint16 each.
+ * 12 bits (the paper's VQ<8,12,2> configuration has an "unaligned 12-bit
+ * storage format", Sec. VII-B; the bit layout is not given, so this is a
+ * reading): the codes form one little-endian bit string, code idx occupying
+ * bits [12 idx, 12 idx + 12) -- two codes in three bytes:
+ *   byte 3p   = low 8 bits of code 2p
+ *   byte 3p+1 = high 4 bits of code 2p (low nibble) | low 4 bits of code 2p+1 (high nibble)
+ *   byte 3p+2 = high 8 bits of code 2p+1
+ */
 static inline uint32_t read_code(const void *codes, int code_bits, size_t idx)
 {
     if (code_bits == 8) return ((const uint8_t *)codes)[idx];
+    if (code_bits == 12) {
+        const uint8_t *b = (const uint8_t *)codes + (idx >> 1) * 3;
+        if ((idx & 1) == 0) return (uint32_t)b[0] | (((uint32_t)b[1] & 0x0Fu) << 8);
+        return ((uint32_t)b[1] >> 4) | ((uint32_t)b[2] << 4);
+    }
     return ((const uint16_t *)codes)[idx];
+}
+
+/* The first n codes of a packed 12-bit string (test access to the reader above). */
+void vq_oracle_unpack12(const uint8_t *packed, size_t n, uint32_t *out)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = read_code(packed, 12, i);
 }
 
 /*

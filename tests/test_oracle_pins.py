@@ -359,3 +359,36 @@ def test_per_tile_codebooks_with_identical_tiles_reduce_to_one_codebook():
     mask = np.zeros((N, K), dtype=bool)
     mask[16:32, 32:48] = True
     assert (d[~mask] == 0).all() and (d[mask] != 0).all()
+
+
+# ---------------------------------------------------------------- 12-bit code strings (reading; Sec. VII-B)
+
+def _pack12_numpy(codes):
+    """Independent packer: build the bit string with Python integers, bit by bit."""
+    codes = [int(c) for c in np.asarray(codes).ravel()]
+    big = 0
+    for i, c in enumerate(codes):
+        big |= c << (12 * i)
+    return np.frombuffer(big.to_bytes(len(codes) * 3 // 2, "little"), dtype=np.uint8).copy()
+
+
+def test_unpack12_hand_worked_bytes():
+    import json, os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "packed12_handworked.json")))
+    got = oracle.unpack12(np.array(g["bytes"], dtype=np.uint8), len(g["codes"]))
+    assert got.tolist() == g["codes"]
+    assert _pack12_numpy(g["codes"]).tolist() == g["bytes"]
+
+
+def test_packed12_weight_equals_the_same_codes_stored_as_uint16():
+    rng = np.random.default_rng(91)
+    N, K, v, R, E = 12, 64, 8, 2, 4096
+    codes = rng.integers(0, E, size=(N, K // v, R)).astype(np.uint16)
+    codes[0, 0, 0], codes[0, 0, 1], codes[-1, -1, -1] = 4095, 0, 4095      # extremes at both ends of the string
+    cb = rng.normal(0, 0.02, size=(R, E, v)).astype(np.float16)
+    packed = oracle.Packed12(_pack12_numpy(codes), codes.shape)
+    assert oracle.unpack12(packed.data, codes.size).tolist() == codes.ravel().tolist()
+    assert oracle.dequant(packed, cb).tobytes() == oracle.dequant(codes, cb).tobytes()
+    x = rng.normal(0, 1, size=(3, K)).astype(np.float16)
+    scale = rng.uniform(0.5, 1.5, size=N).astype(np.float16)
+    assert np.array_equal(oracle.gemm(packed, cb, scale, x), oracle.gemm(codes, cb, scale, x))
