@@ -44,7 +44,7 @@ def parse():
     ap.add_argument("--no-batch", action="store_true",
                     help="one vq_gemv call per matrix (224 launches) instead of vq_gemv_batch for the projections of "
                          "a block that share their input (query/key/value; gate/up)")
-    ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add,zipf,tile")
+    ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add,zipf,tile,bit12")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter run (wrap in rocprofv3 --pmc FETCH_SIZE or WRITE_SIZE): three plain copies of "
                          "known size as calibration, then one eager pass over the headline gemv stack; no timing")
@@ -387,6 +387,29 @@ def main():
             del wds
             torch.cuda.empty_cache()
         result["gemv_per_tile_codebooks_256x4_tiles256"] = tile
+
+    # ------------------------------------------------------------------ secondary: packed 12-bit codes (VQ<8,12,2>)
+    if want("bit12") and not args.skip_secondary:
+        b12 = {}
+        for si in (0, 1, 2):
+            N, K = wl.LLAMA7B_SHAPES[si]
+            n_copies = 24 if si == 0 else 12
+            wds = [vq.weight_to_device(wl.aqlm3_like_layer(si, layer), dev) for layer in range(n_copies)]
+            for bs in (1, 16):
+                x = torch.from_numpy(wl.make_activations(bs, K, wl.seed_for(8, bs))).to(dev)
+                y = torch.empty((bs, N), dtype=torch.float16, device=dev)
+                cs = [GemvCall(wd, x, y) for wd in wds]
+
+                def loop(cs=cs):
+                    for c in cs:
+                        c()
+                ms = timed(loop, 3, 1) / len(wds)
+                b = wds[0].codes.numel() + wds[0].codebooks.numel() * 2 + N * 2 + bs * (K + N) * 2
+                b12["%dx%d_bs%d" % (N, K, bs)] = {"us": round(ms * 1e3, 2),
+                                                   "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2)}
+            del wds
+            torch.cuda.empty_cache()
+        result["gemv_12bit_2x4096x8"] = b12
 
     # ------------------------------------------------------------------ secondary: skewed code usage (Zipf, s = 1)
     if want("zipf") and not args.skip_secondary:

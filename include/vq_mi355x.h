@@ -80,10 +80,14 @@ typedef struct vq_gemv_pack_t {
 typedef struct vq_weight_t {
     int N, K;              /* output / input features; K % v == 0 */
     int v;                 /* vector size: 4 or 8 */
-    int code_bits;         /* storage width of one code: 8 (uint8) or 16 (uint16, little endian) */
+    int code_bits;         /* storage width of one code: 8 (uint8), 16 (uint16, little endian), or 12: the packed
+                              string of VQ<8,12,2> (Sec. VII-B "unaligned 12-bit storage"; layout is this
+                              library's reading): codes in the same [N][K/v][R] order form a little-endian bit
+                              string, code i in bits [12 i, 12 i + 12) -- two codes in three bytes; a row must
+                              hold a multiple of 8 codes; per-tensor codebooks, no gemv_pack */
     int n_codebooks;       /* R >= 1 additive (residual) codebooks, R <= 4 */
     int n_entries;         /* E entries per codebook, 1 <= E <= 2^code_bits */
-    const void *codes;     /* device, [N][K/v][R], r fastest */
+    const void *codes;     /* device, [N][K/v][R], r fastest (12-bit: N * K/v * R * 3/2 bytes) */
     const void *codebooks; /* device, fp16 [R][E][v] */
     const void *scale;     /* device, fp16 [N] per output channel, or NULL (= 1) */
     const vq_gemv_pack_t *gemv_pack; /* host pointer, optional: re-tiled codes for vq_gemv with bs = 1 */

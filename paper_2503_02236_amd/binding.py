@@ -132,7 +132,7 @@ class VQWeightDev:
     def desc(self, use_pack: bool = True) -> vq_weight_t:
         R, E, v = self.codebooks.shape[-3:]
         tn, tk = self.cb_tile if self.cb_tile else (0, 0)
-        code_dt = torch.uint8 if self.code_bits == 8 else torch.uint16
+        code_dt = torch.uint16 if self.code_bits == 16 else torch.uint8   # 12-bit codes: packed bytes
         d = vq_weight_t(self.N, self.K, self.v, self.code_bits, R, E,
                         _dev(self.codes, "codes", code_dt), _dev(self.codebooks, "codebooks", torch.float16),
                         _dev(self.scale, "scale", torch.float16), None, int(self.hot_entries), int(tn), int(tk))
@@ -210,7 +210,7 @@ def weight_to_device(w, device="cuda:0", prepack: bool = False, keep_codes: bool
     import numpy as np
     codes = None
     if keep_codes or not prepack:
-        codes = torch.from_numpy(w.codes.view(np.uint8 if w.code_bits == 8 else np.uint16)).to(device)
+        codes = torch.from_numpy(w.codes.view(np.uint16 if w.code_bits == 16 else np.uint8)).to(device)
     cb = torch.from_numpy(w.codebooks).to(device)
     sc = None if w.scale is None else torch.from_numpy(w.scale).to(device)
     wd = VQWeightDev(w.N, w.K, w.v, w.code_bits, codes, cb, sc, hot_entries=int(getattr(w, "hot_entries", 0)),

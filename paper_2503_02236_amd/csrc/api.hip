@@ -9,10 +9,15 @@ int check_weight(const vq_weight_t *w, bool need_codes) {
     if ((need_codes && !w->codes) || !w->codebooks) return VQ_ERR_NULL;
     if (w->N < 0 || w->K < 0) return VQ_ERR_SHAPE;
     if (w->v != 4 && w->v != 8) return VQ_ERR_UNSUPPORTED;
-    if (w->code_bits != 8 && w->code_bits != 16) return VQ_ERR_UNSUPPORTED;
+    if (w->code_bits != 8 && w->code_bits != 12 && w->code_bits != 16) return VQ_ERR_UNSUPPORTED;
     if (w->n_codebooks < 1 || w->n_codebooks > 4) return VQ_ERR_UNSUPPORTED;
     if (w->n_entries < 1 || w->n_entries > (1 << w->code_bits)) return VQ_ERR_UNSUPPORTED;
     if (w->K % w->v != 0) return VQ_ERR_SHAPE;
+    if (w->code_bits == 12) {
+        // a row of the packed string must be whole 12-byte words (8 codes); per-tensor codebooks only
+        if (((long)(w->K / w->v) * w->n_codebooks) % 8 != 0) return VQ_ERR_SHAPE;
+        if (w->cb_tile_n != 0 || w->cb_tile_k != 0 || w->gemv_pack) return VQ_ERR_UNSUPPORTED;
+    }
     if (w->cb_tile_n != 0 || w->cb_tile_k != 0) {  // per-tile codebooks
         if (w->cb_tile_n <= 0 || w->cb_tile_k <= 0) return VQ_ERR_SHAPE;
         if (w->cb_tile_n % 16 != 0 || w->cb_tile_k % 64 != 0 || w->K % w->cb_tile_k != 0) return VQ_ERR_SHAPE;

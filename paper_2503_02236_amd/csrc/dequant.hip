@@ -7,7 +7,7 @@ namespace vq {
 
 // One thread per sub-vector: W[n][j*V .. j*V+V) = sum_r C_r[code[n][j][r]] (fp32, r ascending).
 template <typename CodeT, int V, bool OUT32>
-__global__ __launch_bounds__(256) void dequant_kernel(const CodeT *__restrict__ codes,
+__global__ __launch_bounds__(256) void dequant_kernel(const void *__restrict__ codes,
                                                       const half_t *__restrict__ cb_all, void *__restrict__ out,
                                                       long n_vec, int R, int E, int J, int tile_n, int tile_j,
                                                       int tiles_k) {
@@ -20,7 +20,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const CodeT *__restrict__ 
         const half_t *cb = cb_all;
         if (tile_n > 0) cb += ((size_t)((i / J) / tile_n) * tiles_k + (size_t)((i % J) / tile_j)) * ((size_t)R * E * V);
         for (int r = 0; r < R; ++r) {
-            unsigned c = codes[i * R + r];
+            unsigned c = read_code<CodeT>(codes, (size_t)i * R + r);
             const half_t *e = cb + ((size_t)r * E + c) * V;
 #pragma unroll
             for (int k = 0; k < V; ++k) {
@@ -53,14 +53,16 @@ int launch_dequant(const vq_weight_t *w, void *W, int out_fp32, hipStream_t s) {
 #define VQ_DQ(CT, V)                                                                                            \
     do {                                                                                                        \
         if (out_fp32)                                                                                           \
-            dequant_kernel<CT, V, true><<<blocks, 256, 0, s>>>((const CT *)w->codes, (const half_t *)w->codebooks, W, \
+            dequant_kernel<CT, V, true><<<blocks, 256, 0, s>>>(w->codes, (const half_t *)w->codebooks, W, \
                                                                n_vec, w->n_codebooks, w->n_entries, J, tile_n, tile_j, tiles_k); \
         else                                                                                                    \
-            dequant_kernel<CT, V, false><<<blocks, 256, 0, s>>>((const CT *)w->codes, (const half_t *)w->codebooks, W, \
+            dequant_kernel<CT, V, false><<<blocks, 256, 0, s>>>(w->codes, (const half_t *)w->codebooks, W, \
                                                                 n_vec, w->n_codebooks, w->n_entries, J, tile_n, tile_j, tiles_k); \
     } while (0)
     if (w->code_bits == 8) {
         if (w->v == 8) VQ_DQ(uint8_t, 8); else VQ_DQ(uint8_t, 4);
+    } else if (w->code_bits == 12) {
+        if (w->v == 8) VQ_DQ(Code12, 8); else VQ_DQ(Code12, 4);
     } else {
         if (w->v == 8) VQ_DQ(uint16_t, 8); else VQ_DQ(uint16_t, 4);
     }

@@ -330,7 +330,7 @@ int launch_gemv_rows(const vq_weight_t *w, const void *x, int bs, void *y, hipSt
         return launch_status();
     }
     if (gemv_mfma_supported(w)) return launch_gemv_mfma(w, x, bs, y, s);  // codebooks in LDS, matrix cores
-    if (w->cb_tile_n > 0) return VQ_ERR_UNSUPPORTED;  // per-tile codebooks exist on that path only
+    if (w->cb_tile_n > 0 || w->code_bits == 12) return VQ_ERR_UNSUPPORTED;  // those formats exist on that path only
     if (w->code_bits == 8) return w->v == 8 ? dispatch<uint8_t, 8>(w, xp, bs, yp, s) : dispatch<uint8_t, 4>(w, xp, bs, yp, s);
     return w->v == 8 ? dispatch<uint16_t, 8>(w, xp, bs, yp, s) : dispatch<uint16_t, 4>(w, xp, bs, yp, s);
 }

@@ -33,12 +33,32 @@ struct GemvMfmaArgs {
 };
 
 // One code load per lane and iteration: 16 bytes, or 8 for single uint8 codes (16 positions would need
-// 16 x operands in registers).
+// 16 x operands in registers); packed 12-bit codes come in 12-byte words of 8 codes.
 template <typename CodeT, int R>
 struct GemvMfmaShape {
+    static constexpr int BITS = (int)sizeof(CodeT) * 8;
     static constexpr int LB = R * (int)sizeof(CodeT) == 1 ? 8 : 16;
     static constexpr int CPL = LB / (R * (int)sizeof(CodeT));
 };
+template <int R>
+struct GemvMfmaShape<Code12, R> {
+    static constexpr int BITS = 12;
+    static constexpr int LB = 12;
+    static constexpr int CPL = 8 / R;
+};
+
+// Code number q of the lane's code word (static q).
+template <typename CodeT>
+__device__ __forceinline__ unsigned word_code(const V16 &cd, int q) {
+    return sizeof(CodeT) == 1 ? cd.b[q] : cd.h[q];
+}
+template <>
+__device__ __forceinline__ unsigned word_code<Code12>(const V16 &cd, int q) {
+    const int bit = 12 * q, wi = bit >> 5, sh = bit & 31;
+    unsigned v = cd.w[wi] >> sh;
+    if (sh > 20) v |= cd.w[wi + 1] << (32 - sh);  // straddles two dwords (q = 2, 5)
+    return v & 0xFFFu;
+}
 
 // HOT: the codebook does not fit LDS.  Its first n_hot entries are cached there and the rest is gathered
 // from global memory (L2): the shared-memory level of the hierarchical codebook cache of Sec. V-B.  It
@@ -50,7 +70,8 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
     constexpr int CPL = GemvMfmaShape<CodeT, R>::CPL;   // sub-vector positions per code load
     constexpr int CPO = 8 / V;                          // codes per MFMA operand (8 consecutive k)
     constexpr int MPI = CPL / CPO;                      // MFMAs per iteration
-    static_assert(CPL * R * sizeof(CodeT) == LB && MPI >= 1, "unsupported code width");
+    constexpr int BITS = GemvMfmaShape<CodeT, R>::BITS;
+    static_assert(CPL * R * BITS == LB * 8 && MPI >= 1, "unsupported code width");
     extern __shared__ __align__(16) unsigned char smem[];
     half_t *cbl = reinterpret_cast<half_t *>(smem);                      // [R][E][V]
     const int set_halves = R * a.n_hot * V;          // one set of codebooks
@@ -63,16 +84,22 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
     const int n = min(n0 + r, a.N - 1);  // rows past the end are computed and dropped
 
     // codes and x of this wavefront's first iteration are requested before the codebook is staged
-    const unsigned char *crow = reinterpret_cast<const unsigned char *>(a.codes) + (size_t)n * a.J * R * sizeof(CodeT);
+    const unsigned char *crow = reinterpret_cast<const unsigned char *>(a.codes) + (size_t)n * a.J * R * BITS / 8;
     auto load_iter = [&](int it, V16 &cd, half8_t (&xb)[MPI]) {
         const int jbase = (it * 4 + g) * CPL;  // first position of this lane; J % CPL == 0
         const bool valid = it < a.nit && jbase < a.J;
         cd.u = make_uint4(0, 0, 0, 0);
         if (valid) {
+            const unsigned char *cp = crow + (size_t)jbase * R * BITS / 8;
             if (LB == 16) {
-                cd = ld16(crow + (size_t)jbase * R * sizeof(CodeT));
+                cd = ld16(cp);
+            } else if (LB == 12) {  // 4-byte aligned: a row is a whole number of 12-byte words
+                const uint32_t *c3 = reinterpret_cast<const uint32_t *>(cp);
+                cd.w[0] = c3[0];
+                cd.w[1] = c3[1];
+                cd.w[2] = c3[2];
             } else {
-                V8 c8 = ld8(crow + (size_t)jbase * R * sizeof(CodeT));
+                V8 c8 = ld8(cp);
                 cd.w[0] = c8.w[0];
                 cd.w[1] = c8.w[1];
             }
@@ -114,7 +141,7 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
                 const int c = m * CPO + h;  // code position inside the 16-byte word
 #pragma unroll
                 for (int rr = 0; rr < R; ++rr) {
-                    const unsigned code = sizeof(CodeT) == 1 ? cd.b[c * R + rr] : cd.h[c * R + rr];
+                    const unsigned code = word_code<CodeT>(cd, c * R + rr);
                     // the entry: from the LDS copy, or (cold entry of a partly cached codebook) from L2.  The two
                     // loads are kept apart by their address spaces, so neither becomes a generic-pointer load
                     V16 ev;
@@ -190,7 +217,7 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
 
 namespace {
 
-constexpr size_t kGemvMfmaLdsCodebook = 48 * 1024;  // whole codebooks up to this size live in LDS
+constexpr size_t kGemvMfmaLdsCodebook = 128 * 1024;  // whole codebooks up to this size live in LDS
 constexpr int kGemvMfmaHotEntries8 = 4096;           // v = 8 entries of a larger codebook cached in LDS (64 KiB)
 
 template <typename CodeT, int V, int R, bool HOT>
@@ -214,6 +241,8 @@ int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s)
     const int n_wg = (a.N + 15) / 16;
     int waves = 16;
     while (waves > 4 && n_wg * waves > 4096) waves >>= 1;
+    // codebooks of more than half the LDS: one workgroup per CU anyway, so give it all 16 wavefronts
+    if ((size_t)R * a.E * V * 2 > 72 * 1024 && w->hot_entries == 0) waves = 16;
     if (waves > a.nit) waves = a.nit;
     if (waves < 1) waves = 1;
     a.tile_n = w->cb_tile_n;
@@ -256,8 +285,8 @@ bool gemv_mfma_supported(const vq_weight_t *w) {
     const int R = w->n_codebooks, sz = w->code_bits / 8;
     if (w->v != 8 && w->v != 4) return false;
     if (R != 1 && R != 2 && R != 4) return false;
-    if (R * sz > 8) return false;
-    const int cpl = (R * sz == 1 ? 8 : 16) / (R * sz), cpo = 8 / w->v;
+    if (w->code_bits != 12 && R * sz > 8) return false;
+    const int cpl = w->code_bits == 12 ? 8 / R : (R * sz == 1 ? 8 : 16) / (R * sz), cpo = 8 / w->v;
     if (cpl < cpo) return false;
     if (w->K <= 0 || (w->K / w->v) % cpl != 0) return false;
     if (w->cb_tile_n > 0) {
@@ -274,6 +303,7 @@ int launch_gemv_mfma(const vq_weight_t *w, const void *x, int bs, void *y, hipSt
     const half_t *xp = (const half_t *)x;
     half_t *yp = (half_t *)y;
     if (w->code_bits == 8) return w->v == 8 ? by_r<uint8_t, 8>(w, xp, bs, yp, s) : by_r<uint8_t, 4>(w, xp, bs, yp, s);
+    if (w->code_bits == 12) return w->v == 8 ? by_r<Code12, 8>(w, xp, bs, yp, s) : by_r<Code12, 4>(w, xp, bs, yp, s);
     return w->v == 8 ? by_r<uint16_t, 8>(w, xp, bs, yp, s) : by_r<uint16_t, 4>(w, xp, bs, yp, s);
 }
 

@@ -62,6 +62,22 @@ __device__ __forceinline__ float wave_max(float x) {
     return x;
 }
 
+// Tag type for packed 12-bit codes (VQ-LLM Sec. VII-B: VQ<8,12,2> has an unaligned 12-bit storage format).
+// Reading of the layout: one little-endian bit string, code i in bits [12 i, 12 i + 12), i.e. two codes in
+// three bytes, in the canonical order [N][K/v][R].
+struct Code12 {};
+
+// Code number idx of a canonical code array.
+template <typename CodeT>
+__device__ __forceinline__ unsigned read_code(const void *codes, size_t idx) {
+    return reinterpret_cast<const CodeT *>(codes)[idx];
+}
+template <>
+__device__ __forceinline__ unsigned read_code<Code12>(const void *codes, size_t idx) {
+    const uint8_t *b = reinterpret_cast<const uint8_t *>(codes) + (idx >> 1) * 3;
+    return (idx & 1) ? ((unsigned)b[1] >> 4) | ((unsigned)b[2] << 4) : (unsigned)b[0] | (((unsigned)b[1] & 0xFu) << 8);
+}
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Host-side validation shared by the entry points (no HIP calls).

@@ -43,7 +43,7 @@ class VQWeight:
     K: int
     v: int
     code_bits: int
-    codes: np.ndarray          # uint8/uint16 [N][K/v][R]
+    codes: np.ndarray          # uint8/uint16 [N][K/v][R]; code_bits = 12: packed uint8 [N][K/v*R*3/2] (pack12)
     codebooks: np.ndarray      # float16 [R][E][v]
     scale: Optional[np.ndarray]  # float16 [N] or None
     hot_entries: int = 0       # set by the frequency reordering tool: leading entries that serve half of the codes
@@ -75,6 +75,8 @@ def make_weight(N: int, K: int, v: int, code_bits: int, R: int, E: int, sigma: f
         raise ValueError("K must be a multiple of v")
     if E > (1 << code_bits):
         raise ValueError("E exceeds the code range")
+    if code_bits == 12 and ((K // v) * R) % 8:
+        raise ValueError("12-bit rows must hold a multiple of 8 codes")
     rng = _rng(seed)
     dt = np.uint8 if code_bits == 8 else np.uint16
     shape = (N, K // v, R)
@@ -85,7 +87,28 @@ def make_weight(N: int, K: int, v: int, code_bits: int, R: int, E: int, sigma: f
     cb_shape = (R, E, v) if cb_tile is None else (-(-N // cb_tile[0]), K // cb_tile[1], R, E, v)
     codebooks = rng.normal(0.0, sigma, size=cb_shape).astype(np.float16)
     scale = rng.uniform(0.5, 1.5, size=(N,)).astype(np.float16) if with_scale else None
+    if code_bits == 12:
+        codes = pack12(codes)
     return VQWeight(N, K, v, code_bits, codes, codebooks, scale, cb_tile=cb_tile)
+
+
+def pack12(codes: np.ndarray) -> np.ndarray:
+    """Logical codes [N][J][R] (< 4096) -> packed uint8 [N][J*R*3/2]: a little-endian bit string per row, code i in
+    bits [12 i, 12 i + 12) (two codes in three bytes).  Storage format only; nothing is computed here."""
+    N = codes.shape[0]
+    c = codes.reshape(N, -1, 2).astype(np.uint32)
+    out = np.empty((N, c.shape[1], 3), dtype=np.uint8)
+    out[..., 0] = c[..., 0] & 0xFF
+    out[..., 1] = (c[..., 0] >> 8) | ((c[..., 1] & 0xF) << 4)
+    out[..., 2] = c[..., 1] >> 4
+    return out.reshape(N, -1)
+
+
+def aqlm3_like_layer(shape_idx: int, layer: int = 0) -> VQWeight:
+    """The paper's VQ<8,12,2> row (Tbl. III): two additive 4096-entry codebooks of 8-vectors, packed 12-bit codes
+    (3 bits per weight), Llama-7B shapes."""
+    N, K = LLAMA7B_SHAPES[shape_idx]
+    return make_weight(N, K, 8, 12, 2, 4096, 0.01, seed_for(8, layer * 3 + shape_idx))
 
 
 def zipf_codes(rng: np.random.Generator, E: int, shape, s: float = 1.0) -> np.ndarray:

@@ -66,7 +66,7 @@ def gemm(w, x=P, M=1, y=P):
     (weight(codebooks=None), VQ_ERR_NULL),
     (weight(v=3), VQ_ERR_UNSUPPORTED),
     (weight(v=16), VQ_ERR_UNSUPPORTED),
-    (weight(code_bits=12), VQ_ERR_UNSUPPORTED),
+    (weight(code_bits=10), VQ_ERR_UNSUPPORTED),
     (weight(n_codebooks=0), VQ_ERR_UNSUPPORTED),
     (weight(n_codebooks=5), VQ_ERR_UNSUPPORTED),
     (weight(n_entries=257), VQ_ERR_UNSUPPORTED),
@@ -175,6 +175,15 @@ def test_per_tile_codebook_descriptor_validation():
     assert gemv(weight(K=256, cb_tile_n=32, cb_tile_k=32)) == VQ_ERR_SHAPE   # columns per tile: multiple of 64
     assert gemv(weight(K=320, cb_tile_n=32, cb_tile_k=128)) == VQ_ERR_SHAPE  # K not a whole number of tiles
     assert gemv(weight(K=64 * 600, cb_tile_n=32, cb_tile_k=64)) == VQ_ERR_UNSUPPORTED  # 600 sets of 4 KiB > LDS
+
+
+def test_packed_12_bit_descriptor_validation():
+    ok = dict(code_bits=12, n_entries=4096, n_codebooks=2, K=256)          # 32 positions x 2 = 64 codes per row
+    assert gemv(weight(**ok), x=None) == VQ_ERR_NULL                        # descriptor accepted, x missing
+    assert gemv(weight(**dict(ok, n_entries=4097))) == VQ_ERR_UNSUPPORTED   # more entries than 12 bits address
+    assert gemv(weight(**dict(ok, K=40))) == VQ_ERR_SHAPE                   # 5 x 2 = 10 codes: not whole 12-byte words
+    assert gemv(weight(**dict(ok, cb_tile_n=32, cb_tile_k=64))) == VQ_ERR_UNSUPPORTED
+    assert gemv(weight(code_bits=10)) == VQ_ERR_UNSUPPORTED
 
 
 def test_gemv_batch_validation():

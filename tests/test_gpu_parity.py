@@ -421,3 +421,39 @@ def test_per_tile_codebooks_full_size_gemv_and_gemm(gpu_device):
     Ys = vq.vq_gemm(wd, dev_x(X[:40], gpu_device))                          # small M: goes through the gemv kernels
     torch.cuda.synchronize()
     assert_close(Ys[:, torch.from_numpy(rows).to(gpu_device)], want[:40], "tiled gemm small M")
+
+
+# ---------------------------------------------------------------- packed 12-bit codes (VQ<8,12,2>, Sec. VII-B)
+
+def ocodes(w):
+    """The codes of a host weight as the oracle takes them."""
+    if w.code_bits == 12:
+        return oracle.Packed12(w.codes, (w.N, w.K // w.v, w.R))
+    return w.codes
+
+
+@pytest.mark.parametrize("N,K,v,R,E", [
+    (200, 512, 8, 2, 4096),      # the paper's configuration: two additive 4096-entry codebooks
+    (96, 256, 8, 1, 3000),       # one codebook, E below the 12-bit range
+    (64, 128, 4, 4, 512),        # v = 4, four residual codebooks
+])
+def test_packed_12_bit_codes_dequant_gemv_gemm(gpu_device, N, K, v, R, E):
+    w = wl.make_weight(N, K, v, 12, R, E, 0.01, seed=8500 + N)
+    want32 = oracle.dequant(ocodes(w), w.codebooks)
+    wd = vq.weight_to_device(w, gpu_device)
+    got32 = vq.vq_dequant(wd, out_fp32=True)
+    torch.cuda.synchronize()
+    assert got32.cpu().numpy().tobytes() == want32.tobytes()                # bit-exact tiles
+    for bs in (1, 9, 16):
+        x = wl.make_activations(bs, K, 8600 + bs)
+        assert_close(vq.vq_gemv(wd, dev_x(x, gpu_device)), oracle.gemv(ocodes(w), w.codebooks, w.scale, x),
+                     f"12-bit gemv bs{bs}")
+    X = wl.make_activations(300, K, 8700)
+    assert_close(vq.vq_gemm(wd, dev_x(X, gpu_device)), oracle.gemm(ocodes(w), w.codebooks, w.scale, X), "12-bit gemm")
+
+
+def test_packed_12_bit_full_size(gpu_device):
+    w = wl.aqlm3_like_layer(0)                                               # 4096 x 4096, 128 KiB of codebooks
+    x = wl.make_activations(4, w.K, 8800)
+    wd = vq.weight_to_device(w, gpu_device)
+    assert_close(vq.vq_gemv(wd, dev_x(x, gpu_device)), oracle.gemv(ocodes(w), w.codebooks, w.scale, x), "AQLM-3-like gemv")
