@@ -27,7 +27,7 @@ def build(force: bool = False) -> str:
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+        cmd = ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
                "-o", tmp, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
         os.replace(tmp, _LIB)
@@ -53,6 +53,8 @@ def _load():
         lib.vq_oracle_unpack12.argtypes = [c_void, ctypes.c_size_t, c_void]
         lib.vq_oracle_gemm.restype = None
         lib.vq_oracle_gemm.argtypes = [c_int] * 8 + [c_void] * 4 + [c_int, c_void, c_int, c_void]
+        lib.vq_oracle_kv_quantize.restype = None
+        lib.vq_oracle_kv_quantize.argtypes = [c_int] * 7 + [c_void] * 3
         lib.vq_oracle_kv_dequant.restype = None
         lib.vq_oracle_kv_dequant.argtypes = [c_int] * 7 + [c_void] * 3
         lib.vq_oracle_attn_decode.restype = None
@@ -221,6 +223,20 @@ def kv_dequant(codes: np.ndarray, codebooks: np.ndarray) -> np.ndarray:
     cb = _f16_bits(codebooks, "codebooks")
     out = np.empty((B, H, T, D), dtype=np.float32)
     _load().vq_oracle_kv_dequant(B, H, D, T, v, E, G, _ptr(codes), _ptr(cb), _ptr(out))
+    return out
+
+
+def kv_quantize(x: np.ndarray, codebooks: np.ndarray) -> np.ndarray:
+    """fp16 vectors [B][H][n][D] + fp16 codebooks [H][G][E][v] -> uint8 codes [B][H][n][D/v]: index of the
+    closest entry per sub-vector (fp32 squared distance, fixed order, ties to the smallest index)."""
+    B, H, n, D = x.shape
+    Hc, G, E, v = codebooks.shape
+    if Hc != H or D % v != 0 or (D // v) % G != 0 or E > 256:
+        raise ValueError("shape mismatch")
+    xb = _f16_bits(x, "x")
+    cb = _f16_bits(codebooks, "codebooks")
+    out = np.empty((B, H, n, D // v), dtype=np.uint8)
+    _load().vq_oracle_kv_quantize(B, H, D, n, v, E, G, _ptr(xb), _ptr(cb), _ptr(out))
     return out
 
 

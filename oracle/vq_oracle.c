@@ -199,6 +199,49 @@ static void kv_dequant_token(const uint8_t *codes, const uint16_t *codebooks,
     }
 }
 
+/*
+ * Quantization of new K or V vectors (the assignment step of Sec. II-A: a
+ * sub-vector is replaced by the index of its closest codebook entry; this is
+ * what the on-the-fly KV quantization of Sec. VII "Quantization Overhead" runs
+ * for every new token).  x: fp16 bits [B][H][n_new][D]; codebooks as above;
+ * out: uint8 [B][H][n_new][D/v].
+ * A floating-point comparison decides an integer here, so the precision and
+ * the order are part of the definition (the paper gives none; this is the
+ * reading the GPU kernel follows too): squared Euclidean distance in fp32,
+ *   d = ((x0-c0)^2 + (x1-c1)^2) + ... , elements in ascending order, every
+ * subtraction, multiplication and addition rounded separately (no fused
+ * multiply-add); the smallest distance wins, ties go to the smallest index.
+ */
+void vq_oracle_kv_quantize(int B, int H, int D, int n_new, int v, int E, int G,
+                           const uint16_t *x, const uint16_t *codebooks, uint8_t *out)
+{
+    int P = D / v;
+#pragma omp parallel for schedule(static)
+    for (long bh = 0; bh < (long)B * H; ++bh) {
+        int h = (int)(bh % H);
+        for (int t = 0; t < n_new; ++t) {
+            const uint16_t *xv = x + ((size_t)bh * n_new + t) * D;
+            for (int p = 0; p < P; ++p) {
+                int g = (int)(((long)p * G) / P);
+                const uint16_t *cb = codebooks + (((size_t)h * G + g) * E) * v;
+                int best = 0;
+                float best_d = 0.0f;
+                for (int e = 0; e < E; ++e) {
+                    volatile float d = 0.0f;   /* volatile: each step is rounded to fp32, nothing is fused */
+                    for (int i = 0; i < v; ++i) {
+                        volatile float diff = vq_oracle_half_to_float(xv[p * v + i])
+                                            - vq_oracle_half_to_float(cb[(size_t)e * v + i]);
+                        volatile float sq = diff * diff;
+                        d = d + sq;
+                    }
+                    if (e == 0 || d < best_d) { best = e; best_d = d; }
+                }
+                out[((size_t)bh * n_new + t) * P + p] = (uint8_t)best;
+            }
+        }
+    }
+}
+
 /* Dense fp32 cache out[B][H][T][D] of one side. */
 void vq_oracle_kv_dequant(int B, int H, int D, int T, int v, int E, int G,
                           const uint8_t *codes, const uint16_t *codebooks, float *out)

@@ -392,3 +392,50 @@ def test_packed12_weight_equals_the_same_codes_stored_as_uint16():
     x = rng.normal(0, 1, size=(3, K)).astype(np.float16)
     scale = rng.uniform(0.5, 1.5, size=N).astype(np.float16)
     assert np.array_equal(oracle.gemm(packed, cb, scale, x), oracle.gemm(codes, cb, scale, x))
+
+
+# ---------------------------------------------------------------- KV quantization: closest entry (Sec. II-A)
+
+def test_kv_quantize_recovers_entries_and_matches_exact_integer_brute_force():
+    rng = np.random.default_rng(101)
+    B, H, n, D, v, E, G = 2, 3, 5, 16, 4, 32, 2
+    # integer-valued entries and vectors: every distance is an exact small integer, so any correct
+    # implementation in any precision agrees, and a brute force in Python integers is the reference
+    cb = rng.integers(-6, 7, size=(H, G, E, v)).astype(np.float16)
+    x = rng.integers(-6, 7, size=(B, H, n, D)).astype(np.float16)
+    got = oracle.kv_quantize(x, cb)
+    P = D // v
+    for b in range(B):
+        for h in range(H):
+            for t in range(n):
+                for p in range(P):
+                    g = p * G // P
+                    xv = [int(a) for a in x[b, h, t, p * v:(p + 1) * v]]
+                    d = [sum((a - int(c)) ** 2 for a, c in zip(xv, cb[h, g, e])) for e in range(E)]
+                    assert got[b, h, t, p] == d.index(min(d))           # ties: the smallest index
+    # a vector that IS an entry gets that entry's index (first of equal entries), and dequantizing the
+    # codes gives the vector back
+    codes = rng.integers(0, E, size=(B, H, n, P)).astype(np.uint8)
+    xd = oracle.kv_dequant(codes, cb).astype(np.float16)
+    back = oracle.kv_quantize(xd, cb)
+    assert np.array_equal(oracle.kv_dequant(back, cb), xd.astype(np.float32))
+
+
+def test_kv_quantize_agrees_with_float64_argmin_when_the_gap_is_clear():
+    rng = np.random.default_rng(102)
+    B, H, n, D, v, E, G = 1, 2, 40, 32, 4, 256, 8
+    cb = rng.normal(0, 1, size=(H, G, E, v)).astype(np.float16)
+    x = rng.normal(0, 1, size=(B, H, n, D)).astype(np.float16)
+    got = oracle.kv_quantize(x, cb)
+    P = D // v
+    checked = 0
+    for h in range(H):
+        for t in range(n):
+            for p in range(P):
+                g = p * G // P
+                d = ((cb[h, g].astype(np.float64) - x[0, h, t, p * v:(p + 1) * v].astype(np.float64)) ** 2).sum(axis=1)
+                order = np.argsort(d)
+                if d[order[1]] - d[order[0]] > 1e-4 * d[order[1]]:       # fp32 rounding cannot flip these
+                    assert got[0, h, t, p] == order[0]
+                    checked += 1
+    assert checked > 0.9 * H * n * P
