@@ -325,7 +325,16 @@ def main():
         result["attn_decode_B16_H32_T4096"] = {"us": round(ms * 1e3, 2), "GBps": round(b / ms / 1e6, 1),
                                                "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2),
                                                "pct_measured_stream_read": round(100 * b / ms / 1e6 / ceil_hbm, 2)}
-        del ring
+        # on-the-fly quantization of new tokens into that cache: one decode step, and a 4096-token prefill
+        kd = ring[0]
+        k1 = torch.randn((kv.B, kv.H, 1, kv.D), device=dev).to(torch.float16)
+        kT = torch.randn((kv.B, kv.H, kv.T, kv.D), device=dev).to(torch.float16)
+        ms1 = timed(lambda: vq.vq_kv_quantize(kd, k1, k1, kv.T - 1), 50, 5)
+        msT = timed(lambda: vq.vq_kv_quantize(kd, kT, kT, 0), 5, 1)
+        result["kv_quantize_B16_H32"] = {"decode_1_token_us": round(ms1 * 1e3, 2),
+                                         "prefill_4096_tokens_us": round(msT * 1e3, 1),
+                                         "prefill_input_GBps": round(2 * kT.numel() * 2 / msT / 1e6, 1)}
+        del k1, kT, kd, ring
         torch.cuda.empty_cache()
         # same shape with the coupled-quantization layout: 32 codebooks per head and side (64 KiB each)
         kv = wl.config5_kv(G=32)

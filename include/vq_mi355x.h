@@ -211,6 +211,19 @@ int vq_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out,
 size_t vq_attn_decode_workspace(const vq_kv_t *kv);
 
 /*
+ * On-the-fly KV quantization (Sec. II-A, assignment step: a sub-vector is replaced by the index of its
+ * closest codebook entry; Sec. VII "Quantization Overhead": run for the new token of every decode step
+ * and for all prompt tokens in prefill).  Quantizes n_new tokens per sequence and WRITES their codes
+ * into kv->k_codes / kv->v_codes at positions [pos, pos + n_new) of every (b, h) row (the const in the
+ * descriptor notwithstanding); kv->seq_lens is not read or changed.
+ *   k_new, v_new: device fp16 [B][H][n_new][D];  0 <= pos, pos + n_new <= T (VQ_ERR_SHAPE otherwise).
+ * Definition of "closest" (the paper gives none): squared Euclidean distance in fp32, elements in
+ * ascending order, each operation rounded separately; ties go to the smallest index.  Codebooks of one
+ * side of a head (cb_groups * n_entries * v * 2 bytes) must fit 64 KiB (VQ_ERR_UNSUPPORTED otherwise).
+ */
+int vq_kv_quantize(const vq_kv_t *kv, const void *k_new, const void *v_new, int n_new, int pos, void *stream);
+
+/*
  * Test hooks: the dequantized operand itself (Sec. II-A), for bit-exact checks.
  * vq_dequant: W[N][K], fp32 (out_fp32 = 1: the fp32 sum of the residual entries)
  *             or fp16 (out_fp32 = 0: that sum rounded to nearest even).

@@ -71,6 +71,8 @@ SYMBOLS = {
     "vq_attn_decode_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_kv_t)]),
     "vq_dequant": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]),
     "vq_kv_dequant": (ctypes.c_int, [ctypes.POINTER(vq_kv_t), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]),
+    "vq_kv_quantize": (ctypes.c_int, [ctypes.POINTER(vq_kv_t), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                      ctypes.c_int, ctypes.c_void_p]),
     "vq_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "vq_probe_read": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]),
     "vq_probe_mfma": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]),
@@ -339,6 +341,14 @@ def vq_dequant(w: VQWeightDev, out_fp32: bool = True) -> torch.Tensor:
     d = w.desc()
     _check(lib().vq_dequant(ctypes.byref(d), _dev(W, "W"), 1 if out_fp32 else 0, _stream()), "vq_dequant")
     return W
+
+
+def vq_kv_quantize(kv: VQKVDev, k_new: torch.Tensor, v_new: torch.Tensor, pos: int) -> None:
+    """Quantize new tokens (fp16 [B][H][n][D] each) and store their codes at positions [pos, pos + n)."""
+    n = k_new.shape[2]
+    d = kv.desc()
+    _check(lib().vq_kv_quantize(ctypes.byref(d), _dev(k_new, "k_new", torch.float16),
+                                _dev(v_new, "v_new", torch.float16), int(n), int(pos), _stream()), "vq_kv_quantize")
 
 
 def vq_kv_dequant(kv: VQKVDev, which: int) -> torch.Tensor:

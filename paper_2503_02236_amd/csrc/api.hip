@@ -180,6 +180,16 @@ int vq_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, 
     return launch_attn_decode(kv, q, sm_scale, out, ws, static_cast<hipStream_t>(stream));
 }
 
+int vq_kv_quantize(const vq_kv_t *kv, const void *k_new, const void *v_new, int n_new, int pos, void *stream) {
+    int st = check_kv(kv);
+    if (st != VQ_OK) return st;
+    if (!k_new || !v_new) return VQ_ERR_NULL;
+    if (n_new < 0 || pos < 0 || (long)pos + n_new > kv->T) return VQ_ERR_SHAPE;
+    if (!aligned16(k_new) || !aligned16(v_new)) return VQ_ERR_ALIGN;
+    if (n_new == 0 || kv->B == 0 || kv->H == 0) return VQ_OK;
+    return launch_kv_quantize(kv, k_new, v_new, n_new, pos, static_cast<hipStream_t>(stream));
+}
+
 int vq_dequant(const vq_weight_t *w, void *W, int out_fp32, void *stream) {
     int st = check_weight(w, true);
     if (st != VQ_OK) return st;

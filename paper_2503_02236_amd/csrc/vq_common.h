@@ -106,6 +106,7 @@ int launch_gemm_dense(const half_t *A, const half_t *B, const half_t *scale, hal
                       hipStream_t s);
 int launch_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, hipStream_t s);
 size_t attn_decode_workspace(const vq_kv_t *kv);
+int launch_kv_quantize(const vq_kv_t *kv, const void *k_new, const void *v_new, int n_new, int pos, hipStream_t s);
 int launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 int launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t s);
 int launch_probe_mfma(int workgroups, int iters, void *sink, hipStream_t s);

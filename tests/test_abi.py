@@ -135,6 +135,19 @@ def test_attention_argument_validation():
     assert lib.vq_attn_decode(ctypes.byref(kvdesc(B=0)), P, 0.1, P, None, 0, None) == 0
 
 
+def test_kv_quantize_argument_validation():
+    lib = vq.lib()
+    kv = kvdesc()
+    f = lib.vq_kv_quantize
+    assert f(ctypes.byref(kv), None, P, 1, 0, None) == VQ_ERR_NULL
+    assert f(ctypes.byref(kv), P, P + 2, 1, 0, None) == VQ_ERR_ALIGN
+    assert f(ctypes.byref(kv), P, P, -1, 0, None) == VQ_ERR_SHAPE
+    assert f(ctypes.byref(kv), P, P, 1, -1, None) == VQ_ERR_SHAPE
+    assert f(ctypes.byref(kv), P, P, 2, kv.T - 1, None) == VQ_ERR_SHAPE     # runs past the end of the cache
+    assert f(ctypes.byref(kv), P, P, 0, 0, None) == 0                       # nothing to do
+    assert f(ctypes.byref(kvdesc(v=3)), P, P, 1, 0, None) == VQ_ERR_UNSUPPORTED
+
+
 def test_packed_gemv_validation():
     import numpy as np
     from paper_2503_02236_amd import workloads as wl

@@ -457,3 +457,48 @@ def test_packed_12_bit_full_size(gpu_device):
     x = wl.make_activations(4, w.K, 8800)
     wd = vq.weight_to_device(w, gpu_device)
     assert_close(vq.vq_gemv(wd, dev_x(x, gpu_device)), oracle.gemv(ocodes(w), w.codebooks, w.scale, x), "AQLM-3-like gemv")
+
+
+# ---------------------------------------------------------------- on-the-fly KV quantization (Sec. II-A, Sec. VII)
+
+@pytest.mark.parametrize("B,H,T,v,G,n_new,pos", [
+    (2, 3, 40, 4, 1, 1, 39),        # decode: one new token at the end of the cache
+    (2, 2, 300, 4, 32, 130, 7),     # prefill chunk, one codebook per sub-space, several token chunks
+    (1, 2, 64, 8, 4, 64, 0),
+    (1, 2, 50, 2, 1, 5, 20),
+])
+def test_kv_quantize_codes_bit_exact_and_in_place(gpu_device, B, H, T, v, G, n_new, pos):
+    kv = wl.make_kv(B, H, 128, T, v, 256, G, seed=9300 + T)
+    rng = np.random.default_rng(9301 + T)
+    k_new = rng.normal(0, 1, size=(B, H, n_new, 128)).astype(np.float16)
+    v_new = rng.normal(0, 1, size=(B, H, n_new, 128)).astype(np.float16)
+    kd = vq.kv_to_device(kv, gpu_device)
+    vq.vq_kv_quantize(kd, dev_x(k_new, gpu_device), dev_x(v_new, gpu_device), pos)
+    torch.cuda.synchronize()
+    want_k, want_v = kv.k_codes.copy(), kv.v_codes.copy()
+    want_k[:, :, pos:pos + n_new] = oracle.kv_quantize(k_new, kv.k_codebooks)
+    want_v[:, :, pos:pos + n_new] = oracle.kv_quantize(v_new, kv.v_codebooks)
+    assert np.array_equal(kd.k_codes.cpu().numpy(), want_k)          # integer result: exact; the rest untouched
+    assert np.array_equal(kd.v_codes.cpu().numpy(), want_v)
+
+
+def test_kv_quantize_then_attend(gpu_device):
+    # a cache written by the quantizer, read by the attention kernel: compare with the oracle's two steps
+    B, H, T = 2, 4, 700
+    kv = wl.make_kv(B, H, 128, T, 4, 256, 1, seed=9400)
+    rng = np.random.default_rng(9401)
+    # realistic new vectors: entries plus noise, so that the closest entry is usually clear
+    k_all = (oracle.kv_dequant(kv.k_codes, kv.k_codebooks) + rng.normal(0, 0.05, size=(B, H, T, 128))).astype(np.float16)
+    v_all = (oracle.kv_dequant(kv.v_codes, kv.v_codebooks) + rng.normal(0, 0.05, size=(B, H, T, 128))).astype(np.float16)
+    kd = vq.kv_to_device(kv, gpu_device)
+    kd.k_codes.zero_()
+    kd.v_codes.zero_()
+    vq.vq_kv_quantize(kd, dev_x(k_all[:, :, :650], gpu_device), dev_x(v_all[:, :, :650], gpu_device), 0)   # prefill
+    for t in range(650, 700, 10):                                                                         # then decode steps
+        vq.vq_kv_quantize(kd, dev_x(k_all[:, :, t:t + 10], gpu_device), dev_x(v_all[:, :, t:t + 10], gpu_device), t)
+    sm = 1.0 / np.sqrt(128.0)
+    out = vq.vq_attn_decode(kd, dev_x(kv.q, gpu_device), sm)
+    torch.cuda.synchronize()
+    kc, vc = oracle.kv_quantize(k_all, kv.k_codebooks), oracle.kv_quantize(v_all, kv.v_codebooks)
+    assert np.array_equal(kd.k_codes.cpu().numpy(), kc) and np.array_equal(kd.v_codes.cpu().numpy(), vc)
+    assert_close(out, oracle.attn_decode(kc, vc, kv.k_codebooks, kv.v_codebooks, kv.q, sm), "quantize + attend")
