@@ -18,7 +18,7 @@
  *   - GeMV / GeMM over a weight matrix held as codes, Sec. III-C (VQ-gemv,
  *     VQ-gemm): y = x * dequant(W)^T.
  *
- * Readings where the paper is silent (also listed in the design notes):
+ * Readings where the paper is silent:
  *   - sub-vectors lie along the input-feature (reduction) axis K of W[N][K];
  *   - codes are stored [N][K/v][R], residual index fastest, as uint8/uint16,
  *     or as a packed 12-bit string in the same order (layout at read_code);

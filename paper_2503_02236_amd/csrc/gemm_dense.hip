@@ -21,7 +21,7 @@
 // segment index with the row (each lane fetches the segment that belongs in its slot).
 // Operand reads of MFMA step s+1 are issued before the MFMAs of step s.
 //
-// Measured limits of this design on MI355X (see the design notes): a stage completes only when
+// Measured limits of this design on MI355X: a stage completes only when
 // its slowest line has arrived, ~16-20 % of the lines are first touches of the die's L2 and come
 // from the last-level cache (~1.7 us), and LDS cannot hold more than two further stages; the
 // memory pipeline alone therefore needs ~55 us for M = 2048, N = K = 4096, the MFMA + LDS loop
