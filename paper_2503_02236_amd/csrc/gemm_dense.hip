@@ -21,11 +21,12 @@
 // segment index with the row (each lane fetches the segment that belongs in its slot).
 // Operand reads of MFMA step s+1 are issued before the MFMAs of step s.
 //
-// Measured limits of this design on MI355X: a stage completes only when
-// its slowest line has arrived, ~16-20 % of the lines are first touches of the die's L2 and come
-// from the last-level cache (~1.7 us), and LDS cannot hold more than two further stages; the
-// memory pipeline alone therefore needs ~55 us for M = 2048, N = K = 4096, the MFMA + LDS loop
-// alone ~44 us, and together they reach ~78 us (35 % of the fp16 peak).
+// Measured limits of this design on MI355X (M = 2048, N = K = 4096): the MFMA + LDS-read loop alone runs
+// in ~44 us, the loads alone in ~55 us, together 78 us (35 % of the fp16 peak).  The loads are the floor:
+// a 256 x 128 tile moves 48 KiB per K block into LDS, and the L2 -> LDS path of one CU sustains only
+// ~27 bytes per clock here, whether the operands come from memory or sit in L2 (pointing every tile at the
+// same 3 MiB gives the same time; touching lines in L2 ahead of time makes it slower).  A larger tile would
+// halve the traffic per flop but leaves half of the 256 CUs without a tile at this problem size.
 #include "vq_common.h"
 
 namespace vq {
