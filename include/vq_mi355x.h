@@ -84,7 +84,8 @@ typedef struct vq_weight_t {
                               string of VQ<8,12,2> (Sec. VII-B "unaligned 12-bit storage"; layout is this
                               library's reading): codes in the same [N][K/v][R] order form a little-endian bit
                               string, code i in bits [12 i, 12 i + 12) -- two codes in three bytes; a row must
-                              hold a multiple of 8 codes; per-tensor codebooks, no gemv_pack */
+                              hold a multiple of 8 codes; per-tensor codebooks, 1, 2 or 4 of them, together at most
+                              128 KiB (R * E * v * 2 bytes); no gemv_pack */
     int n_codebooks;       /* R >= 1 additive (residual) codebooks, R <= 4 */
     int n_entries;         /* E entries per codebook, 1 <= E <= 2^code_bits */
     const void *codes;     /* device, [N][K/v][R], r fastest (12-bit: N * K/v * R * 3/2 bytes) */
@@ -97,7 +98,7 @@ typedef struct vq_weight_t {
                               Otherwise one set per (cb_tile_n x cb_tile_k) tile of W (e.g. 256 x 256):
                               codebooks are fp16 [ceil(N/cb_tile_n)][K/cb_tile_k][R][E][v] and element (n, k)
                               uses set (n / cb_tile_n, k / cb_tile_k).  cb_tile_n % 16 == 0, cb_tile_k % 64 == 0,
-                              K % cb_tile_k == 0; all sets of one row of tiles must fit LDS together
+                              K % cb_tile_k == 0; n_codebooks 1, 2 or 4; all sets of one row of tiles must fit LDS together
                               ((K / cb_tile_k) * R * E * v * 2 <= 128 KiB) */
 } vq_weight_t;
 

@@ -16,14 +16,16 @@ int check_weight(const vq_weight_t *w, bool need_codes) {
     if (w->code_bits == 12) {
         // a row of the packed string must be whole 12-byte words (8 codes); per-tensor codebooks only
         if (((long)(w->K / w->v) * w->n_codebooks) % 8 != 0) return VQ_ERR_SHAPE;
-        if (w->cb_tile_n != 0 || w->cb_tile_k != 0 || w->gemv_pack) return VQ_ERR_UNSUPPORTED;
+        if (w->cb_tile_n != 0 || w->cb_tile_k != 0 || w->gemv_pack || w->n_codebooks == 3) return VQ_ERR_UNSUPPORTED;
+        // the kernels for this format keep all codebooks in LDS
+        if ((size_t)w->n_codebooks * w->n_entries * w->v * 2 > 128 * 1024) return VQ_ERR_UNSUPPORTED;
     }
     if (w->cb_tile_n != 0 || w->cb_tile_k != 0) {  // per-tile codebooks
         if (w->cb_tile_n <= 0 || w->cb_tile_k <= 0) return VQ_ERR_SHAPE;
         if (w->cb_tile_n % 16 != 0 || w->cb_tile_k % 64 != 0 || w->K % w->cb_tile_k != 0) return VQ_ERR_SHAPE;
         if ((size_t)(w->K / w->cb_tile_k) * w->n_codebooks * w->n_entries * w->v * 2 > 128 * 1024)
             return VQ_ERR_UNSUPPORTED;
-        if (w->gemv_pack) return VQ_ERR_UNSUPPORTED;
+        if (w->gemv_pack || w->n_codebooks == 3) return VQ_ERR_UNSUPPORTED;
     }
     if ((w->codes && !aligned16(w->codes)) || !aligned16(w->codebooks)) return VQ_ERR_ALIGN;
     if (w->scale && !aligned16(w->scale)) return VQ_ERR_ALIGN;

@@ -195,6 +195,8 @@ def test_packed_12_bit_descriptor_validation():
     assert gemv(weight(**ok), x=None) == VQ_ERR_NULL                        # descriptor accepted, x missing
     assert gemv(weight(**dict(ok, n_entries=4097))) == VQ_ERR_UNSUPPORTED   # more entries than 12 bits address
     assert gemv(weight(**dict(ok, K=40))) == VQ_ERR_SHAPE                   # 5 x 2 = 10 codes: not whole 12-byte words
+    assert gemv(weight(**dict(ok, n_codebooks=4))) == VQ_ERR_UNSUPPORTED    # 256 KiB of codebooks do not fit LDS
+    assert gemv(weight(**dict(ok, n_codebooks=3, K=512))) == VQ_ERR_UNSUPPORTED
     assert gemv(weight(**dict(ok, cb_tile_n=32, cb_tile_k=64))) == VQ_ERR_UNSUPPORTED
     assert gemv(weight(code_bits=10)) == VQ_ERR_UNSUPPORTED
 

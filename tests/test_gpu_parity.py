@@ -502,3 +502,87 @@ def test_kv_quantize_then_attend(gpu_device):
     kc, vc = oracle.kv_quantize(k_all, kv.k_codebooks), oracle.kv_quantize(v_all, kv.v_codebooks)
     assert np.array_equal(kd.k_codes.cpu().numpy(), kc) and np.array_equal(kd.v_codes.cpu().numpy(), vc)
     assert_close(out, oracle.attn_decode(kc, vc, kv.k_codebooks, kv.v_codebooks, kv.q, sm), "quantize + attend")
+
+
+# ---------------------------------------------------------------- randomized sweep over formats and shapes
+
+def _random_weight_case(rng):
+    v = int(rng.choice([4, 8]))
+    bits = int(rng.choice([8, 12, 16]))
+    R = int(rng.choice([1, 2, 3, 4]))
+    E = int(rng.choice([16, 100, 256])) if bits == 8 else int(rng.choice([256, 1000, 4096]))
+    tile = None
+    if bits != 12 and rng.random() < 0.3:
+        tile = (int(rng.choice([16, 32, 64])), int(rng.choice([64, 128])))
+    if (bits == 12 or tile) and R == 3:
+        R = 2                                   # those formats take 1, 2 or 4 codebooks
+    if bits == 12 and R * E * v * 2 > 128 * 1024:
+        E = 1000                                # 12-bit codes: all codebooks in LDS
+    kmul = tile[1] if tile else 8 * v
+    K = int(rng.integers(1, 9)) * kmul
+    if bits == 12:
+        while ((K // v) * R) % 8:
+            K += kmul
+    if tile and (K // tile[1]) * R * E * v * 2 > 128 * 1024:
+        E = 64
+    N = int(rng.integers(1, 200))
+    return N, K, v, bits, R, E, tile
+
+
+@pytest.mark.parametrize("seed", range(int(__import__("os").environ.get("VQ_TEST_RANDOM_CASES", "24"))))
+def test_gemv_gemm_dequant_random_formats(gpu_device, seed):
+    rng = np.random.default_rng(97000 + seed)
+    N, K, v, bits, R, E, tile = _random_weight_case(rng)
+    w = wl.make_weight(N, K, v, bits, R, E, 0.02, seed=97100 + seed, with_scale=bool(rng.random() < 0.7), cb_tile=tile)
+    what = f"N{N} K{K} v{v} bits{bits} R{R} E{E} tile{tile}"
+    wd = vq.weight_to_device(w, gpu_device)
+    want32 = oracle.dequant(ocodes(w), w.codebooks, cb_tile=tile)
+    got32 = vq.vq_dequant(wd, out_fp32=True)
+    torch.cuda.synchronize()
+    assert got32.cpu().numpy().tobytes() == want32.tobytes(), what
+    for bs in (1, int(rng.integers(2, 17))):
+        x = wl.make_activations(bs, K, 97200 + seed + bs)
+        assert_close(vq.vq_gemv(wd, dev_x(x, gpu_device)),
+                     oracle.gemv(ocodes(w), w.codebooks, w.scale, x, cb_tile=tile), what + f" bs{bs}")
+    M = int(rng.choice([20, 70, 270]))
+    X = wl.make_activations(M, K, 97300 + seed)
+    assert_close(vq.vq_gemm(wd, dev_x(X, gpu_device)),
+                 oracle.gemm(ocodes(w), w.codebooks, w.scale, X, cb_tile=tile), what + f" M{M}")
+
+
+@pytest.mark.parametrize("seed", range(int(__import__("os").environ.get("VQ_TEST_RANDOM_CASES", "16"))))
+def test_attn_random_shapes(gpu_device, seed):
+    rng = np.random.default_rng(98000 + seed)
+    v = int(rng.choice([2, 4, 8]))
+    P = 128 // v
+    G = int(rng.choice([g for g in (1, 2, 4, 8, 16, 32, 64) if P % g == 0 and g * 256 * v * 2 <= 64 * 1024]))
+    B, H = int(rng.integers(1, 6)), int(rng.integers(1, 5))
+    T = int(rng.choice([1, 17, 255, 256, 257, 1000, 1536, 3000]))
+    E = int(rng.choice([16, 200, 256]))
+    kv = wl.make_kv(B, H, 128, T, v, E, G, seed=98100 + seed, ragged=bool(rng.random() < 0.5))
+    if kv.seq_lens is not None and rng.random() < 0.3:
+        kv.seq_lens[int(rng.integers(0, B))] = 0
+    sm = float(rng.choice([1.0 / np.sqrt(128.0), 0.3]))
+    assert_close(run_attn(kv, gpu_device, sm), oracle_attn(kv, sm), f"attn B{B} H{H} T{T} v{v} G{G} E{E}")
+
+
+@pytest.mark.parametrize("seed", range(int(__import__("os").environ.get("VQ_TEST_RANDOM_CASES", "12"))))
+def test_gemv_packed_random_shapes(gpu_device, seed):
+    rng = np.random.default_rng(99000 + seed)
+    E = int(rng.choice([4096, 8192, 16384, 65536]))
+    K = int(rng.integers(1, 40)) * 64 if rng.random() < 0.7 else int(rng.integers(1, 255)) * 8 * 8
+    K = min(K, 2047 * 8)
+    N = int(rng.choice([1, 63, 64, 65, 500, 1500, 4097]))
+    zipf = float(rng.choice([0.8, 1.2])) if rng.random() < 0.3 else None
+    count = int(rng.integers(1, 5))
+    ws = [wl.make_weight(N if i == 0 else int(rng.integers(1, 700)), K, 8, 16, 1, E, 0.02, seed=99100 + 10 * seed + i,
+                         with_scale=bool(rng.random() < 0.7), zipf_s=zipf) for i in range(count)]
+    x = wl.make_activations(1, K, 99200 + seed)
+    xd = dev_x(x, gpu_device)
+    wds = [vq.weight_to_device(w, gpu_device, prepack=True, keep_codes=False) for w in ws]
+    ys = vq.vq_gemv_batch(wds, [xd] * count)
+    torch.cuda.synchronize()
+    for i, (w, wd, y) in enumerate(zip(ws, wds, ys)):
+        what = f"packed N{w.N} K{K} E{E} zipf{zipf} member {i}/{count}"
+        assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), what)
+        assert torch.equal(y, vq.vq_gemv(wd, xd)), what
