@@ -244,10 +244,12 @@ int vq_probe_read(const void *src, size_t bytes, void *sink, void *stream);
 /*
  * vq_probe_mfma: `workgroups` x 4 wavefronts, each running `iters` x 8 back-to-back register-resident
  * v_mfma_f32_32x32x16_f16 (32768 flops each) with no memory traffic: the matrix-core rate this chip
- * sustains, as the second reference beside the vendor peak.  sink: >= 16 device bytes (practically never
- * written).
+ * sustains, as the second reference beside the vendor peak.  random_operands = 0: one smooth operand
+ * pair (few bits toggle); != 0: four pairs of pseudo-random halves in [-1, 1) per lane taken in turn, as
+ * a gemm on real data presents them (the chip clocks lower on these).  sink: >= 16 device bytes
+ * (practically never written).
  */
-int vq_probe_mfma(int workgroups, int iters, void *sink, void *stream);
+int vq_probe_mfma(int workgroups, int iters, int random_operands, void *sink, void *stream);
 
 /* Human-readable name of a status code (static storage). */
 const char *vq_status_str(int status);

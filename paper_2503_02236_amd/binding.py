@@ -75,7 +75,7 @@ SYMBOLS = {
                                       ctypes.c_int, ctypes.c_void_p]),
     "vq_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "vq_probe_read": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]),
-    "vq_probe_mfma": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]),
+    "vq_probe_mfma": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]),
     "vq_status_str": (ctypes.c_char_p, [ctypes.c_int]),
     "vq_version": (ctypes.c_int, []),
 }
@@ -364,9 +364,10 @@ def vq_probe_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
     _check(lib().vq_probe_copy(_dev(dst, "dst"), _dev(src, "src"), n, _stream()), "vq_probe_copy")
 
 
-def vq_probe_mfma(workgroups: int, iters: int, sink: torch.Tensor) -> None:
+def vq_probe_mfma(workgroups: int, iters: int, sink: torch.Tensor, random_operands: bool = False) -> None:
     """Register-resident fp16 MFMA loop (no memory traffic): workgroups x 4 waves x iters x 8 MFMAs."""
-    _check(lib().vq_probe_mfma(int(workgroups), int(iters), _dev(sink, "sink"), _stream()), "vq_probe_mfma")
+    _check(lib().vq_probe_mfma(int(workgroups), int(iters), int(bool(random_operands)), _dev(sink, "sink"), _stream()),
+           "vq_probe_mfma")
 
 
 def vq_probe_read(src: torch.Tensor, sink: torch.Tensor) -> None:

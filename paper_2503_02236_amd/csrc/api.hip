@@ -227,12 +227,12 @@ int vq_probe_read(const void *src, size_t bytes, void *sink, void *stream) {
     return launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream));
 }
 
-int vq_probe_mfma(int workgroups, int iters, void *sink, void *stream) {
+int vq_probe_mfma(int workgroups, int iters, int random_operands, void *sink, void *stream) {
     if (!sink) return VQ_ERR_NULL;
     if (workgroups < 0 || iters < 0 || workgroups > (1 << 20) || iters > (1 << 24)) return VQ_ERR_SHAPE;
     if (!aligned16(sink)) return VQ_ERR_ALIGN;
     if (workgroups == 0) return VQ_OK;
-    return launch_probe_mfma(workgroups, iters, sink, static_cast<hipStream_t>(stream));
+    return launch_probe_mfma(workgroups, iters, random_operands, sink, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

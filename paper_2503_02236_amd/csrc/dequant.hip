@@ -137,21 +137,37 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict
 
 // Register-resident matrix-core loop: 8 independent 32x32x16 fp16 MFMA accumulator chains per wavefront,
 // no memory traffic.  What the fp16 matrix cores sustain on this chip, for the second roofline fraction.
+// RANDOM: four operand pairs of pseudo-random halves in [-1, 1) per lane, taken in turn, as in a gemm on
+// real data; the smooth operands of the other form (one pair, values that barely differ between lanes)
+// toggle far fewer bits, and the chip clocks higher on them.
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink) {
     float16_t acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    half8_t a, b;
+    constexpr int P = RANDOM ? 4 : 1;
+    half8_t a[P], b[P];
+    uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        a[i] = (half_t)(threadIdx.x * 0.001f);
-        b[i] = (half_t)(i * 0.01f);
-    }
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (RANDOM) {
+                h = h * 1664525u + 1013904223u;
+                a[p][i] = (half_t)(((int)(h >> 16) - 32768) * (1.f / 32768.f));
+                h = h * 1664525u + 1013904223u;
+                b[p][i] = (half_t)(((int)(h >> 16) - 32768) * (1.f / 32768.f));
+            } else {
+                a[p][i] = (half_t)(threadIdx.x * 0.001f);
+                b[p][i] = (half_t)(i * 0.01f);
+            }
+        }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+        for (int i = 0; i < 8; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i % P], b[(i / 2) % P], acc[i], 0, 0, 0);
     }
     float t = 0.f;
 #pragma unroll
@@ -159,8 +175,11 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink)
     if (t == 12345.f) sink[0] = t;  // keeps the loop alive; practically never stores
 }
 
-int launch_probe_mfma(int workgroups, int iters, void *sink, hipStream_t s) {
-    probe_mfma_kernel<<<workgroups, 256, 0, s>>>(iters, (float *)sink);
+int launch_probe_mfma(int workgroups, int iters, int random_operands, void *sink, hipStream_t s) {
+    if (random_operands)
+        probe_mfma_kernel<true><<<workgroups, 256, 0, s>>>(iters, (float *)sink);
+    else
+        probe_mfma_kernel<false><<<workgroups, 256, 0, s>>>(iters, (float *)sink);
     return launch_status();
 }
 

@@ -15,19 +15,26 @@
 // are K-contiguous, so a lane's MFMA operand (8 consecutive k) is one 128-bit LDS read.
 //
 // Data movement: global -> LDS directly (global_load_lds_dwordx4, no registers), three LDS
-// stages, so the loads of K block kt+2 are in flight while block kt is multiplied.  The direct
+// stages, so the loads of K blocks kt+1 and kt+2 are in flight while block kt is multiplied.  The direct
 // load writes lane l's 16 bytes at (base + 16 l), so a wavefront fills 8 tile rows of 128
 // bytes; bank conflicts of the operand reads are avoided by a XOR swizzle of the 16-byte
 // segment index with the row (each lane fetches the segment that belongs in its slot).
-// Operand reads of MFMA step s+1 are issued before the MFMAs of step s.
+// Operand reads of MFMA step s+1 are issued between the MFMAs of step s, and so are the loads, one after
+// every second MFMA.
 //
-// Measured limits of this design on MI355X (M = 2048, N = K = 4096): the MFMA + LDS-read loop alone runs
-// in ~44 us, the loads alone in ~55 us, together 78 us (35 % of the fp16 peak).  The loads are the floor:
-// a 256 x 128 tile moves 48 KiB per K block into LDS, and the L2 -> LDS path of one CU sustains only
-// ~27 bytes per clock here, whether the operands come from memory or sit in L2 (pointing every tile at the
-// same 3 MiB gives the same time; touching lines in L2 ahead of time makes it slower).  A larger tile would
-// halve the traffic per flop but leaves half of the 256 CUs without a tile at this problem size.
+// Measured on MI355X (M = 2048, N = K = 4096, parts of the main loop timed alone): MFMAs alone 41 us on
+// all-zero operands and 55 us on random ones (the chip clocks lower the more operand bits toggle: a
+// register-resident MFMA loop sustains 2.05 PFLOP/s on smooth and 1.64 on random operands), with the LDS
+// reads the same; the loads alone 33 us; everything together 60 us on random data, 67 us with the
+// epilogue.  What mattered on the way there: (1) __syncthreads() waits for every outstanding load, so the
+// ring was never more than one stage deep -- a bare s_barrier after a counted wait; (2) twelve loads
+// issued as a burst hold up the wavefront's MFMAs behind them (76 us -> 63 us when spread out);
+// (3) LDS destinations (M0) from a scalar wavefront index (63 -> 59 us); (4) 16-byte stores of whole lines
+// in the epilogue instead of 2-byte stores.  Pointing every tile at the same 3 MiB (all loads hit L2)
+// changes nothing: the loop is bound by the matrix cores at the clock the data allows.
 #include "vq_common.h"
+
+#include <type_traits>
 
 namespace vq {
 
@@ -57,9 +64,12 @@ __global__ __launch_bounds__(256) void gemm_dense_kernel(DenseArgs a) {
     constexpr int kStage = (BM + BN) * kDenseRowB;
     constexpr int A_LOADS = BM / 32;  // wave-wide 1 KiB loads per wavefront per stage (8 rows each)
     constexpr int B_LOADS = BN / 32;
+    constexpr int N_LOADS = A_LOADS + B_LOADS;
+    static_assert(N_LOADS == 2 * (MT + NT) && MT * NT >= MT + NT, "the main loop issues one load after every second operand read");
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // the wavefront index as a scalar: LDS destinations of the direct loads (M0) then need no vector instructions
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int ln = lane & 31, lh = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
 
@@ -100,17 +110,20 @@ __global__ __launch_bounds__(256) void gemm_dense_kernel(DenseArgs a) {
         const int n = min(n0 + r, a.N - 1);
         bsrc[p] = a.B + (size_t)n * a.K + seg * 8;
     }
-    auto issue_stage = [&](int kt, int buf) {
+    // load p of a stage: p < A_LOADS is a chunk of the X tile, the rest chunks of the weight tile
+    auto issue_load = [&](int kt, int buf, int p) {
         unsigned char *ab = smem + (size_t)buf * kStage + (size_t)wave * (BM / 4) * kDenseRowB;
         unsigned char *bb = smem + (size_t)buf * kStage + BM * kDenseRowB + (size_t)wave * (BN / 4) * kDenseRowB;
-#pragma unroll
-        for (int p = 0; p < A_LOADS; ++p)
+        if (p < A_LOADS)
             __builtin_amdgcn_global_load_lds((global_void_t *)(asrc[p] + (size_t)kt * kDenseBK),
                                              (lds_void_t *)(ab + p * 1024), 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds((global_void_t *)(bsrc[p - A_LOADS] + (size_t)kt * kDenseBK),
+                                             (lds_void_t *)(bb + (p - A_LOADS) * 1024), 16, 0, 0);
+    };
+    auto issue_stage = [&](int kt, int buf) {
 #pragma unroll
-        for (int p = 0; p < B_LOADS; ++p)
-            __builtin_amdgcn_global_load_lds((global_void_t *)(bsrc[p] + (size_t)kt * kDenseBK),
-                                             (lds_void_t *)(bb + p * 1024), 16, 0, 0);
+        for (int p = 0; p < N_LOADS; ++p) issue_load(kt, buf, p);
     };
 
     // operand rows of this lane inside a stage; 32 rows further down the swizzle has bit 2 flipped
@@ -121,68 +134,120 @@ __global__ __launch_bounds__(256) void gemm_dense_kernel(DenseArgs a) {
     issue_stage(0, 0);
     if (KT > 1) issue_stage(1, 1);
 
+    // One K block.  MORE: stage kt + 2 exists and is requested while block kt is multiplied.  The loads are
+    // spread over the whole block, one after every second MFMA: issued as a burst they hold up the
+    // wavefront's MFMAs behind them.
+    // The source order of the memory operations below is the intended issue order (direct-to-LDS loads
+    // and LDS reads are not reordered against each other by the compiler); the group barriers place the
+    // MFMAs between them.
     int buf = 0;
-    for (int kt = 0; kt < KT; ++kt) {
-        // stage kt has landed (the newer stage may still be in flight); after the barrier every
-        // wavefront is also done with stage kt-1, whose buffer the next loads overwrite
+    half8_t af[2][MT], bf[2][NT];
+    auto k_block = [&](int kt, auto more_tag) {
+        constexpr bool MORE = decltype(more_tag)::value;
+        // stage kt has landed (the newer stage may still be in flight); after the barrier every wavefront
+        // is also done with stage kt-1, whose buffer the next loads overwrite.  A bare s_barrier:
+        // __syncthreads() carries a fence that waits for every outstanding load, the newer stage included.
         if (kt + 1 < KT)
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(A_LOADS + B_LOADS) : "memory");
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N_LOADS) : "memory");
         else
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (kt + 2 < KT) issue_stage(kt + 2, buf >= 1 ? buf - 1 : kDenseStages - 1);
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        const int lbuf = buf >= 1 ? buf - 1 : kDenseStages - 1;
 
         const unsigned char *ab = smem + (size_t)buf * kStage + (size_t)a_row * kDenseRowB;
         const unsigned char *bb = smem + (size_t)buf * kStage + BM * kDenseRowB + (size_t)b_row * kDenseRowB;
-        half8_t af[2][MT], bf[2][NT];
-        auto read_frags = [&](int s, int slot) {
+        // operand q of MFMA step s: q < MT is a row block of X, the rest column blocks of the weight
+        auto read_operand = [&](int s, int slot, int q) {
             const int ao = (((2 * s + lh) ^ a_swz) << 4), bo = (((2 * s + lh) ^ b_swz) << 4);
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-                af[slot][i] = *reinterpret_cast<const half8_t *>(ab + i * 32 * kDenseRowB + (ao ^ ((i & 1) << 6)));
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-                bf[slot][j] = *reinterpret_cast<const half8_t *>(bb + j * 32 * kDenseRowB + (bo ^ ((j & 1) << 6)));
+            if (q < MT)
+                af[slot][q] = *reinterpret_cast<const half8_t *>(ab + q * 32 * kDenseRowB + (ao ^ ((q & 1) << 6)));
+            else
+                bf[slot][q - MT] = *reinterpret_cast<const half8_t *>(bb + (q - MT) * 32 * kDenseRowB +
+                                                                      (bo ^ (((q - MT) & 1) << 6)));
         };
-        read_frags(0, 0);
+#pragma unroll
+        for (int q = 0; q < MT + NT; ++q) read_operand(0, 0, q);
+        __builtin_amdgcn_sched_group_barrier(0x100, MT + NT, 0);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            if (s < 3) read_frags(s + 1, (s + 1) & 1);
+#pragma unroll
+            for (int q = 0; q < MT + NT; ++q) {
+                if (s < 3) read_operand(s + 1, (s + 1) & 1, q);
+                if (MORE && (q & 1)) issue_load(kt + 2, lbuf, s * (N_LOADS / 4) + q / 2);
+            }
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
                 for (int j = 0; j < NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[s & 1][i], bf[s & 1][j], acc[i][j], 0, 0, 0);
-        }
-        // instruction order for the block above (the compiler would otherwise sink every LDS read to
-        // just before its first use): the reads of step 0, then per step one LDS read of the next
-        // step's operands between consecutive MFMAs of the current one
-        __builtin_amdgcn_sched_group_barrier(0x100, MT + NT, 0);
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[s & 1][j], af[s & 1][i], acc[i][j], 0, 0, 0);
 #pragma unroll
             for (int q = 0; q < MT + NT; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (s < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (MORE && (q & 1)) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
             }
             __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT), 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);
         buf = buf + 1 == kDenseStages ? 0 : buf + 1;
-    }
+    };
+    int kt = 0;
+    for (; kt + 2 < KT; ++kt) k_block(kt, std::true_type{});
+    for (; kt < KT; ++kt) k_block(kt, std::false_type{});
 
-    // epilogue: accumulator register r of lane (ln, lh) is row 8*(r/4) + 4*lh + r%4, column ln
+    // Epilogue.  The weight tile is the MFMA's first operand, so an accumulator holds Y^T: lane (ln, lh),
+    // register r is output row m = ln, column n = 8 (r / 4) + 4 lh + r % 4 of its 32 x 32 block -- four
+    // consecutive columns per lane.  Scaled and rounded, they go through a private LDS region of the
+    // wavefront (rows of 32 NT halves + 16 bytes of padding: conflict-free 8-byte writes and 16-byte reads)
+    // and leave as 16 bytes per lane, whole 128-byte lines per row.  (Two-byte stores straight from the
+    // accumulators, half a line per row and instruction, cost 20 us of an 80 us kernel.)
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");  // every wavefront is done with the ring
+    const int wave_m0 = m0 + wm * 32 * MT, wave_n0 = n0 + wn * 32 * NT;
+    if ((a.N & 7) == 0) {
+        constexpr int kOutRowB = 32 * NT * 2 + 16;
+        constexpr int kSegs = 4 * NT, kRowsPerStore = 64 / kSegs;  // 16-byte segments per row; rows per wave-wide store
+        static_assert(4 * 32 * MT * kOutRowB <= kDenseStages * kStage, "output staging must fit the ring's LDS");
+        unsigned char *out = smem + (size_t)wave * (32 * MT) * kOutRowB;
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int n = n0 + wn * 32 * NT + j * 32 + ln;
-        if (n >= a.N) continue;
-        const float sc = a.scale ? (float)a.scale[n] : 1.f;
+        for (int j = 0; j < NT; ++j) {
 #pragma unroll
-        for (int i = 0; i < MT; ++i) {
+            for (int g = 0; g < 4; ++g) {
+                const int nl = j * 32 + 8 * g + 4 * lh;
+                float sc[4] = {1.f, 1.f, 1.f, 1.f};
+                if (a.scale && wave_n0 + nl < a.N) {  // N is a multiple of 8 here: the four columns are in range together
+                    const half4_t h = *reinterpret_cast<const half4_t *>(a.scale + wave_n0 + nl);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) sc[t] = (float)h[t];
+                }
+#pragma unroll
+                for (int i = 0; i < MT; ++i) {
+                    half4_t o;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) o[t] = (half_t)(acc[i][j][4 * g + t] * sc[t]);
+                    *reinterpret_cast<half4_t *>(out + (i * 32 + ln) * kOutRowB + nl * 2) = o;
+                }
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // same wavefront wrote what it now reads
+#pragma unroll
+        for (int t = 0; t < 32 * MT / kRowsPerStore; ++t) {
+            const int row = t * kRowsPerStore + lane / kSegs, seg = lane % kSegs;
+            const uint4 v = *reinterpret_cast<const uint4 *>(out + row * kOutRowB + seg * 16);
+            const int m = wave_m0 + row, n = wave_n0 + seg * 8;
+            if (m < a.M && n < a.N) *reinterpret_cast<uint4 *>(a.C + (size_t)m * a.N + n) = v;
+        }
+    } else {
+        // rows of Y are not 16-byte aligned: element stores
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * 32 * MT + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                if (m < a.M) a.C[(size_t)m * a.N + n] = (half_t)(acc[i][j][r] * sc);
+                const int n = wave_n0 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (n >= a.N) continue;
+                const float sc = a.scale ? (float)a.scale[n] : 1.f;
+#pragma unroll
+                for (int i = 0; i < MT; ++i) {
+                    const int m = wave_m0 + i * 32 + ln;
+                    if (m < a.M) a.C[(size_t)m * a.N + n] = (half_t)(acc[i][j][r] * sc);
+                }
             }
         }
     }

@@ -109,7 +109,7 @@ size_t attn_decode_workspace(const vq_kv_t *kv);
 int launch_kv_quantize(const vq_kv_t *kv, const void *k_new, const void *v_new, int n_new, int pos, hipStream_t s);
 int launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 int launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t s);
-int launch_probe_mfma(int workgroups, int iters, void *sink, hipStream_t s);
+int launch_probe_mfma(int workgroups, int iters, int random_operands, void *sink, hipStream_t s);
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_LAUNCH; }
 

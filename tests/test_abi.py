@@ -230,9 +230,9 @@ def test_probe_argument_validation():
     assert lib.vq_probe_copy(P, P, 15, None) == VQ_ERR_SHAPE
     assert lib.vq_probe_read(P + 4, 16, P, None) == VQ_ERR_ALIGN
     assert lib.vq_probe_copy(P, P, 0, None) == 0
-    assert lib.vq_probe_mfma(1, 1, None, None) == VQ_ERR_NULL
-    assert lib.vq_probe_mfma(-1, 1, P, None) == VQ_ERR_SHAPE
-    assert lib.vq_probe_mfma(0, 1, P, None) == 0
+    assert lib.vq_probe_mfma(1, 1, 0, None, None) == VQ_ERR_NULL
+    assert lib.vq_probe_mfma(-1, 1, 0, P, None) == VQ_ERR_SHAPE
+    assert lib.vq_probe_mfma(0, 1, 1, P, None) == 0
 
 
 def test_binding_refuses_host_tensors():

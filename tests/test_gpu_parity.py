@@ -273,6 +273,8 @@ def test_gemm_other_formats_use_row_path(gpu_device):
     (300, 130, 256, 8, 8, 2, 256),      # additive uint8 pairs, ragged tiles
     (513, 257, 192, 4, 16, 3, 500),     # three residual codebooks, v = 4
     (1025, 64, 64, 8, 8, 1, 256),       # one K block, five M tiles
+    (700, 200, 320, 8, 8, 1, 256),      # rows of Y 16-byte aligned (vector stores), ragged in M and N
+    (257, 136, 128, 4, 8, 2, 64),       # same store path, second N tile holds one 8-column segment
 ])
 def test_gemm_large_m_any_format_two_stage(gpu_device, M, N, K, v, bits, R, E):
     w = wl.make_weight(N, K, v, bits, R, E, 0.02 / R, seed=4700 + M)
