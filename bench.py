@@ -434,8 +434,7 @@ def main():
         x = torch.from_numpy(wl.make_activations(1, K, wl.seed_for(2, K))).to(dev)
         y = torch.empty((1, N), dtype=torch.float16, device=dev)
         ws = vq.new_workspace(4 << 20, dev)
-        variants = {"canonical_entries_in_quantizer_order": [], "canonical_reordered_by_frequency": [],
-                    "packed_entries_in_quantizer_order": [], "packed_reordered_by_frequency": []}
+        variants = {"canonical_entries_in_quantizer_order": [], "canonical_reordered_by_frequency": []}
         hot_frac = 0.0
         for layer in range(n_copies):
             w = wl.shuffle_entries(wl.make_weight(N, K, 8, 16, 1, 65536, 0.02, wl.seed_for(6, layer), zipf_s=1.0),
@@ -444,10 +443,10 @@ def main():
             hot_frac += float((r.codes < 4096).mean()) / n_copies
             variants["canonical_entries_in_quantizer_order"].append(GemvCall(vq.weight_to_device(w, dev), x, y))
             variants["canonical_reordered_by_frequency"].append(GemvCall(vq.weight_to_device(r, dev), x, y))
-            variants["packed_entries_in_quantizer_order"].append(
-                GemvCall(vq.weight_to_device(w, dev, prepack=True, keep_codes=False), x, y, ws))
-            variants["packed_reordered_by_frequency"].append(
-                GemvCall(vq.weight_to_device(r, dev, prepack=True, keep_codes=False), x, y, ws))
+            # the re-tiled form needs codes that spread evenly over the codebook slices
+            if layer == 0:
+                zipf["vq_gemv_prepack_declines_these_codes"] = bool(vq.vq_gemv_prepack(w)[0] is None and
+                                                                    vq.vq_gemv_prepack(r)[0] is None)
         for name, cs in variants.items():
             def loop(cs=cs):
                 for c in cs:

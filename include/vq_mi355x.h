@@ -56,15 +56,23 @@ typedef enum vq_status {
  * that point into its slice, stored as 24-bit "atoms" (entry index inside the slice, sub-vector
  * position j, valid bit), one row per lane, rows of similar length grouped 64 at a time.  Partial
  * sums of the S slices are added in a fixed order by a second kernel (Sec. VI-A "global reduction").
- * Layout of `data`: see the format description in the source of vq_gemv_prepack.
+ * Every workgroup's atoms have one common shape: its g-th group of 64 rows takes group_steps[g] steps
+ * (768-byte blocks) and starts at block  wg * wg_pitch + sum_{g' < g} group_steps[g'],  so the kernel
+ * derives every address from this struct alone and reads no table before it can ask for its codes.  That
+ * needs codes that spread evenly over the codebook (as quantizers produce them): vq_gemv_prepack declines
+ * (VQ_ERR_UNSUPPORTED, vq_gemv_prepack_bytes = 0) when padding to the common shape would cost more than a
+ * quarter more blocks, or a workgroup has more than VQ_PACK_MAX_GROUPS groups; vq_gemv then runs from the
+ * canonical codes.  Layout of `data`: see the format description in the source of vq_gemv_prepack.
  */
+#define VQ_PACK_MAX_GROUPS 128
 typedef struct vq_gemv_pack_t {
     const void *data;         /* DEVICE pointer when passed to vq_gemv (HOST buffer while packing) */
     uint64_t bytes;           /* size of data */
     uint32_t S, RB;           /* codebook slices, row blocks; S * RB workgroups */
     uint32_t rows_per_block;
-    uint32_t n_groups;        /* 64-row groups in total */
-    uint64_t wg_off, group_off, rowid_off, atom_off; /* byte offsets of the four tables in data */
+    uint32_t wg_pitch;        /* 768-byte atom blocks per workgroup (the sum of group_steps) */
+    uint64_t rowid_off, atom_off; /* byte offsets of the two tables in data */
+    uint16_t group_steps[VQ_PACK_MAX_GROUPS]; /* steps of group g of every workgroup; 0 past the last group */
 } vq_gemv_pack_t;
 
 /*

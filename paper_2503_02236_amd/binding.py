@@ -26,9 +26,9 @@ class VQError(RuntimeError):
 
 class vq_gemv_pack_t(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("bytes", ctypes.c_uint64), ("S", ctypes.c_uint32), ("RB", ctypes.c_uint32),
-                ("rows_per_block", ctypes.c_uint32), ("n_groups", ctypes.c_uint32),
-                ("wg_off", ctypes.c_uint64), ("group_off", ctypes.c_uint64), ("rowid_off", ctypes.c_uint64),
-                ("atom_off", ctypes.c_uint64)]
+                ("rows_per_block", ctypes.c_uint32), ("wg_pitch", ctypes.c_uint32),
+                ("rowid_off", ctypes.c_uint64), ("atom_off", ctypes.c_uint64),
+                ("group_steps", ctypes.c_uint16 * 128)]
 
 
 class vq_weight_t(ctypes.Structure):

@@ -18,12 +18,17 @@
 // same trip count.  The S partial sums of a row are added in slice order by a second small
 // kernel (Sec. VI-A "explicit global reduction"), which keeps the result bit-reproducible.
 //
-// Packed buffer (little endian, all offsets from the start of the buffer, 256-byte aligned):
-//   wg table     [S*RB]      { uint32 first_group, uint32 n_groups }   workgroup = s*RB + rb; every
-//                            workgroup has ceil(rows_per_block / 64) groups, so first_group = wg * n_groups
-//   group table  [n_groups]  { uint32 atom_block, uint32 n_steps }     atom_block in 768-byte units
-//   row ids      [n_groups][64] uint16   row inside the block, 0xFFFF = idle lane
+// Packed buffer (little endian, offsets from the start of the buffer, 256-byte aligned):
+//   row ids      [S*RB][G][64] uint16   row inside the block, 0xFFFF = idle lane; G = ceil(rows_per_block / 64)
 //   atoms        blocks of 768 bytes = 64 lanes x 12 bytes = 4 atoms per lane per step
+// Placement of the atom blocks.  A kernel that has to read a table before it can ask for its atoms
+// pays two dependent first touches of memory (~1.5 us each) before any work.  Codes that spread evenly
+// over the codebook make group g look nearly the same in every workgroup (the g-th 64 rows of a sorted
+// list of equally distributed lengths), so all workgroups are padded to one common shape: group g has
+// group_steps[g] steps everywhere (the maximum over the workgroups; ~5 % more blocks at Llama-7B shapes)
+// and starts at block wg * wg_pitch + sum_{g' < g} group_steps[g'].  Those few numbers travel in the
+// descriptor and reach the kernel as launch arguments.  Codes too uneven for that (more than a quarter
+// more blocks) are declined: the canonical-code kernels serve them.
 #include <algorithm>
 #include <cstring>
 #include <vector>
@@ -87,12 +92,14 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
         for (int j = 0; j < J; ++j) cnt[((size_t)(row[j] >> lb) * p.RB + rb) * p.rows_per_block + ri]++;
     }
     // per workgroup: rows sorted by count (descending, ties by row), groups of 64
-    struct Group { uint32_t atom_block, n_steps; };
-    std::vector<uint32_t> wg_tab((size_t)nwg * 2);
-    std::vector<Group> groups;
+    const uint32_t ng = (p.rows_per_block + 63) / 64;
+    if (ng > VQ_PACK_MAX_GROUPS) return 0;
+    std::vector<uint32_t> steps((size_t)nwg * ng, 0);   // steps a group needs
     std::vector<uint16_t> rowids;
+    rowids.reserve((size_t)nwg * ng * 64);
     std::vector<uint32_t> order(p.rows_per_block);
-    uint64_t atom_blocks = 0;
+    std::vector<uint32_t> max_steps(ng, 0);
+    uint64_t needed_blocks = 0;
     for (uint32_t wg = 0; wg < nwg; ++wg) {
         uint32_t rb = wg % p.RB;
         uint32_t rows_here = 0;
@@ -101,24 +108,27 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
         const uint32_t *c = &cnt[(size_t)wg * p.rows_per_block];
         for (uint32_t i = 0; i < rows_here; ++i) order[i] = i;
         std::stable_sort(order.begin(), order.begin() + rows_here, [&](uint32_t a, uint32_t b) { return c[a] > c[b]; });
-        wg_tab[2 * wg] = (uint32_t)groups.size();   // always wg * groups_per_wg: the kernel computes it
-        const uint32_t ng = (p.rows_per_block + 63) / 64;
-        wg_tab[2 * wg + 1] = ng;
         for (uint32_t g = 0; g < ng; ++g) {
-            Group gr;
-            gr.atom_block = (uint32_t)atom_blocks;
-            gr.n_steps = g * 64 < rows_here ? (c[order[g * 64]] + 3) / 4 : 0;  // a group's first row is its longest
-            atom_blocks += gr.n_steps;
-            groups.push_back(gr);
+            const uint32_t st = g * 64 < rows_here ? (c[order[g * 64]] + 3) / 4 : 0;  // a group's first row is its longest
+            steps[(size_t)wg * ng + g] = st;
+            needed_blocks += st;
+            max_steps[g] = std::max(max_steps[g], st);
             for (uint32_t l = 0; l < 64; ++l) {
                 uint32_t i = g * 64 + l;
                 rowids.push_back(i < rows_here ? (uint16_t)order[i] : (uint16_t)0xFFFF);
             }
         }
     }
-    const uint64_t wg_off = 0;
-    const uint64_t group_off = align256(wg_off + wg_tab.size() * 4);
-    const uint64_t rowid_off = align256(group_off + groups.size() * sizeof(Group));
+    // the common shape of all workgroups
+    uint64_t pitch = 0;
+    std::vector<uint32_t> prefix(ng, 0);
+    for (uint32_t g = 0; g < ng; ++g) {
+        prefix[g] = (uint32_t)pitch;
+        pitch += max_steps[g];
+    }
+    if (pitch > 65535 || pitch * nwg > needed_blocks + needed_blocks / 4 + nwg) return 0;  // too uneven
+    const uint64_t atom_blocks = pitch * nwg;
+    const uint64_t rowid_off = 0;
     const uint64_t atom_off = align256(rowid_off + rowids.size() * 2);
     const uint64_t total = atom_off + atom_blocks * 768;
     if (pack) {
@@ -127,34 +137,31 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
         pack->S = p.S;
         pack->RB = p.RB;
         pack->rows_per_block = p.rows_per_block;
-        pack->n_groups = (uint32_t)groups.size();
-        pack->wg_off = wg_off;
-        pack->group_off = group_off;
+        pack->wg_pitch = (uint32_t)pitch;
         pack->rowid_off = rowid_off;
         pack->atom_off = atom_off;
+        for (uint32_t g = 0; g < VQ_PACK_MAX_GROUPS; ++g) pack->group_steps[g] = g < ng ? (uint16_t)max_steps[g] : (uint16_t)0;
     }
     if (!out) return total;
 
     std::memset(out, 0, (size_t)atom_off);
-    std::memcpy(out + wg_off, wg_tab.data(), wg_tab.size() * 4);
-    std::memcpy(out + group_off, groups.data(), groups.size() * sizeof(Group));
     std::memcpy(out + rowid_off, rowids.data(), rowids.size() * 2);
     unsigned char *atoms = out + atom_off;
     std::memset(atoms, 0, (size_t)(atom_blocks * 768));
-    // fill: lane l of group g walks row rowids[g][l]; its k-th atom of slice s goes to step k/4, slot k%4
+    // fill: lane l of group g walks row rowids[wg][g][l]; its k-th atom of slice s goes to step k/4, slot k%4
     for (uint32_t wg = 0; wg < nwg; ++wg) {
         uint32_t s = wg / p.RB, rb = wg % p.RB;
-        for (uint32_t g = 0; g < wg_tab[2 * wg + 1]; ++g) {
-            const Group &gr = groups[wg_tab[2 * wg] + g];
+        for (uint32_t g = 0; g < ng; ++g) {
+            const uint64_t first_block = (uint64_t)wg * pitch + prefix[g];
             for (uint32_t l = 0; l < 64; ++l) {
-                uint16_t ri = rowids[((size_t)wg_tab[2 * wg] + g) * 64 + l];
+                uint16_t ri = rowids[((size_t)wg * ng + g) * 64 + l];
                 if (ri == 0xFFFF) continue;
                 const uint16_t *row = codes + ((size_t)rb * p.rows_per_block + ri) * J;
                 uint32_t k = 0;
                 for (int j = 0; j < J; ++j) {
                     if ((uint32_t)(row[j] >> lb) != s) continue;
                     uint32_t atom = (row[j] & ((1u << lb) - 1)) | ((uint32_t)j << kPackLocalBits) | kPackValid;
-                    unsigned char *q = atoms + ((size_t)gr.atom_block + k / 4) * 768 + l * 12 + (k % 4) * 3;
+                    unsigned char *q = atoms + (first_block + k / 4) * 768 + l * 12 + (k % 4) * 3;
                     q[0] = (unsigned char)atom;
                     q[1] = (unsigned char)(atom >> 8);
                     q[2] = (unsigned char)(atom >> 16);
@@ -168,22 +175,40 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
 
 // ---------------------------------------------------------------------------------- kernel
 
-struct PackedArgs {
+// What the main kernel needs of the launch arguments before its first vector load leaves ...
+struct PackedCore {
     const unsigned char *data;
-    const half_t *cb, *scale, *x;
-    half_t *y;
+    const half_t *cb, *x;
     float *partial;       // [S][N]
     int N, J, S, RB, rows_per_block, slice_entries;
-    unsigned long long wg_off, group_off, rowid_off, atom_off;
+    unsigned long long rowid_off, atom_off;
+    unsigned wg_pitch;    // group g of workgroup wg: atom blocks from wg * wg_pitch + prefix[g] on
+    int nwaves;           // wavefronts per workgroup of the launch (saves a load of the hidden launch arguments)
 };
+// ... and the rest: one 32-bit word per group, prefix << 16 | steps, so that a scalar load can fetch it
+struct PackedArgs : PackedCore {
+    const half_t *scale;
+    half_t *y;
+    uint32_t group[VQ_PACK_MAX_GROUPS];
+};
+
+// Keeps a launch argument in scalar registers from here on.  Left to itself the compiler fetches each
+// argument where it is first used (and again later rather than keep it): seven dependent round trips of
+// 35 - 400 ns each at the head of the gemv kernel, before the first vector load leaves.
+template <class T>
+__device__ __forceinline__ void pin_scalar(T &v) {
+    asm volatile("" : "+s"(v));
+}
 
 constexpr int kPackMaxSlices = 64;  // 2^16 entries / 1024 per slice
 constexpr int kPackPrefetch = 10;      // 4-atom steps fetched into registers while the slice is being staged
 constexpr int kPackPrefetchBatch = 4;  // batch kernel: a ring of 4 steps in flight (80 registers, three workgroups per CU)
 
-__device__ __forceinline__ float atom_dot(uint32_t atom, const unsigned char *slice, const unsigned char *xl, float acc) {
-    V16 e = *reinterpret_cast<const V16 *>(slice + ((atom & 0xfffu) << 4));
-    V16 xv = *reinterpret_cast<const V16 *>(xl + (((atom >> kPackLocalBits) & 0x7ffu) << 4));
+struct Acc4 {
+    float a0, a1, a2, a3;
+};
+
+__device__ __forceinline__ float atom_fma(uint32_t atom, const V16 &e, const V16 &xv, float acc) {
     float d = dot2(e.h2[0], xv.h2[0], 0.f);
     d = dot2(e.h2[1], xv.h2[1], d);
     d = dot2(e.h2[2], xv.h2[2], d);
@@ -191,28 +216,50 @@ __device__ __forceinline__ float atom_dot(uint32_t atom, const unsigned char *sl
     return (atom & kPackValid) ? acc + d : acc;
 }
 
-struct Acc4 {
-    float a0, a1, a2, a3;
-};
-
+// One step = the lane's next four atoms (three dwords).  The LDS gathers (entry and x_j of each atom)
+// of CL atoms are issued before the first dot product: taken one atom at a time, as the compiler orders
+// them when left alone, every atom waits out a full LDS round trip (~90 clocks per gather with eight
+// wavefronts asking) and the gather phase of a 4096 x 4096 launch lasts 3.1 us.  CL = 4 keeps 32
+// registers of operands in flight, CL = 2 half of that (for the kernels held to 128 registers).
+template <int CL>
 __device__ __forceinline__ void step_dot(uint32_t d0, uint32_t d1, uint32_t d2, const unsigned char *slice,
                                          const unsigned char *xl, Acc4 &acc) {
-    acc.a0 = atom_dot(d0 & 0xffffffu, slice, xl, acc.a0);
-    acc.a1 = atom_dot(__builtin_amdgcn_alignbit(d1, d0, 24) & 0xffffffu, slice, xl, acc.a1);
-    acc.a2 = atom_dot(__builtin_amdgcn_alignbit(d2, d1, 16) & 0xffffffu, slice, xl, acc.a2);
-    acc.a3 = atom_dot(d2 >> 8, slice, xl, acc.a3);
+    const uint32_t at[4] = {d0 & 0xffffffu, __builtin_amdgcn_alignbit(d1, d0, 24) & 0xffffffu,
+                            __builtin_amdgcn_alignbit(d2, d1, 16) & 0xffffffu, d2 >> 8};
+    float *accs[4] = {&acc.a0, &acc.a1, &acc.a2, &acc.a3};
+#pragma unroll
+    for (int h = 0; h < 4; h += CL) {
+        V16 e[CL], xv[CL];
+#pragma unroll
+        for (int i = 0; i < CL; ++i) {
+            e[i] = *reinterpret_cast<const V16 *>(slice + ((at[h + i] & 0xfffu) << 4));
+            xv[i] = *reinterpret_cast<const V16 *>(xl + (((at[h + i] >> kPackLocalBits) & 0x7ffu) << 4));
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * CL, 0);  // these LDS reads first,
+        __builtin_amdgcn_sched_group_barrier(0x002, 8 * CL, 0);  // then the arithmetic on them
+#pragma unroll
+        for (int i = 0; i < CL; ++i) *accs[h + i] = atom_fma(at[h + i], e[i], xv[i], *accs[h + i]);
+    }
 }
 
 // All global loads of a workgroup are issued before anything waits: the kernel is a chain of
 // memory latencies (tables -> atoms -> partials), not a bandwidth problem, at these sizes.
-template <int PF, bool RING>
-__device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int bid) {
+template <int PF, bool RING, int CL>
+__device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int bid) {
     extern __shared__ __align__(16) unsigned char smem[];
+    // all launch arguments in one round of scalar loads
+    const int wave = threadIdx.x >> 6;
+    uint32_t group_word = ka.group[__builtin_amdgcn_readfirstlane(wave)];
+    PackedCore a = ka;
+    pin_scalar(a.data); pin_scalar(a.cb); pin_scalar(a.x); pin_scalar(a.partial);
+    pin_scalar(a.N); pin_scalar(a.J); pin_scalar(a.S); pin_scalar(a.RB); pin_scalar(a.rows_per_block);
+    pin_scalar(a.slice_entries); pin_scalar(a.rowid_off); pin_scalar(a.atom_off); pin_scalar(a.wg_pitch);
+    pin_scalar(a.nwaves); pin_scalar(group_word);
     unsigned char *slice = smem;                                    // slice_entries * 16 bytes
     unsigned char *xl = smem + (size_t)a.slice_entries * 16;        // J * 16 bytes
     float *accbuf = reinterpret_cast<float *>(xl + (size_t)a.J * 16);  // one float per row of the block
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nwaves = blockDim.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, nwaves = a.nwaves;
     // Workgroups are dealt round-robin to the 8 compute dies, each with its own L2.  All row blocks of
     // one codebook slice run on the same die, so a slice is fetched from memory by one L2 only
     // (otherwise every die pulls the whole 1 MiB codebook: 8 MiB per launch).
@@ -226,9 +273,10 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int 
         rb = bid % a.RB;
     }
     const int wg = s * a.RB + rb;  // index into the packed tables
-    const uint2 *gtab = reinterpret_cast<const uint2 *>(a.data + a.group_off);
     const uint16_t *rowids = reinterpret_cast<const uint16_t *>(a.data + a.rowid_off);
-    const unsigned char *atoms = a.data + a.atom_off + lane * 12;
+    // atom block b of this lane: a scalar base (block numbers are wave-uniform) plus a 32-bit lane offset
+    const unsigned char *atoms = a.data + a.atom_off;
+    const uint32_t lane_off = (uint32_t)lane * 12u;
 
     // (1) codebook slice and x go straight from global memory into LDS (no registers): one
     //     wave-wide 1 KiB transfer per 64 entries, lane l's 16 bytes land at base + 16 l
@@ -245,28 +293,29 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int 
                 __builtin_amdgcn_global_load_lds((global_void_t *)(xs + c * 64 + lane), (lds_void_t *)(xl + c * 1024),
                                                  16, 0, 0);
     }
-    // (2) this wavefront's first group: table entry, row ids, then its atoms
+    // (2) this wavefront's first group: where its atoms lie follows from the launch arguments alone, so
+    //     the row ids and the atoms are requested together with the slice
     const uint32_t n_groups = (uint32_t)(a.rows_per_block + 63) / 64, first_group = (uint32_t)wg * n_groups;
-    uint2 gr = make_uint2(0, 0);
+    auto group_of = [&](uint32_t word) { return make_uint2((uint32_t)wg * a.wg_pitch + (word >> 16), word & 0xffffu); };
+    uint2 gr = make_uint2(0, 0);  // .x first atom block, .y steps
     uint32_t ri = 0xFFFFu;
     if ((uint32_t)wave < n_groups) {
-        gr = gtab[first_group + wave];
+        gr = group_of(group_word);
         ri = rowids[((size_t)first_group + wave) * 64 + lane];
     }
     // atoms of steps 0 .. PF-1 of that group into a ring of registers
     uint32_t q[PF][3];
+    // (ring form) unconditional: a step past the end re-reads the group's last block and is never used.  With
+    // a branch around the load the compiler can no longer count which loads are still in flight and waits
+    // for all of them before every use.  Only for groups with at least one step.
     auto load_step = [&](uint32_t (&dst)[3], uint32_t first, uint32_t st, uint32_t steps) {
-        if (st < steps) {
-            const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)first + st) * 768);
-            dst[0] = p[0]; dst[1] = p[1]; dst[2] = p[2];
-        } else {
-            dst[0] = dst[1] = dst[2] = 0;
-        }
+        const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)first + min(st, steps - 1)) * 768 + lane_off);
+        dst[0] = p[0]; dst[1] = p[1]; dst[2] = p[2];
     };
 #pragma unroll
     for (int st = 0; st < PF; ++st) {
         if ((uint32_t)st < gr.y) {
-            const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768);
+            const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768 + lane_off);
             q[st][0] = p[0]; q[st][1] = p[1]; q[st][2] = p[2];
         } else {
             q[st][0] = q[st][1] = q[st][2] = 0;
@@ -280,11 +329,13 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int 
     // (4) gathers and dot products: lane = row; results go to LDS in natural row order
     for (uint32_t g = wave; g < n_groups; g += nwaves) {
         if (g != (uint32_t)wave) {  // later groups of this wavefront (only when a block has more than 16 groups)
-            gr = gtab[first_group + g];
+            gr = group_of(ka.group[__builtin_amdgcn_readfirstlane(g)]);  // (scalar index: a scalar load)
             ri = rowids[((size_t)first_group + g) * 64 + lane];
             if constexpr (RING) {
+                if (gr.y > 0) {
 #pragma unroll
-                for (int k = 0; k < PF; ++k) load_step(q[k], gr.x, k, gr.y);
+                    for (int k = 0; k < PF; ++k) load_step(q[k], gr.x, k, gr.y);
+                }
             }
         }
         Acc4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -296,7 +347,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int 
                 for (int k = 0; k < PF; ++k) {
                     const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
                     load_step(q[k], gr.x, base + k + PF, gr.y);
-                    if (base + k < gr.y) step_dot(d0, d1, d2, slice, xl, acc);
+                    if (base + k < gr.y) step_dot<CL>(d0, d1, d2, slice, xl, acc);
                 }
             }
         } else {
@@ -306,12 +357,12 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int 
             if (g == (uint32_t)wave) {
 #pragma unroll
                 for (int st = 0; st < PF; ++st)
-                    if ((uint32_t)st < gr.y) step_dot(q[st][0], q[st][1], q[st][2], slice, xl, acc);
+                    if ((uint32_t)st < gr.y) step_dot<CL>(q[st][0], q[st][1], q[st][2], slice, xl, acc);
                 st0 = PF;
             }
             for (uint32_t st = st0; st < gr.y; ++st) {
-                const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768);
-                step_dot(p[0], p[1], p[2], slice, xl, acc);
+                const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768 + lane_off);
+                step_dot<CL>(p[0], p[1], p[2], slice, xl, acc);
             }
         }
         if (ri != 0xFFFFu) accbuf[ri] = (acc.a0 + acc.a1) + (acc.a2 + acc.a3);
@@ -330,7 +381,10 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &a, const int 
     }
 }
 
-__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body<kPackPrefetch, false>(a, blockIdx.x); }
+// Two builds of the single-problem kernel: up to 8 wavefronts (512 threads, up to 256 registers: the full
+// gather cluster) and up to 16 (held to 128 registers: half clusters).
+__global__ __launch_bounds__(512) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body<kPackPrefetch, false, 4>(a, blockIdx.x); }
+__global__ __launch_bounds__(1024) void gemv_packed_wide_kernel(PackedArgs a) { gemv_packed_body<kPackPrefetch, false, 2>(a, blockIdx.x); }
 
 // Several independent problems in one launch (blockIdx.y picks the problem): the fixed latencies of a
 // launch (ramp-up, first touches of tables and atoms, drain) are paid once for all of them, and
@@ -342,7 +396,7 @@ struct PackedBatch {
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void gemv_packed_batch_kernel(PackedBatch b) {
     const PackedArgs &a = b.a[blockIdx.y];
     if ((int)blockIdx.x >= a.S * a.RB) return;
-    gemv_packed_body<kPackPrefetchBatch, true>(a, blockIdx.x);
+    gemv_packed_body<kPackPrefetchBatch, true, 4>(a, blockIdx.x);
 }
 
 // y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.  MAXS loads are issued unconditionally
@@ -351,7 +405,7 @@ template <int MAXS>
 __device__ __forceinline__ void gemv_packed_finalize_body(const float *__restrict__ partial,
                                                           const half_t *__restrict__ scale, half_t *__restrict__ y,
                                                           int N, int S) {
-    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = blockIdx.x * 256 + threadIdx.x;  // (the launch shape is fixed: no load of the hidden arguments)
     if (n >= N) return;
     float v[MAXS];
 #pragma unroll
@@ -369,8 +423,18 @@ __global__ __launch_bounds__(256) void gemv_packed_finalize_kernel(const float *
     else
         gemv_packed_finalize_body<kPackMaxSlices>(partial, scale, y, N, S);
 }
-__global__ __launch_bounds__(256) void gemv_packed_finalize_batch_kernel(PackedBatch b) {
-    const PackedArgs &a = b.a[blockIdx.y];
+struct FinalizeArgs {
+    const float *partial;
+    const half_t *scale;
+    half_t *y;
+    int N, S;
+};
+struct FinalizeBatch {
+    FinalizeArgs a[kPackMaxBatch];
+};
+__global__ __launch_bounds__(256) void gemv_packed_finalize_batch_kernel(FinalizeBatch b) {
+    FinalizeArgs a = b.a[blockIdx.y];
+    pin_scalar(a.partial); pin_scalar(a.scale); pin_scalar(a.y); pin_scalar(a.N); pin_scalar(a.S);
     if (a.S <= 32)
         gemv_packed_finalize_body<32>(a.partial, a.scale, a.y, a.N, a.S);
     else
@@ -393,7 +457,14 @@ int check_pack(const vq_weight_t *w) {
     PackPlan plan = pack_plan(w);
     if (p->S != plan.S || p->RB != plan.RB || p->rows_per_block != plan.rows_per_block) return VQ_ERR_SHAPE;
     if (p->S > (uint32_t)kPackMaxSlices) return VQ_ERR_UNSUPPORTED;
-    if (p->atom_off > p->bytes || p->rowid_off > p->atom_off || p->group_off > p->rowid_off) return VQ_ERR_SHAPE;
+    // every address the kernel derives from the descriptor must lie inside the buffer
+    const uint64_t ng = (plan.rows_per_block + 63) / 64, nwg = (uint64_t)p->S * p->RB;
+    if (ng > VQ_PACK_MAX_GROUPS) return VQ_ERR_SHAPE;
+    uint64_t sum = 0;
+    for (uint64_t g = 0; g < ng; ++g) sum += p->group_steps[g];
+    if (sum != p->wg_pitch || sum > 65535) return VQ_ERR_SHAPE;
+    if (p->rowid_off + nwg * ng * 128 > p->atom_off || p->atom_off + nwg * sum * 768 > p->bytes) return VQ_ERR_SHAPE;
+    if ((p->rowid_off & 1) || (p->atom_off & 3)) return VQ_ERR_ALIGN;
     return VQ_OK;
 }
 
@@ -422,14 +493,21 @@ PackedLaunch packed_launch(const vq_weight_t *w, const void *x, void *y, void *p
     a.RB = (int)p->RB;
     a.rows_per_block = (int)p->rows_per_block;
     a.slice_entries = (int)plan.slice_entries;
-    a.wg_off = p->wg_off;
-    a.group_off = p->group_off;
     a.rowid_off = p->rowid_off;
     a.atom_off = p->atom_off;
+    a.wg_pitch = p->wg_pitch;
+    {
+        unsigned at = 0;
+        for (int g = 0; g < VQ_PACK_MAX_GROUPS; ++g) {
+            a.group[g] = (at << 16) | p->group_steps[g];
+            at += p->group_steps[g];
+        }
+    }
     int groups_per_wg = (int)((p->rows_per_block + 63) / 64);
     l.lds = (size_t)plan.slice_entries * 16 + (size_t)a.J * 16 + (size_t)groups_per_wg * 64 * sizeof(float);
     l.waves = groups_per_wg < 16 ? groups_per_wg : 16;
     if (l.waves < 8) l.waves = 8;   // at least 512 threads, so that slice and x are staged with many loads in flight
+    a.nwaves = l.waves;
     l.grid = (int)(p->S * p->RB);
     return l;
 }
@@ -445,9 +523,14 @@ void packed_lds_attr(const void *kernel, size_t lds, size_t *set) {
 
 int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, hipStream_t s) {
     PackedLaunch l = packed_launch(w, x, y, ws);
-    static size_t attr_lds = 0;
-    packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_kernel), l.lds, &attr_lds);
-    gemv_packed_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
+    static size_t attr_lds = 0, attr_lds_wide = 0;
+    if (l.waves <= 8) {
+        packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_kernel), l.lds, &attr_lds);
+        gemv_packed_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
+    } else {
+        packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_wide_kernel), l.lds, &attr_lds_wide);
+        gemv_packed_wide_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
+    }
     gemv_packed_finalize_kernel<<<(l.a.N + 255) / 256, 256, 0, s>>>(l.a.partial, l.a.scale, l.a.y, l.a.N, l.a.S);
     return launch_status();
 }
@@ -478,8 +561,11 @@ int launch_gemv_packed_batch(const vq_weight_t *const *w, const void *const *x, 
     }
     static size_t attr_lds = 0;
     packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_batch_kernel), lds, &attr_lds);
+    for (int i = 0; i < kPackMaxBatch; ++i) b.a[i].nwaves = waves;  // one launch shape for all problems
     gemv_packed_batch_kernel<<<dim3(grid, count), waves * 64, lds, s>>>(b);
-    gemv_packed_finalize_batch_kernel<<<dim3((max_n + 255) / 256, count), 256, 0, s>>>(b);
+    FinalizeBatch f;
+    for (int i = 0; i < kPackMaxBatch; ++i) f.a[i] = {b.a[i].partial, b.a[i].scale, b.a[i].y, b.a[i].N, b.a[i].S};
+    gemv_packed_finalize_batch_kernel<<<dim3((max_n + 255) / 256, count), 256, 0, s>>>(f);
     return launch_status();
 }
 

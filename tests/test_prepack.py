@@ -13,23 +13,25 @@ from paper_2503_02236_amd import workloads as wl
 def decode(buf, pack, N, J, SLICE):
     """Packed buffer -> codes[N][J] plus per-position hit counts, following the documented layout."""
     S, RB, RPB = pack.S, pack.RB, pack.rows_per_block
-    wg = np.frombuffer(buf, dtype=np.uint32, count=2 * S * RB, offset=pack.wg_off).reshape(S * RB, 2)
-    groups = np.frombuffer(buf, dtype=np.uint32, count=2 * pack.n_groups, offset=pack.group_off).reshape(-1, 2)
-    rowids = np.frombuffer(buf, dtype=np.uint16, count=64 * pack.n_groups, offset=pack.rowid_off).reshape(-1, 64)
+    ng = (RPB + 63) // 64
+    steps = [int(pack.group_steps[g]) for g in range(ng)]
+    assert sum(steps) == pack.wg_pitch and all(int(pack.group_steps[g]) == 0 for g in range(ng, 128))
+    prefix = np.concatenate([[0], np.cumsum(steps)])
+    rowids = np.frombuffer(buf, dtype=np.uint16, count=64 * ng * S * RB, offset=pack.rowid_off).reshape(S * RB, ng, 64)
     atoms = np.frombuffer(buf, dtype=np.uint8, offset=pack.atom_off)
+    assert atoms.size == S * RB * pack.wg_pitch * 768
     codes = np.zeros((N, J), dtype=np.int64)
     hits = np.zeros((N, J), dtype=np.int32)
     for w in range(S * RB):
         s, rb = divmod(w, RB)
-        first, ng = int(wg[w, 0]), int(wg[w, 1])
         prev_len = None
-        for g in range(first, first + ng):
-            blk, steps = int(groups[g, 0]), int(groups[g, 1])
-            a = atoms[blk * 768:(blk + steps) * 768].reshape(steps, 64, 4, 3).astype(np.uint32)
+        for g in range(ng):
+            blk = w * pack.wg_pitch + int(prefix[g])
+            a = atoms[blk * 768:(blk + steps[g]) * 768].reshape(steps[g], 64, 4, 3).astype(np.uint32)
             val = a[..., 0] | (a[..., 1] << 8) | (a[..., 2] << 16)          # [steps][lane][4]
-            val = val.transpose(1, 0, 2).reshape(64, steps * 4)             # lane-major atom lists
+            val = val.transpose(1, 0, 2).reshape(64, steps[g] * 4)          # lane-major atom lists
             for lane in range(64):
-                ri = int(rowids[g, lane])
+                ri = int(rowids[w, g, lane])
                 lst = val[lane]
                 valid = (lst >> 23) & 1
                 n_valid = int(valid.sum())
@@ -49,22 +51,28 @@ def decode(buf, pack, N, J, SLICE):
     return codes, hits
 
 
-@pytest.mark.parametrize("N,K,E,zipf", [
-    (200, 1024, 65536, None),
-    (64, 512, 4096, None),
-    (513, 2048, 65536, 1.0),       # skewed codes: some (row, slice) cells are empty, lengths vary a lot
-    (1, 64, 65536, None),
-    (70, 16368, 8192, None),       # longest supported rows (K/8 = 2046)
-    (9000, 64, 65536, None),       # many rows: 4096-entry slices, 16 x 16 workgroups
+@pytest.mark.parametrize("N,K,E", [
+    (200, 1024, 65536),
+    (64, 512, 4096),
+    (513, 2048, 65536),
+    (1, 64, 65536),
+    (70, 16368, 8192),       # longest supported rows (K/8 = 2046)
+    (9000, 64, 65536),       # many rows: 4096-entry slices, 16 x 16 workgroups
 ])
-def test_prepack_round_trip(N, K, E, zipf):
-    w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=77 + N, zipf_s=zipf)
+def test_prepack_round_trip(N, K, E):
+    w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=77 + N)
     buf, pack = vq.vq_gemv_prepack(w)
     assert buf is not None and pack.bytes == buf.size
     assert pack.S in (E // 2048, E // 4096) and pack.S * pack.RB <= 256
     codes, hits = decode(buf, pack, N, K // 8, E // pack.S)
     assert (hits == 1).all()                       # every code appears exactly once
     assert np.array_equal(codes, w.codes[:, :, 0].astype(np.int64))
+
+
+def test_prepack_declines_uneven_codes():
+    """Skewed codes: the slices' loads differ so much that one common workgroup shape would be mostly padding."""
+    w = wl.make_weight(513, 2048, 8, 16, 1, 65536, 0.02, seed=590, zipf_s=1.0)
+    assert vq.vq_gemv_prepack(w) == (None, None)
 
 
 def test_prepack_is_deterministic_and_rejects_other_formats():
