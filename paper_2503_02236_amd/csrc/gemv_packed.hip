@@ -31,6 +31,7 @@
 // more blocks) are declined: the canonical-code kernels serve them.
 #include <algorithm>
 #include <cstring>
+#include <type_traits>
 #include <vector>
 
 #include "vq_common.h"
@@ -119,7 +120,8 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
             }
         }
     }
-    // the common shape of all workgroups
+    // the common shape of all workgroups (at least one block each: the kernel's wavefronts without work read it)
+    if (max_steps[0] == 0) max_steps[0] = 1;
     uint64_t pitch = 0;
     std::vector<uint32_t> prefix(ng, 0);
     for (uint32_t g = 0; g < ng; ++g) {
@@ -273,99 +275,120 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
         rb = bid % a.RB;
     }
     const int wg = s * a.RB + rb;  // index into the packed tables
-    const uint16_t *rowids = reinterpret_cast<const uint16_t *>(a.data + a.rowid_off);
+    // (the pinned pointers went through an asm statement and have to be told again that they are global)
+    typedef const __attribute__((address_space(1))) unsigned char gbyte_t;
+    typedef const __attribute__((address_space(1))) uint16_t gu16_t;
+    typedef const __attribute__((address_space(1))) uint32_t gu32_t;
+    gbyte_t *gdata = (gbyte_t *)a.data;
+    gu16_t *rowids = (gu16_t *)(gdata + a.rowid_off);
     // atom block b of this lane: a scalar base (block numbers are wave-uniform) plus a 32-bit lane offset
-    const unsigned char *atoms = a.data + a.atom_off;
+    gbyte_t *atoms = gdata + a.atom_off;
     const uint32_t lane_off = (uint32_t)lane * 12u;
 
     // (1) codebook slice and x go straight from global memory into LDS (no registers): one
-    //     wave-wide 1 KiB transfer per 64 entries, lane l's 16 bytes land at base + 16 l
+    //     wave-wide 1 KiB transfer per 64 entries, lane l's 16 bytes land at base + 16 l.  Written as an
+    //     asm statement: with the builtin the compiler knows that LDS is being written behind its back and
+    //     makes the first LDS read wait for every outstanding load, the atoms included, which puts the whole
+    //     memory phase of a launch in front of its whole gather phase.  The transfers complete in issue order
+    //     with the other loads, and the counted wait below is what orders them against the gathers.
     {
-        typedef __attribute__((address_space(3))) void lds_void_t;
-        typedef const __attribute__((address_space(1))) void global_void_t;
+        typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+        auto dma16 = [](const uint4 *src, unsigned char *dst_wave_base) {
+            const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t *)dst_wave_base);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src) : "memory", "m0");
+        };
         const uint4 *src = reinterpret_cast<const uint4 *>(a.cb) + (size_t)s * a.slice_entries;
         const uint4 *xs = reinterpret_cast<const uint4 *>(a.x);
         for (int c = wave; c * 64 < a.slice_entries; c += nwaves)  // slices are multiples of 64 entries
-            __builtin_amdgcn_global_load_lds((global_void_t *)(src + c * 64 + lane), (lds_void_t *)(slice + c * 1024),
-                                             16, 0, 0);
+            dma16(src + c * 64 + lane, slice + c * 1024);
         for (int c = wave; c * 64 < a.J; c += nwaves)
-            if (c * 64 + lane < a.J)
-                __builtin_amdgcn_global_load_lds((global_void_t *)(xs + c * 64 + lane), (lds_void_t *)(xl + c * 1024),
-                                                 16, 0, 0);
+            if (c * 64 + lane < a.J) dma16(xs + c * 64 + lane, xl + c * 1024);
     }
     // (2) this wavefront's first group: where its atoms lie follows from the launch arguments alone, so
-    //     the row ids and the atoms are requested together with the slice
+    //     the row ids and the atoms are requested right behind the slice.  Loads complete in the order
+    //     they were issued, so the wait below counts the loads of this step as still in flight and lets
+    //     the gathers start as soon as the slice and x are in, while the atoms stream in behind them
+    //     (waiting for everything put the whole memory phase of a launch in front of its whole LDS
+    //     phase).  The empty statement keeps the compiler from moving a load above the staging transfers.
+    asm volatile("" ::: "memory");
     const uint32_t n_groups = (uint32_t)(a.rows_per_block + 63) / 64, first_group = (uint32_t)wg * n_groups;
     auto group_of = [&](uint32_t word) { return make_uint2((uint32_t)wg * a.wg_pitch + (word >> 16), word & 0xffffu); };
-    uint2 gr = make_uint2(0, 0);  // .x first atom block, .y steps
-    uint32_t ri = 0xFFFFu;
-    if ((uint32_t)wave < n_groups) {
-        gr = group_of(group_word);
-        ri = rowids[((size_t)first_group + wave) * 64 + lane];
-    }
-    // atoms of steps 0 .. PF-1 of that group into a ring of registers
-    uint32_t q[PF][3];
-    // (ring form) unconditional: a step past the end re-reads the group's last block and is never used.  With
-    // a branch around the load the compiler can no longer count which loads are still in flight and waits
-    // for all of them before every use.  Only for groups with at least one step.
+    // A step past the end of a group re-reads its last block and is never used: with a branch around a
+    // load the compiler can no longer count which loads are in flight and waits for all of them before
+    // every use.  Only for groups with at least one step.
     auto load_step = [&](uint32_t (&dst)[3], uint32_t first, uint32_t st, uint32_t steps) {
-        const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)first + min(st, steps - 1)) * 768 + lane_off);
+        gu32_t *p = (gu32_t *)(atoms + ((size_t)first + min(st, steps - 1)) * 768 + lane_off);
         dst[0] = p[0]; dst[1] = p[1]; dst[2] = p[2];
     };
+    // Every wavefront issues the same PF + 1 loads, so the count in the wait holds for all of them: one
+    // without a group, or whose group has no step here, reads the row ids of the last group and the first
+    // block of the workgroup (every workgroup has one) and uses neither.
+    const bool has_group = (uint32_t)wave < n_groups;
+    uint2 gr = make_uint2((uint32_t)wg * a.wg_pitch, 0);  // .x first atom block, .y steps
+    if (has_group) gr = group_of(group_word);
+    uint32_t ri = rowids[((size_t)first_group + min((uint32_t)wave, n_groups - 1)) * 64 + lane];
+    uint32_t q[PF][3];  // atoms of steps 0 .. PF-1 (later: the ring of the next PF steps)
+    {
+        const uint32_t first = gr.y > 0 ? gr.x : (uint32_t)wg * a.wg_pitch, steps = max(gr.y, 1u);
 #pragma unroll
-    for (int st = 0; st < PF; ++st) {
-        if ((uint32_t)st < gr.y) {
-            const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768 + lane_off);
-            q[st][0] = p[0]; q[st][1] = p[1]; q[st][2] = p[2];
-        } else {
-            q[st][0] = q[st][1] = q[st][2] = 0;
-        }
+        for (int st = 0; st < PF; ++st) load_step(q[st], first, st, steps);
     }
-    // (3) everything this wavefront asked for has landed (the direct-to-LDS transfers count as vector
-    //     memory loads); after the barrier the slice and x of all wavefronts are visible
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PF + 1) : "memory");  // PF atom loads and the row ids may be pending
+    // (3) the slice and x of this wavefront have landed (direct-to-LDS transfers count as vector memory
+    //     loads); after the barrier those of all wavefronts are visible.  A bare s_barrier: __syncthreads()
+    //     would wait for the atoms as well.
+    asm volatile("s_barrier" ::: "memory");
 
-    // (4) gathers and dot products: lane = row; results go to LDS in natural row order
-    for (uint32_t g = wave; g < n_groups; g += nwaves) {
-        if (g != (uint32_t)wave) {  // later groups of this wavefront (only when a block has more than 16 groups)
-            gr = group_of(ka.group[__builtin_amdgcn_readfirstlane(g)]);  // (scalar index: a scalar load)
-            ri = rowids[((size_t)first_group + g) * 64 + lane];
-            if constexpr (RING) {
-                if (gr.y > 0) {
-#pragma unroll
-                    for (int k = 0; k < PF; ++k) load_step(q[k], gr.x, k, gr.y);
-                }
-            }
-        }
+    // (4) gathers and dot products: lane = row; results go to LDS in natural row order.  PRE: the group's
+    //     first PF steps are already in q (always so in the ring form).  The wavefront's first group is
+    //     handled outside the loop over further groups: as a loop-carried value q would be copied at the
+    //     loop head, and a copy needs the data -- all of it, at once.
+    auto run_group = [&](auto pre_tag, const uint2 gr, const uint32_t ri) {
+        constexpr bool PRE = decltype(pre_tag)::value;
         Acc4 acc = {0.f, 0.f, 0.f, 0.f};
         if constexpr (RING) {
             // the ring always holds the next PF steps: slot k is refilled with step st + PF as soon as
             // step st has been taken out of it
-            for (uint32_t base = 0; base < gr.y; base += PF) {
+            auto ring_round = [&](uint32_t base) {
 #pragma unroll
                 for (int k = 0; k < PF; ++k) {
                     const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
                     load_step(q[k], gr.x, base + k + PF, gr.y);
                     if (base + k < gr.y) step_dot<CL>(d0, d1, d2, slice, xl, acc);
                 }
-            }
+            };
+            // (the first round outside the loop: at a loop head the ring would be copied, and a copy needs
+            // all of its data)
+            if (gr.y > 0) ring_round(0);
+            for (uint32_t base = PF; base < gr.y; base += PF) ring_round(base);
         } else {
             // the first PF steps of the wavefront's first group are in registers (the whole group for the
             // shapes this was tuned on); everything else is loaded as it goes
-            uint32_t st0 = 0;
-            if (g == (uint32_t)wave) {
+            if constexpr (PRE) {
 #pragma unroll
                 for (int st = 0; st < PF; ++st)
                     if ((uint32_t)st < gr.y) step_dot<CL>(q[st][0], q[st][1], q[st][2], slice, xl, acc);
-                st0 = PF;
             }
-            for (uint32_t st = st0; st < gr.y; ++st) {
-                const uint32_t *p = reinterpret_cast<const uint32_t *>(atoms + ((size_t)gr.x + st) * 768 + lane_off);
+            for (uint32_t st = PRE ? PF : 0; st < gr.y; ++st) {
+                gu32_t *p = (gu32_t *)(atoms + ((size_t)gr.x + st) * 768 + lane_off);
                 step_dot<CL>(p[0], p[1], p[2], slice, xl, acc);
             }
         }
         if (ri != 0xFFFFu) accbuf[ri] = (acc.a0 + acc.a1) + (acc.a2 + acc.a3);
+    };
+    if (has_group) run_group(std::true_type{}, gr, ri);
+    for (uint32_t g = wave + nwaves; g < n_groups; g += nwaves) {  // only when a block has more groups than wavefronts
+        const uint2 gr2 = group_of(ka.group[__builtin_amdgcn_readfirstlane(g)]);  // (scalar index: a scalar load)
+        const uint32_t ri2 = rowids[((size_t)first_group + g) * 64 + lane];
+        if constexpr (RING) {
+            if (gr2.y > 0) {
+#pragma unroll
+                for (int k = 0; k < PF; ++k) load_step(q[k], gr2.x, k, gr2.y);
+            }
+            run_group(std::true_type{}, gr2, ri2);
+        } else {
+            run_group(std::false_type{}, gr2, ri2);
+        }
     }
     __syncthreads();
 
@@ -377,7 +400,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     for (uint32_t c = wave; c < n_groups; c += nwaves) {
         const int r = (int)c * 64 + lane;
         const int n = rb * a.rows_per_block + r;
-        if (r < a.rows_per_block && n < a.N) a.partial[(size_t)s * a.N + n] = accbuf[r];
+        if (r < a.rows_per_block && n < a.N) ((__attribute__((address_space(1))) float *)a.partial)[(size_t)s * a.N + n] = accbuf[r];
     }
 }
 
@@ -462,7 +485,7 @@ int check_pack(const vq_weight_t *w) {
     if (ng > VQ_PACK_MAX_GROUPS) return VQ_ERR_SHAPE;
     uint64_t sum = 0;
     for (uint64_t g = 0; g < ng; ++g) sum += p->group_steps[g];
-    if (sum != p->wg_pitch || sum > 65535) return VQ_ERR_SHAPE;
+    if (sum != p->wg_pitch || sum > 65535 || sum == 0) return VQ_ERR_SHAPE;
     if (p->rowid_off + nwg * ng * 128 > p->atom_off || p->atom_off + nwg * sum * 768 > p->bytes) return VQ_ERR_SHAPE;
     if ((p->rowid_off & 1) || (p->atom_off & 3)) return VQ_ERR_ALIGN;
     return VQ_OK;
