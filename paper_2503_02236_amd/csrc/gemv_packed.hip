@@ -250,8 +250,9 @@ template <int PF, bool RING, int CL>
 __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int bid) {
     extern __shared__ __align__(16) unsigned char smem[];
     // all launch arguments in one round of scalar loads
-    const int wave = threadIdx.x >> 6;
-    uint32_t group_word = ka.group[__builtin_amdgcn_readfirstlane(wave)];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: group lookups, block numbers and
+                                                                         // addresses derived from it stay scalar
+    uint32_t group_word = ka.group[wave];
     PackedCore a = ka;
     pin_scalar(a.data); pin_scalar(a.cb); pin_scalar(a.x); pin_scalar(a.partial);
     pin_scalar(a.N); pin_scalar(a.J); pin_scalar(a.S); pin_scalar(a.RB); pin_scalar(a.rows_per_block);
@@ -266,10 +267,10 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     // one codebook slice run on the same die, so a slice is fetched from memory by one L2 only
     // (otherwise every die pulls the whole 1 MiB codebook: 8 MiB per launch).
     int s, rb;
-    if (a.S % 8 == 0) {
-        const int die = bid & 7, local = bid >> 3, per_die = a.S >> 3;
-        s = die * per_die + local % per_die;
-        rb = local / per_die;
+    if (a.S % 8 == 0) {  // S is a power of two: shifts instead of a division
+        const int die = bid & 7, local = bid >> 3, per_die = a.S >> 3, sh = __builtin_ctz(per_die);
+        s = die * per_die + (local & (per_die - 1));
+        rb = local >> sh;
     } else {
         s = bid / a.RB;
         rb = bid % a.RB;
@@ -378,7 +379,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     };
     if (has_group) run_group(std::true_type{}, gr, ri);
     for (uint32_t g = wave + nwaves; g < n_groups; g += nwaves) {  // only when a block has more groups than wavefronts
-        const uint2 gr2 = group_of(ka.group[__builtin_amdgcn_readfirstlane(g)]);  // (scalar index: a scalar load)
+        const uint2 gr2 = group_of(ka.group[g]);
         const uint32_t ri2 = rowids[((size_t)first_group + g) * 64 + lane];
         if constexpr (RING) {
             if (gr2.y > 0) {
