@@ -20,7 +20,8 @@
 //
 // Packed buffer (little endian, offsets from the start of the buffer, 256-byte aligned):
 //   row ids      [S*RB][G][64] uint16   row inside the block, 0xFFFF = idle lane; G = ceil(rows_per_block / 64)
-//   atoms        blocks of 768 bytes = 64 lanes x 12 bytes = 4 atoms per lane per step
+//   atoms        blocks of 768 bytes = 64 lanes x 12 bytes = 4 atoms per lane per step; 16 zeroed blocks follow
+//                the last workgroup's (the kernels read a few blocks past the end of a group without looking)
 // Placement of the atom blocks.  A kernel that has to read a table before it can ask for its atoms
 // pays two dependent first touches of memory (~1.5 us each) before any work.  Codes that spread evenly
 // over the codebook make group g look nearly the same in every workgroup (the g-th 64 rows of a sorted
@@ -39,6 +40,9 @@
 namespace vq {
 
 constexpr int kPackLocalBits = 12;
+// zeroed atom blocks behind the last workgroup's: the kernels read up to this many blocks past the end of a group
+// without looking (a clamp per load costs more instructions than the load)
+constexpr int kPackTailBlocks = 16;
 constexpr int kPackJBits = 11;
 constexpr uint32_t kPackValid = 1u << 23;
 
@@ -132,7 +136,7 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
     const uint64_t atom_blocks = pitch * nwg;
     const uint64_t rowid_off = 0;
     const uint64_t atom_off = align256(rowid_off + rowids.size() * 2);
-    const uint64_t total = atom_off + atom_blocks * 768;
+    const uint64_t total = atom_off + (atom_blocks + kPackTailBlocks) * 768;
     if (pack) {
         pack->data = out;
         pack->bytes = total;
@@ -149,7 +153,7 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
     std::memset(out, 0, (size_t)atom_off);
     std::memcpy(out + rowid_off, rowids.data(), rowids.size() * 2);
     unsigned char *atoms = out + atom_off;
-    std::memset(atoms, 0, (size_t)(atom_blocks * 768));
+    std::memset(atoms, 0, (size_t)((atom_blocks + kPackTailBlocks) * 768));
     // fill: lane l of group g walks row rowids[wg][g][l]; its k-th atom of slice s goes to step k/4, slot k%4
     for (uint32_t wg = 0; wg < nwg; ++wg) {
         uint32_t s = wg / p.RB, rb = wg % p.RB;
@@ -314,26 +318,28 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     asm volatile("" ::: "memory");
     const uint32_t n_groups = (uint32_t)(a.rows_per_block + 63) / 64, first_group = (uint32_t)wg * n_groups;
     auto group_of = [&](uint32_t word) { return make_uint2((uint32_t)wg * a.wg_pitch + (word >> 16), word & 0xffffu); };
-    // A step past the end of a group re-reads its last block and is never used: with a branch around a
-    // load the compiler can no longer count which loads are in flight and waits for all of them before
-    // every use.  Only for groups with at least one step.
-    auto load_step = [&](uint32_t (&dst)[3], uint32_t first, uint32_t st, uint32_t steps) {
-        gu32_t *p = (gu32_t *)(atoms + ((size_t)first + min(st, steps - 1)) * 768 + lane_off);
+    // Step st of the group whose first block this lane sees at `base`.  No look at the group's length: a
+    // branch around a load keeps the compiler from counting which loads are in flight (it then waits for
+    // all of them before every use), and a clamp costs more instructions than the load.  Blocks past the
+    // end of a group belong to the next one, or to the zeroed tail of the buffer, and are never used.
+    static_assert(PF <= kPackTailBlocks && (!RING || 2 * PF - 2 <= kPackTailBlocks),
+                  "reads run up to PF (ring: 2 PF - 2) blocks past the end of a group");
+    auto load_step = [&](uint32_t (&dst)[3], gbyte_t *base, uint32_t st) {
+        gu32_t *p = (gu32_t *)(base + (size_t)st * 768);
         dst[0] = p[0]; dst[1] = p[1]; dst[2] = p[2];
     };
+    auto lane_base = [&](uint32_t first_block) { return atoms + (size_t)first_block * 768 + lane_off; };
     // Every wavefront issues the same PF + 1 loads, so the count in the wait holds for all of them: one
-    // without a group, or whose group has no step here, reads the row ids of the last group and the first
-    // block of the workgroup (every workgroup has one) and uses neither.
+    // without a group reads the row ids of the last group and the first blocks of the workgroup and uses
+    // neither.
     const bool has_group = (uint32_t)wave < n_groups;
     uint2 gr = make_uint2((uint32_t)wg * a.wg_pitch, 0);  // .x first atom block, .y steps
     if (has_group) gr = group_of(group_word);
     uint32_t ri = rowids[((size_t)first_group + min((uint32_t)wave, n_groups - 1)) * 64 + lane];
     uint32_t q[PF][3];  // atoms of steps 0 .. PF-1 (later: the ring of the next PF steps)
-    {
-        const uint32_t first = gr.y > 0 ? gr.x : (uint32_t)wg * a.wg_pitch, steps = max(gr.y, 1u);
+    gbyte_t *gbase = lane_base(gr.x);
 #pragma unroll
-        for (int st = 0; st < PF; ++st) load_step(q[st], first, st, steps);
-    }
+    for (int st = 0; st < PF; ++st) load_step(q[st], gbase, st);
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PF + 1) : "memory");  // PF atom loads and the row ids may be pending
     // (3) the slice and x of this wavefront have landed (direct-to-LDS transfers count as vector memory
     //     loads); after the barrier those of all wavefronts are visible.  A bare s_barrier: __syncthreads()
@@ -344,7 +350,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     //     first PF steps are already in q (always so in the ring form).  The wavefront's first group is
     //     handled outside the loop over further groups: as a loop-carried value q would be copied at the
     //     loop head, and a copy needs the data -- all of it, at once.
-    auto run_group = [&](auto pre_tag, const uint2 gr, const uint32_t ri) {
+    auto run_group = [&](auto pre_tag, const uint2 gr, const uint32_t ri, gbyte_t *gbase) {
         constexpr bool PRE = decltype(pre_tag)::value;
         Acc4 acc = {0.f, 0.f, 0.f, 0.f};
         if constexpr (RING) {
@@ -354,7 +360,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
 #pragma unroll
                 for (int k = 0; k < PF; ++k) {
                     const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
-                    load_step(q[k], gr.x, base + k + PF, gr.y);
+                    load_step(q[k], gbase, base + k + PF);
                     if (base + k < gr.y) step_dot<CL>(d0, d1, d2, slice, xl, acc);
                 }
             };
@@ -371,24 +377,23 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
                     if ((uint32_t)st < gr.y) step_dot<CL>(q[st][0], q[st][1], q[st][2], slice, xl, acc);
             }
             for (uint32_t st = PRE ? PF : 0; st < gr.y; ++st) {
-                gu32_t *p = (gu32_t *)(atoms + ((size_t)gr.x + st) * 768 + lane_off);
+                gu32_t *p = (gu32_t *)(gbase + (size_t)st * 768);
                 step_dot<CL>(p[0], p[1], p[2], slice, xl, acc);
             }
         }
         if (ri != 0xFFFFu) accbuf[ri] = (acc.a0 + acc.a1) + (acc.a2 + acc.a3);
     };
-    if (has_group) run_group(std::true_type{}, gr, ri);
+    if (has_group) run_group(std::true_type{}, gr, ri, gbase);
     for (uint32_t g = wave + nwaves; g < n_groups; g += nwaves) {  // only when a block has more groups than wavefronts
         const uint2 gr2 = group_of(ka.group[g]);
         const uint32_t ri2 = rowids[((size_t)first_group + g) * 64 + lane];
+        gbyte_t *gbase2 = lane_base(gr2.x);
         if constexpr (RING) {
-            if (gr2.y > 0) {
 #pragma unroll
-                for (int k = 0; k < PF; ++k) load_step(q[k], gr2.x, k, gr2.y);
-            }
-            run_group(std::true_type{}, gr2, ri2);
+            for (int k = 0; k < PF; ++k) load_step(q[k], gbase2, k);
+            run_group(std::true_type{}, gr2, ri2, gbase2);
         } else {
-            run_group(std::false_type{}, gr2, ri2);
+            run_group(std::false_type{}, gr2, ri2, gbase2);
         }
     }
     __syncthreads();
@@ -408,7 +413,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
 // Two builds of the single-problem kernel: up to 8 wavefronts (512 threads, up to 256 registers: the full
 // gather cluster) and up to 16 (held to 128 registers: half clusters).
 __global__ __launch_bounds__(512) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body<kPackPrefetch, false, 4>(a, blockIdx.x); }
-__global__ __launch_bounds__(1024) void gemv_packed_wide_kernel(PackedArgs a) { gemv_packed_body<kPackPrefetch, false, 2>(a, blockIdx.x); }
+__global__ __launch_bounds__(1024) void gemv_packed_wide_kernel(PackedArgs a) { gemv_packed_body<12, false, 4>(a, blockIdx.x); }
 
 // Several independent problems in one launch (blockIdx.y picks the problem): the fixed latencies of a
 // launch (ramp-up, first touches of tables and atoms, drain) are paid once for all of them, and
@@ -487,7 +492,8 @@ int check_pack(const vq_weight_t *w) {
     uint64_t sum = 0;
     for (uint64_t g = 0; g < ng; ++g) sum += p->group_steps[g];
     if (sum != p->wg_pitch || sum > 65535 || sum == 0) return VQ_ERR_SHAPE;
-    if (p->rowid_off + nwg * ng * 128 > p->atom_off || p->atom_off + nwg * sum * 768 > p->bytes) return VQ_ERR_SHAPE;
+    if (p->rowid_off + nwg * ng * 128 > p->atom_off || p->atom_off + (nwg * sum + kPackTailBlocks) * 768 > p->bytes)
+        return VQ_ERR_SHAPE;
     if ((p->rowid_off & 1) || (p->atom_off & 3)) return VQ_ERR_ALIGN;
     return VQ_OK;
 }

@@ -19,7 +19,8 @@ def decode(buf, pack, N, J, SLICE):
     prefix = np.concatenate([[0], np.cumsum(steps)])
     rowids = np.frombuffer(buf, dtype=np.uint16, count=64 * ng * S * RB, offset=pack.rowid_off).reshape(S * RB, ng, 64)
     atoms = np.frombuffer(buf, dtype=np.uint8, offset=pack.atom_off)
-    assert atoms.size == S * RB * pack.wg_pitch * 768
+    assert atoms.size == (S * RB * pack.wg_pitch + 16) * 768          # 16 zeroed blocks behind the last workgroup's
+    assert not atoms[S * RB * pack.wg_pitch * 768:].any()
     codes = np.zeros((N, J), dtype=np.int64)
     hits = np.zeros((N, J), dtype=np.int32)
     for w in range(S * RB):
