@@ -174,12 +174,26 @@ def test_gemv_packed_config2_full_size(gpu_device, shape_idx):
     (300, 2048, 4096, True),      # two slices only
     (257, 16368, 8192, True),     # longest supported rows
     (9000, 512, 65536, True),     # many rows: 4096-entry slices, nine groups per workgroup
+    (20000, 128, 65536, True),    # twenty groups per workgroup, sixteen wavefronts: some take a second group
 ])
 def test_gemv_packed_shapes_and_edges(gpu_device, N, K, E, scale):
     w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=3000 + N + K, with_scale=scale)
     x = wl.make_activations(1, K, seed=3100 + N)
     assert_close(run_gemv_packed(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x),
                  f"packed {N}x{K} E{E}")
+
+
+def test_gemv_batch_more_groups_than_wavefronts(gpu_device):
+    # 20 groups per workgroup: in the batch kernel four wavefronts refill their ring for a second group
+    ws = [wl.make_weight(20000, 128, 8, 16, 1, 65536, 0.02, seed=3300 + i) for i in range(2)]
+    x = wl.make_activations(1, 128, seed=3310)
+    xd = dev_x(x, gpu_device)
+    wds = [vq.weight_to_device(w, gpu_device, prepack=True, keep_codes=False) for w in ws]
+    ys = vq.vq_gemv_batch(wds, [xd, xd])
+    torch.cuda.synchronize()
+    for w, wd, y in zip(ws, wds, ys):
+        assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), "batch, 20 groups")
+        assert torch.equal(y, vq.vq_gemv(wd, xd))
 
 
 def test_gemv_skewed_codes_have_no_packed_form_and_run_from_canonical_codes(gpu_device):

@@ -59,6 +59,7 @@ def decode(buf, pack, N, J, SLICE):
     (1, 64, 65536),
     (70, 16368, 8192),       # longest supported rows (K/8 = 2046)
     (9000, 64, 65536),       # many rows: 4096-entry slices, 16 x 16 workgroups
+    (20000, 64, 65536),      # 20 groups per workgroup
 ])
 def test_prepack_round_trip(N, K, E):
     w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=77 + N)
