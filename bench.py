@@ -133,7 +133,7 @@ def main():
     # ------------------------------------------------------------------ measured ceilings of this chip
     # (second reference beside the vendor peaks): a plain 128-bit streaming read of 1 GiB, cold, and a
     # register-resident fp16 MFMA loop
-    ceil_hbm = ceil_mfma = ceil_mfma_rand = None
+    ceil_hbm = ceil_mfma = ceil_mfma_rand = ceil_mfma_lds = None
     if not args.pmc_probe:
         big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         big.fill_(1)
@@ -144,11 +144,14 @@ def main():
         iters = 2000
         ms = timed(lambda: vq.vq_probe_mfma(1024, iters, sink), 5, 1)
         ceil_mfma = 1024 * 4 * iters * 8 * 32768.0 / (ms * 1e-3) / 1e12
-        ms = timed(lambda: vq.vq_probe_mfma(1024, iters, sink, random_operands=True), 5, 1)
+        ms = timed(lambda: vq.vq_probe_mfma(1024, iters, sink, random_operands=1), 5, 1)
         ceil_mfma_rand = 1024 * 4 * iters * 8 * 32768.0 / (ms * 1e-3) / 1e12
+        ms = timed(lambda: vq.vq_probe_mfma(1024, iters, sink, random_operands=2), 5, 1)
+        ceil_mfma_lds = 1024 * 4 * iters * 8 * 32768.0 / (ms * 1e-3) / 1e12
         result["measured_ceilings"] = {"hbm_stream_read_GBps": round(ceil_hbm, 1),
                                        "mfma_fp16_register_loop_TFLOPs": round(ceil_mfma, 1),
-                                       "mfma_fp16_register_loop_random_operands_TFLOPs": round(ceil_mfma_rand, 1)}
+                                       "mfma_fp16_register_loop_random_operands_TFLOPs": round(ceil_mfma_rand, 1),
+                                       "mfma_fp16_lds_fed_random_operands_TFLOPs": round(ceil_mfma_lds, 1)}
         torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ headline: C2 gemv stack
@@ -309,7 +312,8 @@ def main():
                 gemm["N%d_v%d" % (N, v)] = {"us": round(ms * 1e3, 2), "TFLOPs": round(tf, 1),
                                             "pct_mfma_fp16_peak": round(100 * tf / MFMA_FP16_PEAK_TFLOPS, 2),
                                             "pct_measured_mfma_loop": round(100 * tf / ceil_mfma, 2),
-                                            "pct_measured_mfma_loop_random_operands": round(100 * tf / ceil_mfma_rand, 2)}
+                                            "pct_measured_mfma_loop_random_operands": round(100 * tf / ceil_mfma_rand, 2),
+                                            "pct_measured_mfma_lds_fed_random_operands": round(100 * tf / ceil_mfma_lds, 2)}
                 del wd, Y
         result["gemm_prefill_M2048_K4096"] = gemm
 

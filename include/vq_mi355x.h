@@ -254,7 +254,8 @@ int vq_probe_read(const void *src, size_t bytes, void *sink, void *stream);
  * v_mfma_f32_32x32x16_f16 (32768 flops each) with no memory traffic: the matrix-core rate this chip
  * sustains, as the second reference beside the vendor peak.  random_operands = 0: one smooth operand
  * pair (few bits toggle); != 0: four pairs of pseudo-random halves in [-1, 1) per lane taken in turn, as
- * a gemm on real data presents them (the chip clocks lower on these).  sink: >= 16 device bytes
+ * a gemm on real data presents them (the chip clocks lower on these); 2: six fresh random operands per
+ * iteration read from LDS (32 KiB per workgroup), the way a gemm's main loop is fed.  sink: >= 16 device bytes
  * (practically never written).
  */
 int vq_probe_mfma(int workgroups, int iters, int random_operands, void *sink, void *stream);

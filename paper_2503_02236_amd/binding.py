@@ -364,9 +364,11 @@ def vq_probe_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
     _check(lib().vq_probe_copy(_dev(dst, "dst"), _dev(src, "src"), n, _stream()), "vq_probe_copy")
 
 
-def vq_probe_mfma(workgroups: int, iters: int, sink: torch.Tensor, random_operands: bool = False) -> None:
-    """Register-resident fp16 MFMA loop (no memory traffic): workgroups x 4 waves x iters x 8 MFMAs."""
-    _check(lib().vq_probe_mfma(int(workgroups), int(iters), int(bool(random_operands)), _dev(sink, "sink"), _stream()),
+def vq_probe_mfma(workgroups: int, iters: int, sink: torch.Tensor, random_operands: int = 0) -> None:
+    """fp16 MFMA loop without global memory traffic: workgroups x 4 waves x iters x 8 MFMAs.
+
+    random_operands: 0 smooth register operands, 1 random register operands, 2 fresh random operands from LDS."""
+    _check(lib().vq_probe_mfma(int(workgroups), int(iters), int(random_operands), _dev(sink, "sink"), _stream()),
            "vq_probe_mfma")
 
 

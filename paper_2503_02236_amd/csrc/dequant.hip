@@ -175,8 +175,44 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink)
     if (t == 12345.f) sink[0] = t;  // keeps the loop alive; practically never stores
 }
 
+// The same eight MFMAs per iteration, but fed the way a gemm feeds them: six fresh operands (four of one
+// matrix, two of the other) read from LDS for every iteration, random halves in [-1, 1).  32 KiB of LDS per
+// workgroup, so four workgroups (16 wavefronts) share a CU and cover each other's LDS latency.  No global
+// memory traffic.  This is what the matrix cores sustain on operands that change with every instruction.
+__global__ __launch_bounds__(256) void probe_mfma_lds_kernel(int iters, float *sink) {
+    __shared__ __align__(16) half_t pool[16384];
+    uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 977u;
+    for (int i = threadIdx.x; i < 16384; i += 256) {
+        h = h * 1664525u + 1013904223u;
+        pool[i] = (half_t)(((int)(h >> 16) - 32768) * (1.f / 32768.f));
+    }
+    __syncthreads();
+    float16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    const unsigned char *base = reinterpret_cast<const unsigned char *>(pool) + (threadIdx.x & 63) * 16;
+    unsigned off = (threadIdx.x >> 6) * 6144u;
+    for (int it = 0; it < iters; ++it) {
+        half8_t op[6];
+#pragma unroll
+        for (int q = 0; q < 6; ++q)  // a wave-wide read of 1 KiB of consecutive bytes: no bank conflicts
+            op[q] = *reinterpret_cast<const half8_t *>(base + ((off + q * 1024u) & 0x7C00u));
+        off += 6144u;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[4 + (i & 1)], op[i >> 1], acc[i], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t += acc[i][0];
+    if (t == 12345.f) sink[0] = t;  // keeps the loop alive; practically never stores
+}
+
 int launch_probe_mfma(int workgroups, int iters, int random_operands, void *sink, hipStream_t s) {
-    if (random_operands)
+    if (random_operands == 2)
+        probe_mfma_lds_kernel<<<workgroups, 256, 0, s>>>(iters, (float *)sink);
+    else if (random_operands)
         probe_mfma_kernel<true><<<workgroups, 256, 0, s>>>(iters, (float *)sink);
     else
         probe_mfma_kernel<false><<<workgroups, 256, 0, s>>>(iters, (float *)sink);

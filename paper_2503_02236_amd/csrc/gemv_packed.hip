@@ -300,7 +300,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
         typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
         auto dma16 = [](const uint4 *src, unsigned char *dst_wave_base) {
             const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t *)dst_wave_base);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src) : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src) : "memory");  // (M0 is written and used inside the statement; nothing else in this kernel uses it)
         };
         const uint4 *src = reinterpret_cast<const uint4 *>(a.cb) + (size_t)s * a.slice_entries;
         const uint4 *xs = reinterpret_cast<const uint4 *>(a.x);
