@@ -1,0 +1,70 @@
+"""Compile-time invariants of hand-scheduled kernels, checked on the compiler's own output (no GPU).
+
+The re-tiled gemv lets its gathers start when the codebook slice has landed while the atoms still stream in:
+a counted ``s_waitcnt vmcnt(PF)`` stands between the loads and the barrier.  That is only right if, in every
+build of the kernel, at least PF + 1 ordinary vector loads are issued between the last direct-to-LDS transfer
+and that wait, in straight-line code (loads complete in issue order)."""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2503_02236_amd", "csrc")
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
+def test_gemv_packed_counted_wait_matches_the_loads_in_front_of_it(tmp_path):
+    out = tmp_path / "gemv_packed.s"
+    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "--cuda-device-only", "-S",
+           os.path.join(CSRC, "gemv_packed.hip"), "-o", str(out)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    text = out.read_text()
+    checked = 0
+    for name, pf in (("gemv_packed_kernel", 10), ("gemv_packed_wide_kernel", 12), ("gemv_packed_batch_kernel", 4)):
+        m = re.search(r"^(_ZN2vq\d+%sE\w*):[^\n]*\n(.*?)^\.Lfunc_end" % name, text, re.S | re.M)
+        assert m, name
+        lines = [l.strip() for l in m.group(2).splitlines()]
+        waits = [i for i, l in enumerate(lines) if l == "s_waitcnt vmcnt(%d)" % pf and "ASMSTART" in lines[i - 1]]
+        assert len(waits) == 1, (name, waits)
+        w = waits[0]
+        assert any(l == "s_barrier" for l in lines[w:w + 6]), name          # the wait guards the barrier
+        dma = [i for i in range(w) if lines[i].startswith("global_load_lds_dwordx4")]
+        assert dma, name
+        between = lines[dma[-1] + 1:w]
+        loads = [l for l in between if re.match(r"global_load_(dword|ushort|ubyte|short)", l)]
+        assert len(loads) >= pf + 1, (name, len(loads))
+        # straight-line: no branch may skip one of the loads that the count relies on
+        first = next(i for i, l in enumerate(between) if l in loads)
+        assert not any(l.startswith(("s_cbranch", "s_branch")) or l.endswith(":") for l in between[first:]), name
+        checked += 1
+    assert checked == 3
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
+def test_gemm_dense_ring_wait_matches_the_transfers_of_a_stage(tmp_path):
+    """The dense gemm stage waits with ``s_waitcnt vmcnt(12)`` for the older of two stages in flight: right only
+    if a stage is exactly twelve direct-to-LDS transfers per wavefront and the main loop issues no other vector
+    memory instruction."""
+    out = tmp_path / "gemm_dense.s"
+    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "--cuda-device-only", "-S",
+           os.path.join(CSRC, "gemm_dense.hip"), "-o", str(out)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    lines = [l.strip() for l in out.read_text().splitlines()]
+    # the main loop: from the loop-head wait to the backward branch
+    heads = [i for i, l in enumerate(lines) if l == "s_waitcnt vmcnt(12) lgkmcnt(0)"]
+    assert heads, "counted wait not found"
+    h = heads[0]
+    assert lines[h + 1] == "s_barrier"
+    end = next(i for i in range(h, len(lines)) if lines[i].startswith("s_cbranch"))
+    body = lines[h:end]
+    assert sum(l.startswith("global_load_lds_dwordx4") for l in body) == 12
+    assert not any(re.match(r"(global|flat|buffer)_(load|store)", l) and not l.startswith("global_load_lds") for l in body)
+    assert sum(l.startswith("v_mfma_f32_32x32x16") for l in body) == 32
