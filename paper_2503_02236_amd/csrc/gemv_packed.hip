@@ -340,10 +340,9 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     gbyte_t *gbase = lane_base(gr.x);
 #pragma unroll
     for (int st = 0; st < PF; ++st) load_step(q[st], gbase, st);
-    // PF atom loads were issued behind the row ids and the staging transfers: when at most PF loads are
-    // pending, the transfers (and the row ids) have landed.  (One less than the PF + 1 loads issued since the
-    // last transfer, so that the count stays on the safe side should the compiler ever fold one of them.)
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PF) : "memory");
+    // PF atom loads and the row ids were issued behind the staging transfers: when at most PF + 1 loads are
+    // pending, the transfers have landed.  (A test compiles this file and counts those loads in each build.)
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PF + 1) : "memory");
     // (3) the slice and x of this wavefront have landed (direct-to-LDS transfers count as vector memory
     //     loads); after the barrier those of all wavefronts are visible.  A bare s_barrier: __syncthreads()
     //     would wait for the atoms as well.

@@ -1,7 +1,7 @@
 """Compile-time invariants of hand-scheduled kernels, checked on the compiler's own output (no GPU).
 
 The re-tiled gemv lets its gathers start when the codebook slice has landed while the atoms still stream in:
-a counted ``s_waitcnt vmcnt(PF)`` stands between the loads and the barrier.  That is only right if, in every
+a counted ``s_waitcnt vmcnt(PF + 1)`` stands between the loads and the barrier.  That is only right if, in every
 build of the kernel, at least PF + 1 ordinary vector loads are issued between the last direct-to-LDS transfer
 and that wait, in straight-line code (loads complete in issue order)."""
 import os
@@ -30,7 +30,7 @@ def test_gemv_packed_counted_wait_matches_the_loads_in_front_of_it(tmp_path):
         m = re.search(r"^(_ZN2vq\d+%sE\w*):[^\n]*\n(.*?)^\.Lfunc_end" % name, text, re.S | re.M)
         assert m, name
         lines = [l.strip() for l in m.group(2).splitlines()]
-        waits = [i for i, l in enumerate(lines) if l == "s_waitcnt vmcnt(%d)" % pf and "ASMSTART" in lines[i - 1]]
+        waits = [i for i, l in enumerate(lines) if l == "s_waitcnt vmcnt(%d)" % (pf + 1) and "ASMSTART" in lines[i - 1]]
         assert len(waits) == 1, (name, waits)
         w = waits[0]
         assert any(l == "s_barrier" for l in lines[w:w + 6]), name          # the wait guards the barrier
