@@ -82,6 +82,15 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
     const int r = lane & 15, g = lane >> 4;
     const int n0 = blockIdx.x * 16;
     const int n = min(n0 + r, a.N - 1);  // rows past the end are computed and dropped
+    // per-channel scales of the four output rows this lane writes at the very end (rows n0 + 4 g + i): asked
+    // for now, with everything else -- loaded where they are used they are four dependent round trips to L2
+    // at the tail of a kernel that lasts a few microseconds
+    float sc4[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int nn = min(n0 + 4 * g + i, a.N - 1);
+        sc4[i] = a.scale ? (float)a.scale[nn] : 1.f;
+    }
 
     // codes and x of this wavefront's first iteration are requested before the codebook is staged
     const unsigned char *crow = reinterpret_cast<const unsigned char *>(a.codes) + (size_t)n * a.J * R * BITS / 8;
@@ -133,59 +142,76 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
         // codebook set of this lane's positions (a load never straddles two tiles)
         // (lanes past the end of the row are clamped to the last set; their x operand is zero)
         const half_t *cbt = cbl + (size_t)min(((it * 4 + g) * CPL) / a.tile_j, a.tiles_k - 1) * set_halves;
+        // MC MFMA operands at a time: all their entry lookups are issued before the first is used (taken one
+        // operand at a time, every operand waits out its own LDS round trip)
+        constexpr int MC = MPI % 4 == 0 ? 4 : MPI % 2 == 0 ? 2 : 1;
 #pragma unroll
-        for (int m = 0; m < MPI; ++m) {
-            V16 op;
+        for (int m0 = 0; m0 < MPI; m0 += MC) {
+            V16 ev[MC][CPO][R];
 #pragma unroll
-            for (int h = 0; h < CPO; ++h) {
-                const int c = m * CPO + h;  // code position inside the 16-byte word
+            for (int mi = 0; mi < MC; ++mi)
 #pragma unroll
-                for (int rr = 0; rr < R; ++rr) {
-                    const unsigned code = word_code<CodeT>(cd, c * R + rr);
-                    // the entry: from the LDS copy, or (cold entry of a partly cached codebook) from L2.  The two
-                    // loads are kept apart by their address spaces, so neither becomes a generic-pointer load
-                    V16 ev;
-                    ev.u = make_uint4(0, 0, 0, 0);
-                    typedef unsigned raw4_t __attribute__((ext_vector_type(4)));
-                    typedef unsigned raw2_t __attribute__((ext_vector_type(2)));
-                    const half_t *le = cbt + ((size_t)rr * a.n_hot + code) * V;
-                    const half_t *ge = a.cb + ((size_t)rr * a.E + code) * V;
-                    if (!HOT || code < (unsigned)a.n_hot) {
-                        if (V == 8) {
-                            const raw4_t t = *(const __attribute__((address_space(3))) raw4_t *)le;
-                            ev.w[0] = t.x; ev.w[1] = t.y; ev.w[2] = t.z; ev.w[3] = t.w;
-                        } else {
-                            const raw2_t t = *(const __attribute__((address_space(3))) raw2_t *)le;
-                            ev.w[0] = t.x; ev.w[1] = t.y;
-                        }
-                    } else {
-                        if (V == 8) {
-                            const raw4_t t = *(const __attribute__((address_space(1))) raw4_t *)ge;
-                            ev.w[0] = t.x; ev.w[1] = t.y; ev.w[2] = t.z; ev.w[3] = t.w;
-                        } else {
-                            const raw2_t t = *(const __attribute__((address_space(1))) raw2_t *)ge;
-                            ev.w[0] = t.x; ev.w[1] = t.y;
-                        }
-                    }
-                    if (V == 8) {
-                        if (rr == 0) {
-                            op = ev;
-                        } else {
+                for (int h = 0; h < CPO; ++h) {
+                    const int c = (m0 + mi) * CPO + h;  // code position inside the 16-byte word
 #pragma unroll
-                            for (int q = 0; q < 4; ++q) op.h2[q] += ev.h2[q];
-                        }
-                    } else {
-                        if (rr == 0) {
-                            op.h2[2 * h] = ev.h2[0];
-                            op.h2[2 * h + 1] = ev.h2[1];
+                    for (int rr = 0; rr < R; ++rr) {
+                        const unsigned code = word_code<CodeT>(cd, c * R + rr);
+                        // the entry: from the LDS copy, or (cold entry of a partly cached codebook) from L2.  The two
+                        // loads are kept apart by their address spaces, so neither becomes a generic-pointer load
+                        V16 e;
+                        e.u = make_uint4(0, 0, 0, 0);
+                        typedef unsigned raw4_t __attribute__((ext_vector_type(4)));
+                        typedef unsigned raw2_t __attribute__((ext_vector_type(2)));
+                        const half_t *le = cbt + ((size_t)rr * a.n_hot + code) * V;
+                        const half_t *ge = a.cb + ((size_t)rr * a.E + code) * V;
+                        if (!HOT || code < (unsigned)a.n_hot) {
+                            if (V == 8) {
+                                const raw4_t t = *(const __attribute__((address_space(3))) raw4_t *)le;
+                                e.w[0] = t.x; e.w[1] = t.y; e.w[2] = t.z; e.w[3] = t.w;
+                            } else {
+                                const raw2_t t = *(const __attribute__((address_space(3))) raw2_t *)le;
+                                e.w[0] = t.x; e.w[1] = t.y;
+                            }
                         } else {
-                            op.h2[2 * h] += ev.h2[0];
-                            op.h2[2 * h + 1] += ev.h2[1];
+                            if (V == 8) {
+                                const raw4_t t = *(const __attribute__((address_space(1))) raw4_t *)ge;
+                                e.w[0] = t.x; e.w[1] = t.y; e.w[2] = t.z; e.w[3] = t.w;
+                            } else {
+                                const raw2_t t = *(const __attribute__((address_space(1))) raw2_t *)ge;
+                                e.w[0] = t.x; e.w[1] = t.y;
+                            }
                         }
+                        ev[mi][h][rr] = e;
                     }
                 }
+            if (!HOT) __builtin_amdgcn_sched_group_barrier(0x100, MC * CPO * R, 0);  // the LDS reads first
+#pragma unroll
+            for (int mi = 0; mi < MC; ++mi) {
+                V16 op;
+#pragma unroll
+                for (int h = 0; h < CPO; ++h)
+#pragma unroll
+                    for (int rr = 0; rr < R; ++rr) {
+                        const V16 &e = ev[mi][h][rr];
+                        if (V == 8) {
+                            if (rr == 0) {
+                                op = e;
+                            } else {
+#pragma unroll
+                                for (int q = 0; q < 4; ++q) op.h2[q] += e.h2[q];
+                            }
+                        } else {
+                            if (rr == 0) {
+                                op.h2[2 * h] = e.h2[0];
+                                op.h2[2 * h + 1] = e.h2[1];
+                            } else {
+                                op.h2[2 * h] += e.h2[0];
+                                op.h2[2 * h + 1] += e.h2[1];
+                            }
+                        }
+                    }
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(op.h8, xb[m0 + mi], acc, 0, 0, 0);
             }
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(op.h8, xb[m], acc, 0, 0, 0);
         }
         cd = cd_next;
 #pragma unroll
@@ -206,10 +232,7 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int nn = n0 + 4 * g + i;
-                if (nn < a.N) {
-                    const float sc = a.scale ? (float)a.scale[nn] : 1.f;
-                    a.y[(size_t)r * a.N + nn] = (half_t)(sum[i] * sc);
-                }
+                if (nn < a.N) a.y[(size_t)r * a.N + nn] = (half_t)(sum[i] * sc4[i]);
             }
         }
     }

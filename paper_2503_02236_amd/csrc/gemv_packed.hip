@@ -441,17 +441,23 @@ __device__ __forceinline__ void gemv_packed_finalize_body(const float *__restric
                                                           int N, int S) {
     const int n = blockIdx.x * 256 + threadIdx.x;  // (the launch shape is fixed: no load of the hidden arguments)
     if (n >= N) return;
+    // (pointers that went through pin_scalar have to be told again that they are global)
+    const __attribute__((address_space(1))) float *gp = (const __attribute__((address_space(1))) float *)partial;
+    const __attribute__((address_space(1))) half_t *gs = (const __attribute__((address_space(1))) half_t *)scale;
+    __attribute__((address_space(1))) half_t *gy = (__attribute__((address_space(1))) half_t *)y;
     float v[MAXS];
 #pragma unroll
-    for (int k = 0; k < MAXS; ++k) v[k] = partial[(size_t)(k < S ? k : S - 1) * N + n];
+    for (int k = 0; k < MAXS; ++k) v[k] = gp[(size_t)(k < S ? k : S - 1) * N + n];
+    const float sc = scale ? (float)gs[n] : 1.f;
     float sum = 0.f;
 #pragma unroll
     for (int k = 0; k < MAXS; ++k) sum += k < S ? v[k] : 0.f;
-    y[n] = (half_t)(sum * (scale ? (float)scale[n] : 1.f));
+    gy[n] = (half_t)(sum * sc);
 }
 __global__ __launch_bounds__(256) void gemv_packed_finalize_kernel(const float *__restrict__ partial,
                                                                   const half_t *__restrict__ scale,
                                                                   half_t *__restrict__ y, int N, int S) {
+    pin_scalar(partial); pin_scalar(scale); pin_scalar(y); pin_scalar(N); pin_scalar(S);  // one round of argument loads
     if (S <= 32)
         gemv_packed_finalize_body<32>(partial, scale, y, N, S);
     else
