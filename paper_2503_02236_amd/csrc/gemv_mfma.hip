@@ -82,50 +82,59 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
     const int r = lane & 15, g = lane >> 4;
     const int n0 = blockIdx.x * 16;
     const int n = min(n0 + r, a.N - 1);  // rows past the end are computed and dropped
-    // per-channel scales of the four output rows this lane writes at the very end (rows n0 + 4 g + i): asked
-    // for now, with everything else -- loaded where they are used they are four dependent round trips to L2
-    // at the tail of a kernel that lasts a few microseconds
-    float sc4[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int nn = min(n0 + 4 * g + i, a.N - 1);
-        sc4[i] = a.scale ? (float)a.scale[nn] : 1.f;
-    }
-
     // codes and x of this wavefront's first iteration are requested before the codebook is staged
     const unsigned char *crow = reinterpret_cast<const unsigned char *>(a.codes) + (size_t)n * a.J * R * BITS / 8;
-    auto load_iter = [&](int it, V16 &cd, half8_t (&xb)[MPI]) {
-        const int jbase = (it * 4 + g) * CPL;  // first position of this lane; J % CPL == 0
-        const bool valid = it < a.nit && jbase < a.J;
-        cd.u = make_uint4(0, 0, 0, 0);
-        if (valid) {
-            const unsigned char *cp = crow + (size_t)jbase * R * BITS / 8;
-            if (LB == 16) {
-                cd = ld16(cp);
-            } else if (LB == 12) {  // 4-byte aligned: a row is a whole number of 12-byte words
-                const uint32_t *c3 = reinterpret_cast<const uint32_t *>(cp);
-                cd.w[0] = c3[0];
-                cd.w[1] = c3[1];
-                cd.w[2] = c3[2];
-            } else {
-                V8 c8 = ld8(cp);
-                cd.w[0] = c8.w[0];
-                cd.w[1] = c8.w[1];
-            }
+    // Codes and x operands of iteration `it` (< nit) of this wavefront; returns whether this lane's part
+    // counts.  The loads carry no condition: a lane past the end of the row, or of a token past the batch,
+    // reads a position / token that exists and its x operand is zeroed where it is used (a zero B operand
+    // cancels whatever A holds).  With a branch around the loads their results meet the zeros of the
+    // other path in a register copy right behind them, and a copy waits for the data: the code load was
+    // waited for (a trip to HBM) before the x loads were even issued.
+    auto lane_pos = [&](int it, bool &ok) {
+        const int jb = (it * 4 + g) * CPL;  // first position of this lane; J % CPL == 0
+        ok = jb < a.J;
+        return ok ? jb : a.J - CPL;
+    };
+    auto load_codes = [&](int it, V16 &cd) {
+        bool ok;
+        const unsigned char *cp = crow + (size_t)lane_pos(it, ok) * R * BITS / 8;
+        if (LB == 16) {
+            cd = ld16(cp);
+        } else if (LB == 12) {  // 4-byte aligned: a row is a whole number of 12-byte words
+            const uint32_t *c3 = reinterpret_cast<const uint32_t *>(cp);
+            cd.w[0] = c3[0];
+            cd.w[1] = c3[1];
+            cd.w[2] = c3[2];
+            cd.w[3] = 0;
+        } else {
+            V8 c8 = ld8(cp);
+            cd.w[0] = c8.w[0];
+            cd.w[1] = c8.w[1];
+            cd.w[2] = cd.w[3] = 0;
         }
+    };
+    auto load_x = [&](int it, half8_t (&xb)[MPI]) {
+        bool ok;
+        const half_t *xr = a.x + (size_t)min(r, a.bs - 1) * a.K + (size_t)lane_pos(it, ok) * V;
 #pragma unroll
-        for (int m = 0; m < MPI; ++m) {
-            V16 xv;
-            xv.u = make_uint4(0, 0, 0, 0);
-            // lanes of a k-group are valid or invalid together, and a zero B operand cancels whatever
-            // A holds, so masking x is enough
-            if (valid && r < a.bs) xv = ld16(a.x + (size_t)r * a.K + (size_t)jbase * V + m * 8);
-            xb[m] = xv.h8;
-        }
+        for (int m = 0; m < MPI; ++m) xb[m] = ld16(xr + m * 8).h8;
+        return ok && r < a.bs;
     };
     V16 cd;
     half8_t xb[MPI];
-    load_iter(wave, cd, xb);
+    // (every wavefront loads: one without an iteration repeats the last one and never uses it)
+    load_codes(min(wave, a.nit - 1), cd);
+    bool use_x = load_x(min(wave, a.nit - 1), xb);
+    // per-channel scales of the four output rows this lane writes at the very end (rows n0 + 4 g + i): asked
+    // for now, with everything else, as raw halves and without a branch (without scales: any readable halves,
+    // ignored later).  Loaded where they are used they are four dependent round trips to L2 at the tail of a
+    // kernel that lasts a few microseconds; converted or selected here they would be waited for here.
+    half_t sc4[4];
+    {
+        const half_t *sp = a.scale ? a.scale : a.x;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sc4[i] = sp[a.scale ? min(n0 + 4 * g + i, a.N - 1) : 0];
+    }
 
     // all codebooks (with per-tile codebooks: the sets of the tiles this workgroup's 16 rows cross), or (HOT,
     // one codebook) its first n_hot entries
@@ -136,15 +145,18 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
 
     float4v_t acc = {0.f, 0.f, 0.f, 0.f};
     for (int it = wave; it < a.nit; it += nwaves) {
+        // the next iteration's codes (a trip to HBM) are requested now, its x operands (L2) when this
+        // iteration's have been used: they land while the next iteration's entries are looked up
+        const bool more = it + nwaves < a.nit;
         V16 cd_next;
-        half8_t xb_next[MPI];
-        load_iter(it + nwaves, cd_next, xb_next);
+        if (more) load_codes(it + nwaves, cd_next);
         // codebook set of this lane's positions (a load never straddles two tiles)
         // (lanes past the end of the row are clamped to the last set; their x operand is zero)
         const half_t *cbt = cbl + (size_t)min(((it * 4 + g) * CPL) / a.tile_j, a.tiles_k - 1) * set_halves;
         // MC MFMA operands at a time: all their entry lookups are issued before the first is used (taken one
         // operand at a time, every operand waits out its own LDS round trip)
-        constexpr int MC = MPI % 4 == 0 ? 4 : MPI % 2 == 0 ? 2 : 1;
+        constexpr int kEntryRegs = CPO * R * (V == 8 ? 4 : 2);   // registers of one operand's entries
+        constexpr int MC = (MPI % 4 == 0 && 4 * kEntryRegs <= 32) ? 4 : (MPI % 2 == 0 && 2 * kEntryRegs <= 32) ? 2 : 1;
 #pragma unroll
         for (int m0 = 0; m0 < MPI; m0 += MC) {
             V16 ev[MC][CPO][R];
@@ -210,12 +222,13 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
                             }
                         }
                     }
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(op.h8, xb[m0 + mi], acc, 0, 0, 0);
+                half8_t xop = xb[m0 + mi];
+                if (!use_x) xop = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(op.h8, xop, acc, 0, 0, 0);
             }
         }
         cd = cd_next;
-#pragma unroll
-        for (int m = 0; m < MPI; ++m) xb[m] = xb_next[m];
+        if (more) use_x = load_x(it + nwaves, xb);
     }
 
     // partial tiles -> LDS, summed in wavefront order by the first wavefront.
@@ -232,7 +245,7 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int nn = n0 + 4 * g + i;
-                if (nn < a.N) a.y[(size_t)r * a.N + nn] = (half_t)(sum[i] * sc4[i]);
+                if (nn < a.N) a.y[(size_t)r * a.N + nn] = (half_t)(sum[i] * (a.scale ? (float)sc4[i] : 1.f));
             }
         }
     }
