@@ -11,7 +11,7 @@
 //
 // One workgroup per (batch, head, chunk of new tokens): the head's codebooks of one side (G * E entries) are
 // staged in LDS (converted to fp32 once when that fits), then L lanes share a (token, sub-vector) item: each
-// walks E / L consecutive entries and the L partial winners are merged by (distance, index).  L = 1 for
+// walks every L-th entry and the L partial winners are merged by (distance, index).  L = 1 for
 // prefill-sized calls; a decode step (one token) has only D / v items per head, so 8 lanes split the entries.
 #include <type_traits>
 
@@ -28,10 +28,11 @@ struct KvQuantArgs {
     int H, T, D, v, E, G, n_new, pos;
     int L, tokens_per_wg;  // lanes per item (power of two <= 64, divides E), tokens per workgroup
     int both;              // the codebooks of both sides fit LDS together: staged at once, one barrier
+    int par;               // 512 threads, the two sides handled side by side by 256 threads each (needs both)
 };
 
 template <int V, bool F32>
-__global__ __launch_bounds__(256) void kv_quantize_kernel(KvQuantArgs a) {
+__global__ __launch_bounds__(512) void kv_quantize_kernel(KvQuantArgs a) {
 #pragma clang fp contract(off)  // the distance must not be computed with fused multiply-adds
     extern __shared__ __align__(16) unsigned char smem[];
     typedef typename std::conditional<F32, float, half_t>::type cb_t;
@@ -41,17 +42,49 @@ __global__ __launch_bounds__(256) void kv_quantize_kernel(KvQuantArgs a) {
     const int t0 = blockIdx.y * a.tokens_per_wg;
     const int nt = min(a.tokens_per_wg, a.n_new - t0);
     const int cb_halves = a.G * a.E * V;
-    const int L = a.L, sub = threadIdx.x % L, per_lane = a.E / L;
+    const int nthreads = a.par ? 512 : 256;
+    const int tx = threadIdx.x % 256;             // thread within its side
+    const int side0 = a.par ? (int)threadIdx.x / 256 : 0, side1 = a.par ? side0 + 1 : 2;
+    const int L = a.L, sub = tx % L, per_lane = a.E / L;
+    // the lane's part of item `local` of this workgroup: which (token, sub-vector), and its elements
+    struct Item { bool live; int t, p; };
+    auto item_of = [&](int r) {
+        const int item = (r * 256 + tx) / L;
+        Item it;
+        it.live = item < nt * P;
+        it.t = t0 + (it.live ? item / P : 0);
+        it.p = it.live ? item % P : 0;
+        return it;
+    };
+    auto load_x = [&](int side, const Item &it, float (&xv)[V]) {
+        const half_t *xp = a.x[side] + (((size_t)bh * a.n_new + it.t) * a.D) + it.p * V;
+        if constexpr (V == 8) {
+            const V16 x8 = ld16(xp);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xv[i] = (float)x8.h8[i];
+        } else if constexpr (V == 4) {
+            const V8 x4 = ld8(xp);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xv[i] = (float)x4.h4[i];
+        } else {
+            const half2_t x2 = *reinterpret_cast<const half2_t *>(xp);
+            xv[0] = (float)x2[0];
+            xv[1] = (float)x2[1];
+        }
+    };
+    // the first item's elements are asked for before the codebooks (they come from further away)
+    float x_first[V];
+    load_x(side0, item_of(0), x_first);
     auto stage = [&](int side, cb_t *dst) {
         const half_t *src = a.cb[side] + (size_t)h * cb_halves;
         if (F32) {
-            for (int i = threadIdx.x; i < cb_halves / 8; i += 256) {
+            for (int i = threadIdx.x; i < cb_halves / 8; i += nthreads) {
                 const V16 e8 = ld16(src + i * 8);
 #pragma unroll
                 for (int k = 0; k < 8; ++k) dst[i * 8 + k] = (cb_t)e8.h8[k];
             }
         } else {
-            for (int i = threadIdx.x; i < cb_halves / 8; i += 256)
+            for (int i = threadIdx.x; i < cb_halves / 8; i += nthreads)
                 reinterpret_cast<uint4 *>(dst)[i] = reinterpret_cast<const uint4 *>(src)[i];
         }
     };
@@ -60,7 +93,7 @@ __global__ __launch_bounds__(256) void kv_quantize_kernel(KvQuantArgs a) {
         stage(1, cbl + cb_halves);
         __syncthreads();
     }
-    for (int side = 0; side < 2; ++side) {
+    for (int side = side0; side < side1; ++side) {
         const cb_t *cbs = cbl + (a.both ? side * cb_halves : 0);
         if (!a.both) {
             __syncthreads();  // the previous side's lookups are done before its codebooks are overwritten
@@ -70,30 +103,27 @@ __global__ __launch_bounds__(256) void kv_quantize_kernel(KvQuantArgs a) {
         // all lanes of a wavefront run the same number of rounds (the merge below uses lane shuffles)
         const int n_items = nt * P, rounds = (n_items * L + 255) / 256;
         for (int r = 0; r < rounds; ++r) {
-            const int item = (r * 256 + (int)threadIdx.x) / L;
-            const bool live = item < n_items;
-            const int t = t0 + (live ? item / P : 0), p = live ? item % P : 0;
-            const half_t *xp = a.x[side] + (((size_t)bh * a.n_new + t) * a.D) + p * V;
+            const Item it = item_of(r);
+            const bool live = it.live;
+            const int t = it.t, p = it.p;
             float xv[V];
-            if constexpr (V == 8) {
-                const V16 x8 = ld16(xp);
+            if (side == side0 && r == 0) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) xv[i] = (float)x8.h8[i];
-            } else if constexpr (V == 4) {
-                const V8 x4 = ld8(xp);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) xv[i] = (float)x4.h4[i];
+                for (int i = 0; i < V; ++i) xv[i] = x_first[i];
             } else {
-                const half2_t x2 = *reinterpret_cast<const half2_t *>(xp);
-                xv[0] = (float)x2[0];
-                xv[1] = (float)x2[1];
+                load_x(side, it, xv);
             }
             const cb_t *grp = cbs + (size_t)(p * a.G / P) * a.E * V;
-            const int e0 = sub * per_lane;
-            int best = e0;
+            // the L lanes of an item take the entries in turn (lane `sub`: sub, sub + L, ...), so that at every
+            // step they read L neighbouring entries: with a block of consecutive entries per lane the L
+            // addresses of a step are 16 * E / L bytes apart, all in the same LDS banks -- an 8-way conflict
+            // that made the walk of a decode step 7 us long.  Each lane still meets its entries in ascending
+            // order, so its strict "<" keeps the smallest index among equals.
+            int best = sub;
             float best_d = INFINITY;
 #pragma unroll 4
-            for (int e = e0; e < e0 + per_lane; ++e) {
+            for (int k = 0; k < per_lane; ++k) {
+                const int e = sub + k * L;
                 float d = 0.f;
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
@@ -148,13 +178,16 @@ int launch_kv_quantize(const vq_kv_t *kv, const void *k_new, const void *v_new, 
     int L = 1;
     while (L < 64 && items * (L * 2) <= 256 && kv->n_entries % (L * 2) == 0) L *= 2;
     a.L = L;
+    // a decode-sized call (one round of items per side) runs the two sides side by side
+    a.par = a.both && items * L <= 256;
+    const int threads = a.par ? 512 : 256;
     const dim3 grid(kv->B * kv->H, (n_new + a.tokens_per_wg - 1) / a.tokens_per_wg);
 #define VQ_KVQ(V)                                                         \
     do {                                                                  \
         if (f32)                                                          \
-            kv_quantize_kernel<V, true><<<grid, 256, lds, s>>>(a);        \
+            kv_quantize_kernel<V, true><<<grid, threads, lds, s>>>(a);    \
         else                                                              \
-            kv_quantize_kernel<V, false><<<grid, 256, lds, s>>>(a);       \
+            kv_quantize_kernel<V, false><<<grid, threads, lds, s>>>(a);   \
     } while (0)
     if (kv->v == 8)
         VQ_KVQ(8);
