@@ -61,7 +61,7 @@ typedef enum vq_status {
  * derives every address from this struct alone and reads no table before it can ask for its codes.  That
  * needs codes that spread evenly over the codebook (as quantizers produce them): vq_gemv_prepack declines
  * (VQ_ERR_UNSUPPORTED, vq_gemv_prepack_bytes = 0) when padding to the common shape would cost more than a
- * quarter more blocks, or a workgroup has more than VQ_PACK_MAX_GROUPS groups; vq_gemv then runs from the
+ * quarter more blocks and more than 1 MiB, or a workgroup has more than VQ_PACK_MAX_GROUPS groups; vq_gemv then runs from the
  * canonical codes.  Layout of `data`: see the format description in the source of vq_gemv_prepack.
  */
 #define VQ_PACK_MAX_GROUPS 128

@@ -132,7 +132,11 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
         prefix[g] = (uint32_t)pitch;
         pitch += max_steps[g];
     }
-    if (pitch > 65535 || pitch * nwg > needed_blocks + needed_blocks / 4 + nwg) return 0;  // too uneven
+    // too uneven: more than a quarter more blocks than needed -- unless that is less than 1 MiB (small or
+    // ragged matrices, where a group of a few rows is as long as its longest row in the unluckiest workgroup)
+    const uint64_t padded = pitch * nwg;
+    if (pitch > 65535) return 0;
+    if (padded > needed_blocks + needed_blocks / 4 + nwg && (padded - needed_blocks) * 768 > (1u << 20)) return 0;
     const uint64_t atom_blocks = pitch * nwg;
     const uint64_t rowid_off = 0;
     const uint64_t atom_off = align256(rowid_off + rowids.size() * 2);
