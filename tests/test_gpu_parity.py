@@ -618,3 +618,18 @@ def test_gemv_packed_random_shapes(gpu_device, seed):
         what = f"packed N{w.N} K{K} E{E} zipf{zipf} member {i}/{count} packed={packable[i]}"
         assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), what)
         assert torch.equal(y, vq.vq_gemv(wd, xd)), what
+
+
+# ---------------------------------------------------------------- measurement probes
+
+def test_measurement_probes_run_and_copy_is_exact(gpu_device):
+    # vq_probe_copy is what the HBM counters are calibrated on: it must move exactly the bytes it is given
+    src = torch.randint(0, 256, (1 << 20,), dtype=torch.uint8, device=gpu_device)
+    dst = torch.zeros_like(src)
+    vq.vq_probe_copy(dst, src)
+    sink = torch.zeros(1 << 16, dtype=torch.uint8, device=gpu_device)
+    vq.vq_probe_read(src, sink)
+    for mode in (0, 1, 2):      # smooth register operands, random register operands, random operands from LDS
+        vq.vq_probe_mfma(8, 4, sink, random_operands=mode)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
