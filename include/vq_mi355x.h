@@ -126,7 +126,7 @@ size_t vq_gemv_workspace(const vq_weight_t *w, int bs);
  * HOST memory here (codebooks / scale are not touched); no GPU is needed.
  *   vq_gemv_prepack_bytes: size of the packed buffer for this matrix, 0 if the configuration
  *     has no packed form (supported: v = 8, uint16 codes, one codebook, E a power of two
- *     >= 4096, K / v <= 2047).
+ *     >= 4096, K / v <= 2047, codes that spread evenly over the codebook: see vq_gemv_pack_t).
  *   vq_gemv_prepack: writes the packed buffer into out_host (>= that size, 16-byte aligned)
  *     and fills *pack (pack->data = out_host; replace it by the device copy's address before
  *     passing the struct to vq_gemv).  Errors: NULL / UNSUPPORTED / WORKSPACE (buffer too small).
