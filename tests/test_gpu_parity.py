@@ -495,6 +495,9 @@ def test_packed_12_bit_full_size(gpu_device):
     (2, 2, 300, 4, 32, 130, 7),     # prefill chunk, one codebook per sub-space, several token chunks
     (1, 2, 64, 8, 4, 64, 0),
     (1, 2, 50, 2, 1, 5, 20),
+    (3, 5, 33, 8, 1, 1, 32),        # decode, v = 8: 16 items per side, 16 lanes each
+    (2, 3, 20, 2, 1, 2, 3),         # two new tokens, v = 2: 128 items per side
+    (2, 2, 16, 4, 32, 1, 15),       # decode with one codebook per sub-space (sides staged one after the other)
 ])
 def test_kv_quantize_codes_bit_exact_and_in_place(gpu_device, B, H, T, v, G, n_new, pos):
     kv = wl.make_kv(B, H, 128, T, v, 256, G, seed=9300 + T)
@@ -509,6 +512,26 @@ def test_kv_quantize_codes_bit_exact_and_in_place(gpu_device, B, H, T, v, G, n_n
     want_v[:, :, pos:pos + n_new] = oracle.kv_quantize(v_new, kv.v_codebooks)
     assert np.array_equal(kd.k_codes.cpu().numpy(), want_k)          # integer result: exact; the rest untouched
     assert np.array_equal(kd.v_codes.cpu().numpy(), want_v)
+
+
+def test_kv_quantize_ties_go_to_the_smallest_index(gpu_device):
+    # a codebook of four distinct entries repeated 64 times: every sub-vector has 64 equally close entries,
+    # spread over all the lanes that share the item; the smallest index must win (decode and prefill paths)
+    for n_new in (1, 70):
+        kv = wl.make_kv(2, 2, 128, 80, 4, 256, 1, seed=9100 + n_new)
+        for cb in (kv.k_codebooks, kv.v_codebooks):
+            cb[:] = np.tile(cb[:, :, :4, :], (1, 1, 64, 1))
+        rng = np.random.Generator(np.random.PCG64(9101))
+        k_new = rng.normal(0, 1, size=(2, 2, n_new, 128)).astype(np.float16)
+        v_new = rng.normal(0, 1, size=(2, 2, n_new, 128)).astype(np.float16)
+        kd = vq.kv_to_device(kv, gpu_device)
+        vq.vq_kv_quantize(kd, dev_x(k_new, gpu_device), dev_x(v_new, gpu_device), 5)
+        torch.cuda.synchronize()
+        got_k = kd.k_codes.cpu().numpy()[:, :, 5:5 + n_new]
+        got_v = kd.v_codes.cpu().numpy()[:, :, 5:5 + n_new]
+        assert got_k.max() < 4 and got_v.max() < 4
+        assert np.array_equal(got_k, oracle.kv_quantize(k_new, kv.k_codebooks))
+        assert np.array_equal(got_v, oracle.kv_quantize(v_new, kv.v_codebooks))
 
 
 def test_kv_quantize_then_attend(gpu_device):
@@ -618,6 +641,36 @@ def test_gemv_packed_random_shapes(gpu_device, seed):
         what = f"packed N{w.N} K{K} E{E} zipf{zipf} member {i}/{count} packed={packable[i]}"
         assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), what)
         assert torch.equal(y, vq.vq_gemv(wd, xd)), what
+
+
+@pytest.mark.parametrize("seed", range(int(__import__("os").environ.get("VQ_TEST_RANDOM_CASES", "16"))))
+def test_kv_quantize_random_shapes(gpu_device, seed):
+    rng = np.random.default_rng(96000 + seed)
+    v = int(rng.choice([2, 4, 8]))
+    P = 128 // v
+    G = int(rng.choice([g for g in (1, 2, 4, 8, 16, 32, 64) if P % g == 0 and g * 256 * v * 2 <= 64 * 1024]))
+    E = int(rng.choice([8, 16, 200, 256]))
+    if (G * E * v * 2) % 16 != 0:
+        E = 256
+    B, H = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    n_new = int(rng.choice([1, 1, 2, 3, 7, 8, 9, 64, 65, 150]))
+    T = n_new + int(rng.integers(0, 40))
+    pos = int(rng.integers(0, T - n_new + 1))
+    kv = wl.make_kv(B, H, 128, T, v, E, G, seed=96100 + seed)
+    if rng.random() < 0.3:      # some repeated entries: exact ties
+        for cb in (kv.k_codebooks, kv.v_codebooks):
+            cb[:, :, E // 2:, :] = cb[:, :, :E - E // 2, :]
+    k_new = rng.normal(0, 1, size=(B, H, n_new, 128)).astype(np.float16)
+    v_new = rng.normal(0, 1, size=(B, H, n_new, 128)).astype(np.float16)
+    what = f"kvq B{B} H{H} T{T} v{v} G{G} E{E} n_new{n_new} pos{pos}"
+    kd = vq.kv_to_device(kv, gpu_device)
+    vq.vq_kv_quantize(kd, dev_x(k_new, gpu_device), dev_x(v_new, gpu_device), pos)
+    torch.cuda.synchronize()
+    want_k, want_v = kv.k_codes.copy(), kv.v_codes.copy()
+    want_k[:, :, pos:pos + n_new] = oracle.kv_quantize(k_new, kv.k_codebooks)
+    want_v[:, :, pos:pos + n_new] = oracle.kv_quantize(v_new, kv.v_codebooks)
+    assert np.array_equal(kd.k_codes.cpu().numpy(), want_k), what
+    assert np.array_equal(kd.v_codes.cpu().numpy(), want_v), what
 
 
 # ---------------------------------------------------------------- measurement probes
