@@ -9,9 +9,14 @@
 //   workgroup (s, rb) holds slice s (E/S entries) and the activation vector in LDS and
 //   processes, for the rows of block rb, exactly the codes that point into slice s.
 // Those codes are found offline (Sec. II-C: weights are quantized offline; Sec. V-B already
-// rewrites indices offline) by vq_gemv_prepack and stored as 24-bit atoms:
-//   bits 0..11  entry index inside the slice      bits 12..22  sub-vector position j
-//   bit 23      valid (padding atoms are 0)
+// rewrites indices offline) by vq_gemv_prepack and stored as 24-bit atoms, two 12-bit numbers of
+// 16-byte units in the workgroup's LDS image  [slice: E/S units][x: K/8 units][one zero unit]:
+//   bits 0..11   unit of the entry   = its index inside the slice
+//   bits 12..23  unit of x_j         = E/S + j
+// so an address is a shift and a mask away from the atom.  A padding atom names the zero unit twice and
+// adds 0 * 0: no validity test per atom (the loop around the gathers is bound by vector ALU issue: 15
+// instructions per atom before this format, 9 with it).  The image must fit 4096 units: slices of at most
+// 2048 entries, K/8 <= 2047.
 // One lane owns one row: it walks that row's atoms (j ascending), gathers entry and x_j from
 // LDS and accumulates privately, so there is no cross-lane reduction at all.  Rows of a block
 // are sorted by atom count and grouped 64 at a time, so the lanes of a wavefront run nearly the
@@ -20,8 +25,8 @@
 //
 // Packed buffer (little endian, offsets from the start of the buffer, 256-byte aligned):
 //   row ids      [S*RB][G][64] uint16   row inside the block, 0xFFFF = idle lane; G = ceil(rows_per_block / 64)
-//   atoms        blocks of 768 bytes = 64 lanes x 12 bytes = 4 atoms per lane per step; 16 zeroed blocks follow
-//                the last workgroup's (the kernels read a few blocks past the end of a group without looking)
+//   atoms        blocks of 768 bytes = 64 lanes x 12 bytes = 4 atoms per lane per step; 16 blocks of padding atoms
+//                follow the last workgroup's (the kernels read a few blocks past the end of a group without looking)
 // Placement of the atom blocks.  A kernel that has to read a table before it can ask for its atoms
 // pays two dependent first touches of memory (~1.5 us each) before any work.  Codes that spread evenly
 // over the codebook make group g look nearly the same in every workgroup (the g-th 64 rows of a sorted
@@ -39,12 +44,10 @@
 
 namespace vq {
 
-constexpr int kPackLocalBits = 12;
-// zeroed atom blocks behind the last workgroup's: the kernels read up to this many blocks past the end of a group
+constexpr int kPackFieldBits = 12;   // an atom = two LDS unit numbers of 12 bits
+// atom blocks behind the last workgroup's: the kernels read up to this many blocks past the end of a group
 // without looking (a clamp per load costs more instructions than the load)
 constexpr int kPackTailBlocks = 16;
-constexpr int kPackJBits = 11;
-constexpr uint32_t kPackValid = 1u << 23;
 
 struct PackPlan {
     uint32_t S, RB, rows_per_block, slice_entries;
@@ -54,20 +57,19 @@ static bool pack_supported(const vq_weight_t *w) {
     if (w->v != 8 || w->code_bits != 16 || w->n_codebooks != 1) return false;
     int E = w->n_entries;
     if (E < 4096 || (E & (E - 1)) != 0) return false;
-    if (w->K <= 0 || w->N <= 0 || w->K / 8 >= (1 << kPackJBits)) return false;
+    if (w->K <= 0 || w->N <= 0 || 2048 + w->K / 8 + 1 > (1 << kPackFieldBits)) return false;  // slice + x + zero unit
     return true;
 }
 
-// S * RB = 256 workgroups, one per compute unit.  Slices of 2048 entries (32 KiB) unless that
-// would give a workgroup more than 16 row groups (one per wavefront): then 4096 entries.  Long rows
+// S * RB = 256 workgroups, one per compute unit.  Slices of 2048 entries (32 KiB); a workgroup with more
+// than 16 row groups gives its wavefronts several groups each.  Long rows
 // (K > 8192) take 1024-entry slices: the atom list of a (row, slice) cell is K/8 / S long, and a short
 // list is what keeps every step of a wavefront in its register prefetch (measured on 4096 x 11008:
 // 18.2 -> 14.6 us; on K = 4096 the doubled partial-sum traffic costs more than it saves).
 static PackPlan pack_plan(const vq_weight_t *w) {
     PackPlan p;
     p.slice_entries = 2048;
-    if ((uint64_t)w->N * ((uint32_t)w->n_entries / 2048) > 256u * 1024u) p.slice_entries = 4096;
-    else if (w->K / 8 > 1024 && w->n_entries >= 65536) p.slice_entries = 1024;
+    if (w->K / 8 > 1024 && w->n_entries >= 65536) p.slice_entries = 1024;
     p.S = (uint32_t)w->n_entries / p.slice_entries;
     uint32_t rb = 256 / p.S;
     uint32_t max_rb = ((uint32_t)w->N + 63) / 64;   // at least one full 64-row group per block
@@ -157,7 +159,14 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
     std::memset(out, 0, (size_t)atom_off);
     std::memcpy(out + rowid_off, rowids.data(), rowids.size() * 2);
     unsigned char *atoms = out + atom_off;
-    std::memset(atoms, 0, (size_t)((atom_blocks + kPackTailBlocks) * 768));
+    // padding everywhere first: the zero unit (behind slice and x) as entry and as x_j
+    const uint32_t zero_unit = p.slice_entries + (uint32_t)J;
+    const uint32_t pad_atom = zero_unit | (zero_unit << kPackFieldBits);
+    for (uint64_t i = 0, n_atoms = (atom_blocks + kPackTailBlocks) * 256; i < n_atoms; ++i) {
+        atoms[3 * i] = (unsigned char)pad_atom;
+        atoms[3 * i + 1] = (unsigned char)(pad_atom >> 8);
+        atoms[3 * i + 2] = (unsigned char)(pad_atom >> 16);
+    }
     // fill: lane l of group g walks row rowids[wg][g][l]; its k-th atom of slice s goes to step k/4, slot k%4
     for (uint32_t wg = 0; wg < nwg; ++wg) {
         uint32_t s = wg / p.RB, rb = wg % p.RB;
@@ -170,7 +179,7 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
                 uint32_t k = 0;
                 for (int j = 0; j < J; ++j) {
                     if ((uint32_t)(row[j] >> lb) != s) continue;
-                    uint32_t atom = (row[j] & ((1u << lb) - 1)) | ((uint32_t)j << kPackLocalBits) | kPackValid;
+                    uint32_t atom = (row[j] & ((1u << lb) - 1)) | ((p.slice_entries + (uint32_t)j) << kPackFieldBits);
                     unsigned char *q = atoms + (first_block + k / 4) * 768 + l * 12 + (k % 4) * 3;
                     q[0] = (unsigned char)atom;
                     q[1] = (unsigned char)(atom >> 8);
@@ -218,12 +227,23 @@ struct Acc4 {
     float a0, a1, a2, a3;
 };
 
-__device__ __forceinline__ float atom_fma(uint32_t atom, const V16 &e, const V16 &xv, float acc) {
-    float d = dot2(e.h2[0], xv.h2[0], 0.f);
-    d = dot2(e.h2[1], xv.h2[1], d);
-    d = dot2(e.h2[2], xv.h2[2], d);
-    d = dot2(e.h2[3], xv.h2[3], d);
-    return (atom & kPackValid) ? acc + d : acc;
+// 16 bytes at an absolute LDS address.  The kernels below have no static LDS, so the dynamic region (the
+// image the atoms index) starts at address 0 and a unit number is an address after one shift; going through
+// a pointer into the region would cost one more add per gather for a base the compiler cannot see is 0.
+// (A test compiles this file and checks that these kernels have no static LDS.)
+__device__ __forceinline__ V16 lds_unit(uint32_t byte_address) {
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t v = *(const __attribute__((address_space(3))) u32x4_t *)(uintptr_t)byte_address;
+    V16 r;
+    r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.w[3] = v.w;
+    return r;
+}
+
+__device__ __forceinline__ float atom_fma(const V16 &e, const V16 &xv, float acc) {
+    acc = dot2(e.h2[0], xv.h2[0], acc);
+    acc = dot2(e.h2[1], xv.h2[1], acc);
+    acc = dot2(e.h2[2], xv.h2[2], acc);
+    return dot2(e.h2[3], xv.h2[3], acc);
 }
 
 // One step = the lane's next four atoms (three dwords).  The LDS gathers (entry and x_j of each atom)
@@ -232,23 +252,22 @@ __device__ __forceinline__ float atom_fma(uint32_t atom, const V16 &e, const V16
 // wavefronts asking) and the gather phase of a 4096 x 4096 launch lasts 3.1 us.  CL = 4 keeps 32
 // registers of operands in flight, CL = 2 half of that (for the kernels held to 128 registers).
 template <int CL>
-__device__ __forceinline__ void step_dot(uint32_t d0, uint32_t d1, uint32_t d2, const unsigned char *slice,
-                                         const unsigned char *xl, Acc4 &acc) {
-    const uint32_t at[4] = {d0 & 0xffffffu, __builtin_amdgcn_alignbit(d1, d0, 24) & 0xffffffu,
-                            __builtin_amdgcn_alignbit(d2, d1, 16) & 0xffffffu, d2 >> 8};
+__device__ __forceinline__ void step_dot(uint32_t d0, uint32_t d1, uint32_t d2, Acc4 &acc) {
+    // the 24 bits of atom k start at bit 24 k of the 96-bit string d2:d1:d0
+    const uint32_t at[4] = {d0, __builtin_amdgcn_alignbit(d1, d0, 24), __builtin_amdgcn_alignbit(d2, d1, 16), d2 >> 8};
     float *accs[4] = {&acc.a0, &acc.a1, &acc.a2, &acc.a3};
 #pragma unroll
     for (int h = 0; h < 4; h += CL) {
         V16 e[CL], xv[CL];
 #pragma unroll
         for (int i = 0; i < CL; ++i) {
-            e[i] = *reinterpret_cast<const V16 *>(slice + ((at[h + i] & 0xfffu) << 4));
-            xv[i] = *reinterpret_cast<const V16 *>(xl + (((at[h + i] >> kPackLocalBits) & 0x7ffu) << 4));
+            e[i] = lds_unit((at[h + i] << 4) & 0xfff0u);
+            xv[i] = lds_unit((at[h + i] >> (kPackFieldBits - 4)) & 0xfff0u);
         }
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * CL, 0);  // these LDS reads first,
-        __builtin_amdgcn_sched_group_barrier(0x002, 8 * CL, 0);  // then the arithmetic on them
+        __builtin_amdgcn_sched_group_barrier(0x002, 4 * CL, 0);  // then the arithmetic on them
 #pragma unroll
-        for (int i = 0; i < CL; ++i) *accs[h + i] = atom_fma(at[h + i], e[i], xv[i], *accs[h + i]);
+        for (int i = 0; i < CL; ++i) *accs[h + i] = atom_fma(e[i], xv[i], *accs[h + i]);
     }
 }
 
@@ -266,9 +285,11 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     pin_scalar(a.N); pin_scalar(a.J); pin_scalar(a.S); pin_scalar(a.RB); pin_scalar(a.rows_per_block);
     pin_scalar(a.slice_entries); pin_scalar(a.rowid_off); pin_scalar(a.atom_off); pin_scalar(a.wg_pitch);
     pin_scalar(a.nwaves); pin_scalar(group_word);
-    unsigned char *slice = smem;                                    // slice_entries * 16 bytes
-    unsigned char *xl = smem + (size_t)a.slice_entries * 16;        // J * 16 bytes
-    float *accbuf = reinterpret_cast<float *>(xl + (size_t)a.J * 16);  // one float per row of the block
+    // the LDS image the atoms index, in 16-byte units: [slice][x][one zero unit]; then one float per row of the block
+    unsigned char *slice = smem;
+    unsigned char *xl = smem + (size_t)a.slice_entries * 16;
+    unsigned char *zero_unit = xl + (size_t)a.J * 16;
+    float *accbuf = reinterpret_cast<float *>(zero_unit + 16);
 
     const int tid = threadIdx.x, lane = tid & 63, nwaves = a.nwaves;
     // Workgroups are dealt round-robin to the 8 compute dies, each with its own L2.  All row blocks of
@@ -312,6 +333,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
             dma16(src + c * 64 + lane, slice + c * 1024);
         for (int c = wave; c * 64 < a.J; c += nwaves)
             if (c * 64 + lane < a.J) dma16(xs + c * 64 + lane, xl + c * 1024);
+        if (tid < 4) reinterpret_cast<uint32_t *>(zero_unit)[tid] = 0u;  // what padding atoms point at
     }
     // (2) this wavefront's first group: where its atoms lie follows from the launch arguments alone, so
     //     the row ids and the atoms are requested right behind the slice.  Loads complete in the order
@@ -325,7 +347,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     // Step st of the group whose first block this lane sees at `base`.  No look at the group's length: a
     // branch around a load keeps the compiler from counting which loads are in flight (it then waits for
     // all of them before every use), and a clamp costs more instructions than the load.  Blocks past the
-    // end of a group belong to the next one, or to the zeroed tail of the buffer, and are never used.
+    // end of a group belong to the next one, or to the tail of the buffer, and are never used.
     static_assert(PF <= kPackTailBlocks && (!RING || 2 * PF - 2 <= kPackTailBlocks),
                   "reads run up to PF (ring: 2 PF - 2) blocks past the end of a group");
     auto load_step = [&](uint32_t (&dst)[3], gbyte_t *base, uint32_t st) {
@@ -346,7 +368,8 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     for (int st = 0; st < PF; ++st) load_step(q[st], gbase, st);
     // PF atom loads and the row ids were issued behind the staging transfers: when at most PF + 1 loads are
     // pending, the transfers have landed.  (A test compiles this file and counts those loads in each build.)
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PF + 1) : "memory");
+    // (lgkmcnt: the store of the zero unit)
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(PF + 1) : "memory");
     // (3) the slice and x of this wavefront have landed (direct-to-LDS transfers count as vector memory
     //     loads); after the barrier those of all wavefronts are visible.  A bare s_barrier: __syncthreads()
     //     would wait for the atoms as well.
@@ -367,7 +390,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
                 for (int k = 0; k < PF; ++k) {
                     const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
                     load_step(q[k], gbase, base + k + PF);
-                    if (base + k < gr.y) step_dot<CL>(d0, d1, d2, slice, xl, acc);
+                    if (base + k < gr.y) step_dot<CL>(d0, d1, d2, acc);
                 }
             };
             // (the first round outside the loop: at a loop head the ring would be copied, and a copy needs
@@ -380,11 +403,11 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
             if constexpr (PRE) {
 #pragma unroll
                 for (int st = 0; st < PF; ++st)
-                    if ((uint32_t)st < gr.y) step_dot<CL>(q[st][0], q[st][1], q[st][2], slice, xl, acc);
+                    if ((uint32_t)st < gr.y) step_dot<CL>(q[st][0], q[st][1], q[st][2], acc);
             }
             for (uint32_t st = PRE ? PF : 0; st < gr.y; ++st) {
                 gu32_t *p = (gu32_t *)(gbase + (size_t)st * 768);
-                step_dot<CL>(p[0], p[1], p[2], slice, xl, acc);
+                step_dot<CL>(p[0], p[1], p[2], acc);
             }
         }
         if (ri != 0xFFFFu) accbuf[ri] = (acc.a0 + acc.a1) + (acc.a2 + acc.a3);
@@ -549,8 +572,10 @@ PackedLaunch packed_launch(const vq_weight_t *w, const void *x, void *y, void *p
         }
     }
     int groups_per_wg = (int)((p->rows_per_block + 63) / 64);
-    l.lds = (size_t)plan.slice_entries * 16 + (size_t)a.J * 16 + (size_t)groups_per_wg * 64 * sizeof(float);
-    l.waves = groups_per_wg < 16 ? groups_per_wg : 16;
+    l.lds = ((size_t)plan.slice_entries + (size_t)a.J + 1) * 16 + (size_t)groups_per_wg * 64 * sizeof(float);
+    // every wavefront the same number of groups (the first, longest ones are dealt first, one to each)
+    const int rounds = (groups_per_wg + 15) / 16;
+    l.waves = (groups_per_wg + rounds - 1) / rounds;
     if (l.waves < 8) l.waves = 8;   // at least 512 threads, so that slice and x are staged with many loads in flight
     a.nwaves = l.waves;
     l.grid = (int)(p->S * p->RB);

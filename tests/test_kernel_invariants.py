@@ -30,7 +30,8 @@ def test_gemv_packed_counted_wait_matches_the_loads_in_front_of_it(tmp_path):
         m = re.search(r"^(_ZN2vq\d+%sE\w*):[^\n]*\n(.*?)^\.Lfunc_end" % name, text, re.S | re.M)
         assert m, name
         lines = [l.strip() for l in m.group(2).splitlines()]
-        waits = [i for i, l in enumerate(lines) if l == "s_waitcnt vmcnt(%d)" % (pf + 1) and "ASMSTART" in lines[i - 1]]
+        waits = [i for i, l in enumerate(lines)
+                 if l == "s_waitcnt vmcnt(%d) lgkmcnt(0)" % (pf + 1) and "ASMSTART" in lines[i - 1]]
         assert len(waits) == 1, (name, waits)
         w = waits[0]
         assert any(l == "s_barrier" for l in lines[w:w + 6]), name          # the wait guards the barrier
@@ -42,6 +43,10 @@ def test_gemv_packed_counted_wait_matches_the_loads_in_front_of_it(tmp_path):
         # straight-line: no branch may skip one of the loads that the count relies on
         first = next(i for i, l in enumerate(between) if l in loads)
         assert not any(l.startswith(("s_cbranch", "s_branch")) or l.endswith(":") for l in between[first:]), name
+        # the atoms hold absolute LDS addresses of the dynamic region: it must start at 0, i.e. no static LDS
+        k = re.search(r"\.amdhsa_kernel (_ZN2vq\d+%sE\w*)\n(.*?)\.end_amdhsa_kernel" % name, text, re.S)
+        assert k, name
+        assert re.search(r"\.amdhsa_group_segment_fixed_size 0\b", k.group(2)), name
         checked += 1
     assert checked == 3
 

@@ -19,8 +19,13 @@ def decode(buf, pack, N, J, SLICE):
     prefix = np.concatenate([[0], np.cumsum(steps)])
     rowids = np.frombuffer(buf, dtype=np.uint16, count=64 * ng * S * RB, offset=pack.rowid_off).reshape(S * RB, ng, 64)
     atoms = np.frombuffer(buf, dtype=np.uint8, offset=pack.atom_off)
-    assert atoms.size == (S * RB * pack.wg_pitch + 16) * 768          # 16 zeroed blocks behind the last workgroup's
-    assert not atoms[S * RB * pack.wg_pitch * 768:].any()
+    assert atoms.size == (S * RB * pack.wg_pitch + 16) * 768          # 16 blocks of padding behind the last workgroup's
+    # an atom = two 12-bit numbers of 16-byte units in the LDS image [slice][x][zero unit]; padding names the zero unit twice
+    zero_unit = SLICE + J
+    assert zero_unit < 4096
+    pad = zero_unit | (zero_unit << 12)
+    tail = atoms[S * RB * pack.wg_pitch * 768:].reshape(-1, 3).astype(np.uint32)
+    assert ((tail[:, 0] | (tail[:, 1] << 8) | (tail[:, 2] << 16)) == pad).all()
     codes = np.zeros((N, J), dtype=np.int64)
     hits = np.zeros((N, J), dtype=np.int32)
     for w in range(S * RB):
@@ -34,9 +39,10 @@ def decode(buf, pack, N, J, SLICE):
             for lane in range(64):
                 ri = int(rowids[w, g, lane])
                 lst = val[lane]
-                valid = (lst >> 23) & 1
+                valid = lst != pad
                 n_valid = int(valid.sum())
-                assert (valid[:n_valid] == 1).all() and (lst[n_valid:] == 0).all()   # valid atoms first, padding is zero
+                assert valid[:n_valid].all()                                       # real atoms first, then padding
+                assert ((lst[:n_valid] & 0xFFF) < SLICE).all() and ((lst[:n_valid] >> 12) >= SLICE).all()
                 if ri == 0xFFFF:
                     assert n_valid == 0
                     continue
@@ -45,7 +51,8 @@ def decode(buf, pack, N, J, SLICE):
                 prev_len = n_valid
                 n = rb * RPB + ri
                 assert ri < RPB and n < N
-                js = (lst[:n_valid] >> 12) & 0x7FF
+                js = (lst[:n_valid] >> 12) - SLICE
+                assert (js < J).all()
                 assert (np.diff(js.astype(np.int64)) > 0).all()                # ascending positions: fixed summation order
                 codes[n, js] = s * SLICE + (lst[:n_valid] & 0xFFF)
                 hits[n, js] += 1
@@ -58,14 +65,14 @@ def decode(buf, pack, N, J, SLICE):
     (513, 2048, 65536),
     (1, 64, 65536),
     (70, 16368, 8192),       # longest supported rows (K/8 = 2046)
-    (9000, 64, 65536),       # many rows: 4096-entry slices, 16 x 16 workgroups
+    (9000, 64, 65536),       # many rows: 18 groups per workgroup
     (20000, 64, 65536),      # 20 groups per workgroup
 ])
 def test_prepack_round_trip(N, K, E):
     w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=77 + N)
     buf, pack = vq.vq_gemv_prepack(w)
     assert buf is not None and pack.bytes == buf.size
-    assert pack.S in (E // 2048, E // 4096) and pack.S * pack.RB <= 256
+    assert pack.S == E // 2048 and pack.S * pack.RB <= 256
     codes, hits = decode(buf, pack, N, K // 8, E // pack.S)
     assert (hits == 1).all()                       # every code appears exactly once
     assert np.array_equal(codes, w.codes[:, :, 0].astype(np.int64))
@@ -97,5 +104,5 @@ def test_prepack_llama_shape_size_and_speed():
     dt = time.time() - t0
     ratio = buf.size / w.codes.nbytes
     print(f"prepack 11008x4096: {dt:.2f} s, {buf.size / 2**20:.1f} MiB = {ratio:.3f} x canonical codes")
-    assert (pack.S, pack.RB) == (16, 16)               # 11008 rows: 4096-entry slices
-    assert 1.5 <= ratio < 1.85                     # 3 bytes per code plus padding to whole 4-atom steps
+    assert (pack.S, pack.RB) == (32, 8)                # 2048-entry slices, 22 groups per workgroup
+    assert 1.5 <= ratio < 1.9                      # 3 bytes per code plus padding to whole 4-atom steps and to the common shape
