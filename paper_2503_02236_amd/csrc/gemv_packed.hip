@@ -220,8 +220,11 @@ __device__ __forceinline__ void pin_scalar(T &v) {
 }
 
 constexpr int kPackMaxSlices = 64;  // 2^16 entries / 1024 per slice
-constexpr int kPackPrefetch = 10;      // 4-atom steps fetched into registers while the slice is being staged
-constexpr int kPackPrefetchBatch = 4;  // batch kernel: a ring of 4 steps in flight (80 registers, three workgroups per CU)
+// Steps in flight per wavefront: a ring of 4 (12 registers).  More steps requested before the barrier do not
+// arrive sooner -- a CU's share of the memory system is ~20 KB per microsecond, and what is requested ahead of
+// another wavefront's slice transfer delays that transfer and with it the barrier (measured on 4096 x 11008:
+// 12 steps ahead, barrier 2.6 us after the loads were issued, 9.8 us in all; 4 steps, 1.5 us and 8.8 us).
+constexpr int kPackRing = 4;
 
 struct Acc4 {
     float a0, a1, a2, a3;
@@ -273,7 +276,7 @@ __device__ __forceinline__ void step_dot(uint32_t d0, uint32_t d1, uint32_t d2, 
 
 // All global loads of a workgroup are issued before anything waits: the kernel is a chain of
 // memory latencies (tables -> atoms -> partials), not a bandwidth problem, at these sizes.
-template <int PF, bool RING, int CL>
+template <int PF, int CL>
 __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int bid) {
     extern __shared__ __align__(16) unsigned char smem[];
     // all launch arguments in one round of scalar loads
@@ -348,8 +351,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     // branch around a load keeps the compiler from counting which loads are in flight (it then waits for
     // all of them before every use), and a clamp costs more instructions than the load.  Blocks past the
     // end of a group belong to the next one, or to the tail of the buffer, and are never used.
-    static_assert(PF <= kPackTailBlocks && (!RING || 2 * PF - 2 <= kPackTailBlocks),
-                  "reads run up to PF (ring: 2 PF - 2) blocks past the end of a group");
+    static_assert(2 * PF - 2 <= kPackTailBlocks, "reads run up to 2 PF - 2 blocks past the end of a group");
     auto load_step = [&](uint32_t (&dst)[3], gbyte_t *base, uint32_t st) {
         gu32_t *p = (gu32_t *)(base + (size_t)st * 768);
         dst[0] = p[0]; dst[1] = p[1]; dst[2] = p[2];
@@ -362,7 +364,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     uint2 gr = make_uint2((uint32_t)wg * a.wg_pitch, 0);  // .x first atom block, .y steps
     if (has_group) gr = group_of(group_word);
     uint32_t ri = rowids[((size_t)first_group + min((uint32_t)wave, n_groups - 1)) * 64 + lane];
-    uint32_t q[PF][3];  // atoms of steps 0 .. PF-1 (later: the ring of the next PF steps)
+    uint32_t q[PF][3];  // the ring: the atoms of the next PF steps
     gbyte_t *gbase = lane_base(gr.x);
 #pragma unroll
     for (int st = 0; st < PF; ++st) load_step(q[st], gbase, st);
@@ -375,55 +377,33 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     //     would wait for the atoms as well.
     asm volatile("s_barrier" ::: "memory");
 
-    // (4) gathers and dot products: lane = row; results go to LDS in natural row order.  PRE: the group's
-    //     first PF steps are already in q (always so in the ring form).  The wavefront's first group is
-    //     handled outside the loop over further groups: as a loop-carried value q would be copied at the
-    //     loop head, and a copy needs the data -- all of it, at once.
-    auto run_group = [&](auto pre_tag, const uint2 gr, const uint32_t ri, gbyte_t *gbase) {
-        constexpr bool PRE = decltype(pre_tag)::value;
+    // (4) gathers and dot products: lane = row; results go to LDS in natural row order.  The ring already
+    //     holds the group's first PF steps.
+    auto run_group = [&](const uint2 gr, const uint32_t ri, gbyte_t *gbase) {
         Acc4 acc = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (RING) {
-            // the ring always holds the next PF steps: slot k is refilled with step st + PF as soon as
-            // step st has been taken out of it
-            auto ring_round = [&](uint32_t base) {
+        // slot k is refilled with step st + PF as soon as step st has been taken out of it
+        auto ring_round = [&](uint32_t base) {
 #pragma unroll
-                for (int k = 0; k < PF; ++k) {
-                    const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
-                    load_step(q[k], gbase, base + k + PF);
-                    if (base + k < gr.y) step_dot<CL>(d0, d1, d2, acc);
-                }
-            };
-            // (the first round outside the loop: at a loop head the ring would be copied, and a copy needs
-            // all of its data)
-            if (gr.y > 0) ring_round(0);
-            for (uint32_t base = PF; base < gr.y; base += PF) ring_round(base);
-        } else {
-            // the first PF steps of the wavefront's first group are in registers (the whole group for the
-            // shapes this was tuned on); everything else is loaded as it goes
-            if constexpr (PRE) {
-#pragma unroll
-                for (int st = 0; st < PF; ++st)
-                    if ((uint32_t)st < gr.y) step_dot<CL>(q[st][0], q[st][1], q[st][2], acc);
+            for (int k = 0; k < PF; ++k) {
+                const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
+                load_step(q[k], gbase, base + k + PF);
+                if (base + k < gr.y) step_dot<CL>(d0, d1, d2, acc);
             }
-            for (uint32_t st = PRE ? PF : 0; st < gr.y; ++st) {
-                gu32_t *p = (gu32_t *)(gbase + (size_t)st * 768);
-                step_dot<CL>(p[0], p[1], p[2], acc);
-            }
-        }
+        };
+        // (the first round outside the loop: at a loop head the ring would be copied, and a copy needs
+        // all of its data)
+        if (gr.y > 0) ring_round(0);
+        for (uint32_t base = PF; base < gr.y; base += PF) ring_round(base);
         if (ri != 0xFFFFu) accbuf[ri] = (acc.a0 + acc.a1) + (acc.a2 + acc.a3);
     };
-    if (has_group) run_group(std::true_type{}, gr, ri, gbase);
+    if (has_group) run_group(gr, ri, gbase);
     for (uint32_t g = wave + nwaves; g < n_groups; g += nwaves) {  // only when a block has more groups than wavefronts
         const uint2 gr2 = group_of(ka.group[g]);
         const uint32_t ri2 = rowids[((size_t)first_group + g) * 64 + lane];
         gbyte_t *gbase2 = lane_base(gr2.x);
-        if constexpr (RING) {
 #pragma unroll
-            for (int k = 0; k < PF; ++k) load_step(q[k], gbase2, k);
-            run_group(std::true_type{}, gr2, ri2, gbase2);
-        } else {
-            run_group(std::false_type{}, gr2, ri2, gbase2);
-        }
+        for (int k = 0; k < PF; ++k) load_step(q[k], gbase2, k);
+        run_group(gr2, ri2, gbase2);
     }
     __syncthreads();
 
@@ -442,10 +422,8 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     }
 }
 
-// Two builds of the single-problem kernel: up to 8 wavefronts (512 threads, up to 256 registers: the full
-// gather cluster) and up to 16 (held to 128 registers: half clusters).
-__global__ __launch_bounds__(512) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body<kPackPrefetch, false, 4>(a, blockIdx.x); }
-__global__ __launch_bounds__(1024) void gemv_packed_wide_kernel(PackedArgs a) { gemv_packed_body<12, false, 4>(a, blockIdx.x); }
+// One problem: 8 to 16 wavefronts, one per row group of the block (more groups than that: several each).
+__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body<kPackRing, 4>(a, blockIdx.x); }
 
 // Several independent problems in one launch (blockIdx.y picks the problem): the fixed latencies of a
 // launch (ramp-up, first touches of tables and atoms, drain) are paid once for all of them, and
@@ -457,7 +435,7 @@ struct PackedBatch {
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void gemv_packed_batch_kernel(PackedBatch b) {
     const PackedArgs &a = b.a[blockIdx.y];
     if ((int)blockIdx.x >= a.S * a.RB) return;
-    gemv_packed_body<kPackPrefetchBatch, true, 4>(a, blockIdx.x);
+    gemv_packed_body<kPackRing, 4>(a, blockIdx.x);
 }
 
 // y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.  MAXS loads are issued unconditionally
@@ -593,14 +571,9 @@ void packed_lds_attr(const void *kernel, size_t lds, size_t *set) {
 
 int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, hipStream_t s) {
     PackedLaunch l = packed_launch(w, x, y, ws);
-    static size_t attr_lds = 0, attr_lds_wide = 0;
-    if (l.waves <= 8) {
-        packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_kernel), l.lds, &attr_lds);
-        gemv_packed_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
-    } else {
-        packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_wide_kernel), l.lds, &attr_lds_wide);
-        gemv_packed_wide_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
-    }
+    static size_t attr_lds = 0;
+    packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_kernel), l.lds, &attr_lds);
+    gemv_packed_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
     gemv_packed_finalize_kernel<<<(l.a.N + 255) / 256, 256, 0, s>>>(l.a.partial, l.a.scale, l.a.y, l.a.N, l.a.S);
     return launch_status();
 }
