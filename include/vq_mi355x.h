@@ -53,8 +53,9 @@ typedef enum vq_status {
  *
  * Idea (codebook-centric dataflow, Sec. VI-A, taken to the entry level): the codebook is cut
  * into S slices that fit LDS, rows into RB blocks; workgroup (slice, block) sees only the codes
- * that point into its slice, stored as 24-bit "atoms" (entry index inside the slice, sub-vector
- * position j, valid bit), one row per lane, rows of similar length grouped 64 at a time.  Partial
+ * that point into its slice, stored as 24-bit "atoms" (two 12-bit numbers: where the entry and where
+ * x_j lie in the workgroup's LDS image [slice][x][one zero unit], in 16-byte units; padding atoms name
+ * the zero unit twice), one row per lane, rows of similar length grouped 64 at a time.  Partial
  * sums of the S slices are added in a fixed order by a second kernel (Sec. VI-A "global reduction").
  * Every workgroup's atoms have one common shape: its g-th group of 64 rows takes group_steps[g] steps
  * (768-byte blocks) and starts at block  wg * wg_pitch + sum_{g' < g} group_steps[g'],  so the kernel

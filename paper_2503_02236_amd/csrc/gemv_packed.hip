@@ -220,11 +220,14 @@ __device__ __forceinline__ void pin_scalar(T &v) {
 }
 
 constexpr int kPackMaxSlices = 64;  // 2^16 entries / 1024 per slice
-// Steps in flight per wavefront: a ring of 4 (12 registers).  More steps requested before the barrier do not
-// arrive sooner -- a CU's share of the memory system is ~20 KB per microsecond, and what is requested ahead of
-// another wavefront's slice transfer delays that transfer and with it the barrier (measured on 4096 x 11008:
-// 12 steps ahead, barrier 2.6 us after the loads were issued, 9.8 us in all; 4 steps, 1.5 us and 8.8 us).
-constexpr int kPackRing = 4;
+// Steps in flight per wavefront: a ring of 3 (9 registers), 2 of them requested before the barrier.  More
+// steps requested ahead do not arrive sooner -- a CU's share of the memory system is ~20 KB per microsecond,
+// and what is requested ahead of another wavefront's slice transfer delays that transfer and with it the
+// barrier (measured on 4096 x 11008: 12 steps ahead, barrier 2.6 us after the loads were issued, 9.8 us in
+// all; 4 steps, 1.5 us and 8.8 us).  Llama-7B stack, (ahead, ring): (2,2) 1206, (2,3) 1217, (2,4) 1214,
+// (1,3) 1211, (2,5) 1204 GB/s; nothing ahead of the barrier 1150 - 1166.
+constexpr int kPackRing = 3;
+constexpr int kPackAhead = 2;   // of these, requested before the barrier
 
 struct Acc4 {
     float a0, a1, a2, a3;
@@ -357,7 +360,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
         dst[0] = p[0]; dst[1] = p[1]; dst[2] = p[2];
     };
     auto lane_base = [&](uint32_t first_block) { return atoms + (size_t)first_block * 768 + lane_off; };
-    // Every wavefront issues the same PF + 1 loads, so the count in the wait holds for all of them: one
+    // Every wavefront issues the same kPackAhead + 1 loads, so the count in the wait holds for all of them: one
     // without a group reads the row ids of the last group and the first blocks of the workgroup and uses
     // neither.
     const bool has_group = (uint32_t)wave < n_groups;
@@ -367,33 +370,44 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     uint32_t q[PF][3];  // the ring: the atoms of the next PF steps
     gbyte_t *gbase = lane_base(gr.x);
 #pragma unroll
-    for (int st = 0; st < PF; ++st) load_step(q[st], gbase, st);
-    // PF atom loads and the row ids were issued behind the staging transfers: when at most PF + 1 loads are
-    // pending, the transfers have landed.  (A test compiles this file and counts those loads in each build.)
+    for (int st = 0; st < kPackAhead; ++st) load_step(q[st], gbase, st);
+    // kPackAhead atom loads and the row ids were issued behind the staging transfers: when at most that many
+    // loads are pending, the transfers have landed.  (A test compiles this file and counts those loads in each build.)
     // (lgkmcnt: the store of the zero unit)
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(PF + 1) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kPackAhead + 1) : "memory");
     // (3) the slice and x of this wavefront have landed (direct-to-LDS transfers count as vector memory
     //     loads); after the barrier those of all wavefronts are visible.  A bare s_barrier: __syncthreads()
     //     would wait for the atoms as well.
     asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+    for (int st = kPackAhead; st < PF; ++st) load_step(q[st], gbase, st);  // the rest of the ring
 
     // (4) gathers and dot products: lane = row; results go to LDS in natural row order.  The ring already
     //     holds the group's first PF steps.
     auto run_group = [&](const uint2 gr, const uint32_t ri, gbyte_t *gbase) {
         Acc4 acc = {0.f, 0.f, 0.f, 0.f};
-        // slot k is refilled with step st + PF as soon as step st has been taken out of it
-        auto ring_round = [&](uint32_t base) {
+        // slot k is refilled with step st + PF as soon as step st has been taken out of it -- except in the
+        // group's last round: what would be requested there lies past the end of the group (with a refill in
+        // every round a group of 5 steps read 9 blocks; the blocks read in vain are the next group's, but
+        // they cross the memory system once more all the same).  Measured on the Llama-7B stack: 1163 -> 1214
+        // GB/s; refilling exactly up to the group's end (one copy of the round before the last per number of
+        // refills) was slower again, 1154 - 1181.
+        auto ring_round = [&](uint32_t base, auto refill_tag) {
 #pragma unroll
             for (int k = 0; k < PF; ++k) {
                 const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
-                load_step(q[k], gbase, base + k + PF);
+                if constexpr (decltype(refill_tag)::value) load_step(q[k], gbase, base + k + PF);
                 if (base + k < gr.y) step_dot<CL>(d0, d1, d2, acc);
             }
         };
         // (the first round outside the loop: at a loop head the ring would be copied, and a copy needs
         // all of its data)
-        if (gr.y > 0) ring_round(0);
-        for (uint32_t base = PF; base < gr.y; base += PF) ring_round(base);
+        uint32_t base = 0;
+        if (gr.y > (uint32_t)PF) {
+            ring_round(0, std::true_type{});
+            for (base = PF; base + PF < gr.y; base += PF) ring_round(base, std::true_type{});
+        }
+        if (gr.y > 0) ring_round(base, std::false_type{});
         if (ri != 0xFFFFu) accbuf[ri] = (acc.a0 + acc.a1) + (acc.a2 + acc.a3);
     };
     if (has_group) run_group(gr, ri, gbase);
