@@ -453,12 +453,15 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
 }
 
 // y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.  MAXS loads are issued unconditionally
-// (slices past S re-read the last one) so that none of them waits behind a branch.
+// (slices past S re-read the last one) so that none of them waits behind a branch.  One row per thread, one
+// wavefront per block: the kernel is one memory round trip long, and the fewer requests queue on a CU the
+// shorter it is (256 rows per block: 1209 GB/s on the Llama-7B stack, 64 rows: 1220).
+constexpr int kFinalizeRows = 64;
 template <int MAXS>
 __device__ __forceinline__ void gemv_packed_finalize_body(const float *__restrict__ partial,
                                                           const half_t *__restrict__ scale, half_t *__restrict__ y,
                                                           int N, int S) {
-    const int n = blockIdx.x * 256 + threadIdx.x;  // (the launch shape is fixed: no load of the hidden arguments)
+    const int n = blockIdx.x * kFinalizeRows + threadIdx.x;  // (the launch shape is fixed: no load of the hidden arguments)
     if (n >= N) return;
     // (pointers that went through pin_scalar have to be told again that they are global)
     const __attribute__((address_space(1))) float *gp = (const __attribute__((address_space(1))) float *)partial;
@@ -473,7 +476,7 @@ __device__ __forceinline__ void gemv_packed_finalize_body(const float *__restric
     for (int k = 0; k < MAXS; ++k) sum += k < S ? v[k] : 0.f;
     gy[n] = (half_t)(sum * sc);
 }
-__global__ __launch_bounds__(256) void gemv_packed_finalize_kernel(const float *__restrict__ partial,
+__global__ __launch_bounds__(kFinalizeRows) void gemv_packed_finalize_kernel(const float *__restrict__ partial,
                                                                   const half_t *__restrict__ scale,
                                                                   half_t *__restrict__ y, int N, int S) {
     pin_scalar(partial); pin_scalar(scale); pin_scalar(y); pin_scalar(N); pin_scalar(S);  // one round of argument loads
@@ -491,7 +494,7 @@ struct FinalizeArgs {
 struct FinalizeBatch {
     FinalizeArgs a[kPackMaxBatch];
 };
-__global__ __launch_bounds__(256) void gemv_packed_finalize_batch_kernel(FinalizeBatch b) {
+__global__ __launch_bounds__(kFinalizeRows) void gemv_packed_finalize_batch_kernel(FinalizeBatch b) {
     FinalizeArgs a = b.a[blockIdx.y];
     pin_scalar(a.partial); pin_scalar(a.scale); pin_scalar(a.y); pin_scalar(a.N); pin_scalar(a.S);
     if (a.S <= 32)
@@ -588,7 +591,7 @@ int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, h
     static size_t attr_lds = 0;
     packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_kernel), l.lds, &attr_lds);
     gemv_packed_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
-    gemv_packed_finalize_kernel<<<(l.a.N + 255) / 256, 256, 0, s>>>(l.a.partial, l.a.scale, l.a.y, l.a.N, l.a.S);
+    gemv_packed_finalize_kernel<<<(l.a.N + kFinalizeRows - 1) / kFinalizeRows, kFinalizeRows, 0, s>>>(l.a.partial, l.a.scale, l.a.y, l.a.N, l.a.S);
     return launch_status();
 }
 
@@ -622,7 +625,7 @@ int launch_gemv_packed_batch(const vq_weight_t *const *w, const void *const *x, 
     gemv_packed_batch_kernel<<<dim3(grid, count), waves * 64, lds, s>>>(b);
     FinalizeBatch f;
     for (int i = 0; i < kPackMaxBatch; ++i) f.a[i] = {b.a[i].partial, b.a[i].scale, b.a[i].y, b.a[i].N, b.a[i].S};
-    gemv_packed_finalize_batch_kernel<<<dim3((max_n + 255) / 256, count), 256, 0, s>>>(f);
+    gemv_packed_finalize_batch_kernel<<<dim3((max_n + kFinalizeRows - 1) / kFinalizeRows, count), kFinalizeRows, 0, s>>>(f);
     return launch_status();
 }
 
