@@ -173,8 +173,8 @@ def test_gemv_packed_config2_full_size(gpu_device, shape_idx):
     (1000, 4096, 65536, False),   # ragged row blocks, no scale
     (300, 2048, 4096, True),      # two slices only
     (257, 16368, 8192, True),     # longest supported rows
-    (9000, 512, 65536, True),     # many rows: 4096-entry slices, nine groups per workgroup
-    (20000, 128, 65536, True),    # twenty groups per workgroup, sixteen wavefronts: some take a second group
+    (9000, 512, 65536, True),     # many rows: eighteen groups per workgroup, nine wavefronts with two groups each
+    (20000, 128, 65536, True),    # forty groups per workgroup, fourteen wavefronts with up to three groups each
 ])
 def test_gemv_packed_shapes_and_edges(gpu_device, N, K, E, scale):
     w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=3000 + N + K, with_scale=scale)
@@ -245,6 +245,26 @@ def test_gemv_batch_matches_single_calls_and_oracle(gpu_device):
     torch.cuda.synchronize()
     for w, xx, y in zip((ws3[0], wa, wb), (x, x2, x2), ys):
         assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, xx), "mixed batch member")
+
+
+def test_gemv_packed_padding_never_touches_a_codebook_entry(gpu_device):
+    # entries that no code uses are set to infinity and NaN: padding atoms multiply a zero unit of their own,
+    # not an entry, so every output stays what the oracle says (finite)
+    w = wl.make_weight(200, 1024, 8, 16, 1, 65536, 0.02, seed=7400)
+    used = np.zeros(65536, dtype=bool)
+    used[w.codes.reshape(-1)] = True
+    unused = np.flatnonzero(~used)
+    assert unused.size > 30000
+    w.codebooks[0, unused[0::2]] = np.float16(np.inf)
+    w.codebooks[0, unused[1::2]] = np.float16(np.nan)
+    if not used[0]:
+        assert not np.isfinite(w.codebooks[0, 0]).any()          # entry 0 of slice 0 among them
+    x = wl.make_activations(1, w.K, 7401)
+    want = oracle.gemv(w.codes, w.codebooks, w.scale, x)
+    assert np.isfinite(want).all()
+    got = run_gemv_packed(w, x, gpu_device)
+    assert torch.isfinite(got).all()
+    assert_close(got, want, "packed gemv with non-finite unused entries")
 
 
 def test_gemv_packed_shared_workspace_determinism_and_canonical_agreement(gpu_device):
