@@ -16,6 +16,10 @@
 // MFMAs; x operands for those positions come straight from global memory (L2-resident).
 // Iterations are dealt round-robin to the wavefronts (K = 4096, uint8 pairs: 16 iterations, one
 // per wavefront at N = 4096); the per-wavefront 16 x 16 partial tiles are added in wavefront order through LDS.
+// RT = 2: a workgroup takes 32 rows, two tiles of 16 that share every x operand.  Each workgroup reads all
+// of x once -- bs * K * 2 bytes from L2 --, which at bs = 16 is what the kernel waits for (N = 11008,
+// K = 4096: 688 workgroups x 128 KiB = 88 MB through the L2s at ~11 TB/s, 8 of the 18 us); with two tiles per
+// workgroup it is half of that.  Used where enough workgroups remain to fill the chip.
 #include "vq_common.h"
 
 namespace vq {
@@ -64,8 +68,8 @@ __device__ __forceinline__ unsigned word_code<Code12>(const V16 &cd, int q) {
 // from global memory (L2): the shared-memory level of the hierarchical codebook cache of Sec. V-B.  It
 // pays off when the entries have been reordered by frequency (vq_reorder_by_frequency), so that most
 // codes are small; with uniformly used entries nearly every lookup takes the L2 path.
-template <typename CodeT, int V, int R, bool HOT>
-__global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
+template <typename CodeT, int V, int R, bool HOT, int RT>
+__global__ __launch_bounds__(RT == 1 ? 1024 : 512) void gemv_mfma_kernel(GemvMfmaArgs a) {  // (two tiles: twice the operands in flight, up to 8 wavefronts)
     constexpr int LB = GemvMfmaShape<CodeT, R>::LB;     // bytes of codes per lane and iteration
     constexpr int CPL = GemvMfmaShape<CodeT, R>::CPL;   // sub-vector positions per code load
     constexpr int CPO = 8 / V;                          // codes per MFMA operand (8 consecutive k)
@@ -80,10 +84,14 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nwaves = blockDim.x >> 6;
     const int r = lane & 15, g = lane >> 4;
-    const int n0 = blockIdx.x * 16;
-    const int n = min(n0 + r, a.N - 1);  // rows past the end are computed and dropped
+    const int n0 = blockIdx.x * 16 * RT;
     // codes and x of this wavefront's first iteration are requested before the codebook is staged
-    const unsigned char *crow = reinterpret_cast<const unsigned char *>(a.codes) + (size_t)n * a.J * R * BITS / 8;
+    const unsigned char *crow[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        const int n = min(n0 + 16 * t + r, a.N - 1);  // rows past the end are computed and dropped
+        crow[t] = reinterpret_cast<const unsigned char *>(a.codes) + (size_t)n * a.J * R * BITS / 8;
+    }
     // Codes and x operands of iteration `it` (< nit) of this wavefront; returns whether this lane's part
     // counts.  The loads carry no condition: a lane past the end of the row, or of a token past the batch,
     // reads a position / token that exists and its x operand is zeroed where it is used (a zero B operand
@@ -95,9 +103,9 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
         ok = jb < a.J;
         return ok ? jb : a.J - CPL;
     };
-    auto load_codes = [&](int it, V16 &cd) {
+    auto load_codes = [&](int it, int t, V16 &cd) {
         bool ok;
-        const unsigned char *cp = crow + (size_t)lane_pos(it, ok) * R * BITS / 8;
+        const unsigned char *cp = crow[t] + (size_t)lane_pos(it, ok) * R * BITS / 8;
         if (LB == 16) {
             cd = ld16(cp);
         } else if (LB == 12) {  // 4-byte aligned: a row is a whole number of 12-byte words
@@ -120,20 +128,22 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
         for (int m = 0; m < MPI; ++m) xb[m] = ld16(xr + m * 8).h8;
         return ok && r < a.bs;
     };
-    V16 cd;
+    V16 cd[RT];
     half8_t xb[MPI];
     // (every wavefront loads: one without an iteration repeats the last one and never uses it)
-    load_codes(min(wave, a.nit - 1), cd);
+#pragma unroll
+    for (int t = 0; t < RT; ++t) load_codes(min(wave, a.nit - 1), t, cd[t]);
     bool use_x = load_x(min(wave, a.nit - 1), xb);
     // per-channel scales of the four output rows this lane writes at the very end (rows n0 + 4 g + i): asked
     // for now, with everything else, as raw halves and without a branch (without scales: any readable halves,
     // ignored later).  Loaded where they are used they are four dependent round trips to L2 at the tail of a
     // kernel that lasts a few microseconds; converted or selected here they would be waited for here.
+    // (of the tile whose sums this wavefront adds up at the end: tile wave % RT)
     half_t sc4[4];
     {
         const half_t *sp = a.scale ? a.scale : a.x;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sc4[i] = sp[a.scale ? min(n0 + 4 * g + i, a.N - 1) : 0];
+        for (int i = 0; i < 4; ++i) sc4[i] = sp[a.scale ? min(n0 + 16 * (wave % RT) + 4 * g + i, a.N - 1) : 0];
     }
 
     // all codebooks (with per-tile codebooks: the sets of the tiles this workgroup's 16 rows cross), or (HOT,
@@ -143,13 +153,18 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
         reinterpret_cast<uint4 *>(cbl)[i] = reinterpret_cast<const uint4 *>(cb_src)[i];
     __syncthreads();
 
-    float4v_t acc = {0.f, 0.f, 0.f, 0.f};
+    float4v_t acc[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) acc[t] = float4v_t{0.f, 0.f, 0.f, 0.f};
     for (int it = wave; it < a.nit; it += nwaves) {
         // the next iteration's codes (a trip to HBM) are requested now, its x operands (L2) when this
         // iteration's have been used: they land while the next iteration's entries are looked up
         const bool more = it + nwaves < a.nit;
-        V16 cd_next;
-        if (more) load_codes(it + nwaves, cd_next);
+        V16 cd_next[RT];
+        if (more) {
+#pragma unroll
+            for (int t = 0; t < RT; ++t) load_codes(it + nwaves, t, cd_next[t]);
+        }
         // codebook set of this lane's positions (a load never straddles two tiles)
         // (lanes past the end of the row are clamped to the last set; their x operand is zero)
         const half_t *cbt = cbl + (size_t)min(((it * 4 + g) * CPL) / a.tile_j, a.tiles_k - 1) * set_halves;
@@ -157,6 +172,8 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
         // operand at a time, every operand waits out its own LDS round trip)
         constexpr int kEntryRegs = CPO * R * (V == 8 ? 4 : 2);   // registers of one operand's entries
         constexpr int MC = (MPI % 4 == 0 && 4 * kEntryRegs <= 32) ? 4 : (MPI % 2 == 0 && 2 * kEntryRegs <= 32) ? 2 : 1;
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
 #pragma unroll
         for (int m0 = 0; m0 < MPI; m0 += MC) {
             V16 ev[MC][CPO][R];
@@ -167,7 +184,7 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
                     const int c = (m0 + mi) * CPO + h;  // code position inside the 16-byte word
 #pragma unroll
                     for (int rr = 0; rr < R; ++rr) {
-                        const unsigned code = word_code<CodeT>(cd, c * R + rr);
+                        const unsigned code = word_code<CodeT>(cd[t], c * R + rr);
                         // the entry: from the LDS copy, or (cold entry of a partly cached codebook) from L2.  The two
                         // loads are kept apart by their address spaces, so neither becomes a generic-pointer load
                         V16 e;
@@ -224,28 +241,34 @@ __global__ __launch_bounds__(1024) void gemv_mfma_kernel(GemvMfmaArgs a) {
                     }
                 half8_t xop = xb[m0 + mi];
                 if (!use_x) xop = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(op.h8, xop, acc, 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(op.h8, xop, acc[t], 0, 0, 0);
             }
         }
-        cd = cd_next;
+#pragma unroll
+        for (int t = 0; t < RT; ++t) cd[t] = cd_next[t];
         if (more) use_x = load_x(it + nwaves, xb);
     }
 
-    // partial tiles -> LDS, summed in wavefront order by the first wavefront.
+    // partial tiles -> LDS [tile][wavefront][lane], each tile summed in wavefront order by one wavefront
+    // (tile t by wavefront t; a workgroup with fewer wavefronts than tiles: wavefront 0 takes them in turn).
     // C layout: lane holds token (lane % 16), rows 4 (lane / 16) + 0..3.
-    red[wave * 64 + lane] = acc;
+#pragma unroll
+    for (int t = 0; t < RT; ++t) red[(t * nwaves + wave) * 64 + lane] = acc[t];
     __syncthreads();
-    if (wave == 0) {
-        float4v_t sum = red[lane];
+    for (int t = wave; t < RT; t += nwaves) {
+        float4v_t sum = red[(t * nwaves) * 64 + lane];
         for (int w = 1; w < nwaves; ++w) {
-            const float4v_t p = red[w * 64 + lane];
+            const float4v_t p = red[(t * nwaves + w) * 64 + lane];
             sum += p;
         }
         if (r < a.bs) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int nn = n0 + 4 * g + i;
-                if (nn < a.N) a.y[(size_t)r * a.N + nn] = (half_t)(sum[i] * (a.scale ? (float)sc4[i] : 1.f));
+                const int nn = n0 + 16 * t + 4 * g + i;
+                // (the scales were prefetched for tile wave % RT: any other tile, only with fewer wavefronts than
+                // tiles, reads its own)
+                const float sc = !a.scale ? 1.f : (t == wave % RT ? (float)sc4[i] : (float)a.scale[min(nn, a.N - 1)]);
+                if (nn < a.N) a.y[(size_t)r * a.N + nn] = (half_t)(sum[i] * sc);
             }
         }
     }
@@ -256,7 +279,7 @@ namespace {
 constexpr size_t kGemvMfmaLdsCodebook = 128 * 1024;  // whole codebooks up to this size live in LDS
 constexpr int kGemvMfmaHotEntries8 = 4096;           // v = 8 entries of a larger codebook cached in LDS (64 KiB)
 
-template <typename CodeT, int V, int R, bool HOT>
+template <typename CodeT, int V, int R, bool HOT, int RT>
 int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s) {
     constexpr int CPL = GemvMfmaShape<CodeT, R>::CPL;
     GemvMfmaArgs a;
@@ -274,11 +297,12 @@ int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s)
     // wavefronts per workgroup: the chip holds 16 per CU (4096 in all); with more than 256 workgroups
     // fewer, longer-running wavefronts keep every workgroup resident at once (measured on N = 11008:
     // 4 wavefronts 11.5 us, 8: 13.3, 16: 16.5 at bs = 1)
-    const int n_wg = (a.N + 15) / 16;
+    const int n_wg = (a.N + 16 * RT - 1) / (16 * RT);
     int waves = 16;
     while (waves > 4 && n_wg * waves > 4096) waves >>= 1;
     // codebooks of more than half the LDS: one workgroup per CU anyway, so give it all 16 wavefronts
     if ((size_t)R * a.E * V * 2 > 72 * 1024 && w->hot_entries == 0) waves = 16;
+    if (RT > 1 && waves > 8) waves = 8;  // (that build is compiled for 512 threads)
     if (waves > a.nit) waves = a.nit;
     if (waves < 1) waves = 1;
     a.tile_n = w->cb_tile_n;
@@ -291,25 +315,30 @@ int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s)
         a.n_hot = a.E < cap ? a.E : cap;
     }
     const size_t cb_bytes = (size_t)R * a.n_hot * V * 2 * a.tiles_k;
-    const size_t lds = ((cb_bytes + 15) & ~(size_t)15) + (size_t)waves * 64 * sizeof(float4v_t);
+    const size_t lds = ((cb_bytes + 15) & ~(size_t)15) + (size_t)RT * waves * 64 * sizeof(float4v_t);
     static size_t attr_lds = 0;
     if (lds > 64 * 1024 && lds > attr_lds) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_mfma_kernel<CodeT, V, R, HOT>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_mfma_kernel<CodeT, V, R, HOT, RT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_lds = lds;
     }
-    gemv_mfma_kernel<CodeT, V, R, HOT><<<n_wg, waves * 64, lds, s>>>(a);
+    gemv_mfma_kernel<CodeT, V, R, HOT, RT><<<n_wg, waves * 64, lds, s>>>(a);
     return launch_status();
 }
 
 template <typename CodeT, int V>
 int by_r(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s) {
     const bool hot = w->cb_tile_n == 0 && (size_t)w->n_codebooks * w->n_entries * w->v * 2 > kGemvMfmaLdsCodebook;
-    if (hot) return run<CodeT, V, 1, true>(w, x, bs, y, s);  // only single codebooks are cached partly
+    if (hot) return run<CodeT, V, 1, true, 1>(w, x, bs, y, s);  // only single codebooks are cached partly
+    // two row tiles per workgroup halve the x traffic of a batch, where 32-row workgroups still fill the chip
+    // (per-tile codebooks: the 32 rows must lie in one row of tiles)
+    // (N = 11008, K = 4096, two codebooks: bs = 16 18.3 -> 17.1 us, one codebook per tile 19.0 -> 15.9, 12-bit codes
+    // 26.3 -> 22.9; at bs = 4 the x traffic is small and 344 workgroups spread worse over 256 CUs than 688: 11.1 -> 14.0)
+    const bool two = bs >= 8 && (w->N + 31) / 32 >= 256 && (w->cb_tile_n == 0 || w->cb_tile_n % 32 == 0);
     switch (w->n_codebooks) {
-        case 1: return run<CodeT, V, 1, false>(w, x, bs, y, s);
-        case 2: return run<CodeT, V, 2, false>(w, x, bs, y, s);
-        default: return run<CodeT, V, 4, false>(w, x, bs, y, s);
+        case 1: return two ? run<CodeT, V, 1, false, 2>(w, x, bs, y, s) : run<CodeT, V, 1, false, 1>(w, x, bs, y, s);
+        case 2: return two ? run<CodeT, V, 2, false, 2>(w, x, bs, y, s) : run<CodeT, V, 2, false, 1>(w, x, bs, y, s);
+        default: return two ? run<CodeT, V, 4, false, 2>(w, x, bs, y, s) : run<CodeT, V, 4, false, 1>(w, x, bs, y, s);
     }
 }
 

@@ -601,6 +601,30 @@ def _random_weight_case(rng):
     return N, K, v, bits, R, E, tile
 
 
+@pytest.mark.parametrize("N,K,v,bits,R,E,tile,bs", [
+    (8200, 512, 8, 8, 2, 256, None, 16),        # 257 workgroups of 32 rows, the last one with 8 rows
+    (8192, 1024, 4, 8, 1, 256, None, 11),       # v = 4, batch not a power of two
+    (8192, 512, 8, 12, 2, 4096, None, 16),      # packed 12-bit codes, two 64 KiB codebooks
+    (9000, 256, 8, 16, 1, 4096, None, 8),       # uint16 codes, one codebook in LDS
+    (8208, 512, 8, 8, 4, 256, None, 9),         # four codebooks; 8208 = 256.5 * 32: a workgroup with one tile
+    (8192, 512, 4, 8, 1, 256, (256, 256), 16),  # one codebook per (256, 256) tile
+    (11008, 4096, 8, 8, 2, 256, None, 16),      # the Llama-7B gate/up shape of the additive configuration
+])
+def test_gemv_batched_two_row_tiles_per_workgroup(gpu_device, N, K, v, bits, R, E, tile, bs):
+    # many rows and a batch: a workgroup takes two 16-row tiles that share their x operands
+    w = wl.make_weight(N, K, v, bits, R, E, 0.02, seed=9500 + N + bs, cb_tile=tile)
+    wd = vq.weight_to_device(w, gpu_device)
+    x = wl.make_activations(bs, K, 9501 + bs)
+    want = oracle.gemv(ocodes(w), w.codebooks, w.scale, x, cb_tile=tile)
+    got = vq.vq_gemv(wd, dev_x(x, gpu_device))
+    torch.cuda.synchronize()
+    assert_close(got, want, f"N{N} K{K} v{v} bits{bits} R{R} E{E} tile{tile} bs{bs}")
+    # the same rows one token at a time (one tile per workgroup): same sums up to the order of the wavefronts' parts
+    one = vq.vq_gemv(wd, dev_x(x[:1].copy(), gpu_device))
+    torch.cuda.synchronize()
+    assert_close(one, want[:1], "first token alone")
+
+
 @pytest.mark.parametrize("seed", range(int(__import__("os").environ.get("VQ_TEST_RANDOM_CASES", "24"))))
 def test_gemv_gemm_dequant_random_formats(gpu_device, seed):
     rng = np.random.default_rng(97000 + seed)
