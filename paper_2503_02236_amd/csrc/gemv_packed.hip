@@ -277,9 +277,28 @@ __device__ __forceinline__ void step_dot(uint32_t d0, uint32_t d1, uint32_t d2, 
     }
 }
 
+// Two steps at once: the sixteen gathers of both are issued before the first dot product (a launch with one
+// 8-wavefront workgroup per CU has too few gathers in flight to fill the LDS pipeline otherwise).  The dot
+// products run in the order of two single steps, so the sums are the same bit for bit.
+__device__ __forceinline__ void step_dot_pair(const uint32_t (&da)[3], const uint32_t (&db)[3], Acc4 &acc) {
+    const uint32_t at[8] = {da[0], __builtin_amdgcn_alignbit(da[1], da[0], 24), __builtin_amdgcn_alignbit(da[2], da[1], 16), da[2] >> 8,
+                            db[0], __builtin_amdgcn_alignbit(db[1], db[0], 24), __builtin_amdgcn_alignbit(db[2], db[1], 16), db[2] >> 8};
+    float *accs[4] = {&acc.a0, &acc.a1, &acc.a2, &acc.a3};
+    V16 e[8], xv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        e[i] = lds_unit((at[i] << 4) & 0xfff0u);
+        xv[i] = lds_unit((at[i] >> (kPackFieldBits - 4)) & 0xfff0u);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, 32, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *accs[i & 3] = atom_fma(e[i], xv[i], *accs[i & 3]);
+}
+
 // All global loads of a workgroup are issued before anything waits: the kernel is a chain of
 // memory latencies (tables -> atoms -> partials), not a bandwidth problem, at these sizes.
-template <int PF, int CL>
+template <int PF, int CL, bool PAIR>
 __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int bid) {
     extern __shared__ __align__(16) unsigned char smem[];
     // all launch arguments in one round of scalar loads
@@ -393,11 +412,25 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
         // GB/s; refilling exactly up to the group's end (one copy of the round before the last per number of
         // refills) was slower again, 1154 - 1181.
         auto ring_round = [&](uint32_t base, auto refill_tag) {
+            if constexpr (PAIR) {
+                static_assert(!PAIR || PF % 2 == 0, "steps are taken two at a time");
 #pragma unroll
-            for (int k = 0; k < PF; ++k) {
-                const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
-                if constexpr (decltype(refill_tag)::value) load_step(q[k], gbase, base + k + PF);
-                if (base + k < gr.y) step_dot<CL>(d0, d1, d2, acc);
+                for (int k = 0; k < PF; k += 2) {
+                    const uint32_t da[3] = {q[k][0], q[k][1], q[k][2]}, db[3] = {q[k + 1][0], q[k + 1][1], q[k + 1][2]};
+                    if constexpr (decltype(refill_tag)::value) {
+                        load_step(q[k], gbase, base + k + PF);
+                        load_step(q[k + 1], gbase, base + k + 1 + PF);
+                    }
+                    if (base + k + 1 < gr.y) step_dot_pair(da, db, acc);
+                    else if (base + k < gr.y) step_dot<CL>(da[0], da[1], da[2], acc);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < PF; ++k) {
+                    const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
+                    if constexpr (decltype(refill_tag)::value) load_step(q[k], gbase, base + k + PF);
+                    if (base + k < gr.y) step_dot<CL>(d0, d1, d2, acc);
+                }
             }
         };
         // (the first round outside the loop: at a loop head the ring would be copied, and a copy needs
@@ -437,7 +470,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
 }
 
 // One problem: 8 to 16 wavefronts, one per row group of the block (more groups than that: several each).
-__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body<kPackRing, 4>(a, blockIdx.x); }
+__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body<4, 4, true>(a, blockIdx.x); }
 
 // Several independent problems in one launch (blockIdx.y picks the problem): the fixed latencies of a
 // launch (ramp-up, first touches of tables and atoms, drain) are paid once for all of them, and
@@ -449,7 +482,7 @@ struct PackedBatch {
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void gemv_packed_batch_kernel(PackedBatch b) {
     const PackedArgs &a = b.a[blockIdx.y];
     if ((int)blockIdx.x >= a.S * a.RB) return;
-    gemv_packed_body<kPackRing, 4>(a, blockIdx.x);
+    gemv_packed_body<kPackRing, 4, false>(a, blockIdx.x);
 }
 
 // y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.  MAXS loads are issued unconditionally
