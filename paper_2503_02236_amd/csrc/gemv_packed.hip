@@ -298,7 +298,7 @@ __device__ __forceinline__ void step_dot_pair(const uint32_t (&da)[3], const uin
 
 // All global loads of a workgroup are issued before anything waits: the kernel is a chain of
 // memory latencies (tables -> atoms -> partials), not a bandwidth problem, at these sizes.
-template <int PF, int CL, bool PAIR>
+template <int PF, int CL, bool PAIR, int AHEAD = kPackAhead>
 __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int bid) {
     extern __shared__ __align__(16) unsigned char smem[];
     // all launch arguments in one round of scalar loads
@@ -389,17 +389,17 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     uint32_t q[PF][3];  // the ring: the atoms of the next PF steps
     gbyte_t *gbase = lane_base(gr.x);
 #pragma unroll
-    for (int st = 0; st < kPackAhead; ++st) load_step(q[st], gbase, st);
+    for (int st = 0; st < AHEAD; ++st) load_step(q[st], gbase, st);
     // kPackAhead atom loads and the row ids were issued behind the staging transfers: when at most that many
     // loads are pending, the transfers have landed.  (A test compiles this file and counts those loads in each build.)
     // (lgkmcnt: the store of the zero unit)
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kPackAhead + 1) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(AHEAD + 1) : "memory");
     // (3) the slice and x of this wavefront have landed (direct-to-LDS transfers count as vector memory
     //     loads); after the barrier those of all wavefronts are visible.  A bare s_barrier: __syncthreads()
     //     would wait for the atoms as well.
     asm volatile("s_barrier" ::: "memory");
 #pragma unroll
-    for (int st = kPackAhead; st < PF; ++st) load_step(q[st], gbase, st);  // the rest of the ring
+    for (int st = AHEAD; st < PF; ++st) load_step(q[st], gbase, st);  // the rest of the ring
 
     // (4) gathers and dot products: lane = row; results go to LDS in natural row order.  The ring already
     //     holds the group's first PF steps.
