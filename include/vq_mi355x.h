@@ -81,7 +81,11 @@ typedef struct vq_gemv_pack_t {
  * (N output features, K input features).  Sub-vectors lie along K, the
  * reduction axis, so row n holds K/v sub-vectors.
  *   W[n][j*v + i] = sum_{r < n_codebooks} codebooks[r][codes[n][j][r]][i]
- * summed in fp32, r ascending (Sec. II-A; "Residual" of Tbl. I = n_codebooks).
+ * summed in fp32, r ascending (Sec. II-A; "Residual" of Tbl. I = n_codebooks).  vq_dequant returns exactly
+ * this sum (or its fp16 rounding).  The kernels that feed the matrix cores consume the fp16 rounding of it:
+ * for three or four codebooks the fp32 sum rounded once; for two codebooks one fp16 addition of the two
+ * entries (the exact sum rounded once), which is the same value whenever the fp32 sum is exact, i.e. always
+ * unless the two entries' exponents lie more than 13 apart (then it can differ by one fp16 ulp on a tie).
  * With per-tile codebooks (cb_tile_n, cb_tile_k > 0) `codebooks` above is the set of the tile that holds
  * (n, j*v).  Re-tiled gemv codes (gemv_pack), hot_entries and the fused small-M matrix-core path of vq_gemm
  * apply to per-tensor codebooks only.

@@ -150,8 +150,7 @@ __global__ __launch_bounds__(kAttnWaves * 64 * SEQ) __attribute__((amdgpu_waves_
     extern __shared__ __align__(16) unsigned char smem[];
     // Entry addresses are formed as plain LDS byte offsets (shifted code + constant), which is only
     // right if the dynamic LDS block starts at LDS address 0: true for a kernel without static LDS.
-    // The base is a link-time constant, so this check is decided once per build.
-    if ((unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem != 0u) return;
+    // The launcher checks that (kernel_setup) and returns an error instead of launching otherwise.
     const int cb_bytes = a.G * a.E * V * 2;        // per side
     const int v_off = ONE ? 4096 : cb_bytes;       // LDS offset of the V codebook
     const int tid = threadIdx.x, lane = tid & 63;
@@ -383,12 +382,9 @@ template <int V, bool ONE, int SEQ>
 static int run_attn_seq(const AttnArgs &a, hipStream_t s) {
     const size_t side = ONE ? 4096 : (size_t)a.G * a.E * V * sizeof(half_t);  // matches the kernel's layout
     size_t lds = 2 * side + (size_t)SEQ * kAttnWaves * (128 + 2) * sizeof(float);
-    static size_t attr_lds = 0;
-    if (lds > 64 * 1024 && lds > attr_lds) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_decode_kernel<V, ONE, SEQ>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_lds = lds;
-    }
+    // the kernel forms absolute LDS addresses: refused here, with an error, if it ever had static LDS
+    static KernelSetup setup;
+    if (int st = kernel_setup(reinterpret_cast<const void *>(&attn_decode_kernel<V, ONE, SEQ>), lds, true, setup)) return st;
     const int groups = (a.B + SEQ - 1) / SEQ;
     attn_decode_kernel<V, ONE, SEQ><<<dim3(groups * a.H, a.S), kAttnWaves * 64 * SEQ, lds, s>>>(a);
     if (a.S > 1) attn_merge_kernel<<<a.B * a.H, 128, 0, s>>>(a.ws, a.out, a.S);

@@ -187,12 +187,8 @@ int run_mfma(const vq_weight_t *w, const half_t *X, int M, half_t *Y, hipStream_
     a.tiles_m = (M + BM - 1) / BM;
     a.tiles_n = (w->N + BN - 1) / BN;
     size_t lds = 2 * (size_t)BM * kGemmLdsRow;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mfma_kernel<V, 1, MT, NT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_set = true;
-    }
+    static KernelSetup setup;
+    if (int st = kernel_setup(reinterpret_cast<const void *>(&gemm_mfma_kernel<V, 1, MT, NT>), lds, false, setup)) return st;
     gemm_mfma_kernel<V, 1, MT, NT><<<a.tiles_m * a.tiles_n, 256, lds, s>>>(a);
     return launch_status();
 }

@@ -268,12 +268,8 @@ int launch_gemm_dense(const half_t *A, const half_t *B, const half_t *scale, hal
     a.tiles_m = (M + BM - 1) / BM;
     a.tiles_n = (N + BN - 1) / BN;
     const size_t lds = (size_t)kDenseStages * (BM + BN) * kDenseRowB;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_dense_kernel<MT, NT>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_set = true;
-    }
+    static KernelSetup setup;
+    if (int st = kernel_setup(reinterpret_cast<const void *>(&gemm_dense_kernel<MT, NT>), lds, false, setup)) return st;
     const int n_tiles = a.tiles_m * a.tiles_n;
     const int grid = ((n_tiles + 7) / 8) * 8;
     gemm_dense_kernel<MT, NT><<<grid, 256, lds, s>>>(a);

@@ -217,28 +217,51 @@ __global__ __launch_bounds__(RT == 1 ? 1024 : 512) void gemv_mfma_kernel(GemvMfm
 #pragma unroll
             for (int mi = 0; mi < MC; ++mi) {
                 V16 op;
+                if constexpr (R <= 2) {
+                    // One or two entries: a single fp16 addition rounds the exact sum once, which is the fp32
+                    // sum of Sec. II-A rounded to fp16 whenever that fp32 sum is exact -- always, unless the two
+                    // exponents lie more than 13 apart; then the two roundings of fp32-then-fp16 can differ from
+                    // this single one by one fp16 ulp on a tie.
 #pragma unroll
-                for (int h = 0; h < CPO; ++h)
+                    for (int h = 0; h < CPO; ++h)
 #pragma unroll
-                    for (int rr = 0; rr < R; ++rr) {
-                        const V16 &e = ev[mi][h][rr];
-                        if (V == 8) {
-                            if (rr == 0) {
-                                op = e;
+                        for (int rr = 0; rr < R; ++rr) {
+                            const V16 &e = ev[mi][h][rr];
+                            if (V == 8) {
+                                if (rr == 0) {
+                                    op = e;
+                                } else {
+#pragma unroll
+                                    for (int q = 0; q < 4; ++q) op.h2[q] += e.h2[q];
+                                }
                             } else {
-#pragma unroll
-                                for (int q = 0; q < 4; ++q) op.h2[q] += e.h2[q];
-                            }
-                        } else {
-                            if (rr == 0) {
-                                op.h2[2 * h] = e.h2[0];
-                                op.h2[2 * h + 1] = e.h2[1];
-                            } else {
-                                op.h2[2 * h] += e.h2[0];
-                                op.h2[2 * h + 1] += e.h2[1];
+                                if (rr == 0) {
+                                    op.h2[2 * h] = e.h2[0];
+                                    op.h2[2 * h + 1] = e.h2[1];
+                                } else {
+                                    op.h2[2 * h] += e.h2[0];
+                                    op.h2[2 * h + 1] += e.h2[1];
+                                }
                             }
                         }
-                    }
+                } else {
+                    // Three or more residual entries: fp32 sum, r ascending, rounded to fp16 once -- the
+                    // dequantized tile of Sec. II-A bit for bit (repeated fp16 additions would round R - 1 times).
+                    float f[8];
+#pragma unroll
+                    for (int h = 0; h < CPO; ++h)
+#pragma unroll
+                        for (int rr = 0; rr < R; ++rr) {
+                            const V16 &e = ev[mi][h][rr];
+#pragma unroll
+                            for (int i = 0; i < V; ++i) {
+                                const float t = (float)e.h8[i];
+                                f[h * V + i] = rr == 0 ? t : f[h * V + i] + t;
+                            }
+                        }
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) op.h8[i] = (half_t)f[i];
+                }
                 half8_t xop = xb[m0 + mi];
                 if (!use_x) xop = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
                 acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(op.h8, xop, acc[t], 0, 0, 0);
@@ -316,12 +339,8 @@ int run(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s)
     }
     const size_t cb_bytes = (size_t)R * a.n_hot * V * 2 * a.tiles_k;
     const size_t lds = ((cb_bytes + 15) & ~(size_t)15) + (size_t)RT * waves * 64 * sizeof(float4v_t);
-    static size_t attr_lds = 0;
-    if (lds > 64 * 1024 && lds > attr_lds) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_mfma_kernel<CodeT, V, R, HOT, RT>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_lds = lds;
-    }
+    static KernelSetup setup;
+    if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_mfma_kernel<CodeT, V, R, HOT, RT>), lds, false, setup)) return st;
     gemv_mfma_kernel<CodeT, V, R, HOT, RT><<<n_wg, waves * 64, lds, s>>>(a);
     return launch_status();
 }

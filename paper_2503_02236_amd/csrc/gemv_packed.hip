@@ -610,19 +610,13 @@ PackedLaunch packed_launch(const vq_weight_t *w, const void *x, void *y, void *p
     return l;
 }
 
-void packed_lds_attr(const void *kernel, size_t lds, size_t *set) {
-    if (lds > 64 * 1024 && lds > *set) {
-        (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        *set = lds;
-    }
-}
 
 }  // namespace
 
 int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, hipStream_t s) {
     PackedLaunch l = packed_launch(w, x, y, ws);
-    static size_t attr_lds = 0;
-    packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_kernel), l.lds, &attr_lds);
+    static KernelSetup setup;   // (the atoms hold absolute LDS addresses: no static LDS allowed)
+    if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_packed_kernel), l.lds, true, setup)) return st;
     gemv_packed_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
     gemv_packed_finalize_kernel<<<(l.a.N + kFinalizeRows - 1) / kFinalizeRows, kFinalizeRows, 0, s>>>(l.a.partial, l.a.scale, l.a.y, l.a.N, l.a.S);
     return launch_status();
@@ -652,8 +646,8 @@ int launch_gemv_packed_batch(const vq_weight_t *const *w, const void *const *x, 
             max_n = l.a.N > max_n ? l.a.N : max_n;
         }
     }
-    static size_t attr_lds = 0;
-    packed_lds_attr(reinterpret_cast<const void *>(&gemv_packed_batch_kernel), lds, &attr_lds);
+    static KernelSetup setup;
+    if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_packed_batch_kernel), lds, true, setup)) return st;
     for (int i = 0; i < kPackMaxBatch; ++i) b.a[i].nwaves = waves;  // one launch shape for all problems
     gemv_packed_batch_kernel<<<dim3(grid, count), waves * 64, lds, s>>>(b);
     FinalizeBatch f;

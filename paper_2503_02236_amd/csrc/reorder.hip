@@ -15,12 +15,35 @@ using namespace vq;
 
 namespace {
 
-template <typename CodeT>
-int reorder(const vq_weight_t *w, void *codes_out, void *codebooks_out) {
+// Code i of a canonical code array on the host: uint8, uint16, or the packed 12-bit string (little-endian
+// bit string, code i in bits [12 i, 12 i + 12)).
+unsigned host_code(const void *codes, int bits, size_t i) {
+    if (bits == 8) return ((const uint8_t *)codes)[i];
+    if (bits == 16) return ((const uint16_t *)codes)[i];
+    const uint8_t *b = (const uint8_t *)codes + (i >> 1) * 3;
+    return (i & 1) ? ((unsigned)b[1] >> 4) | ((unsigned)b[2] << 4) : (unsigned)b[0] | (((unsigned)b[1] & 0xFu) << 8);
+}
+void host_code_store(void *codes, int bits, size_t i, unsigned c) {
+    if (bits == 8) {
+        ((uint8_t *)codes)[i] = (uint8_t)c;
+    } else if (bits == 16) {
+        ((uint16_t *)codes)[i] = (uint16_t)c;
+    } else {
+        uint8_t *b = (uint8_t *)codes + (i >> 1) * 3;
+        if (i & 1) {
+            b[1] = (uint8_t)((b[1] & 0x0Fu) | ((c & 0xFu) << 4));
+            b[2] = (uint8_t)(c >> 4);
+        } else {
+            b[0] = (uint8_t)c;
+            b[1] = (uint8_t)((b[1] & 0xF0u) | ((c >> 8) & 0xFu));
+        }
+    }
+}
+
+// `codes` holds the unpacked codes [n_codes][R]; rewritten in place.  Returns the hot-entry count.
+int reorder(const vq_weight_t *w, std::vector<uint16_t> &codes, void *codebooks_out) {
     const int R = w->n_codebooks, E = w->n_entries, v = w->v;
     const size_t n_codes = (size_t)w->N * (w->K / v);  // per codebook
-    const CodeT *codes = (const CodeT *)w->codes;
-    CodeT *out = (CodeT *)codes_out;
     const uint16_t *cb = (const uint16_t *)w->codebooks;  // fp16 bits, moved verbatim
     uint16_t *cb_out = (uint16_t *)codebooks_out;
     std::vector<uint64_t> count(E);
@@ -36,7 +59,7 @@ int reorder(const vq_weight_t *w, void *codes_out, void *codebooks_out) {
             rank[order[pos]] = (uint32_t)pos;
             std::memcpy(cb_out + ((size_t)r * E + pos) * v, cb + ((size_t)r * E + order[pos]) * v, (size_t)v * 2);
         }
-        for (size_t i = 0; i < n_codes; ++i) out[i * R + r] = (CodeT)rank[codes[i * R + r]];
+        for (size_t i = 0; i < n_codes; ++i) codes[i * R + r] = (uint16_t)rank[codes[i * R + r]];
         // leading entries that serve half of this codebook's codes
         uint64_t served = 0;
         int n = 0;
@@ -61,20 +84,19 @@ extern "C" int vq_reorder_by_frequency(const vq_weight_t *w_host, void *codes_ou
         if (hot_entries_out) *hot_entries_out = 0;
         return VQ_OK;
     }
-    // codes >= n_entries would index past the histogram: reject instead of assuming the precondition
-    int hot = 0;
+    // every storage width is unpacked into one working array (the packed 12-bit string of VQ<8,12,2> included:
+    // two codes in three bytes, N * K/v * R * 3/2 bytes in all)
+    const int bits = w_host->code_bits;
     const size_t total = (size_t)w_host->N * (w_host->K / w_host->v) * w_host->n_codebooks;
-    if (w_host->code_bits == 8) {
-        const uint8_t *c = (const uint8_t *)w_host->codes;
-        for (size_t i = 0; i < total; ++i)
-            if (c[i] >= w_host->n_entries) return VQ_ERR_SHAPE;
-        hot = reorder<uint8_t>(w_host, codes_out_host, codebooks_out_host);
-    } else {
-        const uint16_t *c = (const uint16_t *)w_host->codes;
-        for (size_t i = 0; i < total; ++i)
-            if (c[i] >= w_host->n_entries) return VQ_ERR_SHAPE;
-        hot = reorder<uint16_t>(w_host, codes_out_host, codebooks_out_host);
+    std::vector<uint16_t> codes(total);
+    for (size_t i = 0; i < total; ++i) {
+        const unsigned c = host_code(w_host->codes, bits, i);
+        // codes >= n_entries would index past the histogram: reject instead of assuming the precondition
+        if (c >= (unsigned)w_host->n_entries) return VQ_ERR_SHAPE;
+        codes[i] = (uint16_t)c;
     }
+    const int hot = reorder(w_host, codes, codebooks_out_host);
+    for (size_t i = 0; i < total; ++i) host_code_store(codes_out_host, bits, i, codes[i]);
     if (hot_entries_out) *hot_entries_out = hot;
     return VQ_OK;
 }

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "vq_mi355x.h"
 
 namespace vq {
@@ -112,5 +114,36 @@ int launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t s);
 int launch_probe_mfma(int workgroups, int iters, int random_operands, void *sink, hipStream_t s);
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_LAUNCH; }
+
+// Per-kernel launch set-up that HIP keeps per device: the dynamic LDS limit above 64 KiB, and -- for kernels
+// that form absolute LDS addresses, which is only right when their dynamic LDS starts at address 0 -- the
+// check that the kernel has no static LDS.  What has been done is remembered per device in atomics (calls may
+// come from several host threads; doing either step twice is harmless), one object per kernel.
+constexpr int kMaxDevices = 64;
+struct KernelSetup {
+    std::atomic<size_t> lds_granted[kMaxDevices];
+    std::atomic<int> static_lds[kMaxDevices];   // 0: not looked at yet, 1: none, 2: the kernel has static LDS
+};
+// Returns VQ_OK, or VQ_ERR_LAUNCH when the runtime refuses or (need_lds_base_0) the kernel has static LDS.
+inline int kernel_setup(const void *kernel, size_t lds, bool need_lds_base_0, KernelSetup &ks) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return VQ_ERR_LAUNCH;
+    if (need_lds_base_0) {
+        int st = ks.static_lds[dev].load(std::memory_order_relaxed);
+        if (st == 0) {
+            hipFuncAttributes fa;
+            if (hipFuncGetAttributes(&fa, kernel) != hipSuccess) return VQ_ERR_LAUNCH;
+            st = fa.sharedSizeBytes == 0 ? 1 : 2;
+            ks.static_lds[dev].store(st, std::memory_order_relaxed);
+        }
+        if (st != 1) return VQ_ERR_LAUNCH;
+    }
+    if (lds > 64 * 1024 && lds > ks.lds_granted[dev].load(std::memory_order_relaxed)) {
+        if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return VQ_ERR_LAUNCH;
+        ks.lds_granted[dev].store(lds, std::memory_order_relaxed);
+    }
+    return VQ_OK;
+}
 
 }  // namespace vq

@@ -115,6 +115,43 @@ def test_gemv_shapes_and_edges(gpu_device, N, K, v, bits, R, E, bs, scale):
     assert_close(run_gemv(w, x, gpu_device), oracle.gemv(w.codes, w.codebooks, w.scale, x), f"{N}x{K} v{v} R{R} bs{bs}")
 
 
+@pytest.mark.parametrize("v,bits,R,E,sigma", [
+    (8, 8, 1, 256, 0.02),       # entries verbatim
+    (8, 8, 2, 256, 0.01),       # one fp16 addition = the fp32 sum rounded once
+    (8, 8, 4, 256, 0.3),        # four residuals: repeated fp16 additions would differ from the fp32 sum
+    (4, 8, 4, 256, 0.3),
+    (8, 12, 2, 4096, 0.01),     # packed 12-bit codes
+    (8, 12, 4, 2048, 0.3),
+])
+def test_gemv_matrix_core_operand_is_the_oracle_tile(gpu_device, v, bits, R, E, sigma):
+    """The operand the matrix-core gemv consumes, read back through the gemv itself: with one-hot activations
+    (token m = unit vector k_m, no scale) y[m][n] = W[n][k_m] exactly, so sixteen columns of the dequantized
+    weight come back per call.  They must be the oracle's tile (fp32 sum, r ascending, one rounding to fp16)."""
+    N, K = 40, 256
+    w = wl.make_weight(N, K, v, bits, R, E, sigma, seed=4700 + R + v + bits, with_scale=False)
+    want32 = oracle.dequant(ocodes(w), w.codebooks)
+    want = want32.astype(np.float16)
+    if R == 4:   # the case must tell the two summations apart: sequential fp16 additions round differently somewhere
+        un = (oracle.unpack12(w.codes, N * (K // v) * R).reshape(N, K // v, R) if bits == 12 else w.codes).astype(np.int64)
+        seq = w.codebooks[0][un[:, :, 0]].astype(np.float16)
+        for r in range(1, R):
+            seq = (seq + w.codebooks[r][un[:, :, r]]).astype(np.float16)
+        assert (seq.reshape(N, K).view(np.uint16) != want.view(np.uint16)).any()
+    wd = vq.weight_to_device(w, gpu_device)
+    got = np.empty((N, K), dtype=np.float16)
+    for k0 in range(0, K, 16):
+        x = np.zeros((16, K), dtype=np.float16)
+        x[np.arange(16), k0 + np.arange(16)] = 1.0
+        y = vq.vq_gemv(wd, dev_x(x, gpu_device))
+        got[:, k0:k0 + 16] = y.cpu().numpy().T
+    # (a product with a subnormal fp16 factor may be flushed by the matrix cores: such elements may come back as 0)
+    sub = (np.abs(want.astype(np.float32)) < 2.0 ** -14) & (want != 0)
+    same = got.view(np.uint16) == want.view(np.uint16)
+    print(f"subnormal operands: {int(sub.sum())}, of which returned as zero: {int((sub & ~same).sum())}", flush=True)
+    assert same[~sub].all()
+    assert (same | (got == 0))[sub].all()
+
+
 @pytest.mark.parametrize("bs", [1, 5])
 def test_gemv_hot_entry_cache_on_reordered_zipf_codes(gpu_device, bs):
     # skewed code usage, entries in arbitrary order, then sorted by use offline: the first entries are
@@ -340,7 +377,12 @@ def test_gemm_config4_full_size_sampled_columns(gpu_device, N, v):
     Y = vq.vq_gemm(vq.weight_to_device(w, gpu_device), dev_x(X, gpu_device))
     torch.cuda.synchronize()
     r = np.random.Generator(np.random.PCG64(N + v))
-    rows = np.unique(np.concatenate([r.integers(0, N, size=44), [0, 31, 32, 255, 256, N - 1, N - 33]]))
+    # stratified: one output column out of every 64 (so every 64-, 128- and 256-column tile of the kernel's
+    # tile map holds compared elements), all 2048 tokens of each, plus the edges of the first and last tiles
+    n64 = (N + 63) // 64
+    strat = np.arange(n64) * 64 + r.integers(0, 64, size=n64)
+    rows = np.unique(np.concatenate([strat[strat < N], [0, 31, 32, 255, 256, N - 1, N - 33]]))
+    assert len(np.unique(rows // 128)) == (N + 127) // 128
     want = oracle.gemm(w.codes, w.codebooks, w.scale, X, rows=rows)      # all 2048 tokens x sampled columns
     assert_close(Y[:, torch.from_numpy(rows).to(gpu_device)], want, f"C4 N={N} v={v}")
     assert torch.isfinite(Y.float()).all()

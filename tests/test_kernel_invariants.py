@@ -75,3 +75,20 @@ def test_gemm_dense_ring_wait_matches_the_transfers_of_a_stage(tmp_path):
     assert sum(l.startswith("global_load_lds_dwordx4") for l in body) == 12
     assert not any(re.match(r"(global|flat|buffer)_(load|store)", l) and not l.startswith("global_load_lds") for l in body)
     assert sum(l.startswith("v_mfma_f32_32x32x16") for l in body) == 32
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
+def test_attention_kernels_have_no_static_lds(tmp_path):
+    """The attention kernel forms entry addresses as absolute LDS offsets, which needs its dynamic LDS to start
+    at address 0, i.e. no static LDS in any build of it (the launcher checks the same at run time and returns
+    an error instead of launching)."""
+    out = tmp_path / "attn.s"
+    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "--cuda-device-only", "-S",
+           os.path.join(CSRC, "attn.hip"), "-o", str(out)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    kernels = re.findall(r"\.amdhsa_kernel (\S*attn_decode_kernel\S*)\n(.*?)\.end_amdhsa_kernel", out.read_text(), re.S)
+    assert len(kernels) >= 6            # v = 2, 4, 8 x one / several codebooks (x one or two sequences)
+    for name, body in kernels:
+        assert re.search(r"\.amdhsa_group_segment_fixed_size 0\b", body), name

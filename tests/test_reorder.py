@@ -42,6 +42,29 @@ def test_reorder_keeps_the_weight_and_sorts_by_use(N, K, v, bits, R, E, zipf):
     assert np.array_equal(again.codes, r.codes) and again.codebooks.tobytes() == r.codebooks.tobytes()
 
 
+def test_reorder_packed_12bit_codes():
+    """VQ<8,12,2> (Tbl. III): the packed 12-bit string is unpacked, reordered and packed again."""
+    w = wl.shuffle_entries(wl.make_weight(24, 256, 8, 12, 2, 4096, 0.01, seed=812, zipf_s=1.0), seed=9)
+    shape = (w.N, w.K // w.v, 2)
+    r = vq.vq_reorder_by_frequency(w)
+    assert r.codes.dtype == np.uint8 and r.codes.size == w.codes.size          # same packed size, no over-read
+    before = oracle.dequant(oracle.Packed12(w.codes, shape), w.codebooks)
+    after = oracle.dequant(oracle.Packed12(r.codes, shape), r.codebooks)
+    assert before.tobytes() == after.tobytes()
+    un = oracle.unpack12(r.codes, int(np.prod(shape))).reshape(shape)
+    for k in range(2):
+        counts = np.bincount(un[..., k].ravel().astype(np.int64), minlength=4096)
+        assert (np.diff(counts) <= 0).all()
+        assert 2 * counts[:r.hot_entries].sum() >= counts.sum()
+    # a code beyond n_entries in the packed string is rejected (n_entries below 2^12)
+    lib = vq.lib()
+    codes = np.ascontiguousarray(w.codes)
+    cb = np.ascontiguousarray(w.codebooks[:, :1000])
+    d = vq_weight_t(w.N, w.K, 8, 12, 2, 1000, codes.ctypes.data, cb.ctypes.data, None, None)
+    out_c, out_cb = np.empty_like(codes), np.empty_like(cb)
+    assert lib.vq_reorder_by_frequency(ctypes.byref(d), out_c.ctypes.data, out_cb.ctypes.data, None) == -2
+
+
 def test_reorder_argument_validation():
     lib = vq.lib()
     w = wl.make_weight(8, 64, 8, 8, 1, 16, 0.02, seed=1)
