@@ -127,6 +127,23 @@ int vq_gemv(const vq_weight_t *w, const void *x, int bs, void *y,
 size_t vq_gemv_workspace(const vq_weight_t *w, int bs);
 
 /*
+ * vq_gemv for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same operation, arguments, results (bit for bit) and
+ * errors as vq_gemv, but the scratch that the re-tiled bs = 1 path needs (S x N fp32 partial sums) lies
+ * inside the library: a fixed array of vq_gemv_noalloc_max_workspace() bytes (2 MiB) in every GPU's memory,
+ * held until the process ends.  The call allocates nothing and frees nothing.
+ *   - A problem whose vq_gemv_workspace() exceeds that size is refused with VQ_ERR_WORKSPACE (use vq_gemv).
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in time (different streams, or
+ *     graph branches without an edge between them) race on it and must not be issued; calls on one stream
+ *     are safe.  Nothing in the array has to be cleared between calls.
+ *   - The array's address is looked up once per GPU, on the first call there or in vq_init(); call vq_init()
+ *     (no arguments; VQ_OK or VQ_ERR_LAUNCH) once on each GPU before capturing a graph that holds this call.
+ */
+int vq_init(void);
+size_t vq_gemv_noalloc_max_workspace(void);
+int vq_gemv_noalloc(const vq_weight_t *w, const void *x, int bs, void *y, void *stream);
+
+/*
  * Offline re-tiling for vq_gemv (see vq_gemv_pack_t).  HOST function: w->codes is read from
  * HOST memory here (codebooks / scale are not touched); no GPU is needed.
  *   vq_gemv_prepack_bytes: size of the packed buffer for this matrix, 0 if the configuration

@@ -54,6 +54,10 @@ SYMBOLS = {
     "vq_gemv": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "vq_gemv_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t), ctypes.c_int]),
+    "vq_init": (ctypes.c_int, []),
+    "vq_gemv_noalloc_max_workspace": (ctypes.c_size_t, []),
+    "vq_gemv_noalloc": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                                       ctypes.c_void_p]),
     "vq_reorder_by_frequency": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_void_p,
                                                ctypes.POINTER(ctypes.c_int)]),
     "vq_gemv_batch": (ctypes.c_int, [ctypes.POINTER(ctypes.POINTER(vq_weight_t)), ctypes.POINTER(ctypes.c_void_p),
@@ -268,6 +272,14 @@ def vq_gemv(w: VQWeightDev, x: torch.Tensor, y: Optional[torch.Tensor] = None,
     ws_t, ws_p, ws_n = _workspace(int(lib().vq_gemv_workspace(ctypes.byref(d), bs)), x.device, ws)
     _check(lib().vq_gemv(ctypes.byref(d), _dev(x, "x", torch.float16), bs, _dev(y, "y", torch.float16),
                          ws_p, ws_n, _stream()), "vq_gemv")
+    return y
+
+
+def vq_gemv_noalloc(w: VQWeightDev, x: torch.Tensor, y: torch.Tensor) -> torch.Tensor:
+    """``vq_gemv`` with the library's built-in scratch: the caller passes inputs and the output, nothing is allocated."""
+    d = w.desc()
+    _check(lib().vq_gemv_noalloc(ctypes.byref(d), _dev(x, "x", torch.float16), x.shape[0],
+                                 _dev(y, "y", torch.float16), _stream()), "vq_gemv_noalloc")
     return y
 
 

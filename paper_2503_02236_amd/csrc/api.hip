@@ -94,6 +94,57 @@ int vq_gemv(const vq_weight_t *w, const void *x, int bs, void *y, void *ws, size
     return launch_gemv(w, x, bs, y, ws, static_cast<hipStream_t>(stream));
 }
 
+// ---- vq_gemv for callers that cannot allocate: scratch inside the library ------------------------------
+namespace {
+
+// Scratch of vq_gemv_noalloc: the partial sums that the re-tiled bs = 1 gemv exchanges between its two kernels.
+// One copy per GPU, at an address of its own on each, held until the process ends.  In host code the
+// array's name is only a stand-in for the symbol: the address that kernels, copies and fills may use comes
+// from hipGetSymbolAddress, once per device, and is kept in scratch_ptr.
+constexpr size_t kGemvScratchBytes = 2u << 20;
+static __device__ __align__(256) unsigned char scratch[kGemvScratchBytes];
+std::atomic<void *> scratch_ptr[kMaxDevices];
+
+int scratch_address(void **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return VQ_ERR_LAUNCH;
+    void *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return VQ_ERR_LAUNCH;
+        }
+        scratch_ptr[dev].store(p, std::memory_order_release);   // (two threads racing here store the same address)
+    }
+    *out = p;
+    return VQ_OK;
+}
+
+}  // namespace
+
+int vq_init(void) {
+    void *p;
+    return scratch_address(&p);
+}
+
+size_t vq_gemv_noalloc_max_workspace(void) { return kGemvScratchBytes; }
+
+int vq_gemv_noalloc(const vq_weight_t *w, const void *x, int bs, void *y, void *stream) {
+    if (!w) return VQ_ERR_NULL;
+    if (bs < 1 || bs > 16) return VQ_ERR_SHAPE;
+    const bool packed = gemv_uses_pack(w, bs);
+    int st = check_weight(w, !packed);
+    if (st != VQ_OK) return st;
+    if (packed && (st = check_pack(w)) != VQ_OK) return st;
+    const size_t need = gemv_workspace(w, bs);
+    if (need > kGemvScratchBytes) return VQ_ERR_WORKSPACE;   // beyond the built-in scratch: use vq_gemv with a workspace
+    void *ws = nullptr;
+    if (need && (st = scratch_address(&ws)) != VQ_OK) return st;
+    // Nothing in the scratch has to start at zero: every partial sum that the second kernel reads is written
+    // by the first kernel of the same call.
+    return vq_gemv(w, x, bs, y, ws, need ? kGemvScratchBytes : 0, stream);
+}
+
 // Every problem of the batch can run from re-tiled codes in one launch.
 static bool batch_all_packed(const vq_weight_t *const *w, int count) {
     for (int i = 0; i < count; ++i)
