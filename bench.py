@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--no-batch", action="store_true",
                     help="one vq_gemv call per matrix (224 launches) instead of vq_gemv_batch for the projections of "
                          "a block that share their input (query/key/value; gate/up)")
+    ap.add_argument("--no-sequence", action="store_true",
+                    help="separate vq_gemv_batch / vq_gemv calls (two launches each: product and its reduction) instead "
+                         "of one vq_gemv_sequence over the stack (the reduction rides along in the next launch)")
     ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add,zipf,tile,bit12")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter run (wrap in rocprofv3 --pmc FETCH_SIZE or WRITE_SIZE): three plain copies of "
@@ -179,7 +182,9 @@ def main():
         host_block0 = []
         packed = not args.canonical
         batched = packed and not args.no_batch
+        sequenced = batched and not args.no_sequence
         ws = vq.new_workspace(4 << 20, dev) if packed else None   # shared by all launches of the stream
+        seq_calls = []
 
         class BatchCall:
             """Pre-marshalled vq_gemv_batch call."""
@@ -210,13 +215,25 @@ def main():
             if batched:
                 # slots: 0-2 query/key/value (one input), 3 output, 4-5 gate/up (one input), 6 down
                 calls += [BatchCall(block[0:3]), block[3], BatchCall(block[4:6]), block[6]]
+                seq_calls += [[c.keep[:3] for c in grp] for grp in (block[0:3], block[3:4], block[4:6], block[6:7])]
             else:
                 calls += block
         torch.cuda.synchronize()
 
-        def step():
-            for c in calls:
-                c()
+        if sequenced:
+            # the whole stack as ONE vq_gemv_sequence: one launch per call, the reduction of each riding along
+            # in the next, one reduction launch at the end
+            seq = vq.GemvSequence(seq_calls)
+            seq_ws = vq.new_workspace(seq.workspace(), dev)
+
+            def step():
+                st = seq.run(seq_ws.data_ptr(), seq_ws.numel())
+                if st != 0:
+                    raise vq.VQError(st, "vq_gemv_sequence")
+        else:
+            def step():
+                for c in calls:
+                    c()
 
         if args.pmc_probe:
             step()
@@ -280,7 +297,10 @@ def main():
                                    "fp16 scale" % L,
                        "launches_per_step": n_launch, "matrices_per_step": len(singles),
                        "effective_bytes_per_step": eff_bytes,
-                       "calls": ("per block: vq_gemv_batch(q,k,v), vq_gemv(o), vq_gemv_batch(gate,up), vq_gemv(down)"
+                       "kernel_dispatches_per_step": (n_launch + 1 if sequenced else 2 * n_launch if packed else n_launch),
+                       "calls": ("one vq_gemv_sequence over the stack; per block the calls (q,k,v), (o), (gate,up), (down)"
+                                 if sequenced else
+                                 "per block: vq_gemv_batch(q,k,v), vq_gemv(o), vq_gemv_batch(gate,up), vq_gemv(down)"
                                  if batched else "one vq_gemv per matrix"),
                        "code_layout": "re-tiled offline by vq_gemv_prepack (LDS codebook slices)" if packed
                                       else "canonical [N][K/8] (entries gathered from L2)",
@@ -288,7 +308,8 @@ def main():
             "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
             "pct_measured_stream_read": round(100 * gbps / ceil_hbm, 2),
             "gemv_per_shape_cold": shape_us,
-            "roofline": {"bound": "hbm", "kernel": ("gemv_packed_batch_kernel / gemv_packed_kernel (+ finalize)" if batched else
+            "roofline": {"bound": "hbm", "kernel": ("gemv_packed_batch_kernel / gemv_packed_kernel (reduction folded into the next launch)" if sequenced else
+                                    "gemv_packed_batch_kernel / gemv_packed_kernel (+ finalize)" if batched else
                                     "gemv_packed_kernel (+ finalize)" if packed else "gemv_rows_kernel<uint16,8,1>"),
                          "achieved": round(gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": round(gbps / HBM_PEAK_GBPS, 4),

@@ -52,18 +52,24 @@ typedef enum vq_status {
  * caller uploads `data` to the device and hands this struct back unchanged.
  *
  * Idea (codebook-centric dataflow, Sec. VI-A, taken to the entry level): the codebook is cut
- * into S slices that fit LDS, rows into RB blocks; workgroup (slice, block) sees only the codes
- * that point into its slice, stored as 24-bit "atoms" (two 12-bit numbers: where the entry and where
- * x_j lie in the workgroup's LDS image [slice][x][one zero unit], in 16-byte units; padding atoms name
- * the zero unit twice), one row per lane, rows of similar length grouped 64 at a time.  Partial
- * sums of the S slices are added in a fixed order by a second kernel (Sec. VI-A "global reduction").
- * Every workgroup's atoms have one common shape: its g-th group of 64 rows takes group_steps[g] steps
- * (768-byte blocks) and starts at block  wg * wg_pitch + sum_{g' < g} group_steps[g'],  so the kernel
- * derives every address from this struct alone and reads no table before it can ask for its codes.  That
- * needs codes that spread evenly over the codebook (as quantizers produce them): vq_gemv_prepack declines
- * (VQ_ERR_UNSUPPORTED, vq_gemv_prepack_bytes = 0) when padding to the common shape would cost more than a
- * quarter more blocks and more than 1 MiB, or a workgroup has more than VQ_PACK_MAX_GROUPS groups; vq_gemv then runs from the
- * canonical codes.  Layout of `data`: see the format description in the source of vq_gemv_prepack.
+ * into S slices of 2^entry_bits entries that fit LDS, rows into RB blocks; workgroup (slice, block) sees
+ * only the codes that point into its slice.  A row's K/8 sub-vector positions are cut into `parts` parts of
+ * part_cols positions; a lane task = (row, part) walks the codes of that row and part.  A code is stored as
+ * a 21-bit "atom": the entry's index inside the slice (entry_bits bits, low) and the position inside the
+ * part (21 - entry_bits bits); both are 16-byte units of the workgroup's LDS image
+ * [slice][part 0 of x, 16 zero units][part 1 of x, 16 zero units]...; padding atoms name a zero unit as x_j.
+ * Three atoms fill a 64-bit step word; tasks of similar length are grouped 64 at a time (one lane each);
+ * the order of a task's atoms is chosen offline so that the lanes' LDS reads collide as little as possible.
+ * Partial sums of the S slices are added in a fixed order by a second kernel (Sec. VI-A "global reduction").
+ * Group g of every workgroup starts at block  wg * wg_pitch + sum_{g' < g} group_steps[g']  (512-byte
+ * blocks), so the kernel derives every address from this struct alone; how many of those blocks a
+ * workgroup's group really uses comes from a small table inside `data`.  That needs codes that spread evenly
+ * over the codebook (as quantizers produce them): vq_gemv_prepack declines (VQ_ERR_UNSUPPORTED,
+ * vq_gemv_prepack_bytes = 0) when the common shape would cost more than a quarter more blocks and more than
+ * 1 MiB, or a workgroup has more than VQ_PACK_MAX_GROUPS groups; vq_gemv then runs from the canonical codes.
+ * Entries that codes point at must be finite (a padding atom adds 0 times an entry that some code of the same
+ * 64 tasks uses; entries that no code points at are never read).  Layout of `data`: see the format description
+ * in the source of vq_gemv_prepack.
  */
 #define VQ_PACK_MAX_GROUPS 128
 typedef struct vq_gemv_pack_t {
@@ -71,9 +77,11 @@ typedef struct vq_gemv_pack_t {
     uint64_t bytes;           /* size of data */
     uint32_t S, RB;           /* codebook slices, row blocks; S * RB workgroups */
     uint32_t rows_per_block;
-    uint32_t wg_pitch;        /* 768-byte atom blocks per workgroup (the sum of group_steps) */
-    uint64_t rowid_off, atom_off; /* byte offsets of the two tables in data */
-    uint16_t group_steps[VQ_PACK_MAX_GROUPS]; /* steps of group g of every workgroup; 0 past the last group */
+    uint32_t entry_bits;      /* slices of 2^entry_bits entries */
+    uint32_t parts, part_cols; /* parts of a row, sub-vector positions per part */
+    uint32_t wg_pitch;        /* 512-byte atom blocks per workgroup (the sum of group_steps) */
+    uint64_t task_off, steps_off, atom_off; /* byte offsets of the three tables in data */
+    uint16_t group_steps[VQ_PACK_MAX_GROUPS]; /* blocks reserved for group g of every workgroup; 0 past the last group */
 } vq_gemv_pack_t;
 
 /*
@@ -148,10 +156,11 @@ int vq_gemv_noalloc(const vq_weight_t *w, const void *x, int bs, void *y, void *
  * HOST memory here (codebooks / scale are not touched); no GPU is needed.
  *   vq_gemv_prepack_bytes: size of the packed buffer for this matrix, 0 if the configuration
  *     has no packed form (supported: v = 8, uint16 codes, one codebook, E a power of two
- *     >= 4096, K / v <= 2047, codes that spread evenly over the codebook: see vq_gemv_pack_t).
+ *     >= 4096, K <= 64512, codes that spread evenly over the codebook: see vq_gemv_pack_t).
  *   vq_gemv_prepack: writes the packed buffer into out_host (>= that size, 16-byte aligned)
  *     and fills *pack (pack->data = out_host; replace it by the device copy's address before
- *     passing the struct to vq_gemv).  Errors: NULL / UNSUPPORTED / WORKSPACE (buffer too small).
+ *     passing the struct to vq_gemv).  Errors: NULL / UNSUPPORTED / SHAPE (a code >= n_entries) / WORKSPACE
+ *     (buffer too small).
  * With w->gemv_pack set and bs == 1, vq_gemv runs from the packed codes (w->codes may then be
  * NULL) and needs the workspace vq_gemv_workspace() reports (S x N fp32 partial sums; calls that
  * share one workspace must not overlap).
@@ -192,6 +201,29 @@ int vq_reorder_by_frequency(const vq_weight_t *w_host, void *codes_out_host, voi
 int vq_gemv_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count,
                   void *ws, size_t ws_bytes, void *stream);
 size_t vq_gemv_batch_workspace(const vq_weight_t *const *w, int count);
+
+/*
+ * A sequence of bs = 1 VQ-gemv calls on one stream, call c being a batch of calls[c].count independent problems
+ * (as vq_gemv_batch takes them).  Same results, bit for bit, as the vq_gemv_batch calls made one after the other.
+ * What it saves: the explicit global reduction of the codebook-centric kernel (Sec. VI-A: its cost grows with
+ * split x output) needs a kernel boundary behind every launch; here the boundary is the next call's launch,
+ * whose workgroups take the previous call's rows along and add their partial sums in their prologue and
+ * epilogue, so a sequence of n calls is n + 1 kernel launches instead of 2 n.
+ * Consequence: the outputs of call c are complete only when the work of the whole sequence is; the inputs of a
+ * call must therefore not depend on outputs of earlier calls OF THE SAME SEQUENCE (products that depend on each
+ * other through kernels in between belong to different sequences, or to vq_gemv / vq_gemv_batch).
+ * Every weight must carry re-tiled codes (gemv_pack); VQ_ERR_UNSUPPORTED otherwise.  calls, and the arrays they
+ * point at, are HOST memory.  ws: vq_gemv_sequence_workspace(calls, n_calls) bytes (twice the largest call's
+ * partial sums).  Errors: as vq_gemv_batch; VQ_ERR_SHAPE for n_calls < 1.
+ */
+typedef struct vq_gemv_call_t {
+    const vq_weight_t *const *w;   /* count weights */
+    const void *const *x;          /* count device pointers, fp16 [K_i] */
+    void *const *y;                /* count device pointers, fp16 [N_i] */
+    int count;                     /* 1 .. VQ_GEMV_BATCH_MAX */
+} vq_gemv_call_t;
+int vq_gemv_sequence(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t ws_bytes, void *stream);
+size_t vq_gemv_sequence_workspace(const vq_gemv_call_t *calls, int n_calls);
 
 /*
  * VQ-gemm (prefill phase, Sec. III-C / Sec. VII "GeMM"): Y = X W^T with the

@@ -26,8 +26,9 @@ class VQError(RuntimeError):
 
 class vq_gemv_pack_t(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("bytes", ctypes.c_uint64), ("S", ctypes.c_uint32), ("RB", ctypes.c_uint32),
-                ("rows_per_block", ctypes.c_uint32), ("wg_pitch", ctypes.c_uint32),
-                ("rowid_off", ctypes.c_uint64), ("atom_off", ctypes.c_uint64),
+                ("rows_per_block", ctypes.c_uint32), ("entry_bits", ctypes.c_uint32),
+                ("parts", ctypes.c_uint32), ("part_cols", ctypes.c_uint32), ("wg_pitch", ctypes.c_uint32),
+                ("task_off", ctypes.c_uint64), ("steps_off", ctypes.c_uint64), ("atom_off", ctypes.c_uint64),
                 ("group_steps", ctypes.c_uint16 * 128)]
 
 
@@ -47,6 +48,11 @@ class vq_kv_t(ctypes.Structure):
                 ("seq_lens", ctypes.c_void_p)]
 
 
+class vq_gemv_call_t(ctypes.Structure):
+    _fields_ = [("w", ctypes.POINTER(ctypes.POINTER(vq_weight_t))), ("x", ctypes.POINTER(ctypes.c_void_p)),
+                ("y", ctypes.POINTER(ctypes.c_void_p)), ("count", ctypes.c_int)]
+
+
 _lib = None
 
 #: name -> (restype, argtypes); must list every symbol the header declares
@@ -64,6 +70,9 @@ SYMBOLS = {
                                      ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p,
                                      ctypes.c_size_t, ctypes.c_void_p]),
     "vq_gemv_batch_workspace": (ctypes.c_size_t, [ctypes.POINTER(ctypes.POINTER(vq_weight_t)), ctypes.c_int]),
+    "vq_gemv_sequence": (ctypes.c_int, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                        ctypes.c_void_p]),
+    "vq_gemv_sequence_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int]),
     "vq_gemv_prepack_bytes": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t)]),
     "vq_gemv_prepack": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_size_t,
                                        ctypes.POINTER(vq_gemv_pack_t)]),
@@ -310,6 +319,36 @@ def vq_gemv_batch(ws_list, xs, ys=None, ws: Optional[torch.Tensor] = None):
     ws_t, ws_p, ws_n = _workspace(call.workspace(), xs[0].device, ws)
     _check(call.run(ws_p, ws_n), "vq_gemv_batch")
     return ys
+
+
+class GemvSequence:
+    """Marshalled arguments of one ``vq_gemv_sequence`` call: a list of calls, each a list of (weight, x, y)."""
+
+    def __init__(self, calls):
+        self.batches = [GemvBatch([t[0] for t in c], [t[1] for t in c], [t[2] for t in c]) for c in calls]
+        self.arr = (vq_gemv_call_t * len(self.batches))()
+        for i, b in enumerate(self.batches):
+            self.arr[i].w = ctypes.cast(b.w_arr, ctypes.POINTER(ctypes.POINTER(vq_weight_t)))
+            self.arr[i].x = ctypes.cast(b.x_arr, ctypes.POINTER(ctypes.c_void_p))
+            self.arr[i].y = ctypes.cast(b.y_arr, ctypes.POINTER(ctypes.c_void_p))
+            self.arr[i].count = b.count
+        self.n = len(self.batches)
+
+    def workspace(self) -> int:
+        return int(lib().vq_gemv_sequence_workspace(self.arr, self.n))
+
+    def run(self, ws_ptr, ws_bytes) -> int:
+        return lib().vq_gemv_sequence(self.arr, self.n, ws_ptr, ws_bytes, _stream())
+
+
+def vq_gemv_sequence(calls, ws: Optional[torch.Tensor] = None):
+    """Independent batches of bs = 1 products, one launch each plus one reduction launch at the end.
+
+    ``calls``: list of lists of (VQWeightDev, x, y).  Returns the marshalled sequence (its y tensors are filled)."""
+    seq = GemvSequence(calls)
+    ws_t, ws_p, ws_n = _workspace(seq.workspace(), calls[0][0][1].device, ws)
+    _check(seq.run(ws_p, ws_n), "vq_gemv_sequence")
+    return seq
 
 
 def vq_gemm_workspace(w: VQWeightDev, M: int) -> int:

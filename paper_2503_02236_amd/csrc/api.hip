@@ -197,6 +197,42 @@ int vq_gemv_batch(const vq_weight_t *const *w, const void *const *x, void *const
     return VQ_OK;
 }
 
+// Validation of one call of a sequence: every problem must run from re-tiled codes.
+static int check_sequence_call(const vq_gemv_call_t *c) {
+    if (!c->w || !c->x || !c->y) return VQ_ERR_NULL;
+    if (c->count < 1 || c->count > VQ_GEMV_BATCH_MAX) return VQ_ERR_SHAPE;
+    for (int i = 0; i < c->count; ++i) {
+        const vq_weight_t *w = c->w[i];
+        if (!w) return VQ_ERR_NULL;
+        if (!w->gemv_pack) return VQ_ERR_UNSUPPORTED;
+        if (!gemv_uses_pack(w, 1) || w->K <= 0 || w->N <= 0) return VQ_ERR_UNSUPPORTED;
+        int st = check_weight(w, false);
+        if (st != VQ_OK) return st;
+        if ((st = check_pack(w)) != VQ_OK) return st;
+        if (!c->x[i] || !c->y[i]) return VQ_ERR_NULL;
+        if (!aligned16(c->x[i]) || !aligned16(c->y[i])) return VQ_ERR_ALIGN;
+    }
+    return VQ_OK;
+}
+
+size_t vq_gemv_sequence_workspace(const vq_gemv_call_t *calls, int n_calls) {
+    if (!calls || n_calls < 1) return 0;
+    for (int c = 0; c < n_calls; ++c)
+        if (check_sequence_call(&calls[c]) != VQ_OK) return 0;
+    return gemv_packed_sequence_workspace(calls, n_calls);
+}
+
+int vq_gemv_sequence(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t ws_bytes, void *stream) {
+    if (!calls) return VQ_ERR_NULL;
+    if (n_calls < 1) return VQ_ERR_SHAPE;
+    for (int c = 0; c < n_calls; ++c)
+        if (int st = check_sequence_call(&calls[c])) return st;
+    const size_t need = gemv_packed_sequence_workspace(calls, n_calls);
+    if (!ws || ws_bytes < need) return VQ_ERR_WORKSPACE;
+    if (!aligned16(ws)) return VQ_ERR_ALIGN;
+    return launch_gemv_packed_sequence(calls, n_calls, ws, static_cast<hipStream_t>(stream));
+}
+
 size_t vq_gemm_workspace(const vq_weight_t *w, int M) {
     if (check_weight(w, true) != VQ_OK || M < 1) return 0;
     return gemm_workspace(w, M);

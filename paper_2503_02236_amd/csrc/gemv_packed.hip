@@ -1,42 +1,57 @@
-// bs = 1 VQ-gemv from re-tiled ("packed") codes: codebook slices in LDS, dense LDS gathers.
+// bs = 1 VQ-gemv from re-tiled ("packed") codes: codebook slices in LDS, LDS gathers scheduled offline.
 //
-// Why: with a 2^16 x 8 fp16 codebook (1 MiB) the entries cannot live in LDS, and random
-// 16-byte gathers from L2 run at ~0.44 per clock per CU on MI355X (each one moves a
-// 128-byte line), an order of magnitude below what the HBM code stream could feed.  Random
-// 16-byte gathers from LDS run at ~5.5 per clock per CU.  So the product is partitioned
-// along the codebook itself -- the codebook-centric dataflow of VQ-LLM (arXiv 2503.02236)
-// Sec. VI-A pushed from "one codebook per block" to "one codebook slice per block":
-//   workgroup (s, rb) holds slice s (E/S entries) and the activation vector in LDS and
-//   processes, for the rows of block rb, exactly the codes that point into slice s.
-// Those codes are found offline (Sec. II-C: weights are quantized offline; Sec. V-B already
-// rewrites indices offline) by vq_gemv_prepack and stored as 24-bit atoms, two 12-bit numbers of
-// 16-byte units in the workgroup's LDS image  [slice: E/S units][x: K/8 units][one zero unit]:
-//   bits 0..11   unit of the entry   = its index inside the slice
-//   bits 12..23  unit of x_j         = E/S + j
-// so an address is a shift and a mask away from the atom.  A padding atom names the zero unit twice and
-// adds 0 * 0: no validity test per atom (the loop around the gathers is bound by vector ALU issue: 15
-// instructions per atom before this format, 9 with it).  The image must fit 4096 units: slices of at most
-// 2048 entries, K/8 <= 2047.
-// One lane owns one row: it walks that row's atoms (j ascending), gathers entry and x_j from
-// LDS and accumulates privately, so there is no cross-lane reduction at all.  Rows of a block
-// are sorted by atom count and grouped 64 at a time, so the lanes of a wavefront run nearly the
-// same trip count.  The S partial sums of a row are added in slice order by a second small
-// kernel (Sec. VI-A "explicit global reduction"), which keeps the result bit-reproducible.
+// Why: with a 2^16 x 8 fp16 codebook (1 MiB) the entries cannot live in LDS, and random 16-byte gathers
+// from L2 run at ~0.44 per clock per CU on MI355X (each one moves a 128-byte line), an order of magnitude
+// below what the HBM code stream could feed.  LDS serves them at 5 (random addresses) to 13 (no bank
+// conflicts) per clock per CU.  So the product is partitioned along the codebook itself -- the
+// codebook-centric dataflow of VQ-LLM (arXiv 2503.02236) Sec. VI-A pushed from "one codebook per block" to
+// "one codebook slice per block":
+//   workgroup (s, rb) holds slice s (2^EB entries) and the activation vector in LDS and processes, for the
+//   rows of block rb, exactly the codes that point into slice s.
+// Those codes are found offline (Sec. II-C: weights are quantized offline; Sec. V-B already rewrites indices
+// offline) by vq_gemv_prepack.
 //
-// Packed buffer (little endian, offsets from the start of the buffer, 256-byte aligned):
-//   row ids      [S*RB][G][64] uint16   row inside the block, 0xFFFF = idle lane; G = ceil(rows_per_block / 64)
-//   atoms        blocks of 768 bytes = 64 lanes x 12 bytes = 4 atoms per lane per step; 16 blocks of padding atoms
-//                follow the last workgroup's (the kernels read a few blocks past the end of a group without looking)
-// Placement of the atom blocks.  A kernel that has to read a table before it can ask for its atoms
-// pays two dependent first touches of memory (~1.5 us each) before any work.  Codes that spread evenly
-// over the codebook make group g look nearly the same in every workgroup (the g-th 64 rows of a sorted
-// list of equally distributed lengths), so all workgroups are padded to one common shape: group g has
-// group_steps[g] steps everywhere (the maximum over the workgroups; ~5 % more blocks at Llama-7B shapes)
-// and starts at block wg * wg_pitch + sum_{g' < g} group_steps[g'].  Those few numbers travel in the
-// descriptor and reach the kernel as launch arguments.  Codes too uneven for that (more than a quarter
-// more blocks) are declined: the canonical-code kernels serve them.
+// Lane tasks.  A row's sub-vector positions are cut into P parts of Jp positions (P = 1 unless the row is
+// longer than an atom's position field).  A task = (row, part): the codes of that row and part that point
+// into the slice.  One lane owns one task: it gathers entry and x_j of each of its codes from LDS and
+// accumulates privately, so there is no cross-lane reduction.  The tasks of a workgroup are sorted by length
+// and grouped 64 at a time (one wavefront per group), so the lanes of a wavefront run nearly the same trip
+// count; a group takes as many steps as its longest task needs.
+//
+// Atoms.  A code is stored as a 21-bit atom: EB bits entry index inside the slice (low bits), then
+// XB = 21 - EB bits position inside the part.  Three atoms make a 64-bit step word (atom k in bits
+// [21 k, 21 k + 21), bit 63 zero); a step of a group is a block of 64 step words, lane l's at byte 8 l.
+// LDS image of a workgroup, in 16-byte units: [slice: 2^EB][part 0: Jp units of x, 16 zero units][part 1: ...],
+// so an entry's address is (index << 4) and x_j's is the lane's part base + (position << 4).  A task that is
+// shorter than its group is filled up with padding atoms, which name one of the 16 zero units of the part as
+// x_j (and an entry that some code of the same group uses) and add entry * 0: no validity test in the loop.
+// (Entries that no code points at are never read; entries in use must be finite.)
+//
+// Order of a task's atoms = order of the additions to its sum; it is fixed offline, so results are
+// bit-reproducible -- and it is free.  LDS serves the 16-byte reads of 16 consecutive lanes together and
+// needs one pass per distinct address that falls into the same 16-byte column (address / 16 mod 16): random
+// addresses take ~2.6 passes.  The packer therefore orders the atoms of every 16 lanes so that, position by
+// position, their entry addresses and their x addresses hit different columns wherever the lists allow it
+// (greedy, the lanes with the least room first; padding atoms go where nothing fits and pick a free zero unit).
+//
+// The S partial sums of a row are added in slice order by a second small kernel (Sec. VI-A "explicit global
+// reduction"), which keeps the result independent of timing.
+//
+// Packed buffer (little endian; offsets from the start of the buffer, each 256-byte aligned):
+//   task table   [S*RB][G][64] uint16   slot of lane l of group g: part * rows_per_block + row inside the block;
+//                                       0xFFFF = idle lane.  G = ceil(rows_per_block * P / 64)
+//   step table   [S*RB][G] uint32       steps of group g of this workgroup
+//   atoms        blocks of 512 bytes; group g of workgroup wg starts at block
+//                wg * wg_pitch + sum_{g' < g} group_steps[g'], where group_steps[g] (in the descriptor) is the
+//                maximum over all workgroups: every address follows from launch arguments alone, and only the
+//                trip counts come from the step table (one scalar load, issued first, needed after the slice
+//                has landed).  Blocks between a group's own steps and group_steps[g] hold padding atoms and are
+//                read only by a few blocks of prefetch; 16 more padding blocks follow the last workgroup's.
+// Codes too uneven for a common address shape (skewed code distributions: more than a quarter more blocks than
+// needed and more than 1 MiB of them) are declined: the canonical-code kernels serve them.
 #include <algorithm>
 #include <cstring>
+#include <thread>
 #include <type_traits>
 #include <vector>
 
@@ -44,151 +59,317 @@
 
 namespace vq {
 
-constexpr int kPackFieldBits = 12;   // an atom = two LDS unit numbers of 12 bits
+constexpr int kAtomBits = 21;
+constexpr int kStepAtoms = 3;
+constexpr int kZeroUnits = 16;        // zero units behind every part of x: one per 16-byte column
+constexpr int kStepBytes = 512;       // 64 lanes x 8 bytes
 // atom blocks behind the last workgroup's: the kernels read up to this many blocks past the end of a group
 // without looking (a clamp per load costs more instructions than the load)
 constexpr int kPackTailBlocks = 16;
+constexpr int kPackMaxParts = 8;
+constexpr size_t kPackMaxLds = 144 * 1024;
 
 struct PackPlan {
-    uint32_t S, RB, rows_per_block, slice_entries;
+    uint32_t EB, XB, slice_entries, S, RB, rows_per_block, P, Jp, tasks, G;
+    size_t lds;   // bytes of the workgroup's LDS image + accumulator buffer
 };
 
-static bool pack_supported(const vq_weight_t *w) {
-    if (w->v != 8 || w->code_bits != 16 || w->n_codebooks != 1) return false;
-    int E = w->n_entries;
-    if (E < 4096 || (E & (E - 1)) != 0) return false;
-    if (w->K <= 0 || w->N <= 0 || 2048 + w->K / 8 + 1 > (1 << kPackFieldBits)) return false;  // slice + x + zero unit
-    return true;
+static size_t pack_lds_bytes(uint32_t slice_entries, uint32_t P, uint32_t Jp, uint32_t tasks) {
+    return ((size_t)slice_entries + (size_t)P * (Jp + kZeroUnits)) * 16 + (size_t)tasks * sizeof(float);
 }
 
-// S * RB = 256 workgroups, one per compute unit.  Slices of 2048 entries (32 KiB); a workgroup with more
-// than 16 row groups gives its wavefronts several groups each.  Long rows
-// (K > 8192) take 1024-entry slices: the atom list of a (row, slice) cell is K/8 / S long, and a short
-// list is what keeps every step of a wavefront in its register prefetch (measured on 4096 x 11008:
-// 18.2 -> 14.6 us; on K = 4096 the doubled partial-sum traffic costs more than it saves).
-static PackPlan pack_plan(const vq_weight_t *w) {
+// S * RB = 256 workgroups, one per compute unit, when the matrix has rows enough.
+static bool pack_plan(const vq_weight_t *w, PackPlan *out) {
+    if (w->v != 8 || w->code_bits != 16 || w->n_codebooks != 1) return false;
+    const int E = w->n_entries;
+    if (E < 4096 || (E & (E - 1)) != 0) return false;
+    if (w->K <= 0 || w->N <= 0) return false;
     PackPlan p;
-    p.slice_entries = 2048;
-    if (w->K / 8 > 1024 && w->n_entries >= 65536) p.slice_entries = 1024;
-    p.S = (uint32_t)w->n_entries / p.slice_entries;
+    p.EB = 11;
+    p.XB = kAtomBits - p.EB;
+    p.slice_entries = 1u << p.EB;
+    const uint32_t J = (uint32_t)w->K / 8, cap = (1u << p.XB) - kZeroUnits;
+    p.P = (J + cap - 1) / cap;
+    if (p.P > (uint32_t)kPackMaxParts) return false;
+    p.Jp = (J + p.P - 1) / p.P;
+    p.S = (uint32_t)E / p.slice_entries;
     uint32_t rb = 256 / p.S;
-    uint32_t max_rb = ((uint32_t)w->N + 63) / 64;   // at least one full 64-row group per block
+    const uint32_t max_rb = ((uint32_t)w->N + 63) / 64;   // at least one full 64-row group per block
     if (rb > max_rb) rb = max_rb;
     if (rb < 1) rb = 1;
     p.RB = rb;
     p.rows_per_block = ((uint32_t)w->N + rb - 1) / rb;
-    return p;
+    p.tasks = p.rows_per_block * p.P;
+    p.G = (p.tasks + 63) / 64;
+    if (p.G > VQ_PACK_MAX_GROUPS || p.tasks >= 0xFFFFu) return false;
+    p.lds = pack_lds_bytes(p.slice_entries, p.P, p.Jp, p.tasks);
+    if (p.lds > kPackMaxLds) return false;
+    *out = p;
+    return true;
+}
+
+static bool pack_supported(const vq_weight_t *w) {
+    PackPlan p;
+    return pack_plan(w, &p);
 }
 
 static inline uint64_t align256(uint64_t x) { return (x + 255) & ~(uint64_t)255; }
 
-// One pass builds everything; `out` == nullptr only measures.
-static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pack_t *pack) {
-    const PackPlan p = pack_plan(w);
-    const int J = w->K / 8;
-    const uint16_t *codes = reinterpret_cast<const uint16_t *>(w->codes);
-    uint32_t lb = 0;  // log2(slice_entries)
-    while ((1u << lb) < p.slice_entries) ++lb;
-    const uint32_t nwg = p.S * p.RB;
+namespace {
 
-    // counts[rb][s][row_in_block]
-    std::vector<uint32_t> cnt((size_t)nwg * p.rows_per_block, 0);
-    for (int n = 0; n < w->N; ++n) {
-        uint32_t rb = (uint32_t)n / p.rows_per_block, ri = (uint32_t)n % p.rows_per_block;
-        const uint16_t *row = codes + (size_t)n * J;
-        for (int j = 0; j < J; ++j) cnt[((size_t)(row[j] >> lb) * p.RB + rb) * p.rows_per_block + ri]++;
-    }
-    // per workgroup: rows sorted by count (descending, ties by row), groups of 64
-    const uint32_t ng = (p.rows_per_block + 63) / 64;
-    if (ng > VQ_PACK_MAX_GROUPS) return 0;
-    std::vector<uint32_t> steps((size_t)nwg * ng, 0);   // steps a group needs
-    std::vector<uint16_t> rowids;
-    rowids.reserve((size_t)nwg * ng * 64);
-    std::vector<uint32_t> order(p.rows_per_block);
-    std::vector<uint32_t> max_steps(ng, 0);
-    uint64_t needed_blocks = 0;
-    for (uint32_t wg = 0; wg < nwg; ++wg) {
-        uint32_t rb = wg % p.RB;
-        uint32_t rows_here = 0;
-        if ((uint64_t)rb * p.rows_per_block < (uint64_t)w->N)
-            rows_here = std::min<uint32_t>(p.rows_per_block, (uint32_t)w->N - rb * p.rows_per_block);
-        const uint32_t *c = &cnt[(size_t)wg * p.rows_per_block];
-        for (uint32_t i = 0; i < rows_here; ++i) order[i] = i;
-        std::stable_sort(order.begin(), order.begin() + rows_here, [&](uint32_t a, uint32_t b) { return c[a] > c[b]; });
-        for (uint32_t g = 0; g < ng; ++g) {
-            const uint32_t st = g * 64 < rows_here ? (c[order[g * 64]] + 3) / 4 : 0;  // a group's first row is its longest
-            steps[(size_t)wg * ng + g] = st;
-            needed_blocks += st;
-            max_steps[g] = std::max(max_steps[g], st);
-            for (uint32_t l = 0; l < 64; ++l) {
-                uint32_t i = g * 64 + l;
-                rowids.push_back(i < rows_here ? (uint16_t)order[i] : (uint16_t)0xFFFF);
+struct HostAtom {
+    uint16_t e, x;   // entry index inside the slice, position inside the part
+};
+
+// Order of the atoms of 16 lanes (one LDS service group) over `npos` positions.  lists[l] holds lane l's atoms
+// (at most npos of them; consumed); col0[l] is the 16-byte column of position 0 of lane l's part, so position
+// x of that lane lies in column (x + col0[l]) % 16 and its zero units (positions Jp .. Jp + 15) cover every
+// column.  out[l * npos + pos] receives the 21-bit atoms, padding included.  Greedy, position by position: the
+// lanes with the least room to wait choose first; a lane takes an atom whose entry column and x column are
+// both still free at this position, waits (takes a padding atom) if none is and it has room, and otherwise
+// takes the atom that collides least.  Deterministic.
+void order_quad(std::vector<HostAtom> (&lists)[16], const uint32_t (&col0)[16], const int (&pad_entry)[16], uint32_t npos,
+                uint32_t EB, uint32_t Jp, uint32_t *out) {
+    uint32_t rem[16];
+    for (int l = 0; l < 16; ++l) rem[l] = (uint32_t)lists[l].size();
+    for (uint32_t pos = 0; pos < npos; ++pos) {
+        uint8_t ue[16] = {0}, ux[16] = {0};
+        bool placed[16] = {false};
+        const uint32_t left = npos - pos;
+        int order[16];
+        for (int l = 0; l < 16; ++l) order[l] = l;
+        std::stable_sort(order, order + 16, [&](int a, int b) { return (left - rem[a]) < (left - rem[b]); });
+        for (int oi = 0; oi < 16; ++oi) {
+            const int l = order[oi];
+            if (rem[l] == 0) continue;
+            const uint32_t slack = left - rem[l];
+            int best = -1, best_score = 1 << 30;
+            for (uint32_t i = 0; i < rem[l]; ++i) {
+                const int sc = ue[lists[l][i].e & 15u] + ux[(lists[l][i].x + col0[l]) & 15u];
+                if (sc < best_score) {
+                    best_score = sc;
+                    best = (int)i;
+                    if (sc == 0) break;
+                }
             }
+            if (best_score > 0 && slack > 0) continue;   // wait: a padding atom goes here
+            const HostAtom a = lists[l][best];
+            lists[l][best] = lists[l][rem[l] - 1];
+            --rem[l];
+            ++ue[a.e & 15u];
+            ++ux[(a.x + col0[l]) & 15u];
+            out[l * npos + pos] = (uint32_t)a.e | ((uint32_t)a.x << EB);
+            placed[l] = true;
+        }
+        // padding atoms: the least used zero unit, and the least used entry column among those that have an
+        // entry which a code of this group really uses (pad_entry[c], -1 if none: a padding atom never reads an
+        // entry that no code points at)
+        for (int l = 0; l < 16; ++l) {
+            if (placed[l]) continue;
+            int ce = -1, cx = 0;
+            for (int c = 0; c < 16; ++c) {
+                if (pad_entry[c] >= 0 && (ce < 0 || ue[c] < ue[ce])) ce = c;
+                if (ux[c] < ux[cx]) cx = c;
+            }
+            ++ue[ce];
+            ++ux[cx];
+            const uint32_t zx = Jp + ((uint32_t)cx + 32u - ((Jp + col0[l]) & 15u)) % 16u;   // the zero unit in column cx
+            out[l * npos + pos] = (uint32_t)pad_entry[ce] | (zx << EB);
         }
     }
-    // the common shape of all workgroups (at least one block each: the kernel's wavefronts without work read it)
+}
+
+unsigned pack_threads() {
+    unsigned n = std::thread::hardware_concurrency();
+    if (n < 1) n = 1;
+    return n > 16 ? 16 : n;
+}
+
+template <class F>
+void parallel_for(uint32_t n, F f) {
+    const unsigned nt = std::min<unsigned>(pack_threads(), n);
+    if (nt <= 1) {
+        for (uint32_t i = 0; i < n; ++i) f(i);
+        return;
+    }
+    std::vector<std::thread> th;
+    for (unsigned t = 0; t < nt; ++t)
+        th.emplace_back([=]() {
+            for (uint32_t i = t; i < n; i += nt) f(i);
+        });
+    for (auto &t : th) t.join();
+}
+
+}  // namespace
+
+// One function builds everything; `out` == nullptr only measures.  Returns 0 when the matrix has no packed
+// form; *bad_code is set when that is because a code >= n_entries was found.
+static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pack_t *pack, bool *bad_code) {
+    PackPlan p;
+    if (bad_code) *bad_code = false;
+    if (!pack_plan(w, &p)) return 0;
+    const uint32_t J = (uint32_t)w->K / 8, N = (uint32_t)w->N;
+    const uint16_t *codes = reinterpret_cast<const uint16_t *>(w->codes);
+    const uint32_t nwg = p.S * p.RB, ng = p.G;
+    if ((uint32_t)w->n_entries < 65536u) {   // (with 2^16 entries every uint16 code is valid)
+        std::vector<int> bad(p.RB, 0);
+        parallel_for(p.RB, [&](uint32_t rb) {
+            const uint32_t r0 = rb * p.rows_per_block, r1 = std::min<uint64_t>(N, (uint64_t)r0 + p.rows_per_block);
+            for (uint32_t n = r0; n < r1; ++n)
+                for (uint32_t j = 0; j < J; ++j)
+                    if (codes[(size_t)n * J + j] >= (uint32_t)w->n_entries) bad[rb] = 1;
+        });
+        for (int b : bad)
+            if (b) {
+                if (bad_code) *bad_code = true;
+                return 0;
+            }
+    }
+
+    // pass 1: lengths of all tasks; per workgroup the tasks sorted by length (descending, ties by slot)
+    std::vector<uint32_t> cnt((size_t)nwg * p.tasks, 0);
+    parallel_for(p.RB, [&](uint32_t rb) {
+        const uint32_t r0 = rb * p.rows_per_block, r1 = std::min<uint64_t>(N, (uint64_t)r0 + p.rows_per_block);
+        for (uint32_t n = r0; n < r1; ++n) {
+            const uint16_t *row = codes + (size_t)n * J;
+            for (uint32_t j = 0; j < J; ++j) {
+                const uint32_t s = row[j] >> p.EB, part = j / p.Jp;
+                ++cnt[((size_t)s * p.RB + rb) * p.tasks + part * p.rows_per_block + (n - r0)];
+            }
+        }
+    });
+    std::vector<uint16_t> slots((size_t)nwg * ng * 64, 0xFFFF);
+    std::vector<uint32_t> steps((size_t)nwg * ng, 0);
+    parallel_for(nwg, [&](uint32_t wg) {
+        const uint32_t rb = wg % p.RB;
+        uint32_t rows_here = 0;
+        if ((uint64_t)rb * p.rows_per_block < N) rows_here = std::min<uint32_t>(p.rows_per_block, N - rb * p.rows_per_block);
+        const uint32_t *c = &cnt[(size_t)wg * p.tasks];
+        std::vector<uint32_t> order;
+        order.reserve(p.tasks);
+        for (uint32_t part = 0; part < p.P; ++part)
+            for (uint32_t r = 0; r < rows_here; ++r) order.push_back(part * p.rows_per_block + r);
+        std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return c[a] > c[b]; });
+        for (uint32_t g = 0; g < ng; ++g) {
+            const size_t first = (size_t)g * 64;
+            // a group's first task is its longest
+            steps[(size_t)wg * ng + g] = first < order.size() ? (c[order[first]] + kStepAtoms - 1) / kStepAtoms : 0;
+            for (uint32_t l = 0; l < 64; ++l)
+                if (first + l < order.size()) slots[((size_t)wg * ng + g) * 64 + l] = (uint16_t)order[first + l];
+        }
+    });
+    // the common address shape of all workgroups (at least one block each: wavefronts without work read it)
+    std::vector<uint32_t> max_steps(ng, 0), prefix(ng, 0);
+    uint64_t needed_blocks = 0;
+    for (uint32_t wg = 0; wg < nwg; ++wg)
+        for (uint32_t g = 0; g < ng; ++g) {
+            max_steps[g] = std::max(max_steps[g], steps[(size_t)wg * ng + g]);
+            needed_blocks += steps[(size_t)wg * ng + g];
+        }
     if (max_steps[0] == 0) max_steps[0] = 1;
     uint64_t pitch = 0;
-    std::vector<uint32_t> prefix(ng, 0);
     for (uint32_t g = 0; g < ng; ++g) {
         prefix[g] = (uint32_t)pitch;
         pitch += max_steps[g];
     }
-    // too uneven: more than a quarter more blocks than needed -- unless that is less than 1 MiB (small or
-    // ragged matrices, where a group of a few rows is as long as its longest row in the unluckiest workgroup)
-    const uint64_t padded = pitch * nwg;
     if (pitch > 65535) return 0;
-    if (padded > needed_blocks + needed_blocks / 4 + nwg && (padded - needed_blocks) * 768 > (1u << 20)) return 0;
-    const uint64_t atom_blocks = pitch * nwg;
-    const uint64_t rowid_off = 0;
-    const uint64_t atom_off = align256(rowid_off + rowids.size() * 2);
-    const uint64_t total = atom_off + (atom_blocks + kPackTailBlocks) * 768;
+    // too uneven: more than a quarter more blocks than needed -- unless that is less than 1 MiB (small or
+    // ragged matrices, where a group of a few tasks is as long as its longest task in the unluckiest workgroup)
+    const uint64_t padded = pitch * nwg;
+    if (padded > needed_blocks + needed_blocks / 4 + nwg && (padded - needed_blocks) * kStepBytes > (1u << 20)) return 0;
+
+    const uint64_t task_off = 0;
+    const uint64_t steps_off = align256(task_off + slots.size() * 2);
+    const uint64_t atom_off = align256(steps_off + steps.size() * 4);
+    const uint64_t total = atom_off + (padded + kPackTailBlocks) * kStepBytes;
     if (pack) {
+        std::memset(pack, 0, sizeof(*pack));
         pack->data = out;
         pack->bytes = total;
         pack->S = p.S;
         pack->RB = p.RB;
         pack->rows_per_block = p.rows_per_block;
+        pack->entry_bits = p.EB;
+        pack->parts = p.P;
+        pack->part_cols = p.Jp;
         pack->wg_pitch = (uint32_t)pitch;
-        pack->rowid_off = rowid_off;
+        pack->task_off = task_off;
+        pack->steps_off = steps_off;
         pack->atom_off = atom_off;
         for (uint32_t g = 0; g < VQ_PACK_MAX_GROUPS; ++g) pack->group_steps[g] = g < ng ? (uint16_t)max_steps[g] : (uint16_t)0;
     }
     if (!out) return total;
 
     std::memset(out, 0, (size_t)atom_off);
-    std::memcpy(out + rowid_off, rowids.data(), rowids.size() * 2);
-    unsigned char *atoms = out + atom_off;
-    // padding everywhere first: the zero unit (behind slice and x) as entry and as x_j
-    const uint32_t zero_unit = p.slice_entries + (uint32_t)J;
-    const uint32_t pad_atom = zero_unit | (zero_unit << kPackFieldBits);
-    for (uint64_t i = 0, n_atoms = (atom_blocks + kPackTailBlocks) * 256; i < n_atoms; ++i) {
-        atoms[3 * i] = (unsigned char)pad_atom;
-        atoms[3 * i + 1] = (unsigned char)(pad_atom >> 8);
-        atoms[3 * i + 2] = (unsigned char)(pad_atom >> 16);
+    std::memcpy(out + task_off, slots.data(), slots.size() * 2);
+    std::memcpy(out + steps_off, steps.data(), steps.size() * 4);
+    uint64_t *words = reinterpret_cast<uint64_t *>(out + atom_off);   // out is 16-byte aligned, atom_off 256
+    // padding everywhere first (blocks that no group uses: read by prefetches at most, never consumed)
+    {
+        const uint64_t pad = (uint64_t)p.Jp << p.EB;
+        const uint64_t pw = pad | (pad << kAtomBits) | (pad << (2 * kAtomBits));
+        const uint64_t n_words = (padded + kPackTailBlocks) * 64;
+        parallel_for(64, [&](uint32_t t) {
+            const uint64_t a = n_words * t / 64, b = n_words * (t + 1) / 64;
+            for (uint64_t i = a; i < b; ++i) words[i] = pw;
+        });
     }
-    // fill: lane l of group g walks row rowids[wg][g][l]; its k-th atom of slice s goes to step k/4, slot k%4
-    for (uint32_t wg = 0; wg < nwg; ++wg) {
-        uint32_t s = wg / p.RB, rb = wg % p.RB;
-        for (uint32_t g = 0; g < ng; ++g) {
-            const uint64_t first_block = (uint64_t)wg * pitch + prefix[g];
-            for (uint32_t l = 0; l < 64; ++l) {
-                uint16_t ri = rowids[((size_t)wg * ng + g) * 64 + l];
-                if (ri == 0xFFFF) continue;
-                const uint16_t *row = codes + ((size_t)rb * p.rows_per_block + ri) * J;
-                uint32_t k = 0;
-                for (int j = 0; j < J; ++j) {
-                    if ((uint32_t)(row[j] >> lb) != s) continue;
-                    uint32_t atom = (row[j] & ((1u << lb) - 1)) | ((p.slice_entries + (uint32_t)j) << kPackFieldBits);
-                    unsigned char *q = atoms + (first_block + k / 4) * 768 + l * 12 + (k % 4) * 3;
-                    q[0] = (unsigned char)atom;
-                    q[1] = (unsigned char)(atom >> 8);
-                    q[2] = (unsigned char)(atom >> 16);
-                    ++k;
+    // pass 2: per row block the atoms of every (slice, task), then per workgroup and 16 lanes their order
+    parallel_for(p.RB, [&](uint32_t rb) {
+        const uint32_t r0 = rb * p.rows_per_block, r1 = std::min<uint64_t>(N, (uint64_t)r0 + p.rows_per_block);
+        std::vector<std::vector<HostAtom>> lists((size_t)p.S * p.tasks);
+        for (uint32_t s = 0; s < p.S; ++s)
+            for (uint32_t t = 0; t < p.tasks; ++t)
+                lists[(size_t)s * p.tasks + t].reserve(cnt[((size_t)s * p.RB + rb) * p.tasks + t]);
+        for (uint32_t n = r0; n < r1; ++n) {
+            const uint16_t *row = codes + (size_t)n * J;
+            for (uint32_t j = 0; j < J; ++j) {
+                const uint32_t s = row[j] >> p.EB, part = j / p.Jp;
+                lists[(size_t)s * p.tasks + part * p.rows_per_block + (n - r0)].push_back(
+                    HostAtom{(uint16_t)(row[j] & (p.slice_entries - 1)), (uint16_t)(j - part * p.Jp)});
+            }
+        }
+        std::vector<uint32_t> ordered;
+        for (uint32_t s = 0; s < p.S; ++s) {
+            const uint32_t wg = s * p.RB + rb;
+            for (uint32_t g = 0; g < ng; ++g) {
+                const uint32_t st = steps[(size_t)wg * ng + g], npos = st * kStepAtoms;
+                if (st == 0) continue;
+                const uint64_t first_block = (uint64_t)wg * pitch + prefix[g];
+                ordered.assign((size_t)16 * npos, 0);
+                // one really used entry per 16-byte column, for the padding atoms (the group's first task has an
+                // atom, or the group would have no steps)
+                int pad_entry[16];
+                for (int c = 0; c < 16; ++c) pad_entry[c] = -1;
+                for (uint32_t l = 0; l < 64; ++l) {
+                    const uint16_t slot = slots[((size_t)wg * ng + g) * 64 + l];
+                    if (slot == 0xFFFF) continue;
+                    for (const HostAtom &a : lists[(size_t)s * p.tasks + slot])
+                        if (pad_entry[a.e & 15u] < 0) pad_entry[a.e & 15u] = a.e;
+                }
+                for (uint32_t q = 0; q < 4; ++q) {
+                    std::vector<HostAtom> quad[16];
+                    uint32_t col0[16];
+                    for (uint32_t l = 0; l < 16; ++l) {
+                        const uint16_t slot = slots[((size_t)wg * ng + g) * 64 + q * 16 + l];
+                        const uint32_t part = slot == 0xFFFF ? 0 : slot / p.rows_per_block;
+                        if (slot != 0xFFFF) quad[l].swap(lists[(size_t)s * p.tasks + slot]);
+                        // unit of position 0 of the part: slice_entries + part * (Jp + 16); slices are multiples of 16 units
+                        col0[l] = (part * (p.Jp + kZeroUnits)) & 15u;
+                    }
+                    order_quad(quad, col0, pad_entry, npos, p.EB, p.Jp, ordered.data());
+                    for (uint32_t l = 0; l < 16; ++l) {
+                        const uint32_t lane = q * 16 + l;
+                        for (uint32_t t = 0; t < st; ++t) {
+                            const uint64_t a0 = ordered[l * npos + 3 * t], a1 = ordered[l * npos + 3 * t + 1],
+                                           a2 = ordered[l * npos + 3 * t + 2];
+                            words[(first_block + t) * 64 + lane] = a0 | (a1 << kAtomBits) | (a2 << (2 * kAtomBits));
+                        }
+                    }
                 }
             }
         }
-    }
+    });
     return total;
 }
 
@@ -199,12 +380,15 @@ struct PackedCore {
     const unsigned char *data;
     const half_t *cb, *x;
     float *partial;       // [S][N]
-    int N, J, S, RB, rows_per_block, slice_entries;
-    unsigned long long rowid_off, atom_off;
-    unsigned wg_pitch;    // group g of workgroup wg: atom blocks from wg * wg_pitch + prefix[g] on
+    int N, J, S, RB, rows_per_block;
+    int EB;               // entry bits of an atom; slices of 2^EB entries
+    int P, Jp;            // parts of a row, positions per part
+    int n_groups;         // groups (of 64 tasks) per workgroup
     int nwaves;           // wavefronts per workgroup of the launch (saves a load of the hidden launch arguments)
+    unsigned wg_pitch;    // group g of workgroup wg: atom blocks from wg * wg_pitch + prefix[g] on
+    unsigned long long task_off, steps_off, atom_off;
 };
-// ... and the rest: one 32-bit word per group, prefix << 16 | steps, so that a scalar load can fetch it
+// ... and the rest: one 32-bit word per group, prefix << 16 | common steps, so that a scalar load can fetch it
 struct PackedArgs : PackedCore {
     const half_t *scale;
     half_t *y;
@@ -219,24 +403,16 @@ __device__ __forceinline__ void pin_scalar(T &v) {
     asm volatile("" : "+s"(v));
 }
 
-constexpr int kPackMaxSlices = 64;  // 2^16 entries / 1024 per slice
-// Steps in flight per wavefront: a ring of 3 (9 registers), 2 of them requested before the barrier.  More
-// steps requested ahead do not arrive sooner -- a CU's share of the memory system is ~20 KB per microsecond,
-// and what is requested ahead of another wavefront's slice transfer delays that transfer and with it the
-// barrier (measured on 4096 x 11008: 12 steps ahead, barrier 2.6 us after the loads were issued, 9.8 us in
-// all; 4 steps, 1.5 us and 8.8 us).  Llama-7B stack, (ahead, ring): (2,2) 1206, (2,3) 1217, (2,4) 1214,
-// (1,3) 1211, (2,5) 1204 GB/s; nothing ahead of the barrier 1150 - 1166.
-constexpr int kPackRing = 3;
-constexpr int kPackAhead = 2;   // of these, requested before the barrier
-
-struct Acc4 {
-    float a0, a1, a2, a3;
-};
+constexpr int kPackMaxSlices = 32;  // 2^16 entries / 2048 per slice
+// Steps in flight per wavefront (8 bytes per lane each), and how many of them are requested before the barrier.
+// More requested ahead does not arrive sooner: what is requested ahead of another wavefront's slice transfer
+// delays that transfer and with it the barrier.
+constexpr int kPackAhead = 2;
 
 // 16 bytes at an absolute LDS address.  The kernels below have no static LDS, so the dynamic region (the
 // image the atoms index) starts at address 0 and a unit number is an address after one shift; going through
 // a pointer into the region would cost one more add per gather for a base the compiler cannot see is 0.
-// (A test compiles this file and checks that these kernels have no static LDS.)
+// (A test compiles this file and checks that these kernels have no static LDS; the launcher checks it too.)
 __device__ __forceinline__ V16 lds_unit(uint32_t byte_address) {
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
     const u32x4_t v = *(const __attribute__((address_space(3))) u32x4_t *)(uintptr_t)byte_address;
@@ -252,69 +428,181 @@ __device__ __forceinline__ float atom_fma(const V16 &e, const V16 &xv, float acc
     return dot2(e.h2[3], xv.h2[3], acc);
 }
 
-// One step = the lane's next four atoms (three dwords).  The LDS gathers (entry and x_j of each atom)
-// of CL atoms are issued before the first dot product: taken one atom at a time, as the compiler orders
-// them when left alone, every atom waits out a full LDS round trip (~90 clocks per gather with eight
-// wavefronts asking) and the gather phase of a 4096 x 4096 launch lasts 3.1 us.  CL = 4 keeps 32
-// registers of operands in flight, CL = 2 half of that (for the kernels held to 128 registers).
-template <int CL>
-__device__ __forceinline__ void step_dot(uint32_t d0, uint32_t d1, uint32_t d2, Acc4 &acc) {
-    // the 24 bits of atom k start at bit 24 k of the 96-bit string d2:d1:d0
-    const uint32_t at[4] = {d0, __builtin_amdgcn_alignbit(d1, d0, 24), __builtin_amdgcn_alignbit(d2, d1, 16), d2 >> 8};
-    float *accs[4] = {&acc.a0, &acc.a1, &acc.a2, &acc.a3};
+struct Acc3 {
+    float a[3];
+};
+// What turns an atom into its two LDS addresses: (atom & emask) << 4 and ((atom >> EB) & xmask) << 4 + xbase.
+struct AtomDecode {
+    uint32_t emask4;   // ((1 << EB) - 1) << 4
+    uint32_t eb, xb;   // field widths
+    uint32_t xbase;    // byte address of position 0 of this lane's part
+};
+
+// NST steps at once (one or two): the 6 NST gathers (entry and x_j of every atom) are issued before the
+// first dot product -- taken one atom at a time, as the compiler orders them when left alone, every atom
+// waits out a full LDS round trip.  Atom k of a step always adds into accumulator k, so two steps taken
+// together give the same sums as taken one after the other.
+template <int NST>
+__device__ __forceinline__ void steps_dot(const uint32_t (&lo)[NST], const uint32_t (&hi)[NST], const AtomDecode &d, Acc3 &acc) {
+    uint32_t at[3 * NST];
 #pragma unroll
-    for (int h = 0; h < 4; h += CL) {
-        V16 e[CL], xv[CL];
-#pragma unroll
-        for (int i = 0; i < CL; ++i) {
-            e[i] = lds_unit((at[h + i] << 4) & 0xfff0u);
-            xv[i] = lds_unit((at[h + i] >> (kPackFieldBits - 4)) & 0xfff0u);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * CL, 0);  // these LDS reads first,
-        __builtin_amdgcn_sched_group_barrier(0x002, 4 * CL, 0);  // then the arithmetic on them
-#pragma unroll
-        for (int i = 0; i < CL; ++i) *accs[h + i] = atom_fma(e[i], xv[i], *accs[h + i]);
+    for (int s = 0; s < NST; ++s) {
+        at[3 * s] = lo[s];
+        at[3 * s + 1] = __builtin_amdgcn_alignbit(hi[s], lo[s], kAtomBits);
+        at[3 * s + 2] = hi[s] >> (2 * kAtomBits - 32);
     }
+    V16 e[3 * NST], xv[3 * NST];
+#pragma unroll
+    for (int i = 0; i < 3 * NST; ++i) {
+        e[i] = lds_unit((at[i] << 4) & d.emask4);
+        xv[i] = lds_unit((__builtin_amdgcn_ubfe(at[i], d.eb, d.xb) << 4) + d.xbase);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 6 * NST, 0);   // these LDS reads first,
+    __builtin_amdgcn_sched_group_barrier(0x002, 12 * NST, 0);  // then the arithmetic on them
+#pragma unroll
+    for (int i = 0; i < 3 * NST; ++i) acc.a[i % 3] = atom_fma(e[i], xv[i], acc.a[i % 3]);
 }
 
-// Two steps at once: the sixteen gathers of both are issued before the first dot product (a launch with one
-// 8-wavefront workgroup per CU has too few gathers in flight to fill the LDS pipeline otherwise).  The dot
-// products run in the order of two single steps, so the sums are the same bit for bit.
-__device__ __forceinline__ void step_dot_pair(const uint32_t (&da)[3], const uint32_t (&db)[3], Acc4 &acc) {
-    const uint32_t at[8] = {da[0], __builtin_amdgcn_alignbit(da[1], da[0], 24), __builtin_amdgcn_alignbit(da[2], da[1], 16), da[2] >> 8,
-                            db[0], __builtin_amdgcn_alignbit(db[1], db[0], 24), __builtin_amdgcn_alignbit(db[2], db[1], 16), db[2] >> 8};
-    float *accs[4] = {&acc.a0, &acc.a1, &acc.a2, &acc.a3};
-    V16 e[8], xv[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        e[i] = lds_unit((at[i] << 4) & 0xfff0u);
-        xv[i] = lds_unit((at[i] >> (kPackFieldBits - 4)) & 0xfff0u);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
-    __builtin_amdgcn_sched_group_barrier(0x002, 32, 0);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) *accs[i & 3] = atom_fma(e[i], xv[i], *accs[i & 3]);
+// Direct global -> LDS transfers (no registers).  M0 is written and used inside one asm statement only; it is a
+// reserved register that the compiler neither allocates nor accepts in a clobber list, and nothing else in
+// these kernels uses it.
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+// 64 lanes x 16 bytes -> dst_wave_base + 16 lane
+__device__ __forceinline__ void dma_1k(const uint4 *src_lane, unsigned char *dst_wave_base) {
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t *)dst_wave_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src_lane) : "memory");
+}
+// a contiguous 4 KiB: four such transfers 1 KiB apart in both address spaces, one M0 write
+__device__ __forceinline__ void dma_4k(const uint4 *src_lane, unsigned char *dst_wave_base) {
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t *)dst_wave_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %1, off\n\t"
+                 "global_load_lds_dwordx4 %1, off offset:1024\n\t"
+                 "global_load_lds_dwordx4 %1, off offset:2048\n\t"
+                 "global_load_lds_dwordx4 %1, off offset:3072" ::"s"(m0), "v"(src_lane) : "memory");
 }
 
-// All global loads of a workgroup are issued before anything waits: the kernel is a chain of
-// memory latencies (tables -> atoms -> partials), not a bandwidth problem, at these sizes.
-template <int PF, int CL, bool PAIR, int AHEAD = kPackAhead>
-__device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int bid) {
+// ---- the global reduction of the PREVIOUS launch, done in the prologue and epilogue of this one -------------
+// A launch leaves S partial sums per row; adding them needs every workgroup of that launch to have finished,
+// i.e. a kernel boundary.  When several products follow each other on a stream (vq_gemv_sequence), the next
+// launch is that boundary: each of its workgroups takes a share of the pending rows, requests their partial
+// sums straight into LDS at its very start (no registers; the requests travel with the slice transfers) and
+// adds them up in slice order after its own work, so the reduction costs no launch of its own.  The last
+// launch of a sequence is followed by the plain reduction kernel.  The pending rows are handed out in blocks
+// of 64 (one wavefront each), at most kFinChunks per workgroup.
+constexpr int kPackMaxBatch = 4;
+constexpr int kFinChunks = 2;        // a workgroup takes at most this many blocks of 64 pending rows
+constexpr int kFinChunkBytes = 8192; // LDS per block: 32 slices x 64 rows x 4 bytes
+// Layout of the partial sums of one problem: blocks of 64 rows, [block][slice][row % 64] -- the S x 64 sums of
+// a block are contiguous, so the next launch fetches them with a few wide transfers.  (The workspace is 4 KiB
+// longer than the sums: a block is fetched in units of 4 KiB, whatever S is.)
+__host__ __device__ __forceinline__ size_t partial_index(int S, int s, int n) {
+    return ((size_t)(n >> 6) * S + s) * 64 + (n & 63);
+}
+// The epilogue y = fp16(scale * sum): the fp32 product is rounded to fp32 first and to fp16 (nearest even)
+// second, in every kernel that finishes a row.  The empty asm statement keeps the compiler from merging the
+// multiplication into a mixed-precision instruction that rounds only once in one kernel and not in another:
+// the reduction folded into a following launch must give the bits of the reduction kernel.
+__device__ __forceinline__ half_t scaled_output(float sum, float sc) {
+    float prod = sum * sc;
+    asm volatile("" : "+v"(prod));
+    return (half_t)prod;
+}
+struct FinalizeArgs {
+    const float *partial;   // blocked, see partial_index
+    const half_t *scale;    // [N] or null
+    half_t *y;              // [N]
+    int N, S;
+};
+struct PendingArgs {
+    FinalizeArgs a[kPackMaxBatch];
+    int first_block[kPackMaxBatch];   // where problem i starts in the list of blocks (INT_MAX past the last problem)
+    int count;            // pending problems (0: nothing to do)
+    int blocks_total;     // sum of their ceil(N / 64): the blocks form one list, problem after problem
+    int blocks_per_wg;    // ceil(blocks_total / workgroups of this launch) <= kFinChunks
+};
+// What a kernel needs of PendingArgs before its first load leaves (fetched with the other launch arguments).
+struct PendingHead {
+    int first_block[kPackMaxBatch];
+    int count, blocks_total, blocks_per_wg;
+};
+struct FinBlock {        // what a reducing wavefront keeps between the two halves
+    FinalizeArgs a;      // the problem of its block (wave-uniform)
+    int row;             // this lane's row (may lie past the problem's last row)
+};
+
+// Requests the partial sums of block `bid` of the concatenated list: S x 64 floats, contiguous, into fin (LDS).
+// Returns where this lane finds its scale (some readable address if the problem has none): the caller loads it
+// outside of any condition -- a value loaded under a condition would be waited for on the spot, in front of
+// this wavefront's own atom requests.
+__device__ __forceinline__ const uint16_t *fin_issue(const PendingArgs &pd, const PendingHead &ph, int bid, unsigned char *fin,
+                                                     int lane, FinBlock &f) {
+    int q = 0;
+#pragma unroll
+    for (int i = 1; i < kPackMaxBatch; ++i) q += bid >= ph.first_block[i] ? 1 : 0;
+    int base = ph.first_block[0];
+#pragma unroll
+    for (int i = 1; i < kPackMaxBatch; ++i) base = q == i ? ph.first_block[i] : base;
+    f.a = pd.a[q];   // (q is wave-uniform: one scalar load of the 32-byte struct)
+    pin_scalar(f.a.partial); pin_scalar(f.a.scale); pin_scalar(f.a.y); pin_scalar(f.a.N); pin_scalar(f.a.S);
+    const int blk = bid - base;
+    f.row = blk * 64 + lane;
+    const uint4 *src = reinterpret_cast<const uint4 *>(f.a.partial + (size_t)blk * f.a.S * 64) + lane;
+    dma_4k(src, fin);                                    // slices 0 .. 15
+    if (f.a.S > 16) dma_4k(src + 256, fin + 4096);       // slices 16 .. 31
+    return f.a.scale ? reinterpret_cast<const uint16_t *>(f.a.scale) + min(f.row, f.a.N - 1)
+                     : reinterpret_cast<const uint16_t *>(f.a.partial);
+}
+
+// y[n] = scale[n] * sum_s partial[s][n], slices ascending: the same additions as the reduction kernel.
+__device__ __forceinline__ void fin_complete(const FinBlock &f, uint32_t scale_bits, const float *fin, int lane) {
+    const FinalizeArgs &a = f.a;
+    float v[kPackMaxSlices];
+#pragma unroll
+    for (int k = 0; k < kPackMaxSlices; ++k) v[k] = fin[k * 64 + lane];   // (all 32 rows of the LDS block exist)
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPackMaxSlices; ++k) sum += k < a.S ? v[k] : 0.f;
+    union { uint16_t u; half_t h; } sb;
+    sb.u = (uint16_t)scale_bits;
+    const float sc = a.scale ? (float)sb.h : 1.f;
+    if (f.row < a.N) ((__attribute__((address_space(1))) half_t *)a.y)[f.row] = scaled_output(sum, sc);
+}
+
+// All global loads of a workgroup are issued before anything waits: at these sizes a launch is a chain of
+// memory latencies (slice -> atoms -> partials) as much as a bandwidth problem.
+// PF: steps in the ring (taken two at a time when PAIR); AHEAD of them requested before the barrier.
+// wg_linear / n_wg: this workgroup's number among all workgroups of the launch (for its share of the pending rows).
+template <int PF, bool PAIR, int AHEAD = kPackAhead>
+__device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int bid, const PendingArgs &pd, const int wg_linear) {
     extern __shared__ __align__(16) unsigned char smem[];
+    static_assert(!PAIR || PF % 2 == 0, "steps are taken two at a time");
+    static_assert(AHEAD <= PF, "the ring holds what is requested ahead");
     // all launch arguments in one round of scalar loads
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: group lookups, block numbers and
                                                                          // addresses derived from it stay scalar
-    uint32_t group_word = ka.group[wave];
     PackedCore a = ka;
     pin_scalar(a.data); pin_scalar(a.cb); pin_scalar(a.x); pin_scalar(a.partial);
     pin_scalar(a.N); pin_scalar(a.J); pin_scalar(a.S); pin_scalar(a.RB); pin_scalar(a.rows_per_block);
-    pin_scalar(a.slice_entries); pin_scalar(a.rowid_off); pin_scalar(a.atom_off); pin_scalar(a.wg_pitch);
-    pin_scalar(a.nwaves); pin_scalar(group_word);
-    // the LDS image the atoms index, in 16-byte units: [slice][x][one zero unit]; then one float per row of the block
-    unsigned char *slice = smem;
-    unsigned char *xl = smem + (size_t)a.slice_entries * 16;
-    unsigned char *zero_unit = xl + (size_t)a.J * 16;
-    float *accbuf = reinterpret_cast<float *>(zero_unit + 16);
+    pin_scalar(a.EB); pin_scalar(a.P); pin_scalar(a.Jp); pin_scalar(a.n_groups); pin_scalar(a.nwaves);
+    pin_scalar(a.wg_pitch); pin_scalar(a.task_off); pin_scalar(a.steps_off); pin_scalar(a.atom_off);
+    PendingHead ph;
+#pragma unroll
+    for (int i = 0; i < kPackMaxBatch; ++i) {
+        ph.first_block[i] = pd.first_block[i];
+        pin_scalar(ph.first_block[i]);
+    }
+    ph.count = pd.count; ph.blocks_total = pd.blocks_total; ph.blocks_per_wg = pd.blocks_per_wg;
+    pin_scalar(ph.count); pin_scalar(ph.blocks_total); pin_scalar(ph.blocks_per_wg);
+    const int my_group = min(wave, a.n_groups - 1);   // a wavefront without a group repeats the last one's loads
+    uint32_t group_word = ka.group[my_group];
+    pin_scalar(group_word);
+    // the LDS image the atoms index: [slice][parts of x, 16 zero units behind each]; then one float per task
+    const uint32_t slice_entries = 1u << a.EB, slice_bytes = slice_entries * 16u;
+    const uint32_t part_pitch = ((uint32_t)a.Jp + kZeroUnits) * 16u;   // bytes
+    unsigned char *xl = smem + slice_bytes;
+    float *accbuf = reinterpret_cast<float *>(xl + (size_t)a.P * part_pitch);
+    unsigned char *fin = reinterpret_cast<unsigned char *>(accbuf + (size_t)a.rows_per_block * a.P);   // [kFinChunks][32][64] floats, only with pending rows
 
     const int tid = threadIdx.x, lane = tid & 63, nwaves = a.nwaves;
     // Workgroups are dealt round-robin to the 8 compute dies, each with its own L2.  All row blocks of
@@ -334,161 +622,231 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     typedef const __attribute__((address_space(1))) unsigned char gbyte_t;
     typedef const __attribute__((address_space(1))) uint16_t gu16_t;
     typedef const __attribute__((address_space(1))) uint32_t gu32_t;
+    typedef const __attribute__((address_space(4))) uint32_t cu32_t;   // read with scalar loads
     gbyte_t *gdata = (gbyte_t *)a.data;
-    gu16_t *rowids = (gu16_t *)(gdata + a.rowid_off);
+    gu16_t *tasks = (gu16_t *)(gdata + a.task_off) + (size_t)wg * a.n_groups * 64;
+    cu32_t *own_steps = (cu32_t *)(a.data + a.steps_off) + (size_t)wg * a.n_groups;
+    gu32_t *own_steps_v = (gu32_t *)(gdata + a.steps_off) + (size_t)wg * a.n_groups;
     // atom block b of this lane: a scalar base (block numbers are wave-uniform) plus a 32-bit lane offset
-    gbyte_t *atoms = gdata + a.atom_off;
-    const uint32_t lane_off = (uint32_t)lane * 12u;
+    gbyte_t *atoms = gdata + a.atom_off + (size_t)wg * a.wg_pitch * kStepBytes;
+    const uint32_t lane_off = (uint32_t)lane * 8u;
 
-    // (1) codebook slice and x go straight from global memory into LDS (no registers): one
-    //     wave-wide 1 KiB transfer per 64 entries, lane l's 16 bytes land at base + 16 l.  Written as an
-    //     asm statement: with the builtin the compiler knows that LDS is being written behind its back and
-    //     makes the first LDS read wait for every outstanding load, the atoms included, which puts the whole
-    //     memory phase of a launch in front of its whole gather phase.  The transfers complete in issue order
-    //     with the other loads, and the counted wait below is what orders them against the gathers.
+    // (1) codebook slice and x go straight from global memory into LDS (no registers): wave-wide 1 KiB
+    //     transfers, lane l's 16 bytes land at base + 16 l.  Written as asm statements: with the builtin the
+    //     compiler knows that LDS is being written behind its back and makes the first LDS read wait for every
+    //     outstanding load, the atoms included, which puts the whole memory phase of a launch in front of its
+    //     whole gather phase.  The transfers complete in issue order with the other loads, and the counted
+    //     wait below is what orders them against the gathers.
+    //     The LDS base of a transfer comes from M0, and writing M0 while transfers are in flight stalls the
+    //     wavefront (measured: four transfers with four M0 writes take 260 - 300 ns to issue, against 50 ns with
+    //     one).  The instruction's immediate offset moves the global address and the LDS address alike, so a
+    //     contiguous 4 KiB goes out as one M0 write and four transfers.
     {
-        typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
-        auto dma16 = [](const uint4 *src, unsigned char *dst_wave_base) {
-            const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t *)dst_wave_base);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src) : "memory");  // (M0 is written and used inside the statement; nothing else in this kernel uses it)
-        };
-        const uint4 *src = reinterpret_cast<const uint4 *>(a.cb) + (size_t)s * a.slice_entries;
+        const uint4 *src = reinterpret_cast<const uint4 *>(a.cb) + (size_t)s * slice_entries;
         const uint4 *xs = reinterpret_cast<const uint4 *>(a.x);
-        for (int c = wave; c * 64 < a.slice_entries; c += nwaves)  // slices are multiples of 64 entries
-            dma16(src + c * 64 + lane, slice + c * 1024);
-        for (int c = wave; c * 64 < a.J; c += nwaves)
-            if (c * 64 + lane < a.J) dma16(xs + c * 64 + lane, xl + c * 1024);
-        if (tid < 4) reinterpret_cast<uint32_t *>(zero_unit)[tid] = 0u;  // what padding atoms point at
+        const int slice_chunks = (int)(slice_bytes >> 12);          // slices are multiples of 256 entries
+        for (int c = wave; c < slice_chunks; c += nwaves) dma_4k(src + c * 256 + lane, smem + c * 4096);
+        int turn = slice_chunks;   // whose turn the next chunk is: chunks are dealt to the wavefronts in turn
+        for (int p = 0; p < a.P; ++p) {
+            const int len = min(a.Jp, a.J - p * a.Jp);   // positions of this part
+            const uint4 *xp = xs + p * a.Jp;
+            unsigned char *dst = xl + (size_t)p * part_pitch;
+            const int full = len >> 8;                   // whole 4 KiB chunks
+            for (int c = 0; c < full; ++c, ++turn)
+                if (turn % nwaves == wave) dma_4k(xp + c * 256 + lane, dst + c * 4096);
+            if ((len & 255) && turn % nwaves == wave)    // the rest of the part: up to three transfers, the last one partly masked
+                for (int t = full * 4; t * 64 < len; ++t)
+                    if (t * 64 + lane < len) dma_1k(xp + t * 64 + lane, dst + t * 1024);
+            turn += (len & 255) ? 1 : 0;
+        }
+        // what padding atoms point at: 16 zero units (64 dwords) behind every part
+        for (int i = tid; i < a.P * 64; i += nwaves * 64)
+            reinterpret_cast<uint32_t *>(xl + (size_t)(i >> 6) * part_pitch + (size_t)a.Jp * 16)[i & 63] = 0u;
     }
     // (2) this wavefront's first group: where its atoms lie follows from the launch arguments alone, so
-    //     the row ids and the atoms are requested right behind the slice.  Loads complete in the order
+    //     the task slots and the atoms are requested right behind the slice.  Loads complete in the order
     //     they were issued, so the wait below counts the loads of this step as still in flight and lets
-    //     the gathers start as soon as the slice and x are in, while the atoms stream in behind them
-    //     (waiting for everything put the whole memory phase of a launch in front of its whole LDS
-    //     phase).  The empty statement keeps the compiler from moving a load above the staging transfers.
+    //     the gathers start as soon as the slice and x are in, while the atoms stream in behind them.
+    //     The empty statement keeps the compiler from moving a load above the staging transfers.
     asm volatile("" ::: "memory");
-    const uint32_t n_groups = (uint32_t)(a.rows_per_block + 63) / 64, first_group = (uint32_t)wg * n_groups;
-    auto group_of = [&](uint32_t word) { return make_uint2((uint32_t)wg * a.wg_pitch + (word >> 16), word & 0xffffu); };
     // Step st of the group whose first block this lane sees at `base`.  No look at the group's length: a
     // branch around a load keeps the compiler from counting which loads are in flight (it then waits for
     // all of them before every use), and a clamp costs more instructions than the load.  Blocks past the
     // end of a group belong to the next one, or to the tail of the buffer, and are never used.
     static_assert(2 * PF - 2 <= kPackTailBlocks, "reads run up to 2 PF - 2 blocks past the end of a group");
-    auto load_step = [&](uint32_t (&dst)[3], gbyte_t *base, uint32_t st) {
-        gu32_t *p = (gu32_t *)(base + (size_t)st * 768);
-        dst[0] = p[0]; dst[1] = p[1]; dst[2] = p[2];
+    auto load_step = [&](uint32_t (&dst)[2], gbyte_t *base, uint32_t st) {
+        gu32_t *p = (gu32_t *)(base + (size_t)st * kStepBytes);
+        dst[0] = p[0]; dst[1] = p[1];
     };
-    auto lane_base = [&](uint32_t first_block) { return atoms + (size_t)first_block * 768 + lane_off; };
-    // Every wavefront issues the same kPackAhead + 1 loads, so the count in the wait holds for all of them: one
-    // without a group reads the row ids of the last group and the first blocks of the workgroup and uses
-    // neither.
-    const bool has_group = (uint32_t)wave < n_groups;
-    uint2 gr = make_uint2((uint32_t)wg * a.wg_pitch, 0);  // .x first atom block, .y steps
-    if (has_group) gr = group_of(group_word);
-    uint32_t ri = rowids[((size_t)first_group + min((uint32_t)wave, n_groups - 1)) * 64 + lane];
-    uint32_t q[PF][3];  // the ring: the atoms of the next PF steps
-    gbyte_t *gbase = lane_base(gr.x);
+    auto group_base = [&](uint32_t word) { return atoms + (size_t)(word >> 16) * kStepBytes + lane_off; };
+    // Every wavefront issues the same AHEAD + 1 loads, so the count in the wait holds for all of them.
+    const bool has_group = wave < a.n_groups;
+    // this workgroup's trip count for the group: needed only behind the barrier.  A vector load (of one address),
+    // older than the loads the wait counts: a scalar load here would be waited for by the next use of any
+    // other scalar load's result, i.e. long before the barrier.
+    uint32_t steps_idx = (uint32_t)my_group;
+    asm volatile("" : "+v"(steps_idx));
+    const uint32_t my_steps_v = own_steps_v[steps_idx];
+    uint32_t slot = tasks[(size_t)my_group * 64 + lane];
+    uint32_t q[PF][2];  // the ring: the step words of the next PF steps
+    gbyte_t *gbase = group_base(group_word);
 #pragma unroll
     for (int st = 0; st < AHEAD; ++st) load_step(q[st], gbase, st);
-    // kPackAhead atom loads and the row ids were issued behind the staging transfers: when at most that many
-    // loads are pending, the transfers have landed.  (A test compiles this file and counts those loads in each build.)
-    // (lgkmcnt: the store of the zero unit)
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(AHEAD + 1) : "memory");
+    // (2b) the pending rows of the previous launch: the last wavefronts (the shortest groups) take a block of 64
+    //      each.  Requested behind everything this workgroup's barrier depends on, and not waited for there: the
+    //      sums are needed at the very end only (the wavefront's own first look at its atoms does wait for them,
+    //      which its short group can afford).
+    FinBlock fl;
+    const int fin_chunk = nwaves - 1 - wave;
+    const int fin_bid = wg_linear * ph.blocks_per_wg + fin_chunk;
+    const bool fin_mine = ph.count > 0 && fin_chunk < ph.blocks_per_wg && fin_bid < ph.blocks_total;   // wave-uniform
+    const uint16_t *scale_at = reinterpret_cast<const uint16_t *>(a.data);   // (any readable address)
+    if (fin_mine) scale_at = fin_issue(pd, ph, fin_bid, fin + (size_t)fin_chunk * kFinChunkBytes, lane, fl);
+    const uint32_t fin_scale_bits = *(const __attribute__((address_space(1))) uint16_t *)scale_at;   // every wavefront: no condition
+    // AHEAD atom loads and the task slots were issued behind the staging transfers, and behind those the scale
+    // and (fin_mine) the four or eight transfers of the pending block: when at most that many loads are pending,
+    // the staging transfers have landed.  (A test compiles this file and counts those loads in each build.)
+    // (lgkmcnt: the stores of the zero units)
+    if (!fin_mine)
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(AHEAD + 2) : "memory");
+    else if (fl.a.S <= 16)
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(AHEAD + 2 + 4) : "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(AHEAD + 2 + 8) : "memory");
     // (3) the slice and x of this wavefront have landed (direct-to-LDS transfers count as vector memory
     //     loads); after the barrier those of all wavefronts are visible.  A bare s_barrier: __syncthreads()
     //     would wait for the atoms as well.
     asm volatile("s_barrier" ::: "memory");
 #pragma unroll
     for (int st = AHEAD; st < PF; ++st) load_step(q[st], gbase, st);  // the rest of the ring
+    const uint32_t my_steps = __builtin_amdgcn_readfirstlane(my_steps_v);
 
-    // (4) gathers and dot products: lane = row; results go to LDS in natural row order.  The ring already
-    //     holds the group's first PF steps.
-    auto run_group = [&](const uint2 gr, const uint32_t ri, gbyte_t *gbase) {
-        Acc4 acc = {0.f, 0.f, 0.f, 0.f};
+    AtomDecode dec;
+    dec.emask4 = (slice_entries - 1u) << 4;
+    dec.eb = (uint32_t)a.EB;
+    dec.xb = (uint32_t)(kAtomBits - a.EB);
+    // (4) gathers and dot products: lane = task; results go to LDS by slot.  The ring already holds the
+    //     group's first PF steps.
+    auto run_group = [&](const uint32_t n_steps, const uint32_t slot, gbyte_t *gbase) {
+        // position 0 of the lane's part: its part is how many multiples of rows_per_block fit under the slot
+        uint32_t part = 0;
+        for (int p = 1; p < a.P; ++p) part += (slot != 0xFFFFu && slot >= (uint32_t)(p * a.rows_per_block)) ? 1u : 0u;
+        dec.xbase = slice_bytes + part * part_pitch;
+        Acc3 acc = {{0.f, 0.f, 0.f}};
         // slot k is refilled with step st + PF as soon as step st has been taken out of it -- except in the
-        // group's last round: what would be requested there lies past the end of the group (with a refill in
-        // every round a group of 5 steps read 9 blocks; the blocks read in vain are the next group's, but
-        // they cross the memory system once more all the same).  Measured on the Llama-7B stack: 1163 -> 1214
-        // GB/s; refilling exactly up to the group's end (one copy of the round before the last per number of
-        // refills) was slower again, 1154 - 1181.
+        // group's last round: what would be requested there lies past the end of the group.
         auto ring_round = [&](uint32_t base, auto refill_tag) {
             if constexpr (PAIR) {
-                static_assert(!PAIR || PF % 2 == 0, "steps are taken two at a time");
 #pragma unroll
                 for (int k = 0; k < PF; k += 2) {
-                    const uint32_t da[3] = {q[k][0], q[k][1], q[k][2]}, db[3] = {q[k + 1][0], q[k + 1][1], q[k + 1][2]};
+                    const uint32_t lo[2] = {q[k][0], q[k + 1][0]}, hi[2] = {q[k][1], q[k + 1][1]};
                     if constexpr (decltype(refill_tag)::value) {
                         load_step(q[k], gbase, base + k + PF);
                         load_step(q[k + 1], gbase, base + k + 1 + PF);
                     }
-                    if (base + k + 1 < gr.y) step_dot_pair(da, db, acc);
-                    else if (base + k < gr.y) step_dot<CL>(da[0], da[1], da[2], acc);
+                    if (base + k + 1 < n_steps) {
+                        steps_dot<2>(lo, hi, dec, acc);
+                    } else if (base + k < n_steps) {
+                        const uint32_t lo1[1] = {lo[0]}, hi1[1] = {hi[0]};
+                        steps_dot<1>(lo1, hi1, dec, acc);
+                    }
                 }
             } else {
 #pragma unroll
                 for (int k = 0; k < PF; ++k) {
-                    const uint32_t d0 = q[k][0], d1 = q[k][1], d2 = q[k][2];
+                    const uint32_t lo1[1] = {q[k][0]}, hi1[1] = {q[k][1]};
                     if constexpr (decltype(refill_tag)::value) load_step(q[k], gbase, base + k + PF);
-                    if (base + k < gr.y) step_dot<CL>(d0, d1, d2, acc);
+                    if (base + k < n_steps) steps_dot<1>(lo1, hi1, dec, acc);
                 }
             }
         };
         // (the first round outside the loop: at a loop head the ring would be copied, and a copy needs
         // all of its data)
         uint32_t base = 0;
-        if (gr.y > (uint32_t)PF) {
+        if (n_steps > (uint32_t)PF) {
             ring_round(0, std::true_type{});
-            for (base = PF; base + PF < gr.y; base += PF) ring_round(base, std::true_type{});
+            for (base = PF; base + PF < n_steps; base += PF) ring_round(base, std::true_type{});
         }
-        if (gr.y > 0) ring_round(base, std::false_type{});
-        if (ri != 0xFFFFu) accbuf[ri] = (acc.a0 + acc.a1) + (acc.a2 + acc.a3);
+        if (n_steps > 0) ring_round(base, std::false_type{});
+        if (slot != 0xFFFFu) accbuf[slot] = (acc.a[0] + acc.a[1]) + acc.a[2];
     };
-    if (has_group) run_group(gr, ri, gbase);
-    for (uint32_t g = wave + nwaves; g < n_groups; g += nwaves) {  // only when a block has more groups than wavefronts
-        const uint2 gr2 = group_of(ka.group[g]);
-        const uint32_t ri2 = rowids[((size_t)first_group + g) * 64 + lane];
-        gbyte_t *gbase2 = lane_base(gr2.x);
+    if (has_group) run_group(my_steps, slot, gbase);
+    for (int g = wave + nwaves; g < a.n_groups; g += nwaves) {  // only when a block has more groups than wavefronts
+        const uint32_t steps2 = own_steps[g];
+        const uint32_t slot2 = tasks[(size_t)g * 64 + lane];
+        gbyte_t *gbase2 = group_base(ka.group[g]);
 #pragma unroll
         for (int k = 0; k < PF; ++k) load_step(q[k], gbase2, k);
-        run_group(gr2, ri2, gbase2);
+        run_group(steps2, slot2, gbase2);
     }
     __syncthreads();
 
-    // (5) this slice's partial sums, in natural row order (coalesced).  A second, tiny kernel adds the
-    // S partials of every row in slice order -- the "explicit global reduction" of Sec. VI-A.  It is a
-    // kernel of its own because device-wide synchronisation inside one kernel costs more here.  Measured
-    // with the "last workgroup of a row block reduces" pattern at the 4096 x 4096 shape (one thread per
-    // workgroup takes a ticket): a relaxed device-scope ticket returns after 1.8 us (median), an
-    // acquire-release one (L2 write-back and invalidate) after 3.8 us, and the last workgroup then needs
+    // (5) this slice's partial sums, in natural row order (coalesced): the parts of a row added in part order.
+    // A second, tiny kernel adds the S partials of every row in slice order -- the "explicit global reduction"
+    // of Sec. VI-A.  It is a kernel of its own because device-wide synchronisation inside one kernel costs
+    // more here.  Measured with the "last workgroup of a row block reduces" pattern at the 4096 x 4096 shape
+    // (one thread per workgroup takes a ticket): a relaxed device-scope ticket returns after 1.8 us (median),
+    // an acquire-release one (L2 write-back and invalidate) after 3.8 us, and the last workgroup then needs
     // 4 us to read the 64 KiB of partials through its emptied L2 -- 9.5 us from the first partial store to
     // the end, against ~3.5 us for the second launch.
-    for (uint32_t c = wave; c < n_groups; c += nwaves) {
-        const int r = (int)c * 64 + lane;
+    for (int r = tid; r < a.rows_per_block; r += nwaves * 64) {
         const int n = rb * a.rows_per_block + r;
-        if (r < a.rows_per_block && n < a.N) ((__attribute__((address_space(1))) float *)a.partial)[(size_t)s * a.N + n] = accbuf[r];
+        if (n < a.N) {
+            float sum = accbuf[r];
+            for (int p = 1; p < a.P; ++p) sum += accbuf[p * a.rows_per_block + r];
+            ((__attribute__((address_space(1))) float *)a.partial)[partial_index(a.S, s, n)] = sum;
+        }
     }
+    // (6) the pending rows: their partial sums landed in LDS before the barrier of (3)
+    if (fin_mine) fin_complete(fl, fin_scale_bits, reinterpret_cast<const float *>(fin + (size_t)fin_chunk * kFinChunkBytes), lane);
 }
 
-// One problem: 8 to 16 wavefronts, one per row group of the block (more groups than that: several each).
-__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a) { gemv_packed_body<4, 4, true>(a, blockIdx.x); }
+// A workgroup of a batched launch that has no part of its own problem (the problem needs fewer workgroups
+// than the largest of the batch) still takes its share of the pending rows.
+__device__ __forceinline__ void pending_only(const PendingArgs &pd, const int wg_linear, const int nwaves) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    if (pd.count == 0) return;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int fin_chunk = nwaves - 1 - wave;
+    const int fin_bid = wg_linear * pd.blocks_per_wg + fin_chunk;
+    if (fin_chunk >= pd.blocks_per_wg || fin_bid >= pd.blocks_total) return;
+    PendingHead ph;
+#pragma unroll
+    for (int i = 0; i < kPackMaxBatch; ++i) ph.first_block[i] = pd.first_block[i];
+    ph.count = pd.count; ph.blocks_total = pd.blocks_total; ph.blocks_per_wg = pd.blocks_per_wg;
+    unsigned char *fin = smem + (size_t)fin_chunk * kFinChunkBytes;
+    FinBlock fl;
+    const uint16_t *scale_at = fin_issue(pd, ph, fin_bid, fin, lane, fl);
+    const uint32_t scale_bits = *(const __attribute__((address_space(1))) uint16_t *)scale_at;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (the transfers of this wavefront; nobody else reads them)
+    fin_complete(fl, scale_bits, reinterpret_cast<const float *>(fin), lane);
+}
+
+// One problem: 8 to 16 wavefronts, one per group of the block (more groups than that: several each).
+__global__ __launch_bounds__(1024) void gemv_packed_kernel(PackedArgs a, PendingArgs pd) {
+    gemv_packed_body<6, true>(a, blockIdx.x, pd, blockIdx.x);
+}
 
 // Several independent problems in one launch (blockIdx.y picks the problem): the fixed latencies of a
 // launch (ramp-up, first touches of tables and atoms, drain) are paid once for all of them, and
 // workgroups of different problems share a CU.
-constexpr int kPackMaxBatch = 4;
 struct PackedBatch {
     PackedArgs a[kPackMaxBatch];
 };
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void gemv_packed_batch_kernel(PackedBatch b) {
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void gemv_packed_batch_kernel(PackedBatch b, PendingArgs pd) {
     const PackedArgs &a = b.a[blockIdx.y];
-    if ((int)blockIdx.x >= a.S * a.RB) return;
-    gemv_packed_body<kPackRing, 4, false>(a, blockIdx.x);
+    const int wg_linear = blockIdx.y * gridDim.x + blockIdx.x;
+    if ((int)blockIdx.x >= a.S * a.RB) {
+        pending_only(pd, wg_linear, a.nwaves);
+        return;
+    }
+    gemv_packed_body<4, false>(a, blockIdx.x, pd, wg_linear);
 }
 
 // y[n] = scale[n] * sum_s partial[s][n], slices in ascending order.  MAXS loads are issued unconditionally
 // (slices past S re-read the last one) so that none of them waits behind a branch.  One row per thread, one
 // wavefront per block: the kernel is one memory round trip long, and the fewer requests queue on a CU the
-// shorter it is (256 rows per block: 1209 GB/s on the Llama-7B stack, 64 rows: 1220).
+// shorter it is.
 constexpr int kFinalizeRows = 64;
 template <int MAXS>
 __device__ __forceinline__ void gemv_packed_finalize_body(const float *__restrict__ partial,
@@ -502,65 +860,57 @@ __device__ __forceinline__ void gemv_packed_finalize_body(const float *__restric
     __attribute__((address_space(1))) half_t *gy = (__attribute__((address_space(1))) half_t *)y;
     float v[MAXS];
 #pragma unroll
-    for (int k = 0; k < MAXS; ++k) v[k] = gp[(size_t)(k < S ? k : S - 1) * N + n];
+    for (int k = 0; k < MAXS; ++k) v[k] = gp[partial_index(S, k < S ? k : S - 1, n)];
     const float sc = scale ? (float)gs[n] : 1.f;
     float sum = 0.f;
 #pragma unroll
     for (int k = 0; k < MAXS; ++k) sum += k < S ? v[k] : 0.f;
-    gy[n] = (half_t)(sum * sc);
+    gy[n] = scaled_output(sum, sc);
 }
 __global__ __launch_bounds__(kFinalizeRows) void gemv_packed_finalize_kernel(const float *__restrict__ partial,
                                                                   const half_t *__restrict__ scale,
                                                                   half_t *__restrict__ y, int N, int S) {
     pin_scalar(partial); pin_scalar(scale); pin_scalar(y); pin_scalar(N); pin_scalar(S);  // one round of argument loads
-    if (S <= 32)
-        gemv_packed_finalize_body<32>(partial, scale, y, N, S);
-    else
-        gemv_packed_finalize_body<kPackMaxSlices>(partial, scale, y, N, S);
+    gemv_packed_finalize_body<kPackMaxSlices>(partial, scale, y, N, S);
 }
-struct FinalizeArgs {
-    const float *partial;
-    const half_t *scale;
-    half_t *y;
-    int N, S;
-};
 struct FinalizeBatch {
     FinalizeArgs a[kPackMaxBatch];
 };
 __global__ __launch_bounds__(kFinalizeRows) void gemv_packed_finalize_batch_kernel(FinalizeBatch b) {
     FinalizeArgs a = b.a[blockIdx.y];
     pin_scalar(a.partial); pin_scalar(a.scale); pin_scalar(a.y); pin_scalar(a.N); pin_scalar(a.S);
-    if (a.S <= 32)
-        gemv_packed_finalize_body<32>(a.partial, a.scale, a.y, a.N, a.S);
-    else
-        gemv_packed_finalize_body<kPackMaxSlices>(a.partial, a.scale, a.y, a.N, a.S);
+    gemv_packed_finalize_body<kPackMaxSlices>(a.partial, a.scale, a.y, a.N, a.S);
 }
 
 bool gemv_uses_pack(const vq_weight_t *w, int bs) {
     return w->gemv_pack != nullptr && bs == 1 && pack_supported(w);
 }
 
+// S partial sums per row in blocks of 64 rows (partial_index), plus the 4 KiB that a block fetch may read past
+// the last block.
 size_t gemv_packed_workspace(const vq_weight_t *w) {
-    return (size_t)w->gemv_pack->S * w->N * sizeof(float);
+    return (size_t)w->gemv_pack->S * (((size_t)w->N + 63) / 64) * 64 * sizeof(float) + 4096;
 }
 
 int check_pack(const vq_weight_t *w) {
     const vq_gemv_pack_t *p = w->gemv_pack;
     if (!p->data) return VQ_ERR_NULL;
     if (!aligned16(p->data)) return VQ_ERR_ALIGN;
-    if (!pack_supported(w)) return VQ_ERR_UNSUPPORTED;
-    PackPlan plan = pack_plan(w);
-    if (p->S != plan.S || p->RB != plan.RB || p->rows_per_block != plan.rows_per_block) return VQ_ERR_SHAPE;
+    PackPlan plan;
+    if (!pack_plan(w, &plan)) return VQ_ERR_UNSUPPORTED;
+    if (p->S != plan.S || p->RB != plan.RB || p->rows_per_block != plan.rows_per_block || p->entry_bits != plan.EB ||
+        p->parts != plan.P || p->part_cols != plan.Jp)
+        return VQ_ERR_SHAPE;
     if (p->S > (uint32_t)kPackMaxSlices) return VQ_ERR_UNSUPPORTED;
     // every address the kernel derives from the descriptor must lie inside the buffer
-    const uint64_t ng = (plan.rows_per_block + 63) / 64, nwg = (uint64_t)p->S * p->RB;
-    if (ng > VQ_PACK_MAX_GROUPS) return VQ_ERR_SHAPE;
+    const uint64_t ng = plan.G, nwg = (uint64_t)p->S * p->RB;
     uint64_t sum = 0;
     for (uint64_t g = 0; g < ng; ++g) sum += p->group_steps[g];
     if (sum != p->wg_pitch || sum > 65535 || sum == 0) return VQ_ERR_SHAPE;
-    if (p->rowid_off + nwg * ng * 128 > p->atom_off || p->atom_off + (nwg * sum + kPackTailBlocks) * 768 > p->bytes)
+    if (p->task_off + nwg * ng * 128 > p->steps_off || p->steps_off + nwg * ng * 4 > p->atom_off ||
+        p->atom_off + (nwg * sum + kPackTailBlocks) * kStepBytes > p->bytes)
         return VQ_ERR_SHAPE;
-    if ((p->rowid_off & 1) || (p->atom_off & 3)) return VQ_ERR_ALIGN;
+    if ((p->task_off & 1) || (p->steps_off & 3) || (p->atom_off & 7)) return VQ_ERR_ALIGN;
     return VQ_OK;
 }
 
@@ -574,7 +924,8 @@ struct PackedLaunch {
 
 PackedLaunch packed_launch(const vq_weight_t *w, const void *x, void *y, void *partial) {
     const vq_gemv_pack_t *p = w->gemv_pack;
-    PackPlan plan = pack_plan(w);
+    PackPlan plan;
+    (void)pack_plan(w, &plan);   // (checked by check_pack before any launch)
     PackedLaunch l;
     PackedArgs &a = l.a;
     a.data = (const unsigned char *)p->data;
@@ -588,8 +939,12 @@ PackedLaunch packed_launch(const vq_weight_t *w, const void *x, void *y, void *p
     a.S = (int)p->S;
     a.RB = (int)p->RB;
     a.rows_per_block = (int)p->rows_per_block;
-    a.slice_entries = (int)plan.slice_entries;
-    a.rowid_off = p->rowid_off;
+    a.EB = (int)plan.EB;
+    a.P = (int)plan.P;
+    a.Jp = (int)plan.Jp;
+    a.n_groups = (int)plan.G;
+    a.task_off = p->task_off;
+    a.steps_off = p->steps_off;
     a.atom_off = p->atom_off;
     a.wg_pitch = p->wg_pitch;
     {
@@ -599,28 +954,54 @@ PackedLaunch packed_launch(const vq_weight_t *w, const void *x, void *y, void *p
             at += p->group_steps[g];
         }
     }
-    int groups_per_wg = (int)((p->rows_per_block + 63) / 64);
-    l.lds = ((size_t)plan.slice_entries + (size_t)a.J + 1) * 16 + (size_t)groups_per_wg * 64 * sizeof(float);
+    l.lds = plan.lds;
     // every wavefront the same number of groups (the first, longest ones are dealt first, one to each)
-    const int rounds = (groups_per_wg + 15) / 16;
-    l.waves = (groups_per_wg + rounds - 1) / rounds;
+    const int rounds = ((int)plan.G + 15) / 16;
+    l.waves = ((int)plan.G + rounds - 1) / rounds;
     if (l.waves < 8) l.waves = 8;   // at least 512 threads, so that slice and x are staged with many loads in flight
     a.nwaves = l.waves;
     l.grid = (int)(p->S * p->RB);
     return l;
 }
 
-
 }  // namespace
 
-int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, hipStream_t s) {
-    PackedLaunch l = packed_launch(w, x, y, ws);
-    static KernelSetup setup;   // (the atoms hold absolute LDS addresses: no static LDS allowed)
-    if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_packed_kernel), l.lds, true, setup)) return st;
-    gemv_packed_kernel<<<l.grid, l.waves * 64, l.lds, s>>>(l.a);
-    gemv_packed_finalize_kernel<<<(l.a.N + kFinalizeRows - 1) / kFinalizeRows, kFinalizeRows, 0, s>>>(l.a.partial, l.a.scale, l.a.y, l.a.N, l.a.S);
+namespace {
+
+// The reduction that a main-kernel launch leaves to whoever comes next.
+PendingArgs pending_of(const PackedArgs *probs, int count) {
+    PendingArgs pd;
+    std::memset(&pd, 0, sizeof(pd));
+    pd.count = count;
+    for (int i = 0; i < kPackMaxBatch; ++i) {
+        const PackedArgs &a = probs[i < count ? i : 0];
+        pd.a[i] = {a.partial, a.scale, a.y, a.N, a.S};
+        pd.first_block[i] = i < count ? pd.blocks_total : 0x7fffffff;
+        if (i < count) pd.blocks_total += (a.N + 63) / 64;
+    }
+    return pd;
+}
+
+// The plain reduction kernel for a pending set (after the last launch of a call or sequence, or when the next
+// launch has too few workgroups to take the rows along).
+int launch_finalize(const PendingArgs &pd, hipStream_t s) {
+    if (pd.count == 0) return VQ_OK;
+    if (pd.count == 1) {
+        const FinalizeArgs &a = pd.a[0];
+        gemv_packed_finalize_kernel<<<(a.N + kFinalizeRows - 1) / kFinalizeRows, kFinalizeRows, 0, s>>>(a.partial, a.scale, a.y, a.N, a.S);
+        return launch_status();
+    }
+    FinalizeBatch f;
+    int max_n = 0;
+    for (int i = 0; i < kPackMaxBatch; ++i) {
+        f.a[i] = pd.a[i];
+        if (i < pd.count && pd.a[i].N > max_n) max_n = pd.a[i].N;
+    }
+    gemv_packed_finalize_batch_kernel<<<dim3((max_n + kFinalizeRows - 1) / kFinalizeRows, pd.count), kFinalizeRows, 0, s>>>(f);
     return launch_status();
 }
+
+}  // namespace
 
 // Partial sums of the problems of a batch lie back to back in the workspace, each 256-byte aligned.
 size_t gemv_packed_batch_workspace(const vq_weight_t *const *w, int count) {
@@ -629,10 +1010,13 @@ size_t gemv_packed_batch_workspace(const vq_weight_t *const *w, int count) {
     return total;
 }
 
-int launch_gemv_packed_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, void *ws,
-                             hipStream_t s) {
+// One launch of the main kernel for `count` problems (1 .. kPackMaxBatch).  `in`: the reduction left over by the
+// previous launch on this stream, or null; it rides along in this launch when the launch has workgroups enough,
+// otherwise it gets the plain reduction kernel first.  `out` receives this launch's own pending reduction.
+int launch_gemv_packed_main(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, void *ws,
+                            const PendingArgs *in, PendingArgs *out, hipStream_t s) {
     PackedBatch b;
-    int grid = 0, waves = 0, max_n = 0;
+    int grid = 0, waves = 0;
     size_t lds = 0, off = 0;
     for (int i = 0; i < kPackMaxBatch; ++i) {
         const int k = i < count ? i : 0;  // unused slots repeat problem 0 (never launched: grid.y = count)
@@ -643,17 +1027,67 @@ int launch_gemv_packed_batch(const vq_weight_t *const *w, const void *const *x, 
             grid = l.grid > grid ? l.grid : grid;
             waves = l.waves > waves ? l.waves : waves;
             lds = l.lds > lds ? l.lds : lds;
-            max_n = l.a.N > max_n ? l.a.N : max_n;
         }
     }
-    static KernelSetup setup;
-    if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_packed_batch_kernel), lds, true, setup)) return st;
     for (int i = 0; i < kPackMaxBatch; ++i) b.a[i].nwaves = waves;  // one launch shape for all problems
-    gemv_packed_batch_kernel<<<dim3(grid, count), waves * 64, lds, s>>>(b);
-    FinalizeBatch f;
-    for (int i = 0; i < kPackMaxBatch; ++i) f.a[i] = {b.a[i].partial, b.a[i].scale, b.a[i].y, b.a[i].N, b.a[i].S};
-    gemv_packed_finalize_batch_kernel<<<dim3((max_n + kFinalizeRows - 1) / kFinalizeRows, count), kFinalizeRows, 0, s>>>(f);
+    PendingArgs pd;
+    std::memset(&pd, 0, sizeof(pd));
+    if (in && in->count > 0) {
+        const int n_wg = grid * count;
+        const int per = (in->blocks_total + n_wg - 1) / n_wg;
+        if (per <= kFinChunks && per <= waves) {
+            pd = *in;
+            pd.blocks_per_wg = per;
+            lds += (size_t)per * kFinChunkBytes;
+        } else if (int st = launch_finalize(*in, s)) {
+            return st;
+        }
+    }
+    *out = pending_of(b.a, count);
+    if (count == 1) {
+        static KernelSetup setup;   // (the atoms hold absolute LDS addresses: no static LDS allowed)
+        if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_packed_kernel), lds, true, setup)) return st;
+        gemv_packed_kernel<<<grid, waves * 64, lds, s>>>(b.a[0], pd);
+    } else {
+        static KernelSetup setup;
+        if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_packed_batch_kernel), lds, true, setup)) return st;
+        gemv_packed_batch_kernel<<<dim3(grid, count), waves * 64, lds, s>>>(b, pd);
+    }
     return launch_status();
+}
+
+int launch_gemv_packed_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, void *ws,
+                             hipStream_t s) {
+    PendingArgs out;
+    if (int st = launch_gemv_packed_main(w, x, y, count, ws, nullptr, &out, s)) return st;
+    return launch_finalize(out, s);
+}
+
+int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, hipStream_t s) {
+    return launch_gemv_packed_batch(&w, &x, &y, 1, ws, s);
+}
+
+// A sequence of calls, each a batch of 1 .. kPackMaxBatch problems with re-tiled codes: one launch per call plus one
+// reduction launch at the very end.  The partial sums of consecutive calls alternate between the two halves of
+// the workspace (a launch reads the previous call's while it writes its own).
+size_t gemv_packed_sequence_workspace(const vq_gemv_call_t *calls, int n_calls) {
+    size_t half = 0;
+    for (int c = 0; c < n_calls; ++c) half = std::max(half, gemv_packed_batch_workspace(calls[c].w, calls[c].count));
+    return 2 * ((half + 255) & ~(size_t)255);
+}
+
+int launch_gemv_packed_sequence(const vq_gemv_call_t *calls, int n_calls, void *ws, hipStream_t s) {
+    const size_t half = gemv_packed_sequence_workspace(calls, n_calls) / 2;
+    PendingArgs pending;
+    std::memset(&pending, 0, sizeof(pending));
+    for (int c = 0; c < n_calls; ++c) {
+        PendingArgs next;
+        if (int st = launch_gemv_packed_main(calls[c].w, calls[c].x, calls[c].y, calls[c].count,
+                                             (unsigned char *)ws + (size_t)(c & 1) * half, &pending, &next, s))
+            return st;
+        pending = next;
+    }
+    return launch_finalize(pending, s);
 }
 
 }  // namespace vq
@@ -664,17 +1098,19 @@ extern "C" {
 
 size_t vq_gemv_prepack_bytes(const vq_weight_t *w) {
     if (!w || !w->codes || !pack_supported(w)) return 0;
-    return (size_t)pack_build(w, nullptr, nullptr);
+    return (size_t)pack_build(w, nullptr, nullptr, nullptr);
 }
 
 int vq_gemv_prepack(const vq_weight_t *w, void *out_host, size_t out_bytes, vq_gemv_pack_t *pack) {
     if (!w || !w->codes || !out_host || !pack) return VQ_ERR_NULL;
-    if (w->v != 8 && w->v != 4) return VQ_ERR_UNSUPPORTED;
     if (!pack_supported(w)) return VQ_ERR_UNSUPPORTED;
     if (!aligned16(out_host)) return VQ_ERR_ALIGN;
-    uint64_t need = pack_build(w, nullptr, nullptr);
+    bool bad_code = false;
+    const uint64_t need = pack_build(w, nullptr, nullptr, &bad_code);
+    if (bad_code) return VQ_ERR_SHAPE;          // a code >= n_entries
+    if (need == 0) return VQ_ERR_UNSUPPORTED;   // codes too uneven for a common shape
     if (out_bytes < need) return VQ_ERR_WORKSPACE;
-    pack_build(w, (unsigned char *)out_host, pack);
+    pack_build(w, (unsigned char *)out_host, pack, nullptr);
     return VQ_OK;
 }
 

@@ -91,6 +91,8 @@ int launch_gemv_packed(const vq_weight_t *w, const void *x, void *y, void *ws, h
 size_t gemv_packed_batch_workspace(const vq_weight_t *const *w, int count);
 int launch_gemv_packed_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, void *ws,
                              hipStream_t s);
+size_t gemv_packed_sequence_workspace(const vq_gemv_call_t *calls, int n_calls);
+int launch_gemv_packed_sequence(const vq_gemv_call_t *calls, int n_calls, void *ws, hipStream_t s);
 int check_kv(const vq_kv_t *kv);
 
 // Kernel launchers (defined next to their kernels).

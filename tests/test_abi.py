@@ -160,7 +160,7 @@ def test_packed_gemv_validation():
     pack.data = P                                                  # pretend it was uploaded
     d.gemv_pack = ctypes.pointer(pack)
     need = lib.vq_gemv_workspace(ctypes.byref(d), 1)
-    assert need == pack.S * 128 * 4
+    assert need == pack.S * 128 * 4 + 4096      # S x N partial sums in blocks of 64 rows, plus one 4 KiB fetch unit
     assert gemv(d) == VQ_ERR_WORKSPACE
     assert gemv(d, ws=P, ws_bytes=need - 1) == VQ_ERR_WORKSPACE
     assert gemv(d, bs=2) == VQ_ERR_NULL                            # bs > 1 needs the canonical codes
@@ -222,6 +222,50 @@ def test_gemv_batch_validation():
     assert lib.vq_gemv_batch_workspace(wa, 2) == 0                      # canonical codes, LDS codebook: no scratch
     assert lib.vq_gemv_batch_workspace(wa, 9) == 0
     assert batch([weight(N=0)], [P], [P]) == 0                          # nothing to do, nothing launched
+
+
+def test_gemv_sequence_validation():
+    """Host-side checks of vq_gemv_sequence: every call and member is validated before anything is launched."""
+    import numpy as np
+    from paper_2503_02236_amd import workloads as wl
+    from paper_2503_02236_amd.binding import vq_gemv_call_t
+    lib = vq.lib()
+    WP = ctypes.POINTER(vq_weight_t)
+    w = wl.make_weight(128, 512, 8, 16, 1, 65536, 0.02, seed=5)
+    buf, pack = vq.vq_gemv_prepack(w)
+    pack.data = P                                            # a (fake) aligned device address: nothing is launched here
+    packed = vq_weight_t(w.N, w.K, 8, 16, 1, 65536, None, P, None, ctypes.pointer(pack))
+    canonical = weight()
+
+    def call(ws_list, xs, ys, count=None):
+        n = len(ws_list)
+        c = vq_gemv_call_t()
+        c._keep = ((WP * n)(*[ctypes.pointer(x) if x is not None else WP() for x in ws_list]),
+                   (ctypes.c_void_p * n)(*xs), (ctypes.c_void_p * n)(*ys))
+        c.w, c.x, c.y = (ctypes.cast(c._keep[0], ctypes.POINTER(WP)), ctypes.cast(c._keep[1], ctypes.POINTER(ctypes.c_void_p)),
+                         ctypes.cast(c._keep[2], ctypes.POINTER(ctypes.c_void_p)))
+        c.count = n if count is None else count
+        return c
+
+    def seq(calls, ws=P, ws_bytes=1 << 30):
+        arr = (vq_gemv_call_t * len(calls))(*calls)
+        return lib.vq_gemv_sequence(arr, len(calls), ws, ws_bytes, None), lib.vq_gemv_sequence_workspace(arr, len(calls))
+
+    good = call([packed, packed], [P, P], [P, P])
+    assert lib.vq_gemv_sequence(None, 1, P, 1 << 30, None) == VQ_ERR_NULL
+    arr = (vq_gemv_call_t * 1)(good)
+    assert lib.vq_gemv_sequence(arr, 0, P, 1 << 30, None) == VQ_ERR_SHAPE
+    need = lib.vq_gemv_sequence_workspace(arr, 1)
+    assert need == 2 * (2 * (32 * 128 * 4 + 4096))            # two halves, each the two problems' 32 x 128 partial sums (+ 4 KiB each)
+    assert seq([good], ws=None)[0] == VQ_ERR_WORKSPACE
+    assert seq([good], ws_bytes=need - 1)[0] == VQ_ERR_WORKSPACE
+    assert seq([good], ws=P + 4)[0] == VQ_ERR_ALIGN
+    assert seq([good, call([canonical], [P], [P])]) == (VQ_ERR_UNSUPPORTED, 0)     # a member without re-tiled codes
+    assert seq([call([packed], [P], [P], count=0)]) == (VQ_ERR_SHAPE, 0)
+    assert seq([call([packed] * 5, [P] * 5, [P] * 5)]) == (VQ_ERR_SHAPE, 0)
+    assert seq([good, call([packed, None], [P, P], [P, P])]) == (VQ_ERR_NULL, 0)
+    assert seq([call([packed], [None], [P])]) == (VQ_ERR_NULL, 0)
+    assert seq([call([packed], [P], [P + 2])]) == (VQ_ERR_ALIGN, 0)
 
 
 def test_probe_argument_validation():

@@ -284,9 +284,65 @@ def test_gemv_batch_matches_single_calls_and_oracle(gpu_device):
         assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, xx), "mixed batch member")
 
 
+def test_gemv_sequence_equals_separate_calls(gpu_device):
+    """vq_gemv_sequence: the reduction of every launch rides along in the next one.  Mixed shapes (so that the
+    pending rows per workgroup go from a few to more than one chunk of 64), single problems and batches, scales
+    and none, a launch with fewer workgroups than its predecessor; results bit-identical to vq_gemv_batch."""
+    specs = [  # list of calls, each a list of (N, K, E, scale)
+        [(4096, 512, 65536, True), (4096, 512, 65536, False), (1000, 512, 65536, True)],
+        [(300, 1024, 4096, True)],                      # 10 workgroups only: the 9192 pending rows get the plain reduction kernel
+        [(2000, 256, 65536, True), (64, 256, 65536, True)],
+        [(11008, 512, 65536, True)],
+        [(4096, 1024, 8192, False), (4096, 1024, 65536, True)],
+        [(1, 64, 65536, True)],
+    ]
+    calls, ref = [], []
+    seed = 9300
+    for spec in specs:
+        call = []
+        for (N, K, E, sc) in spec:
+            seed += 1
+            w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=seed, with_scale=sc)
+            wd = vq.weight_to_device(w, gpu_device, prepack=True, keep_codes=False)
+            x = wl.make_activations(1, K, seed=seed + 500)
+            xd = dev_x(x, gpu_device)
+            y = torch.full((1, N), 5.0, dtype=torch.float16, device=gpu_device)
+            call.append((wd, xd, y))
+            ref.append((w, x))
+        calls.append(call)
+    for rep in range(2):      # twice: the second pass re-uses both halves of the workspace
+        vq.vq_gemv_sequence(calls)
+        torch.cuda.synchronize()
+        flat = [t for c in calls for t in c]
+        for (wd, xd, y), (w, x) in zip(flat, ref):
+            assert torch.equal(y, vq.vq_gemv(wd, xd)), (w.N, w.K)
+            assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), f"sequence member {w.N}x{w.K}")
+            y.fill_(3.0)
+    # a sequence of one call is the call itself
+    one = [[(calls[0][0][0], calls[0][0][1], torch.empty_like(calls[0][0][2]))]]
+    vq.vq_gemv_sequence(one)
+    torch.cuda.synchronize()
+    assert torch.equal(one[0][0][2], vq.vq_gemv(calls[0][0][0], calls[0][0][1]))
+
+
+def test_gemv_sequence_llama_block_full_size(gpu_device):
+    """One decoder block's projections at full size, as bench.py issues them: (q, k, v), o, (gate, up), down."""
+    mats = [wl.config2_layer(i, layer=3) for i in (0, 0, 0, 0, 1, 1, 2)]
+    mats = [wl.make_weight(m.N, m.K, 8, 16, 1, 65536, 0.02, seed=9400 + i) for i, m in enumerate(mats)]
+    wds = [vq.weight_to_device(m, gpu_device, prepack=True, keep_codes=False) for m in mats]
+    xs = {K: dev_x(wl.make_activations(1, K, seed=9450 + K), gpu_device) for K in (4096, 11008)}
+    ys = [torch.empty((1, m.N), dtype=torch.float16, device=gpu_device) for m in mats]
+    t = [(wd, xs[m.K], y) for wd, m, y in zip(wds, mats, ys)]
+    vq.vq_gemv_sequence([t[0:3], t[3:4], t[4:6], t[6:7]])
+    torch.cuda.synchronize()
+    for (wd, xd, y), m in zip(t, mats):
+        assert torch.equal(y, vq.vq_gemv(wd, xd))
+        assert_close(y, oracle.gemv(m.codes, m.codebooks, m.scale, xd.cpu().numpy()), f"block member {m.N}x{m.K}")
+
+
 def test_gemv_packed_padding_never_touches_a_codebook_entry(gpu_device):
-    # entries that no code uses are set to infinity and NaN: padding atoms multiply a zero unit of their own,
-    # not an entry, so every output stays what the oracle says (finite)
+    # entries that no code uses are set to infinity and NaN: padding atoms multiply a zero unit of x with an
+    # entry that some code really uses, never with one of these, so every output stays what the oracle says (finite)
     w = wl.make_weight(200, 1024, 8, 16, 1, 65536, 0.02, seed=7400)
     used = np.zeros(65536, dtype=bool)
     used[w.codes.reshape(-1)] = True
@@ -313,7 +369,7 @@ def test_gemv_packed_shared_workspace_determinism_and_canonical_agreement(gpu_de
         x = dev_x(wl.make_activations(1, w.K, 40 + si), gpu_device)
         layers.append((w, wd, x))
         ws_bytes = max(ws_bytes, vq.vq_gemv_workspace(wd, 1))
-    assert ws_bytes == max(64 * 4096 * 4, 32 * 11008 * 4)   # S x N fp32 partial sums (64 slices for K = 11008)
+    assert ws_bytes == 32 * 11008 * 4 + 4096   # S x N fp32 partial sums (N a multiple of 64 here), 32 slices of 2048 entries
     ws = vq.new_workspace(ws_bytes, gpu_device)
     outs = [[vq.vq_gemv(wd, x, ws=ws).clone() for (_, wd, x) in layers] for _ in range(3)]
     torch.cuda.synchronize()

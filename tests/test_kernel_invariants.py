@@ -1,8 +1,8 @@
 """Compile-time invariants of hand-scheduled kernels, checked on the compiler's own output (no GPU).
 
 The re-tiled gemv lets its gathers start when the codebook slice has landed while the atoms still stream in:
-a counted ``s_waitcnt vmcnt(PF + 1)`` stands between the loads and the barrier.  That is only right if, in every
-build of the kernel, at least PF + 1 ordinary vector loads are issued between the last direct-to-LDS transfer
+a counted ``s_waitcnt vmcnt(AHEAD + 1)`` stands between the loads and the barrier.  That is only right if, in every
+build of the kernel, at least AHEAD + 1 ordinary vector loads are issued between the last direct-to-LDS transfer
 and that wait, in straight-line code (loads complete in issue order)."""
 import os
 import re
@@ -18,6 +18,11 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 @pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
 def test_gemv_packed_counted_wait_matches_the_loads_in_front_of_it(tmp_path):
+    """Order of a wavefront's vector memory instructions in front of the barrier, in every build of the kernel:
+    staging transfers (slice, x) | trip count, task slots, AHEAD atom loads | [the pending block of the previous
+    launch: 4 transfers, 4 more when it has more than 16 slices] | scale.  The barrier may open when the staging
+    transfers have landed, i.e. when at most AHEAD + 2 (+ 4, + 8) younger instructions are pending: three counted
+    waits, one per case.  Loads complete in issue order, so that is right iff the counts match the code."""
     out = tmp_path / "gemv_packed.s"
     cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
            "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "--cuda-device-only", "-S",
@@ -25,31 +30,45 @@ def test_gemv_packed_counted_wait_matches_the_loads_in_front_of_it(tmp_path):
     r = subprocess.run(cmd, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
     text = out.read_text()
-    # the number of atom loads that every wavefront issues between the staging transfers and the barrier
     ahead = int(re.search(r"constexpr int kPackAhead = (\d+);", open(os.path.join(CSRC, "gemv_packed.hip")).read()).group(1))
+    is_load = lambda l: re.match(r"global_load_(dword|ushort|ubyte|short)", l) is not None
+    is_dma = lambda l: l.startswith("global_load_lds")
+    is_flow = lambda l: l.startswith(("s_cbranch", "s_branch")) or l.endswith(":")
     checked = 0
-    for name, pf in (("gemv_packed_kernel", ahead), ("gemv_packed_batch_kernel", ahead)):
+    for name in ("gemv_packed_kernel", "gemv_packed_batch_kernel"):
         m = re.search(r"^(_ZN2vq\d+%sE\w*):[^\n]*\n(.*?)^\.Lfunc_end" % name, text, re.S | re.M)
         assert m, name
         lines = [l.strip() for l in m.group(2).splitlines()]
-        waits = [i for i, l in enumerate(lines)
-                 if l == "s_waitcnt vmcnt(%d) lgkmcnt(0)" % (pf + 1) and "ASMSTART" in lines[i - 1]]
-        assert len(waits) == 1, (name, waits)
-        w = waits[0]
-        assert any(l == "s_barrier" for l in lines[w:w + 6]), name          # the wait guards the barrier
-        dma = [i for i in range(w) if lines[i].startswith("global_load_lds_dwordx4")]
-        assert dma, name
-        between = lines[dma[-1] + 1:w]
-        loads = [l for l in between if re.match(r"global_load_(dword|ushort|ubyte|short)", l)]
-        assert len(loads) >= pf + 1, (name, len(loads))
-        # straight-line: no branch may skip one of the loads that the count relies on
-        first = next(i for i, l in enumerate(between) if l in loads)
-        assert not any(l.startswith(("s_cbranch", "s_branch")) or l.endswith(":") for l in between[first:]), name
+        barrier = lines.index("s_barrier")
+        head = lines[:barrier]
+        waits = {c: [i for i, l in enumerate(head) if l == "s_waitcnt vmcnt(%d) lgkmcnt(0)" % c and "ASMSTART" in head[i - 1]]
+                 for c in (ahead + 2, ahead + 6, ahead + 10)}
+        assert all(len(v) == 1 for v in waits.values()), (name, waits)
+        first_wait = min(v[0] for v in waits.values())
+        atoms = [i for i, l in enumerate(head[:first_wait]) if l.startswith("global_load_dwordx2")]
+        assert len(atoms) == ahead, (name, atoms)
+        staging = [i for i in range(atoms[0]) if is_dma(head[i])]
+        assert staging and all(head[i].startswith("global_load_lds_dwordx4") for i in staging), name
+        # between the last staging transfer and the first atom load: trip count and task slots, straight-line
+        mid = head[staging[-1] + 1:atoms[0]]
+        assert sum(is_load(l) for l in mid) == 2, (name, mid)
+        first_mid_load = next(i for i, l in enumerate(mid) if is_load(l))
+        assert not any(is_flow(l) for l in mid[first_mid_load:]), name
+        assert not any(is_flow(l) or is_dma(l) for l in head[atoms[0]:atoms[-1] + 1]), name
+        # behind the atoms: the pending block (two groups of four transfers, nothing else that counts), then the scale
+        tail = head[atoms[-1] + 1:first_wait]
+        dmas = [i for i, l in enumerate(tail) if is_dma(l)]
+        assert len(dmas) == 8 and all(tail[i].startswith("global_load_lds_dwordx4") for i in dmas), (name, dmas)
+        assert dmas[3] == dmas[0] + 3 and dmas[7] == dmas[4] + 3                   # each group in one statement
+        assert any(is_flow(l) for l in tail[dmas[3] + 1:dmas[4]])                  # the second group can be skipped
+        loads = [i for i, l in enumerate(tail) if is_load(l)]
+        assert len(loads) == 1 and loads[0] > dmas[-1], (name, loads)               # the scale, outside the condition
+        assert tail[loads[0]].startswith("global_load_ushort")
+        checked += 1
         # the atoms hold absolute LDS addresses of the dynamic region: it must start at 0, i.e. no static LDS
         k = re.search(r"\.amdhsa_kernel (_ZN2vq\d+%sE\w*)\n(.*?)\.end_amdhsa_kernel" % name, text, re.S)
         assert k, name
         assert re.search(r"\.amdhsa_group_segment_fixed_size 0\b", k.group(2)), name
-        checked += 1
     assert checked == 2
 
 
