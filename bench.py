@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--no-sequence", action="store_true",
                     help="separate vq_gemv_batch / vq_gemv calls (two launches each: product and its reduction) instead "
                          "of one vq_gemv_sequence over the stack (the reduction rides along in the next launch)")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="HIP streams the sequence is spread over (vq_gemv_sequence_streams; 1 = vq_gemv_sequence)")
     ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add,zipf,tile,bit12")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter run (wrap in rocprofv3 --pmc FETCH_SIZE or WRITE_SIZE): three plain copies of "
@@ -224,12 +226,14 @@ def main():
             # the whole stack as ONE vq_gemv_sequence: one launch per call, the reduction of each riding along
             # in the next, one reduction launch at the end
             seq = vq.GemvSequence(seq_calls)
-            seq_ws = vq.new_workspace(seq.workspace(), dev)
+            n_streams = max(1, min(args.streams, 8))
+            seq_ws = vq.new_workspace(seq.workspace_streams(n_streams), dev)
+            seq_side = vq.SideStreams(n_streams - 1, dev)
 
             def step():
-                st = seq.run(seq_ws.data_ptr(), seq_ws.numel())
+                st = seq.run_streams(seq_ws.data_ptr(), seq_ws.numel(), seq_side)
                 if st != 0:
-                    raise vq.VQError(st, "vq_gemv_sequence")
+                    raise vq.VQError(st, "vq_gemv_sequence_streams")
         else:
             def step():
                 for c in calls:
@@ -288,6 +292,8 @@ def main():
         shape_us["4096x4096_warm_us"] = round(warm_ms * 1e3, 3)
 
         n_launch = len(calls)
+        if not sequenced:
+            n_streams = 1
         result.update({
             "metric": "VQ-GEMV bs=1 effective HBM bandwidth, Llama-7B shapes, 2^16x8 codebook",
             "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -297,8 +303,10 @@ def main():
                                    "fp16 scale" % L,
                        "launches_per_step": n_launch, "matrices_per_step": len(singles),
                        "effective_bytes_per_step": eff_bytes,
-                       "kernel_dispatches_per_step": (n_launch + 1 if sequenced else 2 * n_launch if packed else n_launch),
-                       "calls": ("one vq_gemv_sequence over the stack; per block the calls (q,k,v), (o), (gate,up), (down)"
+                       "kernel_dispatches_per_step": (n_launch + n_streams if sequenced else 2 * n_launch if packed else n_launch),
+                       "streams": n_streams if sequenced else 1,
+                       "calls": ("one vq_gemv_sequence_streams over the stack (contiguous runs of calls on %d streams); per "
+                                 "block the calls (q,k,v), (o), (gate,up), (down)" % n_streams
                                  if sequenced else
                                  "per block: vq_gemv_batch(q,k,v), vq_gemv(o), vq_gemv_batch(gate,up), vq_gemv(down)"
                                  if batched else "one vq_gemv per matrix"),

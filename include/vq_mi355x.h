@@ -226,6 +226,32 @@ int vq_gemv_sequence(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t 
 size_t vq_gemv_sequence_workspace(const vq_gemv_call_t *calls, int n_calls);
 
 /*
+ * The same sequence spread over several HIP streams of the caller, so that launches of different calls overlap
+ * on the GPU (the calls of a sequence are independent of each other by contract; on one stream every launch
+ * waits for the previous one to drain, and a bs = 1 product is too short to hide its own start-up).
+ * The calls are cut into side->n + 1 contiguous runs; run 0 goes to `stream`, run i to side->stream[i - 1], each
+ * run being a vq_gemv_sequence of its own.  Ordering towards the caller is that of a call on `stream` alone:
+ * the side streams first wait for side->start (recorded on `stream` at entry), and `stream` finally waits for
+ * side->done[i] of every side stream, so work queued on `stream` afterwards sees every output.
+ * side: HOST struct; streams (default priority) and events (hipEventDisableTiming is enough) are created and
+ * owned by the caller and must not be in use by anything else during the call; NULL or n = 0 gives
+ * vq_gemv_sequence.  The call may be captured into a HIP graph from `stream` (the side streams join the capture
+ * through the events).  ws: vq_gemv_sequence_streams_workspace(calls, n_calls, side->n + 1) bytes.
+ * Errors: as vq_gemv_sequence; VQ_ERR_SHAPE for side->n outside 0..VQ_SEQUENCE_MAX_SIDE_STREAMS; VQ_ERR_NULL for a
+ * missing stream or event; VQ_ERR_LAUNCH if the runtime refuses an event operation.
+ */
+#define VQ_SEQUENCE_MAX_SIDE_STREAMS 7
+typedef struct vq_side_streams_t {
+    int n;                                        /* side streams in use */
+    void *stream[VQ_SEQUENCE_MAX_SIDE_STREAMS];   /* hipStream_t */
+    void *done[VQ_SEQUENCE_MAX_SIDE_STREAMS];     /* hipEvent_t, one per side stream */
+    void *start;                                  /* hipEvent_t */
+} vq_side_streams_t;
+int vq_gemv_sequence_streams(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t ws_bytes, void *stream,
+                             const vq_side_streams_t *side);
+size_t vq_gemv_sequence_streams_workspace(const vq_gemv_call_t *calls, int n_calls, int n_streams);
+
+/*
  * VQ-gemm (prefill phase, Sec. III-C / Sec. VII "GeMM"): Y = X W^T with the
  * dequantized tile fed to the fp16 matrix cores, fp32 accumulation.
  *   Y[m][n] = scale[n] * sum_k W[n][k] * X[m][k],   m < M

@@ -53,6 +53,11 @@ class vq_gemv_call_t(ctypes.Structure):
                 ("y", ctypes.POINTER(ctypes.c_void_p)), ("count", ctypes.c_int)]
 
 
+class vq_side_streams_t(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int), ("stream", ctypes.c_void_p * 7), ("done", ctypes.c_void_p * 7),
+                ("start", ctypes.c_void_p)]
+
+
 _lib = None
 
 #: name -> (restype, argtypes); must list every symbol the header declares
@@ -73,6 +78,9 @@ SYMBOLS = {
     "vq_gemv_sequence": (ctypes.c_int, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
                                         ctypes.c_void_p]),
     "vq_gemv_sequence_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int]),
+    "vq_gemv_sequence_streams": (ctypes.c_int, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int, ctypes.c_void_p,
+                                                ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(vq_side_streams_t)]),
+    "vq_gemv_sequence_streams_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int, ctypes.c_int]),
     "vq_gemv_prepack_bytes": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t)]),
     "vq_gemv_prepack": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_size_t,
                                        ctypes.POINTER(vq_gemv_pack_t)]),
@@ -339,6 +347,30 @@ class GemvSequence:
 
     def run(self, ws_ptr, ws_bytes) -> int:
         return lib().vq_gemv_sequence(self.arr, self.n, ws_ptr, ws_bytes, _stream())
+
+    def workspace_streams(self, n_streams: int) -> int:
+        return int(lib().vq_gemv_sequence_streams_workspace(self.arr, self.n, n_streams))
+
+    def run_streams(self, ws_ptr, ws_bytes, side: "SideStreams") -> int:
+        return lib().vq_gemv_sequence_streams(self.arr, self.n, ws_ptr, ws_bytes, _stream(), ctypes.byref(side.c))
+
+
+class SideStreams:
+    """Side streams and events for ``vq_gemv_sequence_streams``: torch streams (default priority) and torch events
+    (no timing), kept alive here; the C struct holds their raw handles."""
+
+    def __init__(self, n: int, device="cuda:0"):
+        self.streams = [torch.cuda.Stream(device=device) for _ in range(n)]
+        self.events = [torch.cuda.Event(enable_timing=False) for _ in range(n + 1)]
+        for e in self.events:      # torch creates the HIP event on first use
+            e.record(torch.cuda.current_stream(device))
+        torch.cuda.synchronize(device)
+        self.c = vq_side_streams_t()
+        self.c.n = n
+        for i, st in enumerate(self.streams):
+            self.c.stream[i] = int(st.cuda_stream)
+            self.c.done[i] = int(self.events[i].cuda_event)
+        self.c.start = int(self.events[n].cuda_event)
 
 
 def vq_gemv_sequence(calls, ws: Optional[torch.Tensor] = None):

@@ -233,6 +233,62 @@ int vq_gemv_sequence(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t 
     return launch_gemv_packed_sequence(calls, n_calls, ws, static_cast<hipStream_t>(stream));
 }
 
+// Run r of n_runs contiguous runs of the calls: [first, first + count).
+static void sequence_run(int n_calls, int n_runs, int r, int *first, int *count) {
+    const int per = (n_calls + n_runs - 1) / n_runs;
+    *first = r * per < n_calls ? r * per : n_calls;
+    *count = n_calls - *first < per ? n_calls - *first : per;
+}
+
+size_t vq_gemv_sequence_streams_workspace(const vq_gemv_call_t *calls, int n_calls, int n_streams) {
+    if (!calls || n_calls < 1 || n_streams < 1 || n_streams > VQ_SEQUENCE_MAX_SIDE_STREAMS + 1) return 0;
+    for (int c = 0; c < n_calls; ++c)
+        if (check_sequence_call(&calls[c]) != VQ_OK) return 0;
+    size_t total = 0;
+    for (int r = 0; r < n_streams; ++r) {
+        int first, count;
+        sequence_run(n_calls, n_streams, r, &first, &count);
+        if (count > 0) total += gemv_packed_sequence_workspace(calls + first, count);
+    }
+    return total;
+}
+
+int vq_gemv_sequence_streams(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t ws_bytes, void *stream,
+                             const vq_side_streams_t *side) {
+    if (!side || side->n == 0) return vq_gemv_sequence(calls, n_calls, ws, ws_bytes, stream);
+    if (!calls) return VQ_ERR_NULL;
+    if (n_calls < 1 || side->n < 0 || side->n > VQ_SEQUENCE_MAX_SIDE_STREAMS) return VQ_ERR_SHAPE;
+    if (!side->start) return VQ_ERR_NULL;
+    for (int i = 0; i < side->n; ++i)
+        if (!side->stream[i] || !side->done[i]) return VQ_ERR_NULL;
+    for (int c = 0; c < n_calls; ++c)
+        if (int st = check_sequence_call(&calls[c])) return st;
+    const int n_runs = side->n + 1;
+    const size_t need = vq_gemv_sequence_streams_workspace(calls, n_calls, n_runs);
+    if (!ws || ws_bytes < need) return VQ_ERR_WORKSPACE;
+    if (!aligned16(ws)) return VQ_ERR_ALIGN;
+    hipStream_t main_stream = static_cast<hipStream_t>(stream);
+    if (hipEventRecord(static_cast<hipEvent_t>(side->start), main_stream) != hipSuccess) return VQ_ERR_LAUNCH;
+    size_t off = 0;
+    int status = VQ_OK;
+    for (int r = 0; r < n_runs; ++r) {
+        int first, count;
+        sequence_run(n_calls, n_runs, r, &first, &count);
+        hipStream_t s = r == 0 ? main_stream : static_cast<hipStream_t>(side->stream[r - 1]);
+        if (r > 0 && hipStreamWaitEvent(s, static_cast<hipEvent_t>(side->start), 0) != hipSuccess) status = VQ_ERR_LAUNCH;
+        if (count > 0 && status == VQ_OK) {
+            status = launch_gemv_packed_sequence(calls + first, count, (unsigned char *)ws + off, s);
+            off += gemv_packed_sequence_workspace(calls + first, count);
+        }
+        // the join is made even after a failure, so that a capture in progress is left in a consistent state
+        if (r > 0) {
+            if (hipEventRecord(static_cast<hipEvent_t>(side->done[r - 1]), s) != hipSuccess) status = VQ_ERR_LAUNCH;
+            if (hipStreamWaitEvent(main_stream, static_cast<hipEvent_t>(side->done[r - 1]), 0) != hipSuccess) status = VQ_ERR_LAUNCH;
+        }
+    }
+    return status;
+}
+
 size_t vq_gemm_workspace(const vq_weight_t *w, int M) {
     if (check_weight(w, true) != VQ_OK || M < 1) return 0;
     return gemm_workspace(w, M);

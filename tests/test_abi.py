@@ -266,6 +266,25 @@ def test_gemv_sequence_validation():
     assert seq([good, call([packed, None], [P, P], [P, P])]) == (VQ_ERR_NULL, 0)
     assert seq([call([packed], [None], [P])]) == (VQ_ERR_NULL, 0)
     assert seq([call([packed], [P], [P + 2])]) == (VQ_ERR_ALIGN, 0)
+    # several streams: the struct is validated before any event or stream is touched
+    from paper_2503_02236_amd.binding import vq_side_streams_t
+    side = vq_side_streams_t()
+    f = lib.vq_gemv_sequence_streams
+    assert lib.vq_gemv_sequence_streams_workspace(arr, 1, 1) == need
+    assert lib.vq_gemv_sequence_streams_workspace(arr, 1, 0) == 0 and lib.vq_gemv_sequence_streams_workspace(arr, 1, 9) == 0
+    two = (vq_gemv_call_t * 2)(good, good)
+    assert lib.vq_gemv_sequence_streams_workspace(two, 2, 2) == 2 * need          # one run per stream, two halves each
+    assert lib.vq_gemv_sequence_streams_workspace(two, 2, 4) == 2 * need          # runs without calls need nothing
+    side.n = 8
+    assert f(arr, 1, P, 1 << 30, None, ctypes.byref(side)) == VQ_ERR_SHAPE
+    side.n = -1
+    assert f(arr, 1, P, 1 << 30, None, ctypes.byref(side)) == VQ_ERR_SHAPE
+    side.n = 1
+    assert f(arr, 1, P, 1 << 30, None, ctypes.byref(side)) == VQ_ERR_NULL           # no start event
+    side.start = P
+    assert f(arr, 1, P, 1 << 30, None, ctypes.byref(side)) == VQ_ERR_NULL           # no side stream / done event
+    side.n = 0
+    assert f(arr, 1, None, 0, None, ctypes.byref(side)) == VQ_ERR_WORKSPACE         # n = 0: the one-stream call
 
 
 def test_probe_argument_validation():

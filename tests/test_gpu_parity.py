@@ -340,6 +340,54 @@ def test_gemv_sequence_llama_block_full_size(gpu_device):
         assert_close(y, oracle.gemv(m.codes, m.codebooks, m.scale, xd.cpu().numpy()), f"block member {m.N}x{m.K}")
 
 
+@pytest.mark.parametrize("n_side", [1, 3])
+def test_gemv_sequence_on_several_streams_eager_and_graph(gpu_device, n_side):
+    """vq_gemv_sequence_streams: the calls spread over side streams; same bits as separate calls, eagerly and as a
+    captured graph replayed several times with eager work and synchronisations in between."""
+    calls, flat = [], []
+    for c in range(7):                                   # seven calls over 2 or 4 streams: runs of 4 + 3 or 2 + 2 + 2 + 1
+        call = []
+        for k in range(1 + c % 3):
+            N, K = [(4096, 512), (1000, 1024), (2500, 256)][(c + k) % 3]
+            w = wl.make_weight(N, K, 8, 16, 1, 65536, 0.02, seed=9600 + 10 * c + k)
+            wd = vq.weight_to_device(w, gpu_device, prepack=True, keep_codes=False)
+            xd = dev_x(wl.make_activations(1, K, seed=9700 + 10 * c + k), gpu_device)
+            call.append((wd, xd, torch.full((1, N), 7.0, dtype=torch.float16, device=gpu_device)))
+        calls.append(call)
+        flat += call
+    want = [vq.vq_gemv(wd, xd).clone() for (wd, xd, _) in flat]
+    torch.cuda.synchronize()
+    seq = vq.GemvSequence(calls)
+    side = vq.SideStreams(n_side, gpu_device)
+    ws = vq.new_workspace(seq.workspace_streams(n_side + 1), gpu_device)
+
+    def run():
+        st = seq.run_streams(ws.data_ptr(), ws.numel(), side)
+        assert st == 0, vq.status_str(st)
+
+    def check(tag):
+        torch.cuda.synchronize()
+        for (wd, xd, y), w_ in zip(flat, want):
+            assert torch.equal(y, w_), tag
+            y.fill_(7.0)
+        torch.cuda.synchronize()
+
+    run()
+    check("eager")
+    run()
+    check("eager, second time")
+    g = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(g, stream=cap):
+            run()
+    for rep in range(4):
+        g.replay()
+        check(f"replay {rep}")
+        vq.vq_gemv(flat[0][0], flat[0][1])               # eager work of the program between the replays
+        torch.cuda.synchronize()
+
+
 def test_gemv_packed_padding_never_touches_a_codebook_entry(gpu_device):
     # entries that no code uses are set to infinity and NaN: padding atoms multiply a zero unit of x with an
     # entry that some code really uses, never with one of these, so every output stays what the oracle says (finite)
