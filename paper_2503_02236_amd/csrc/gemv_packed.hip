@@ -28,11 +28,14 @@
 // (Entries that no code points at are never read; entries in use must be finite.)
 //
 // Order of a task's atoms = order of the additions to its sum; it is fixed offline, so results are
-// bit-reproducible -- and it is free.  LDS serves the 16-byte reads of 16 consecutive lanes together and
-// needs one pass per distinct address that falls into the same 16-byte column (address / 16 mod 16): random
-// addresses take ~2.6 passes.  The packer therefore orders the atoms of every 16 lanes so that, position by
-// position, their entry addresses and their x addresses hit different columns wherever the lists allow it
-// (greedy, the lanes with the least room first; padding atoms go where nothing fits and pick a free zero unit).
+// bit-reproducible -- and it is free.  LDS serves the 16-byte reads of a wavefront in four passes of 16 lanes
+// (measured on MI355X, two lanes at a time against a background of one shared address: lanes 0-3, 12-15 and
+// 20-27 go together, lanes 4-11, 16-19 and 28-31, and the same two sets in the upper half of the wavefront) and
+// needs one more pass for every further distinct address that falls into the same 16-byte column
+// (address / 16 mod 16) inside such a set: random addresses take ~2.6 passes each.  The packer therefore orders
+// the atoms of every such set of 16 lanes so that, position by position, their entry addresses and their x
+// addresses hit different columns wherever the lists allow it (greedy, the lanes with the least room first;
+// padding atoms go where nothing fits and pick a free zero unit).
 //
 // The S partial sums of a row are added in slice order by a second small kernel (Sec. VI-A "explicit global
 // reduction"), which keeps the result independent of timing.
@@ -117,11 +120,18 @@ static inline uint64_t align256(uint64_t x) { return (x + 255) & ~(uint64_t)255;
 
 namespace {
 
+// The four sets of 16 lanes whose 16-byte LDS reads are served in one pass each (see the head of this file).
+const uint8_t kLdsPassLanes[4][16] = {
+    {0, 1, 2, 3, 12, 13, 14, 15, 20, 21, 22, 23, 24, 25, 26, 27},
+    {4, 5, 6, 7, 8, 9, 10, 11, 16, 17, 18, 19, 28, 29, 30, 31},
+    {32, 33, 34, 35, 44, 45, 46, 47, 52, 53, 54, 55, 56, 57, 58, 59},
+    {36, 37, 38, 39, 40, 41, 42, 43, 48, 49, 50, 51, 60, 61, 62, 63}};
+
 struct HostAtom {
     uint16_t e, x;   // entry index inside the slice, position inside the part
 };
 
-// Order of the atoms of 16 lanes (one LDS service group) over `npos` positions.  lists[l] holds lane l's atoms
+// Order of the atoms of 16 lanes that LDS serves in one pass, over `npos` positions.  lists[l] holds lane l's atoms
 // (at most npos of them; consumed); col0[l] is the 16-byte column of position 0 of lane l's part, so position
 // x of that lane lies in column (x + col0[l]) % 16 and its zero units (positions Jp .. Jp + 15) cover every
 // column.  out[l * npos + pos] receives the 21-bit atoms, padding included.  Greedy, position by position: the
@@ -351,7 +361,7 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
                     std::vector<HostAtom> quad[16];
                     uint32_t col0[16];
                     for (uint32_t l = 0; l < 16; ++l) {
-                        const uint16_t slot = slots[((size_t)wg * ng + g) * 64 + q * 16 + l];
+                        const uint16_t slot = slots[((size_t)wg * ng + g) * 64 + kLdsPassLanes[q][l]];
                         const uint32_t part = slot == 0xFFFF ? 0 : slot / p.rows_per_block;
                         if (slot != 0xFFFF) quad[l].swap(lists[(size_t)s * p.tasks + slot]);
                         // unit of position 0 of the part: slice_entries + part * (Jp + 16); slices are multiples of 16 units
@@ -359,7 +369,7 @@ static uint64_t pack_build(const vq_weight_t *w, unsigned char *out, vq_gemv_pac
                     }
                     order_quad(quad, col0, pad_entry, npos, p.EB, p.Jp, ordered.data());
                     for (uint32_t l = 0; l < 16; ++l) {
-                        const uint32_t lane = q * 16 + l;
+                        const uint32_t lane = kLdsPassLanes[q][l];
                         for (uint32_t t = 0; t < st; ++t) {
                             const uint64_t a0 = ordered[l * npos + 3 * t], a1 = ordered[l * npos + 3 * t + 1],
                                            a2 = ordered[l * npos + 3 * t + 2];

@@ -12,6 +12,8 @@ from paper_2503_02236_amd.binding import vq_gemv_pack_t, vq_weight_t
 
 ATOM_BITS = 21
 ZERO_UNITS = 16
+_HALF = [[0, 1, 2, 3, 12, 13, 14, 15, 20, 21, 22, 23, 24, 25, 26, 27], [4, 5, 6, 7, 8, 9, 10, 11, 16, 17, 18, 19, 28, 29, 30, 31]]
+PASS_LANES = [np.array(g) for g in _HALF] + [np.array(g) + 32 for g in _HALF]
 
 
 def decode(buf, pack, N, J):
@@ -91,10 +93,11 @@ def decode(buf, pack, N, J):
                 pad_atoms += st * 3 - n_valid
             if st:
                 assert st == -(-max(int((x[l] < JP).sum()) for l in range(64)) // 3)   # as long as its longest task
-                # bank model: 16 consecutive lanes are served together; passes = max multiplicity of a 16-byte column
+                # bank model: the 16-byte reads of these sets of 16 lanes are served together; passes = max
+                # multiplicity of a 16-byte column inside a set
                 unit_x = slice_entries + part[:, None] * (JP + ZERO_UNITS) + x
-                for q in range(4):
-                    for col in (e[q * 16:(q + 1) * 16] % 16, unit_x[q * 16:(q + 1) * 16] % 16):
+                for lanes in PASS_LANES:
+                    for col in (e[lanes] % 16, unit_x[lanes] % 16):
                         onehot = (col[:, :, None] == np.arange(16)[None, None, :]).sum(axis=0)   # [pos][16]
                         conflict_passes += int(onehot.max(axis=1).sum())
                     positions += 2 * st * 3
