@@ -71,6 +71,10 @@ constexpr int kStepBytes = 512;       // 64 lanes x 8 bytes
 constexpr int kPackTailBlocks = 16;
 constexpr int kPackMaxParts = 8;
 constexpr size_t kPackMaxLds = 144 * 1024;
+#ifndef VQ_PACK_TARGET_WGS
+#define VQ_PACK_TARGET_WGS 256
+#endif
+constexpr uint32_t kPackTargetWgs = VQ_PACK_TARGET_WGS;
 
 struct PackPlan {
     uint32_t EB, XB, slice_entries, S, RB, rows_per_block, P, Jp, tasks, G;
@@ -96,7 +100,7 @@ static bool pack_plan(const vq_weight_t *w, PackPlan *out) {
     if (p.P > (uint32_t)kPackMaxParts) return false;
     p.Jp = (J + p.P - 1) / p.P;
     p.S = (uint32_t)E / p.slice_entries;
-    uint32_t rb = 256 / p.S;
+    uint32_t rb = kPackTargetWgs / p.S;
     const uint32_t max_rb = ((uint32_t)w->N + 63) / 64;   // at least one full 64-row group per block
     if (rb > max_rb) rb = max_rb;
     if (rb < 1) rb = 1;
@@ -136,46 +140,114 @@ struct HostAtom {
 // x of that lane lies in column (x + col0[l]) % 16 and its zero units (positions Jp .. Jp + 15) cover every
 // column.  out[l * npos + pos] receives the 21-bit atoms, padding included.  Greedy, position by position: the
 // lanes with the least room to wait choose first; a lane takes an atom whose entry column and x column are
-// both still free at this position, waits (takes a padding atom) if none is and it has room, and otherwise
-// takes the atom that collides least.  Deterministic.
+// both still free at this position; if none is, it looks for one lane that chose before it and can move to
+// another of its atoms to make room; failing that it waits (takes a padding atom) if it has room, and otherwise
+// takes the atom that adds the fewest passes.  Deterministic.
 void order_quad(std::vector<HostAtom> (&lists)[16], const uint32_t (&col0)[16], const int (&pad_entry)[16], uint32_t npos,
                 uint32_t EB, uint32_t Jp, uint32_t *out) {
     uint32_t rem[16];
     for (int l = 0; l < 16; ++l) rem[l] = (uint32_t)lists[l].size();
+    auto ecol = [&](int l, int i) { return (int)(lists[l][i].e & 15u); };
+    auto xcol = [&](int l, int i) { return (int)((lists[l][i].x + col0[l]) & 15u); };
     for (uint32_t pos = 0; pos < npos; ++pos) {
         uint8_t ue[16] = {0}, ux[16] = {0};
-        bool placed[16] = {false};
+        int8_t owner_e[16], owner_x[16];   // the lane that holds a column alone (-1: free or shared)
+        for (int c = 0; c < 16; ++c) owner_e[c] = owner_x[c] = -1;
+        int chosen[16];                     // index of the atom a lane takes at this position, -1: padding
+        for (int l = 0; l < 16; ++l) chosen[l] = -1;
         const uint32_t left = npos - pos;
         int order[16];
         for (int l = 0; l < 16; ++l) order[l] = l;
         std::stable_sort(order, order + 16, [&](int a, int b) { return (left - rem[a]) < (left - rem[b]); });
+        auto take = [&](int l, int i) {
+            chosen[l] = i;
+            const int ce = ecol(l, i), cx = xcol(l, i);
+            owner_e[ce] = ue[ce] == 0 ? (int8_t)l : (int8_t)-1;
+            owner_x[cx] = ux[cx] == 0 ? (int8_t)l : (int8_t)-1;
+            ++ue[ce];
+            ++ux[cx];
+        };
+        auto drop = [&](int l) {   // only for a lane that holds both of its columns alone
+            const int ce = ecol(l, chosen[l]), cx = xcol(l, chosen[l]);
+            ue[ce] = ux[cx] = 0;
+            owner_e[ce] = owner_x[cx] = -1;
+            chosen[l] = -1;
+        };
         for (int oi = 0; oi < 16; ++oi) {
             const int l = order[oi];
             if (rem[l] == 0) continue;
             const uint32_t slack = left - rem[l];
             int best = -1, best_score = 1 << 30;
             for (uint32_t i = 0; i < rem[l]; ++i) {
-                const int sc = ue[lists[l][i].e & 15u] + ux[(lists[l][i].x + col0[l]) & 15u];
+                const int sc = ue[ecol(l, (int)i)] + ux[xcol(l, (int)i)];
                 if (sc < best_score) {
                     best_score = sc;
                     best = (int)i;
                     if (sc == 0) break;
                 }
             }
-            if (best_score > 0 && slack > 0) continue;   // wait: a padding atom goes here
-            const HostAtom a = lists[l][best];
-            lists[l][best] = lists[l][rem[l] - 1];
+            if (best_score == 0) {
+                take(l, best);
+                continue;
+            }
+            // no atom of this lane fits as things stand: see whether ONE lane that chose earlier can move to
+            // another of its atoms and make room (its columns are its own, so moving it frees them)
+            bool done = false;
+            for (uint32_t i = 0; i < rem[l] && !done; ++i) {
+                const int ce = ecol(l, (int)i), cx = xcol(l, (int)i);
+                if (ue[ce] > 1 || ux[cx] > 1) continue;
+                const int be = ue[ce] ? owner_e[ce] : -1, bx = ux[cx] ? owner_x[cx] : -1;
+                if ((ue[ce] && be < 0) || (ux[cx] && bx < 0)) continue;
+                if (be >= 0 && bx >= 0 && be != bx) continue;        // two different lanes in the way
+                const int b = be >= 0 ? be : bx;
+                const int bce = ecol(b, chosen[b]), bcx = xcol(b, chosen[b]);
+                if (owner_e[bce] != b || owner_x[bcx] != b) continue;  // (b shares a column already: leave it)
+                const int old = chosen[b];
+                drop(b);
+                for (uint32_t k = 0; k < rem[b]; ++k) {
+                    if ((int)k == old) continue;
+                    const int kce = ecol(b, (int)k), kcx = xcol(b, (int)k);
+                    if (ue[kce] || ux[kcx] || kce == ce || kcx == cx) continue;
+                    take(b, (int)k);
+                    take(l, (int)i);
+                    done = true;
+                    break;
+                }
+                if (!done) take(b, old);
+            }
+            if (done) continue;
+            if (slack > 0) continue;   // wait: a padding atom goes here
+            // must go now: the atom that raises the passes of this position least
+            int me = 0, mx = 0;
+            for (int c = 0; c < 16; ++c) {
+                me = std::max<int>(me, ue[c]);
+                mx = std::max<int>(mx, ux[c]);
+            }
+            best = 0;
+            best_score = 1 << 30;
+            for (uint32_t i = 0; i < rem[l]; ++i) {
+                const int ce = ecol(l, (int)i), cx = xcol(l, (int)i);
+                const int sc = 16 * (std::max(me, ue[ce] + 1) + std::max(mx, ux[cx] + 1)) + ue[ce] + ux[cx];
+                if (sc < best_score) {
+                    best_score = sc;
+                    best = (int)i;
+                }
+            }
+            take(l, best);
+        }
+        // write the position out and remove the atoms taken (highest list index first is not needed: one per lane)
+        for (int l = 0; l < 16; ++l) {
+            if (chosen[l] < 0) continue;
+            const HostAtom a = lists[l][chosen[l]];
+            lists[l][chosen[l]] = lists[l][rem[l] - 1];
             --rem[l];
-            ++ue[a.e & 15u];
-            ++ux[(a.x + col0[l]) & 15u];
             out[l * npos + pos] = (uint32_t)a.e | ((uint32_t)a.x << EB);
-            placed[l] = true;
         }
         // padding atoms: the least used zero unit, and the least used entry column among those that have an
         // entry which a code of this group really uses (pad_entry[c], -1 if none: a padding atom never reads an
         // entry that no code points at)
         for (int l = 0; l < 16; ++l) {
-            if (placed[l]) continue;
+            if (chosen[l] >= 0) continue;
             int ce = -1, cx = 0;
             for (int c = 0; c < 16; ++c) {
                 if (pad_entry[c] >= 0 && (ce < 0 || ue[c] < ue[ce])) ce = c;
