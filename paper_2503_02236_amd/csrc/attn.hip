@@ -138,8 +138,21 @@ __device__ __forceinline__ unsigned byte_shl(unsigned w, unsigned sh) {
 // the SAME head and share its codebooks in LDS: the layout with one codebook per sub-space needs 128 KiB
 // for them, so only one workgroup fits a CU, and this keeps 16 wavefronts on it and stages the
 // codebooks once per pair.
-template <int V, bool ONE, int SEQ>
+//
+// REP (v = 4, one codebook per head and side): every entry is stored 32 times, copy c of entry e at byte
+// e * 256 + c * 8, and lane l reads copy l % 32.  LDS serves the 8-byte reads of 32 consecutive lanes in one pass
+// if they fall into 32 different 8-byte columns (address / 8 mod 32) and needs one more pass per further address
+// in a column: the 32 lanes of a pass now sit in 32 different columns whatever their codes are, where random
+// entries of one shared copy take 2.4 passes (the paper's takeaway on shared-memory bank conflicts, Sec. III-B).
+// 64 KiB per side; one workgroup of two sequences (SEQ = 2) per compute unit.  An address is one byte
+// permute: (code << 8) | lane constant, the V side's constant carrying its base of 64 KiB.
+constexpr int kAttnRepCopies = 32;
+constexpr int kAttnRepSide = 65536;   // bytes per side: 256 entries x 32 copies x 8 bytes
+constexpr int kAttnRepMinWgs = 192;   // fewer workgroups than this: two small workgroups per CU (shared copy) fill the chip better
+
+template <int V, bool ONE, int SEQ, bool REP = false>
 __global__ __launch_bounds__(kAttnWaves * 64 * SEQ) __attribute__((amdgpu_waves_per_eu(4, 4))) void attn_decode_kernel(AttnArgs a) {
+    static_assert(!REP || (V == 4 && ONE), "replicated codebooks: one codebook of 8-byte entries per side");
     constexpr int D = 128;
     constexpr int P = D / V;          // codes (bytes) per token and side
     constexpr int CB = 32 / V;        // codes (bytes) per lane, step and side: the lane's 32 channels
@@ -152,7 +165,7 @@ __global__ __launch_bounds__(kAttnWaves * 64 * SEQ) __attribute__((amdgpu_waves_
     // right if the dynamic LDS block starts at LDS address 0: true for a kernel without static LDS.
     // The launcher checks that (kernel_setup) and returns an error instead of launching otherwise.
     const int cb_bytes = a.G * a.E * V * 2;        // per side
-    const int v_off = ONE ? 4096 : cb_bytes;       // LDS offset of the V codebook
+    const int v_off = REP ? kAttnRepSide : ONE ? 4096 : cb_bytes;       // LDS offset of the V codebook
     const int tid = threadIdx.x, lane = tid & 63;
     const int seq = (tid >> 6) / kAttnWaves, wave = (tid >> 6) % kAttnWaves;  // sequence of the workgroup, wavefront in it
     const int tok = lane & 15, g = lane >> 4;
@@ -199,7 +212,7 @@ __global__ __launch_bounds__(kAttnWaves * 64 * SEQ) __attribute__((amdgpu_waves_
     const uint4 *ks = reinterpret_cast<const uint4 *>(a.k_cb + (size_t)h * (cb_bytes / 2));
     const uint4 *vs = reinterpret_cast<const uint4 *>(a.v_cb + (size_t)h * (cb_bytes / 2));
     uint4 kst = make_uint4(0, 0, 0, 0), vst = kst;
-    if (tid < n16) {
+    if (!REP && tid < n16) {
         kst = ks[tid];
         vst = vs[tid];
     }
@@ -215,22 +228,40 @@ __global__ __launch_bounds__(kAttnWaves * 64 * SEQ) __attribute__((amdgpu_waves_
 #pragma unroll
         for (int i = 0; i < 4; ++i) qop[i] = ld16(a.q + (size_t)bh * D + 32 * g + 8 * i).h8;
     }
-    if (tid < n16) {
-        reinterpret_cast<uint4 *>(smem)[tid] = kst;
-        reinterpret_cast<uint4 *>(smem + v_off)[tid] = vst;
-    }
-    for (int i = tid + (int)blockDim.x; i < n16; i += (int)blockDim.x) {  // larger codebooks
-        reinterpret_cast<uint4 *>(smem)[i] = ks[i];
-        reinterpret_cast<uint4 *>(smem + v_off)[i] = vs[i];
+    if constexpr (REP) {
+        // 32 copies of every entry: consecutive lanes write consecutive 8-byte units (copy c = unit % 32 of entry
+        // unit / 32); the 32 lanes of a copy set read one global address
+        const uint2 *k8 = reinterpret_cast<const uint2 *>(ks), *v8 = reinterpret_cast<const uint2 *>(vs);
+        for (int u = tid; u < a.E * kAttnRepCopies; u += (int)blockDim.x) {
+            reinterpret_cast<uint2 *>(smem)[u] = k8[u >> 5];
+            reinterpret_cast<uint2 *>(smem + kAttnRepSide)[u] = v8[u >> 5];
+        }
+    } else {
+        if (tid < n16) {
+            reinterpret_cast<uint4 *>(smem)[tid] = kst;
+            reinterpret_cast<uint4 *>(smem + v_off)[tid] = vst;
+        }
+        for (int i = tid + (int)blockDim.x; i < n16; i += (int)blockDim.x) {  // larger codebooks
+            reinterpret_cast<uint4 *>(smem)[i] = ks[i];
+            reinterpret_cast<uint4 *>(smem + v_off)[i] = vs[i];
+        }
     }
     __syncthreads();
 
     const unsigned sh = SH;
     // gathers of one group: the CB entries of step s, into a 64-byte register block in channel order
+    // REP: lane constants of the two sides, byte 0 = 8 (lane % 32), byte 2 = the side's base / 65536
+    const unsigned rep_k = (unsigned)(lane & 31) * 8u, rep_v = rep_k + (unsigned)kAttnRepSide;
     auto gather = [&](const uint32_t (&codes)[NS][CW], int s, int base, V16 (&blk)[4]) {
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
             const unsigned w = codes[s][c / 4];
+            if constexpr (REP) {
+                // address bytes: [lane constant b0][code][lane constant b2][0]
+                const unsigned sel = 0x0c020000u | ((4u + (unsigned)(c % 4)) << 8);
+                lds_entry_into<V>(blk, c * V * 2, __builtin_amdgcn_perm(w, base ? rep_v : rep_k, sel));
+                continue;
+            }
             unsigned off = (c % 4) == 0 ? byte_shl<0>(w, sh)
                            : (c % 4) == 1 ? byte_shl<1>(w, sh)
                            : (c % 4) == 2 ? byte_shl<2>(w, sh) : byte_shl<3>(w, sh);
@@ -378,15 +409,15 @@ size_t attn_decode_workspace(const vq_kv_t *kv) {
     return (size_t)kv->B * kv->H * S * (kv->D + 2) * sizeof(float);
 }
 
-template <int V, bool ONE, int SEQ>
+template <int V, bool ONE, int SEQ, bool REP = false>
 static int run_attn_seq(const AttnArgs &a, hipStream_t s) {
-    const size_t side = ONE ? 4096 : (size_t)a.G * a.E * V * sizeof(half_t);  // matches the kernel's layout
+    const size_t side = REP ? (size_t)kAttnRepSide : ONE ? 4096 : (size_t)a.G * a.E * V * sizeof(half_t);  // matches the kernel's layout
     size_t lds = 2 * side + (size_t)SEQ * kAttnWaves * (128 + 2) * sizeof(float);
     // the kernel forms absolute LDS addresses: refused here, with an error, if it ever had static LDS
     static KernelSetup setup;
-    if (int st = kernel_setup(reinterpret_cast<const void *>(&attn_decode_kernel<V, ONE, SEQ>), lds, true, setup)) return st;
+    if (int st = kernel_setup(reinterpret_cast<const void *>(&attn_decode_kernel<V, ONE, SEQ, REP>), lds, true, setup)) return st;
     const int groups = (a.B + SEQ - 1) / SEQ;
-    attn_decode_kernel<V, ONE, SEQ><<<dim3(groups * a.H, a.S), kAttnWaves * 64 * SEQ, lds, s>>>(a);
+    attn_decode_kernel<V, ONE, SEQ, REP><<<dim3(groups * a.H, a.S), kAttnWaves * 64 * SEQ, lds, s>>>(a);
     if (a.S > 1) attn_merge_kernel<<<a.B * a.H, 128, 0, s>>>(a.ws, a.out, a.S);
     return launch_status();
 }
@@ -396,6 +427,12 @@ static int run_attn(const AttnArgs &a, hipStream_t s) {
     // two sequences of a head per workgroup when the codebooks are so large that only one workgroup fits a CU
     const size_t side = ONE ? 4096 : (size_t)a.G * a.E * V * sizeof(half_t);
     if (!ONE && a.B >= 2 && 2 * (2 * side + 4200) > 160 * 1024) return run_attn_seq<V, false, 2>(a, s);
+    if constexpr (ONE && V == 4) {
+        // replicated codebooks (no bank conflicts) where pairs of sequences give every compute unit a workgroup:
+        // 128 KiB of LDS per workgroup, so exactly one fits
+        const long long wgs = (long long)((a.B + 1) / 2) * a.H * a.S;
+        if (a.B >= 2 && a.E * kAttnRepCopies * 8 <= kAttnRepSide && wgs >= kAttnRepMinWgs) return run_attn_seq<4, true, 2, true>(a, s);
+    }
     return run_attn_seq<V, ONE, 1>(a, s);
 }
 

@@ -546,6 +546,25 @@ def test_attn_two_sequences_per_workgroup_odd_batch_and_empty_sequences(gpu_devi
     assert_close(out, oracle_attn(kv, sm), "attn pairs")
 
 
+@pytest.mark.parametrize("B,H,T,E,lens", [
+    (3, 64, 1000, 256, [1000, 0, 513]),      # odd batch, an empty sequence, two token ranges per sequence
+    (4, 96, 300, 256, None),                 # one range, 192 workgroups
+    (2, 256, 77, 200, [77, 5]),              # fewer entries than 256, a single ragged tile
+])
+def test_attn_replicated_codebooks(gpu_device, B, H, T, E, lens):
+    """One codebook per head and side, enough (head, sequence pair) workgroups for one per compute unit: the
+    kernel with 32 copies of every entry in LDS (no bank conflicts), two sequences per workgroup."""
+    kv = wl.make_kv(B, H, 128, T, 4, E, 1, seed=5300 + B + H)
+    if lens is not None:
+        kv.seq_lens = np.array(lens, dtype=np.int32)
+    sm = 1.0 / np.sqrt(128.0)
+    out = run_attn(kv, gpu_device, sm)
+    assert_close(out, oracle_attn(kv, sm), f"attn replicated B{B} H{H} T{T}")
+    assert torch.equal(out, run_attn(kv, gpu_device, sm))
+    if lens is not None and 0 in lens:
+        assert (out[lens.index(0)] == 0).all()
+
+
 def test_attn_zero_length_sequence_and_sharp_softmax(gpu_device):
     kv = wl.make_kv(3, 2, 128, 600, 4, 256, 1, seed=5100)
     kv.seq_lens = np.array([600, 0, 1], dtype=np.int32)
