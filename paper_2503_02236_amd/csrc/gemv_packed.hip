@@ -518,6 +518,7 @@ struct AtomDecode {
     uint32_t emask4;   // ((1 << EB) - 1) << 4
     uint32_t eb, xb;   // field widths
     uint32_t xbase;    // byte address of position 0 of this lane's part
+    uint32_t ebase;    // byte address of the slice (a multiple of the slice size: OR-ed in); 0 in the one-image kernels
 };
 
 // NST steps at once (one or two): the 6 NST gathers (entry and x_j of every atom) are issued before the
@@ -536,7 +537,7 @@ __device__ __forceinline__ void steps_dot(const uint32_t (&lo)[NST], const uint3
     V16 e[3 * NST], xv[3 * NST];
 #pragma unroll
     for (int i = 0; i < 3 * NST; ++i) {
-        e[i] = lds_unit((at[i] << 4) & d.emask4);
+        e[i] = lds_unit(((at[i] << 4) & d.emask4) | d.ebase);
         xv[i] = lds_unit((__builtin_amdgcn_ubfe(at[i], d.eb, d.xb) << 4) + d.xbase);
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 6 * NST, 0);   // these LDS reads first,
@@ -807,6 +808,7 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     dec.emask4 = (slice_entries - 1u) << 4;
     dec.eb = (uint32_t)a.EB;
     dec.xb = (uint32_t)(kAtomBits - a.EB);
+    dec.ebase = 0u;
     // (4) gathers and dot products: lane = task; results go to LDS by slot.  The ring already holds the
     //     group's first PF steps.
     auto run_group = [&](const uint32_t n_steps, const uint32_t slot, gbyte_t *gbase) {
