@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--no-sequence", action="store_true",
                     help="separate vq_gemv_batch / vq_gemv calls (two launches each: product and its reduction) instead "
                          "of one vq_gemv_sequence over the stack (the reduction rides along in the next launch)")
+    ap.add_argument("--mode", choices=["pipeline", "streams"], default="pipeline",
+                    help="how the stack is issued: 'pipeline' = vq_gemv_pipeline (one persistent launch for all matrices "
+                         "plus one reduction launch), 'streams' = vq_gemv_sequence_streams (one launch per call)")
     ap.add_argument("--streams", type=int, default=4,
                     help="HIP streams the sequence is spread over (vq_gemv_sequence_streams; 1 = vq_gemv_sequence)")
     ap.add_argument("--only", default="", help="comma list of sections for profiling runs: gemv,gemm,attn,add,zipf,tile,bit12")
@@ -222,7 +225,18 @@ def main():
                 calls += block
         torch.cuda.synchronize()
 
-        if sequenced:
+        pipelined = sequenced and args.mode == "pipeline"
+        if pipelined:
+            # the whole stack as ONE persistent launch: every workgroup walks through all matrices, staging the next
+            # one's codebook slice and x while it gathers the current one
+            pipe = vq.GemvPipeline(seq_calls)
+            n_streams = 1
+
+            def step():
+                st = pipe.run()
+                if st != 0:
+                    raise vq.VQError(st, "vq_gemv_pipeline_run")
+        elif sequenced:
             # the whole stack as ONE vq_gemv_sequence: one launch per call, the reduction of each riding along
             # in the next, one reduction launch at the end
             seq = vq.GemvSequence(seq_calls)
@@ -294,6 +308,10 @@ def main():
         n_launch = len(calls)
         if not sequenced:
             n_streams = 1
+        if pipelined and pipe.status() != 0:
+            raise RuntimeError("vq_gemv_pipeline: a wavefront gave up a bounded wait; the timed runs are invalid")
+        n_dispatch = 2 if pipelined else n_launch + n_streams if sequenced else 2 * n_launch if packed else n_launch
+        main_launches = 1 if pipelined else n_launch
         result.update({
             "metric": "VQ-GEMV bs=1 effective HBM bandwidth, Llama-7B shapes, 2^16x8 codebook",
             "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -303,9 +321,12 @@ def main():
                                    "fp16 scale" % L,
                        "launches_per_step": n_launch, "matrices_per_step": len(singles),
                        "effective_bytes_per_step": eff_bytes,
-                       "kernel_dispatches_per_step": (n_launch + n_streams if sequenced else 2 * n_launch if packed else n_launch),
+                       "kernel_dispatches_per_step": n_dispatch,
                        "streams": n_streams if sequenced else 1,
-                       "calls": ("one vq_gemv_sequence_streams over the stack (contiguous runs of calls on %d streams); per "
+                       "calls": ("one vq_gemv_pipeline over the stack: a persistent launch of 256 workgroups that walk through "
+                                 "all %d matrices, plus one reduction launch" % len(singles)
+                                 if pipelined else
+                                 "one vq_gemv_sequence_streams over the stack (contiguous runs of calls on %d streams); per "
                                  "block the calls (q,k,v), (o), (gate,up), (down)" % n_streams
                                  if sequenced else
                                  "per block: vq_gemv_batch(q,k,v), vq_gemv(o), vq_gemv_batch(gate,up), vq_gemv(down)"
@@ -316,14 +337,15 @@ def main():
             "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
             "pct_measured_stream_read": round(100 * gbps / ceil_hbm, 2),
             "gemv_per_shape_cold": shape_us,
-            "roofline": {"bound": "hbm", "kernel": ("gemv_packed_batch_kernel / gemv_packed_kernel (reduction folded into the next launch)" if sequenced else
+            "roofline": {"bound": "hbm", "kernel": ("gemv_pipeline_kernel (one launch = the whole step)" if pipelined else
+                                    "gemv_packed_batch_kernel / gemv_packed_kernel (reduction folded into the next launch)" if sequenced else
                                     "gemv_packed_batch_kernel / gemv_packed_kernel (+ finalize)" if batched else
                                     "gemv_packed_kernel (+ finalize)" if packed else "gemv_rows_kernel<uint16,8,1>"),
                          "achieved": round(gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": round(gbps / HBM_PEAK_GBPS, 4),
                          "traffic": read_traffic(args.traffic_file) if batched else None,
-                         "bytes_per_launch": eff_bytes // n_launch,
-                         "avg_launch_us": round(ms_step * 1e3 / n_launch, 3)},
+                         "bytes_per_launch": eff_bytes // main_launches,
+                         "avg_launch_us": round(ms_step * 1e3 / main_launches, 3)},
         })
 
         # ---- CPU oracle baseline on a bounded sample: one decoder block (7 matrices), bs = 1

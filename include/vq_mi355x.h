@@ -252,6 +252,40 @@ int vq_gemv_sequence_streams(const vq_gemv_call_t *calls, int n_calls, void *ws,
 size_t vq_gemv_sequence_streams_workspace(const vq_gemv_call_t *calls, int n_calls, int n_streams);
 
 /*
+ * The same sequence as ONE persistent launch (plus one reduction launch): 256 workgroups, one per compute unit,
+ * each of which walks through a list of problems with two LDS images -- its producer wavefronts stage the
+ * codebook slice and x of problem k + 1 while its consumer wavefronts gather problem k, and the consumers'
+ * requests for re-tiled codes run two pieces of work ahead, across problem boundaries.  Separate launches
+ * (vq_gemv_sequence) run staging, gathers and stores of a product in lockstep on all units, so that memory, LDS
+ * and arithmetic take turns idling; at Llama-7B sizes each of these phases is 1 - 4 us long.  When every problem
+ * has row blocks enough, a workgroup takes 2 or 4 row blocks of its slice per image and the launch splits into 2
+ * or 4 lanes of workgroups that work on different problems at the same time.  (The dataflow inside a problem is
+ * that of Sec. VI-A: codebook slice in shared memory, split-x partial sums, explicit global reduction.)
+ * Contract as vq_gemv_sequence (independent calls, outputs complete when the whole run is); every output has the
+ * bits vq_gemv gives (the same additions in the same order).
+ *   vq_gemv_pipeline_create: validates the calls, writes the problem table into ws (a synchronous copy on
+ *     `stream`; calls and their arrays need not outlive the call) and returns a HOST handle.  x, y, weights and
+ *     ws are bound at creation: a pipeline is re-created when any of these pointers changes.
+ *     ws: device, 256-byte aligned (VQ_ERR_ALIGN), vq_gemv_pipeline_workspace(calls, n_calls) bytes, owned by the
+ *     caller and in use by the pipeline until it is destroyed.
+ *     VQ_ERR_UNSUPPORTED: a weight without re-tiled codes, or one that does not fit the persistent launch
+ *     (more than 256 row-block x slice workgroups, an LDS image above 64 KiB, x in more than about three parts).
+ *   vq_gemv_pipeline_run: two kernel launches on `stream`; no allocation, no synchronisation; capturable.  Runs of
+ *     one pipeline must not overlap (they share ws).  VQ_ERR_LAUNCH when called with another GPU current.
+ *   vq_gemv_pipeline_status: copies the device status word to *status (synchronises `stream`): 0, or 1 if a
+ *     wavefront of some run gave up one of its bounded waits inside the kernel (the outputs of that run are then
+ *     invalid; this takes a workgroup whose own wavefronts stop making progress for tens of milliseconds).
+ *   vq_gemv_pipeline_destroy: frees the handle (not ws); NULL is allowed.
+ */
+typedef struct vq_gemv_pipeline vq_gemv_pipeline_t;
+size_t vq_gemv_pipeline_workspace(const vq_gemv_call_t *calls, int n_calls);
+int vq_gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t ws_bytes, void *stream,
+                            vq_gemv_pipeline_t **out);
+int vq_gemv_pipeline_run(const vq_gemv_pipeline_t *p, void *stream);
+int vq_gemv_pipeline_status(const vq_gemv_pipeline_t *p, void *stream, int *status);
+void vq_gemv_pipeline_destroy(vq_gemv_pipeline_t *p);
+
+/*
  * VQ-gemm (prefill phase, Sec. III-C / Sec. VII "GeMM"): Y = X W^T with the
  * dequantized tile fed to the fp16 matrix cores, fp32 accumulation.
  *   Y[m][n] = scale[n] * sum_k W[n][k] * X[m][k],   m < M

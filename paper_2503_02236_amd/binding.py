@@ -81,6 +81,12 @@ SYMBOLS = {
     "vq_gemv_sequence_streams": (ctypes.c_int, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int, ctypes.c_void_p,
                                                 ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(vq_side_streams_t)]),
     "vq_gemv_sequence_streams_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int, ctypes.c_int]),
+    "vq_gemv_pipeline_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int]),
+    "vq_gemv_pipeline_create": (ctypes.c_int, [ctypes.POINTER(vq_gemv_call_t), ctypes.c_int, ctypes.c_void_p,
+                                                ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]),
+    "vq_gemv_pipeline_run": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p]),
+    "vq_gemv_pipeline_status": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)]),
+    "vq_gemv_pipeline_destroy": (None, [ctypes.c_void_p]),
     "vq_gemv_prepack_bytes": (ctypes.c_size_t, [ctypes.POINTER(vq_weight_t)]),
     "vq_gemv_prepack": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_size_t,
                                        ctypes.POINTER(vq_gemv_pack_t)]),
@@ -353,6 +359,45 @@ class GemvSequence:
 
     def run_streams(self, ws_ptr, ws_bytes, side: "SideStreams") -> int:
         return lib().vq_gemv_sequence_streams(self.arr, self.n, ws_ptr, ws_bytes, _stream(), ctypes.byref(side.c))
+
+
+class GemvPipeline:
+    """``vq_gemv_pipeline_*``: all products of a sequence in one persistent launch.  ``calls`` as for GemvSequence;
+    the workspace tensor (256-byte aligned, allocated here unless given) and the handle live as long as this object."""
+
+    def __init__(self, calls, ws: Optional[torch.Tensor] = None):
+        self.seq = GemvSequence(calls)
+        need = int(lib().vq_gemv_pipeline_workspace(self.seq.arr, self.seq.n))
+        self.handle = ctypes.c_void_p()
+        if need == 0:   # invalid calls: let create name the error
+            _check(lib().vq_gemv_pipeline_create(self.seq.arr, self.seq.n, None, 0, _stream(), ctypes.byref(self.handle)),
+                   "vq_gemv_pipeline_create")
+        device = calls[0][0][1].device
+        self.ws = ws if ws is not None else torch.empty(need + 256, dtype=torch.uint8, device=device)
+        base = self.ws.data_ptr()
+        self.ws_ptr = (base + 255) & ~255
+        self.ws_bytes = self.ws.numel() - (self.ws_ptr - base)
+        _check(lib().vq_gemv_pipeline_create(self.seq.arr, self.seq.n, self.ws_ptr, self.ws_bytes, _stream(),
+                                             ctypes.byref(self.handle)), "vq_gemv_pipeline_create")
+
+    def run(self) -> int:
+        return lib().vq_gemv_pipeline_run(self.handle, _stream())
+
+    def status(self) -> int:
+        v = ctypes.c_int(-1)
+        _check(lib().vq_gemv_pipeline_status(self.handle, _stream(), ctypes.byref(v)), "vq_gemv_pipeline_status")
+        return int(v.value)
+
+    def close(self):
+        if self.handle:
+            lib().vq_gemv_pipeline_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class SideStreams:

@@ -1,5 +1,7 @@
 // C ABI of libvqmi: host-side argument validation and dispatch to the gfx950 kernels.
 // Operand format and operations: VQ-LLM (arXiv 2503.02236) Sec. II-A, II-B, III-C.
+#include <new>
+
 #include "vq_common.h"
 
 namespace vq {
@@ -231,6 +233,59 @@ int vq_gemv_sequence(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t 
     if (!ws || ws_bytes < need) return VQ_ERR_WORKSPACE;
     if (!aligned16(ws)) return VQ_ERR_ALIGN;
     return launch_gemv_packed_sequence(calls, n_calls, ws, static_cast<hipStream_t>(stream));
+}
+
+struct vq_gemv_pipeline {
+    GemvPipeline *impl;
+};
+
+static int check_pipeline_calls(const vq_gemv_call_t *calls, int n_calls) {
+    if (!calls) return VQ_ERR_NULL;
+    if (n_calls < 1) return VQ_ERR_SHAPE;
+    for (int c = 0; c < n_calls; ++c) {
+        if (int st = check_sequence_call(&calls[c])) return st;
+        for (int i = 0; i < calls[c].count; ++i)
+            if (!gemv_pipeline_supports(calls[c].w[i])) return VQ_ERR_UNSUPPORTED;
+    }
+    return VQ_OK;
+}
+
+size_t vq_gemv_pipeline_workspace(const vq_gemv_call_t *calls, int n_calls) {
+    if (check_pipeline_calls(calls, n_calls) != VQ_OK) return 0;
+    return gemv_pipeline_workspace(calls, n_calls);
+}
+
+int vq_gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t ws_bytes, void *stream,
+                            vq_gemv_pipeline_t **out) {
+    if (!out) return VQ_ERR_NULL;
+    *out = nullptr;
+    if (int st = check_pipeline_calls(calls, n_calls)) return st;
+    if (!ws || ws_bytes < gemv_pipeline_workspace(calls, n_calls)) return VQ_ERR_WORKSPACE;
+    if (((uintptr_t)ws & 255) != 0) return VQ_ERR_ALIGN;
+    vq_gemv_pipeline *h = new (std::nothrow) vq_gemv_pipeline;
+    if (!h) return VQ_ERR_LAUNCH;
+    if (int st = gemv_pipeline_create(calls, n_calls, ws, static_cast<hipStream_t>(stream), &h->impl)) {
+        delete h;
+        return st;
+    }
+    *out = h;
+    return VQ_OK;
+}
+
+int vq_gemv_pipeline_run(const vq_gemv_pipeline_t *p, void *stream) {
+    if (!p || !p->impl) return VQ_ERR_NULL;
+    return launch_gemv_pipeline(p->impl, static_cast<hipStream_t>(stream));
+}
+
+int vq_gemv_pipeline_status(const vq_gemv_pipeline_t *p, void *stream, int *status) {
+    if (!p || !p->impl || !status) return VQ_ERR_NULL;
+    return gemv_pipeline_status(p->impl, static_cast<hipStream_t>(stream), status);
+}
+
+void vq_gemv_pipeline_destroy(vq_gemv_pipeline_t *p) {
+    if (!p) return;
+    gemv_pipeline_destroy(p->impl);
+    delete p;
 }
 
 // Run r of n_runs contiguous runs of the calls: [first, first + count).

@@ -56,6 +56,8 @@
 #include <cstring>
 #include <thread>
 #include <type_traits>
+#include <cstddef>
+#include <new>
 #include <vector>
 
 #include "vq_common.h"
@@ -546,6 +548,66 @@ __device__ __forceinline__ void steps_dot(const uint32_t (&lo)[NST], const uint3
     for (int i = 0; i < 3 * NST; ++i) acc.a[i % 3] = atom_fma(e[i], xv[i], acc.a[i % 3]);
 }
 
+// (pointers that went through pin_scalar, or came out of a table, have to be told that they are global)
+typedef const __attribute__((address_space(1))) unsigned char gbyte_t;
+typedef const __attribute__((address_space(1))) uint16_t gu16_t;
+typedef const __attribute__((address_space(1))) uint32_t gu32_t;
+typedef const __attribute__((address_space(4))) uint32_t cu32_t;   // read with scalar loads
+
+// Step st of the group whose first block this lane sees at `base`.  No look at the group's length: a
+// branch around a load keeps the compiler from counting which loads are in flight (it then waits for
+// all of them before every use), and a clamp costs more instructions than the load.  Blocks past the
+// end of a group belong to the next one, or to the tail of the buffer, and are never used.
+__device__ __forceinline__ void load_step(uint32_t (&dst)[2], gbyte_t *base, uint32_t st) {
+    gu32_t *p = (gu32_t *)(base + (size_t)st * kStepBytes);
+    dst[0] = p[0]; dst[1] = p[1];
+}
+
+// The sum of one task (lane) over the n_steps steps of its group.  The ring q holds the group's first PF
+// steps (requested, not necessarily landed); slot k is refilled with step st + PF as soon as step st has been
+// taken out of it -- except in the group's last round: what would be requested there lies past the end of the
+// group.  Steps are taken two at a time when PAIR.
+template <int PF, bool PAIR>
+__device__ __forceinline__ float unit_sum(uint32_t (&q)[PF][2], gbyte_t *gbase, const uint32_t n_steps, const AtomDecode &dec) {
+    static_assert(!PAIR || PF % 2 == 0, "steps are taken two at a time");
+    static_assert(2 * PF - 2 <= kPackTailBlocks, "reads run up to 2 PF - 2 blocks past the end of a group");
+    Acc3 acc = {{0.f, 0.f, 0.f}};
+    auto ring_round = [&](uint32_t base, auto refill_tag) {
+        if constexpr (PAIR) {
+#pragma unroll
+            for (int k = 0; k < PF; k += 2) {
+                const uint32_t lo[2] = {q[k][0], q[k + 1][0]}, hi[2] = {q[k][1], q[k + 1][1]};
+                if constexpr (decltype(refill_tag)::value) {
+                    load_step(q[k], gbase, base + k + PF);
+                    load_step(q[k + 1], gbase, base + k + 1 + PF);
+                }
+                if (base + k + 1 < n_steps) {
+                    steps_dot<2>(lo, hi, dec, acc);
+                } else if (base + k < n_steps) {
+                    const uint32_t lo1[1] = {lo[0]}, hi1[1] = {hi[0]};
+                    steps_dot<1>(lo1, hi1, dec, acc);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < PF; ++k) {
+                const uint32_t lo1[1] = {q[k][0]}, hi1[1] = {q[k][1]};
+                if constexpr (decltype(refill_tag)::value) load_step(q[k], gbase, base + k + PF);
+                if (base + k < n_steps) steps_dot<1>(lo1, hi1, dec, acc);
+            }
+        }
+    };
+    // (the first round outside the loop: at a loop head the ring would be copied, and a copy needs
+    // all of its data)
+    uint32_t base = 0;
+    if (n_steps > (uint32_t)PF) {
+        ring_round(0, std::true_type{});
+        for (base = PF; base + PF < n_steps; base += PF) ring_round(base, std::true_type{});
+    }
+    if (n_steps > 0) ring_round(base, std::false_type{});
+    return (acc.a[0] + acc.a[1]) + acc.a[2];
+}
+
 // Direct global -> LDS transfers (no registers).  M0 is written and used inside one asm statement only; it is a
 // reserved register that the compiler neither allocates nor accepts in a clobber list, and nothing else in
 // these kernels uses it.
@@ -563,6 +625,48 @@ __device__ __forceinline__ void dma_4k(const uint4 *src_lane, unsigned char *dst
                  "global_load_lds_dwordx4 %1, off offset:1024\n\t"
                  "global_load_lds_dwordx4 %1, off offset:2048\n\t"
                  "global_load_lds_dwordx4 %1, off offset:3072" ::"s"(m0), "v"(src_lane) : "memory");
+}
+
+// Workgroup number -> (codebook slice, row block).  Workgroups are dealt round-robin to the 8 compute dies, each
+// with its own L2.  All row blocks of one codebook slice run on the same die, so a slice is fetched from memory
+// by one L2 only (otherwise every die pulls the whole 1 MiB codebook: 8 MiB per launch).
+__device__ __forceinline__ void slice_and_block(int bid, int S, int RB, int &s, int &rb) {
+    if (S % 8 == 0) {  // S is a power of two: shifts instead of a division
+        const int die = bid & 7, local = bid >> 3, per_die = S >> 3, sh = __builtin_ctz(per_die);
+        s = die * per_die + (local & (per_die - 1));
+        rb = local >> sh;
+    } else {
+        s = bid / RB;
+        rb = bid % RB;
+    }
+}
+
+// The LDS image of one workgroup: codebook slice s, then the parts of x with kZeroUnits zero units (what padding
+// atoms point at) behind each.  Wavefronts wave = 0 .. nwaves - 1 share the transfers: 4 KiB chunks dealt in turn.
+__device__ __forceinline__ void stage_image(const half_t *cb, const half_t *x, int s, uint32_t slice_entries, int P, int Jp,
+                                            int J, unsigned char *img, int wave, int nwaves, int lane) {
+    const uint32_t slice_bytes = slice_entries * 16u;
+    const uint32_t part_pitch = ((uint32_t)Jp + kZeroUnits) * 16u;
+    unsigned char *xl = img + slice_bytes;
+    const uint4 *src = reinterpret_cast<const uint4 *>(cb) + (size_t)s * slice_entries;
+    const uint4 *xs = reinterpret_cast<const uint4 *>(x);
+    const int slice_chunks = (int)(slice_bytes >> 12);          // slices are multiples of 256 entries
+    for (int c = wave; c < slice_chunks; c += nwaves) dma_4k(src + c * 256 + lane, img + c * 4096);
+    int turn = slice_chunks;   // whose turn the next chunk is
+    for (int p = 0; p < P; ++p) {
+        const int len = min(Jp, J - p * Jp);   // positions of this part
+        const uint4 *xp = xs + p * Jp;
+        unsigned char *dst = xl + (size_t)p * part_pitch;
+        const int full = len >> 8;             // whole 4 KiB chunks
+        for (int c = 0; c < full; ++c, ++turn)
+            if (turn % nwaves == wave) dma_4k(xp + c * 256 + lane, dst + c * 4096);
+        if ((len & 255) && turn % nwaves == wave)    // the rest of the part: up to three transfers, the last one partly masked
+            for (int t = full * 4; t * 64 < len; ++t)
+                if (t * 64 + lane < len) dma_1k(xp + t * 64 + lane, dst + t * 1024);
+        turn += (len & 255) ? 1 : 0;
+    }
+    for (int i = wave * 64 + lane; i < P * 64; i += nwaves * 64)
+        reinterpret_cast<uint32_t *>(xl + (size_t)(i >> 6) * part_pitch + (size_t)Jp * 16)[i & 63] = 0u;
 }
 
 // ---- the global reduction of the PREVIOUS launch, done in the prologue and epilogue of this one -------------
@@ -659,7 +763,6 @@ __device__ __forceinline__ void fin_complete(const FinBlock &f, uint32_t scale_b
 template <int PF, bool PAIR, int AHEAD = kPackAhead>
 __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int bid, const PendingArgs &pd, const int wg_linear) {
     extern __shared__ __align__(16) unsigned char smem[];
-    static_assert(!PAIR || PF % 2 == 0, "steps are taken two at a time");
     static_assert(AHEAD <= PF, "the ring holds what is requested ahead");
     // all launch arguments in one round of scalar loads
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: group lookups, block numbers and
@@ -688,24 +791,9 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     unsigned char *fin = reinterpret_cast<unsigned char *>(accbuf + (size_t)a.rows_per_block * a.P);   // [kFinChunks][32][64] floats, only with pending rows
 
     const int tid = threadIdx.x, lane = tid & 63, nwaves = a.nwaves;
-    // Workgroups are dealt round-robin to the 8 compute dies, each with its own L2.  All row blocks of
-    // one codebook slice run on the same die, so a slice is fetched from memory by one L2 only
-    // (otherwise every die pulls the whole 1 MiB codebook: 8 MiB per launch).
     int s, rb;
-    if (a.S % 8 == 0) {  // S is a power of two: shifts instead of a division
-        const int die = bid & 7, local = bid >> 3, per_die = a.S >> 3, sh = __builtin_ctz(per_die);
-        s = die * per_die + (local & (per_die - 1));
-        rb = local >> sh;
-    } else {
-        s = bid / a.RB;
-        rb = bid % a.RB;
-    }
+    slice_and_block(bid, a.S, a.RB, s, rb);
     const int wg = s * a.RB + rb;  // index into the packed tables
-    // (the pinned pointers went through an asm statement and have to be told again that they are global)
-    typedef const __attribute__((address_space(1))) unsigned char gbyte_t;
-    typedef const __attribute__((address_space(1))) uint16_t gu16_t;
-    typedef const __attribute__((address_space(1))) uint32_t gu32_t;
-    typedef const __attribute__((address_space(4))) uint32_t cu32_t;   // read with scalar loads
     gbyte_t *gdata = (gbyte_t *)a.data;
     gu16_t *tasks = (gu16_t *)(gdata + a.task_off) + (size_t)wg * a.n_groups * 64;
     cu32_t *own_steps = (cu32_t *)(a.data + a.steps_off) + (size_t)wg * a.n_groups;
@@ -724,43 +812,13 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
     //     wavefront (measured: four transfers with four M0 writes take 260 - 300 ns to issue, against 50 ns with
     //     one).  The instruction's immediate offset moves the global address and the LDS address alike, so a
     //     contiguous 4 KiB goes out as one M0 write and four transfers.
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(a.cb) + (size_t)s * slice_entries;
-        const uint4 *xs = reinterpret_cast<const uint4 *>(a.x);
-        const int slice_chunks = (int)(slice_bytes >> 12);          // slices are multiples of 256 entries
-        for (int c = wave; c < slice_chunks; c += nwaves) dma_4k(src + c * 256 + lane, smem + c * 4096);
-        int turn = slice_chunks;   // whose turn the next chunk is: chunks are dealt to the wavefronts in turn
-        for (int p = 0; p < a.P; ++p) {
-            const int len = min(a.Jp, a.J - p * a.Jp);   // positions of this part
-            const uint4 *xp = xs + p * a.Jp;
-            unsigned char *dst = xl + (size_t)p * part_pitch;
-            const int full = len >> 8;                   // whole 4 KiB chunks
-            for (int c = 0; c < full; ++c, ++turn)
-                if (turn % nwaves == wave) dma_4k(xp + c * 256 + lane, dst + c * 4096);
-            if ((len & 255) && turn % nwaves == wave)    // the rest of the part: up to three transfers, the last one partly masked
-                for (int t = full * 4; t * 64 < len; ++t)
-                    if (t * 64 + lane < len) dma_1k(xp + t * 64 + lane, dst + t * 1024);
-            turn += (len & 255) ? 1 : 0;
-        }
-        // what padding atoms point at: 16 zero units (64 dwords) behind every part
-        for (int i = tid; i < a.P * 64; i += nwaves * 64)
-            reinterpret_cast<uint32_t *>(xl + (size_t)(i >> 6) * part_pitch + (size_t)a.Jp * 16)[i & 63] = 0u;
-    }
+    stage_image(a.cb, a.x, s, slice_entries, a.P, a.Jp, a.J, smem, wave, nwaves, lane);
     // (2) this wavefront's first group: where its atoms lie follows from the launch arguments alone, so
     //     the task slots and the atoms are requested right behind the slice.  Loads complete in the order
     //     they were issued, so the wait below counts the loads of this step as still in flight and lets
     //     the gathers start as soon as the slice and x are in, while the atoms stream in behind them.
     //     The empty statement keeps the compiler from moving a load above the staging transfers.
     asm volatile("" ::: "memory");
-    // Step st of the group whose first block this lane sees at `base`.  No look at the group's length: a
-    // branch around a load keeps the compiler from counting which loads are in flight (it then waits for
-    // all of them before every use), and a clamp costs more instructions than the load.  Blocks past the
-    // end of a group belong to the next one, or to the tail of the buffer, and are never used.
-    static_assert(2 * PF - 2 <= kPackTailBlocks, "reads run up to 2 PF - 2 blocks past the end of a group");
-    auto load_step = [&](uint32_t (&dst)[2], gbyte_t *base, uint32_t st) {
-        gu32_t *p = (gu32_t *)(base + (size_t)st * kStepBytes);
-        dst[0] = p[0]; dst[1] = p[1];
-    };
     auto group_base = [&](uint32_t word) { return atoms + (size_t)(word >> 16) * kStepBytes + lane_off; };
     // Every wavefront issues the same AHEAD + 1 loads, so the count in the wait holds for all of them.
     const bool has_group = wave < a.n_groups;
@@ -816,43 +874,8 @@ __device__ __forceinline__ void gemv_packed_body(const PackedArgs &ka, const int
         uint32_t part = 0;
         for (int p = 1; p < a.P; ++p) part += (slot != 0xFFFFu && slot >= (uint32_t)(p * a.rows_per_block)) ? 1u : 0u;
         dec.xbase = slice_bytes + part * part_pitch;
-        Acc3 acc = {{0.f, 0.f, 0.f}};
-        // slot k is refilled with step st + PF as soon as step st has been taken out of it -- except in the
-        // group's last round: what would be requested there lies past the end of the group.
-        auto ring_round = [&](uint32_t base, auto refill_tag) {
-            if constexpr (PAIR) {
-#pragma unroll
-                for (int k = 0; k < PF; k += 2) {
-                    const uint32_t lo[2] = {q[k][0], q[k + 1][0]}, hi[2] = {q[k][1], q[k + 1][1]};
-                    if constexpr (decltype(refill_tag)::value) {
-                        load_step(q[k], gbase, base + k + PF);
-                        load_step(q[k + 1], gbase, base + k + 1 + PF);
-                    }
-                    if (base + k + 1 < n_steps) {
-                        steps_dot<2>(lo, hi, dec, acc);
-                    } else if (base + k < n_steps) {
-                        const uint32_t lo1[1] = {lo[0]}, hi1[1] = {hi[0]};
-                        steps_dot<1>(lo1, hi1, dec, acc);
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int k = 0; k < PF; ++k) {
-                    const uint32_t lo1[1] = {q[k][0]}, hi1[1] = {q[k][1]};
-                    if constexpr (decltype(refill_tag)::value) load_step(q[k], gbase, base + k + PF);
-                    if (base + k < n_steps) steps_dot<1>(lo1, hi1, dec, acc);
-                }
-            }
-        };
-        // (the first round outside the loop: at a loop head the ring would be copied, and a copy needs
-        // all of its data)
-        uint32_t base = 0;
-        if (n_steps > (uint32_t)PF) {
-            ring_round(0, std::true_type{});
-            for (base = PF; base + PF < n_steps; base += PF) ring_round(base, std::true_type{});
-        }
-        if (n_steps > 0) ring_round(base, std::false_type{});
-        if (slot != 0xFFFFu) accbuf[slot] = (acc.a[0] + acc.a[1]) + acc.a[2];
+        const float sum = unit_sum<PF, PAIR>(q, gbase, n_steps, dec);
+        if (slot != 0xFFFFu) accbuf[slot] = sum;
     };
     if (has_group) run_group(my_steps, slot, gbase);
     for (int g = wave + nwaves; g < a.n_groups; g += nwaves) {  // only when a block has more groups than wavefronts
@@ -964,6 +987,404 @@ __global__ __launch_bounds__(kFinalizeRows) void gemv_packed_finalize_batch_kern
     FinalizeArgs a = b.a[blockIdx.y];
     pin_scalar(a.partial); pin_scalar(a.scale); pin_scalar(a.y); pin_scalar(a.N); pin_scalar(a.S);
     gemv_packed_finalize_body<kPackMaxSlices>(a.partial, a.scale, a.y, a.N, a.S);
+}
+
+// ------------------------------------------------------------------------ pipelined kernel
+// Many products in ONE launch of 256 persistent workgroups (one per compute unit).  A launch of the kernel above
+// runs its phases in lockstep on all units -- staging (latency bound, LDS and arithmetic idle), gathers (LDS
+// bound, memory idle for want of requests), stores -- and at Llama sizes each phase is 1 - 4 us long.  Here a
+// workgroup holds TWO LDS images: while its consumer wavefronts gather problem k from one, its producer
+// wavefronts stage problem k + 1 into the other, and the atom requests of the consumers run one group ahead,
+// across problem boundaries.  Workgroup b of the launch takes block b of EVERY problem.
+//
+// Synchronisation inside the workgroup is by four LDS counters instead of barriers (a barrier would make
+// every wavefront wait for the slowest of each problem):
+//   staged[k & 1]: +1 by each producer when its share of problem k has landed   (k staged: >= NP (k/2 + 1))
+//   done  [k & 1]: +1 by each consumer when it has left problem k               (k done:   >= NC (k/2 + 1))
+// A consumer enters problem k after seeing it staged; a producer stages k after seeing k - 2 done.  No wavefront
+// can be two problems ahead of another, so the counters of one parity are never ambiguous.  A consumer writes
+// the sum of a task straight to global memory: one partial sum per (row, slice, part of the row), S * P per row.  Every wait is bounded: after
+// kPipeSpinLimit looks a wavefront gives up waiting for the rest of the launch and raises the status word,
+// so the grid always drains.
+// The S partial sums per row of all problems are added by one reduction launch behind it.
+constexpr int kPipeWgs = 256;
+constexpr int kPipeConsumers = 13, kPipeProducers = 2;   // wavefronts 0 .. 12 and 14, 15; wavefront 13 is the scout
+constexpr int kPipeScout = kPipeConsumers, kPipeFirstProducer = kPipeConsumers + 1;
+constexpr int kPipeOps = 12;                            // staging operations per producer and problem
+constexpr uint32_t kPipeImage = 65536;                  // LDS bytes from one image to the other
+constexpr uint32_t kPipeFlags = 2 * kPipeImage;         // staged[2], done[2]
+constexpr uint32_t kPipeLds = kPipeFlags + 64;
+constexpr uint32_t kPipeSpinLimit = 1u << 20;
+
+// One problem as the kernel reads it (a table in device memory, written once when the pipeline is created).
+struct PipeProblem {
+    const unsigned char *atoms, *tasks, *steps;   // the three regions of the packed buffer
+    const half_t *cb, *x;
+    float *partial;
+    const half_t *scale;
+    half_t *y;
+    int N, J, S, RB, rows_per_block, EB, P, Jp, n_groups;
+    uint32_t wg_pitch;
+    uint32_t item_first;   // groups of all earlier problems: group g of this one is item item_first + g
+    uint32_t item_end;
+    uint32_t bpi;          // row blocks per LDS image: a workgroup of the launch takes bpi consecutive row blocks of its slice
+    uint32_t pad[3];
+    // How producer w builds the LDS image, worked out on the host (the kernel's instruction issue is a scarce
+    // resource: four wavefronts per SIMD): pairs (source byte offset, PipeOp word), the list ends at a zero word.
+    uint32_t ops[kPipeProducers][kPipeOps][2];
+    uint32_t group[VQ_PACK_MAX_GROUPS];   // prefix << 16 | common steps
+};
+static_assert(sizeof(PipeProblem) % 64 == 0 && offsetof(PipeProblem, ops) == 128, "the scout touches the descriptor by 64-byte lines");
+// PipeOp word: bits 0..16 LDS byte offset in the image, 17..18 kind, 19..25 lanes (kind 2), 31 valid.
+enum : uint32_t {
+    kOpSlice4k = 0,   // 4 KiB of the codebook slice (source offset from the slice)
+    kOpX4k = 1,       // 4 KiB of x
+    kOpX1k = 2,       // up to 1 KiB of x: `lanes` units of 16 bytes
+    kOpZero = 3,      // 256 zero bytes (the units behind a part of x that padding atoms point at)
+};
+__host__ __device__ constexpr uint32_t pipe_op(uint32_t lds_off, uint32_t kind, uint32_t lanes) {
+    return lds_off | (kind << 17) | (lanes << 19) | (1u << 31);
+}
+typedef const __attribute__((address_space(4))) PipeProblem cproblem_t;   // read with scalar loads
+typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
+
+struct PipeSync {
+    bool broken;          // a wait ran out: no more waiting in this wavefront (it raises the status word when it ends)
+};
+// Waits until the LDS counter at `addr` has reached `target`.
+__device__ __forceinline__ void pipe_wait(uint32_t addr, uint32_t target, PipeSync &sy) {
+    if (!sy.broken) {
+        uint32_t spin = 0;
+        for (;;) {
+            const uint32_t v = __builtin_amdgcn_readfirstlane(
+                __hip_atomic_load((lds_u32_t *)(uintptr_t)addr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+            if (v >= target) break;
+            if (++spin == kPipeSpinLimit) {
+                sy.broken = true;   // (no store here: a memory operation inside this loop would keep the compiler
+                break;              // from counting the requests in flight around it)
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+    }
+    asm volatile("" ::: "memory");   // what follows reads what the counter announces
+}
+// +1 on an LDS counter, after everything this wavefront wrote to LDS before.
+__device__ __forceinline__ void pipe_signal(uint32_t addr, int lane) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (lane == 0) __hip_atomic_fetch_add((lds_u32_t *)(uintptr_t)addr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// A consumer's unit of work: up to PF consecutive steps of group g of problem i (of this workgroup's block), all
+// of them requested at once.  A group of more steps is taken in several pieces, one after the other by the
+// same wavefront, the sums carried in registers.
+template <int PF>
+struct PipePiece {
+    uint32_t i;          // problem (n: no more work)
+    uint32_t valid;      // the workgroup has a block of this problem
+    uint32_t first;      // first step of the piece in its group
+    uint32_t last;       // the group ends with this piece
+    uint32_t EB, P, Jp, rows_per_block;
+    uint32_t N, planes, plane0, row0;   // rows of the matrix; S * P; s * P; first row of the block
+    float *partial;
+    uint32_t slot, steps_v;
+    uint32_t q[PF][2];
+};
+// Partial sums of a pipelined problem: blocks of 64 rows, [block][slice * P + part][row % 64].
+__host__ __device__ __forceinline__ size_t pipe_partial_index(uint32_t planes, uint32_t plane, uint32_t row) {
+    return ((size_t)(row >> 6) * planes + plane) * 64 + (row & 63);
+}
+// What a consumer requests next: piece h of flat group t (groups of all problems numbered through), which lies in
+// problem i or a later one.
+struct PipeCursor {
+    uint32_t t, i, h;
+};
+
+template <int PF>
+__device__ __forceinline__ void pipe_fetch(PipePiece<PF> &it, PipeCursor &cu, cproblem_t *table, uint32_t n, uint32_t total_items,
+                                           int bid, int lane, uint32_t zero_v) {
+    const bool none = cu.t >= total_items;
+    const uint32_t tt = none ? total_items - 1 : cu.t;   // (past the end: the last group's loads once more, never used)
+    uint32_t i = cu.i;
+    while (tt >= table[i].item_end) ++i;
+    i = __builtin_amdgcn_readfirstlane(i);
+    cproblem_t &pr = table[i];
+    const int S = pr.S, RB = pr.RB, ng = pr.n_groups, bpi = (int)pr.bpi;
+    // item -> (row block of the image, group): the groups of the first row block, then those of the second, ...
+    uint32_t g = tt - pr.item_first;
+    int jb = 0;
+    while (g >= (uint32_t)ng) { g -= (uint32_t)ng; ++jb; }
+    const int RBv = RB / bpi;   // (bpi is 1, 2 or 4 and divides RB)
+    const bool in = bid < S * RBv;
+    int s, rb;
+    slice_and_block(in ? bid : 0, S, RBv, s, rb);
+    rb = rb * bpi + jb;
+    const uint32_t wg = (uint32_t)(s * RB + rb);
+    const uint32_t word = pr.group[g];
+    const uint32_t common = word & 0xFFFFu, first = cu.h * PF;
+    gbyte_t *gbase = (gbyte_t *)pr.atoms + ((size_t)wg * pr.wg_pitch + (word >> 16) + first) * kStepBytes + (uint32_t)lane * 8u;
+    // (a vector load of one address: a scalar load would be waited for with the next LDS read.  The address is a
+    // scalar base plus a register that holds 0 for the whole kernel, so that no register is written here that an
+    // earlier request may still be writing to.)
+    it.steps_v = *(gu32_t *)((gbyte_t *)((gu32_t *)pr.steps + (wg * (uint32_t)ng + g)) + zero_v);
+    it.slot = ((gu16_t *)pr.tasks)[(size_t)(wg * (uint32_t)ng + g) * 64 + lane];
+#pragma unroll
+    for (int st = 0; st < PF; ++st) load_step(it.q[st], gbase, st);
+    it.i = none ? n : i;
+    it.valid = (in && !none) ? 1u : 0u;
+    it.first = first;
+    it.last = first + PF >= common ? 1u : 0u;
+    it.EB = (uint32_t)pr.EB; it.P = (uint32_t)pr.P; it.Jp = (uint32_t)pr.Jp; it.rows_per_block = (uint32_t)pr.rows_per_block;
+    it.N = (uint32_t)pr.N; it.planes = (uint32_t)(S * pr.P); it.plane0 = (uint32_t)(s * pr.P);
+    it.row0 = (uint32_t)(rb * pr.rows_per_block);
+    it.partial = pr.partial;
+    // what comes after this piece
+    cu.i = i;
+    if (it.last) { cu.t += kPipeConsumers; cu.h = 0; } else { ++cu.h; }
+}
+
+// Where a consumer stands: in problem `cur` (seen staged), all earlier ones left.
+struct PipeConsumer {
+    uint32_t cur, n;
+    PipeSync sy;
+};
+__device__ __forceinline__ void pipe_enter(PipeConsumer &c, uint32_t k) {
+    pipe_wait(kPipeFlags + (k & 1u) * 4u, (uint32_t)kPipeProducers * (k / 2u + 1u), c.sy);
+}
+// Leaves problems until it stands in problem `to` (n: until the end).
+__device__ __forceinline__ void pipe_advance(PipeConsumer &c, uint32_t to, int lane) {
+    while (c.cur < to) {
+        pipe_signal(kPipeFlags + 8u + (c.cur & 1u) * 4u, lane);
+        ++c.cur;
+        if (c.cur < c.n) pipe_enter(c, c.cur);
+    }
+}
+
+template <int PF>
+__device__ __forceinline__ void pipe_consume(PipePiece<PF> &it, Acc3 &acc, PipeConsumer &c, int lane) {
+    static_assert(PF % 2 == 0 && PF <= kPackTailBlocks, "steps in pairs; requests run up to PF - 1 blocks past the end of a group");
+    pipe_advance(c, it.i, lane);
+    if (it.i >= c.n) return;
+    const uint32_t own = it.valid ? __builtin_amdgcn_readfirstlane(it.steps_v) : 0u;
+    const uint32_t n_steps = own > it.first ? own - it.first : 0u;   // of this piece (those past PF belong to the next one)
+    const uint32_t slot = it.valid ? it.slot : 0xFFFFu;
+    const uint32_t img = (it.i & 1u) * kPipeImage;
+    const uint32_t slice_bytes = 16u << it.EB, part_pitch = (it.Jp + kZeroUnits) * 16u;
+    uint32_t part = 0;
+    for (uint32_t p = 1; p < it.P; ++p) part += (slot != 0xFFFFu && slot >= p * it.rows_per_block) ? 1u : 0u;
+    AtomDecode dec;
+    dec.emask4 = ((1u << it.EB) - 1u) << 4;
+    dec.eb = it.EB;
+    dec.xb = (uint32_t)kAtomBits - it.EB;
+    dec.ebase = img;
+    dec.xbase = img + slice_bytes + part * part_pitch;
+    if (it.first == 0) acc = {{0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int k = 0; k < PF; k += 2) {
+        const uint32_t lo[2] = {it.q[k][0], it.q[k + 1][0]}, hi[2] = {it.q[k][1], it.q[k + 1][1]};
+        if ((uint32_t)k + 1 < n_steps) {
+            steps_dot<2>(lo, hi, dec, acc);
+        } else if ((uint32_t)k < n_steps) {
+            const uint32_t lo1[1] = {lo[0]}, hi1[1] = {hi[0]};
+            steps_dot<1>(lo1, hi1, dec, acc);
+        }
+    }
+    if (it.last && slot != 0xFFFFu) {
+        const uint32_t row = it.row0 + (slot - part * it.rows_per_block);
+        if (row < it.N)
+            ((__attribute__((address_space(1))) float *)it.partial)[pipe_partial_index(it.planes, it.plane0 + part, row)] =
+                (acc.a[0] + acc.a[1]) + acc.a[2];
+    }
+}
+// Declares every requested step of a piece used.  The steps past the end of a short group are never looked at, and
+// the compiler would hand their registers out again while the requests are still in flight -- which costs a wait
+// for (nearly) everything in flight, the other piece's requests included.  After this, what is in flight is the
+// other piece's requests and nothing else.
+template <int PF>
+__device__ __forceinline__ void pipe_retire(const PipePiece<PF> &it) {
+#pragma unroll
+    for (int k = 0; k < PF; ++k) asm volatile("" ::"v"(it.q[k][0]), "v"(it.q[k][1]));
+    asm volatile("" ::"v"(it.slot), "v"(it.steps_v));
+}
+
+// Producer w's share of the image of problem k, from the list the host prepared: read (all of it, into scalar
+// registers) before the producer starts waiting for its turn, carried out after.
+struct PipeStage {
+    const uint4 *slice, *x;
+    uint32_t op[kPipeOps][2];
+};
+__device__ __forceinline__ PipeStage pipe_stage_read(cproblem_t *table, uint32_t k, int bid, int pw) {
+    cproblem_t &pr = table[k];
+    PipeStage st;
+    const int S = pr.S, RB = pr.RB / (int)pr.bpi;
+    const bool mine = bid < S * RB;
+    int s, rb;
+    slice_and_block(mine ? bid : 0, S, RB, s, rb);
+    st.slice = reinterpret_cast<const uint4 *>(pr.cb) + ((size_t)s << pr.EB);
+    st.x = reinterpret_cast<const uint4 *>(pr.x);
+    pin_scalar(st.slice); pin_scalar(st.x);
+#pragma unroll
+    for (int j = 0; j < kPipeOps; ++j) {
+        st.op[j][0] = pr.ops[pw][j][0];
+        st.op[j][1] = mine ? pr.ops[pw][j][1] : 0u;
+        pin_scalar(st.op[j][0]); pin_scalar(st.op[j][1]);
+    }
+    return st;
+}
+__device__ __forceinline__ void pipe_stage(const PipeStage &st, int lane, unsigned char *img) {
+#pragma unroll
+    for (int j = 0; j < kPipeOps; ++j) {
+        const uint32_t src = st.op[j][0], w = st.op[j][1];
+        if (w == 0u) break;
+        unsigned char *dst = img + (w & 0x1FFFFu);
+        const uint32_t kind = (w >> 17) & 3u;
+        if (kind == kOpSlice4k) {
+            dma_4k(st.slice + (src >> 4) + lane, dst);
+        } else if (kind == kOpX4k) {
+            dma_4k(st.x + (src >> 4) + lane, dst);
+        } else if (kind == kOpX1k) {
+            if ((uint32_t)lane < ((w >> 19) & 127u)) dma_1k(st.x + (src >> 4) + lane, dst);
+        } else {
+            reinterpret_cast<uint32_t *>(dst)[lane] = 0u;
+        }
+    }
+}
+
+// The scout runs ahead of everybody: it reads the descriptor of a coming problem through the scalar cache and
+// touches the lines of its codebook slice and of its x, so that the producers' and consumers' scalar loads hit
+// the scalar cache and the producers' transfers hit this die's L2.  A first touch of anything costs a trip to
+// memory, 1.5 - 2 us under this load: as long as a short problem's gathers.
+__device__ __forceinline__ void pipe_scout(cproblem_t *table, uint32_t n, int bid, int lane, PipeSync &sy) {
+    for (uint32_t k = 0; k < n; ++k) {
+        // not more than three problems ahead of the slowest consumer: what is touched must still be cached when used
+        if (k >= 3) pipe_wait(kPipeFlags + 8u + ((k - 3u) & 1u) * 4u, (uint32_t)kPipeConsumers * ((k - 3u) / 2u + 1u), sy);
+        cu32_t *words = (cu32_t *)&table[k];
+        uint32_t acc = 0;
+#pragma unroll
+        for (int l = 0; l < (int)(sizeof(PipeProblem) / 64); ++l) acc |= words[l * 16];   // (one word per 64-byte line)
+        asm volatile("" ::"s"(acc));
+        cproblem_t &pr = table[k];
+        const int S = pr.S, RB = pr.RB / (int)pr.bpi;
+        uint32_t warm = 0u;
+        if (bid < S * RB) {
+            int s, rb;
+            slice_and_block(bid, S, RB, s, rb);
+            const uint32_t slice_bytes = 16u << pr.EB, x_bytes = (uint32_t)pr.J * 16u;
+            const gbyte_t *slice = (gbyte_t *)pr.cb + (size_t)s * slice_bytes;
+            const gbyte_t *x = (gbyte_t *)pr.x;
+            for (uint32_t line = (uint32_t)lane * 128u; line < slice_bytes; line += 64u * 128u)
+                warm |= *(const volatile gu32_t *)(slice + line);
+            for (uint32_t line = (uint32_t)lane * 128u; line < x_bytes; line += 64u * 128u)
+                warm |= *(const volatile gu32_t *)(x + line);
+        }
+        asm volatile("" ::"v"(warm));
+    }
+}
+
+// The 256 workgroups form 1, 2, 4 or 8 independent lanes, each with a problem list of its own (problem k of the
+// pipeline goes to lane k % lanes): a problem whose blocks are taken bpi at a time needs only S RB / bpi
+// workgroups, and a workgroup that stages one image for bpi blocks has bpi times the work between two image
+// changes -- more groups to spread over its consumers, and more time to stage the next image in.
+struct PipeLanes {
+    uint32_t first[8], n[8], items[8];   // per lane: where its problems start in the table, how many, their groups
+    uint32_t log2_lanes;
+};
+__global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *table_, PipeLanes lanes, uint32_t *status) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    // workgroup number = [index in the lane : lane : die] (the low three bits are the die the workgroup lands on;
+    // they stay the low bits of its number within the lane, so that a codebook slice is still staged by one die)
+    const uint32_t my_lane = (blockIdx.x >> 3) & ((1u << lanes.log2_lanes) - 1u);
+    const int bid = (int)((blockIdx.x & 7u) | ((blockIdx.x >> (3u + lanes.log2_lanes)) << 3));
+    uint32_t n = lanes.n[my_lane], total_items = lanes.items[my_lane];
+    table_ += lanes.first[my_lane];
+    pin_scalar(table_); pin_scalar(n); pin_scalar(total_items); pin_scalar(status);
+    if (n == 0u) return;
+    cproblem_t *table = (cproblem_t *)table_;
+    if (threadIdx.x < 4) reinterpret_cast<uint32_t *>(smem + kPipeFlags)[threadIdx.x] = 0u;
+    __syncthreads();
+    PipeSync sy = {false};
+    if (wave == kPipeScout) {
+        pipe_scout(table, n, bid, lane, sy);
+        if (sy.broken && lane == 0) *status = 1u;
+        return;
+    }
+    if (wave >= kPipeFirstProducer) {
+        // ---- producer
+        const int pw = wave - kPipeFirstProducer;
+        for (uint32_t k = 0; k < n; ++k) {
+            const PipeStage st = pipe_stage_read(table, k, bid, pw);
+            if (k >= 2) pipe_wait(kPipeFlags + 8u + (k & 1u) * 4u, (uint32_t)kPipeConsumers * ((k - 2u) / 2u + 1u), sy);
+            pipe_stage(st, lane, smem + (k & 1u) * kPipeImage);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the transfers of this wavefront
+            pipe_signal(kPipeFlags + (k & 1u) * 4u, lane);
+        }
+        if (sy.broken && lane == 0) *status = 1u;
+        return;
+    }
+    // ---- consumer: groups wave, wave + NC, ... of the list of all groups; the requests of one piece are in
+    //      flight while the piece before it is worked on
+    constexpr int PF = 8;
+    PipeConsumer c = {0u, n, sy};
+    pipe_enter(c, 0u);
+    // three pieces in rotation: while one is worked on, the requests of the next two are in flight (a piece is
+    // 4 - 8 steps, about a microsecond of this wavefront's time; a request that misses the caches takes two)
+    PipePiece<PF> a, b, d;
+    PipeCursor cu = {(uint32_t)wave, 0u, 0u};
+    Acc3 acc = {{0.f, 0.f, 0.f}};
+    uint32_t zero_v = 0u;
+    asm volatile("" : "+v"(zero_v));
+    pipe_fetch(a, cu, table, n, total_items, bid, lane, zero_v);
+    pipe_fetch(b, cu, table, n, total_items, bid, lane, zero_v);
+    pipe_fetch(d, cu, table, n, total_items, bid, lane, zero_v);
+    for (;;) {
+        pipe_consume(a, acc, c, lane);
+        pipe_retire(a);
+        if (b.i >= n) break;
+        pipe_fetch(a, cu, table, n, total_items, bid, lane, zero_v);
+        pipe_consume(b, acc, c, lane);
+        pipe_retire(b);
+        if (d.i >= n) break;
+        pipe_fetch(b, cu, table, n, total_items, bid, lane, zero_v);
+        pipe_consume(d, acc, c, lane);
+        pipe_retire(d);
+        if (a.i >= n) break;
+        pipe_fetch(d, cu, table, n, total_items, bid, lane, zero_v);
+    }
+    pipe_advance(c, n, lane);
+    if (c.sy.broken && lane == 0) *status = 1u;
+}
+
+// y of every problem of a pipeline: blockIdx.y picks the problem.  y[n] = scale[n] * sum_s (sum_p partial[s][p][n]):
+// the parts of a row added first, in part order, then the slices in ascending order -- the additions of the
+// one-problem kernels, in their order.
+__global__ __launch_bounds__(kFinalizeRows) void gemv_pipeline_finalize_kernel(const PipeProblem *table_) {
+    cproblem_t &pr = ((cproblem_t *)table_)[blockIdx.y];
+    const float *partial = pr.partial;
+    const half_t *scale = pr.scale;
+    half_t *y = pr.y;
+    int N = pr.N, S = pr.S, P = pr.P;
+    pin_scalar(partial); pin_scalar(scale); pin_scalar(y); pin_scalar(N); pin_scalar(S); pin_scalar(P);
+    const int n = blockIdx.x * kFinalizeRows + threadIdx.x;
+    if (n >= N) return;
+    const __attribute__((address_space(1))) float *gp = (const __attribute__((address_space(1))) float *)partial;
+    const __attribute__((address_space(1))) half_t *gs = (const __attribute__((address_space(1))) half_t *)scale;
+    __attribute__((address_space(1))) half_t *gy = (__attribute__((address_space(1))) half_t *)y;
+    const float sc = scale ? (float)gs[n] : 1.f;
+    float sum = 0.f;
+    if (P == 1) {
+        float v[kPackMaxSlices];
+#pragma unroll
+        for (int k = 0; k < kPackMaxSlices; ++k) v[k] = gp[pipe_partial_index((uint32_t)S, (uint32_t)(k < S ? k : S - 1), (uint32_t)n)];
+#pragma unroll
+        for (int k = 0; k < kPackMaxSlices; ++k) sum += k < S ? v[k] : 0.f;
+    } else {
+        for (int k = 0; k < S; ++k) {
+            float t = gp[pipe_partial_index((uint32_t)(S * P), (uint32_t)(k * P), (uint32_t)n)];
+            for (int p = 1; p < P; ++p) t += gp[pipe_partial_index((uint32_t)(S * P), (uint32_t)(k * P + p), (uint32_t)n)];
+            sum += t;
+        }
+    }
+    gy[n] = scaled_output(sum, sc);
 }
 
 bool gemv_uses_pack(const vq_weight_t *w, int bs) {
@@ -1172,6 +1593,166 @@ int launch_gemv_packed_sequence(const vq_gemv_call_t *calls, int n_calls, void *
         pending = next;
     }
     return launch_finalize(pending, s);
+}
+
+// ---- the pipelined launch: host side -----------------------------------------------------------------------
+// Workspace: [status word, 256 B][problem table][partial sums of every problem, each 256-byte aligned].
+namespace {
+constexpr size_t kPipeHeader = 256;
+size_t pipe_table_bytes(int n) { return ((size_t)n * sizeof(PipeProblem) + 255) & ~(size_t)255; }
+int pipe_problems(const vq_gemv_call_t *calls, int n_calls) {
+    int n = 0;
+    for (int c = 0; c < n_calls; ++c) n += calls[c].count;
+    return n;
+}
+}  // namespace
+
+// The staging operations of a problem's LDS image ([slice][parts of x, kZeroUnits zero units behind each]), dealt to
+// the producers in turn.  False if a producer would get more than kPipeOps of them.
+static bool pipe_build_ops(PipeProblem &p) {
+    std::vector<std::pair<uint32_t, uint32_t>> ops;
+    const uint32_t slice_bytes = 16u << p.EB, part_pitch = ((uint32_t)p.Jp + kZeroUnits) * 16u;
+    for (uint32_t c = 0; c < slice_bytes / 4096; ++c) ops.push_back({c * 4096, pipe_op(c * 4096, kOpSlice4k, 0)});
+    for (int q = 0; q < p.P; ++q) {
+        const uint32_t len = (uint32_t)std::min(p.Jp, p.J - q * p.Jp);   // positions of this part
+        const uint32_t src0 = (uint32_t)q * (uint32_t)p.Jp * 16u, dst0 = slice_bytes + (uint32_t)q * part_pitch;
+        const uint32_t full = len >> 8;
+        for (uint32_t c = 0; c < full; ++c) ops.push_back({src0 + c * 4096, pipe_op(dst0 + c * 4096, kOpX4k, 0)});
+        for (uint32_t t = full * 4; t * 64 < len; ++t)
+            ops.push_back({src0 + t * 1024, pipe_op(dst0 + t * 1024, kOpX1k, std::min(64u, len - t * 64))});
+        ops.push_back({0u, pipe_op(dst0 + (uint32_t)p.Jp * 16u, kOpZero, 0)});
+    }
+    if (ops.size() > (size_t)kPipeProducers * kPipeOps) return false;
+    std::memset(p.ops, 0, sizeof(p.ops));
+    for (size_t j = 0; j < ops.size(); ++j) {
+        p.ops[j % kPipeProducers][j / kPipeProducers][0] = ops[j].first;
+        p.ops[j % kPipeProducers][j / kPipeProducers][1] = ops[j].second;
+    }
+    return true;
+}
+
+struct GemvPipeline {
+    int device;
+    uint32_t n;
+    PipeLanes lanes;
+    int max_n;
+    PipeProblem *table;    // device
+    uint32_t *status;      // device
+};
+
+// S * P partial sums per row in blocks of 64 rows (pipe_partial_index), 256-byte aligned.
+static size_t pipe_partial_bytes(const vq_weight_t *w) {
+    const vq_gemv_pack_t *p = w->gemv_pack;
+    return (size_t)p->S * p->parts * (((size_t)w->N + 63) / 64) * 64 * sizeof(float);
+}
+size_t gemv_pipeline_workspace(const vq_gemv_call_t *calls, int n_calls) {
+    size_t total = kPipeHeader + pipe_table_bytes(pipe_problems(calls, n_calls));
+    for (int c = 0; c < n_calls; ++c)
+        for (int i = 0; i < calls[c].count; ++i) total += pipe_partial_bytes(calls[c].w[i]);
+    return total;
+}
+
+// Whether the pipelined kernel can take this (already validated) weight: its block fits one workgroup of the
+// persistent launch, and its LDS image one of the two slots.
+bool gemv_pipeline_supports(const vq_weight_t *w) {
+    PackPlan plan;
+    if (!pack_plan(w, &plan)) return false;
+    const size_t image = ((size_t)plan.slice_entries + (size_t)plan.P * (plan.Jp + kZeroUnits)) * 16;
+    return plan.S * plan.RB <= (uint32_t)kPipeWgs && image <= kPipeImage;
+}
+
+// Builds the problem table in the workspace (a synchronous copy: the calls' arrays need not outlive this).
+int gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, hipStream_t s, GemvPipeline **out) {
+    const int n = pipe_problems(calls, n_calls);
+    std::vector<PipeProblem> probs((size_t)n);
+    unsigned char *base = (unsigned char *)ws;
+    size_t off = kPipeHeader + pipe_table_bytes(n);
+    int k = 0, max_n = 0;
+    uint32_t bpi = 4, max_vwg = 1;   // blocks per image: the largest of 4, 2, 1 that divides every problem's row blocks
+    for (int c = 0; c < n_calls; ++c)
+        for (int i = 0; i < calls[c].count; ++i)
+            while (calls[c].w[i]->gemv_pack->RB % bpi) bpi >>= 1;
+    for (int c = 0; c < n_calls; ++c)
+        for (int i = 0; i < calls[c].count; ++i, ++k) {
+            const vq_weight_t *w = calls[c].w[i];
+            const PackedLaunch l = packed_launch(w, calls[c].x[i], calls[c].y[i], base + off);
+            off += pipe_partial_bytes(w);
+            const PackedArgs &a = l.a;
+            PipeProblem &p = probs[(size_t)k];
+            std::memset(&p, 0, sizeof(p));
+            p.atoms = a.data + a.atom_off;
+            p.tasks = a.data + a.task_off;
+            p.steps = a.data + a.steps_off;
+            p.cb = a.cb; p.x = a.x; p.partial = a.partial; p.scale = a.scale; p.y = a.y;
+            p.N = a.N; p.J = a.J; p.S = a.S; p.RB = a.RB; p.rows_per_block = a.rows_per_block;
+            p.EB = a.EB; p.P = a.P; p.Jp = a.Jp; p.n_groups = a.n_groups;
+            p.wg_pitch = a.wg_pitch;
+            p.bpi = bpi;
+            std::memcpy(p.group, a.group, sizeof(p.group));
+            if (!pipe_build_ops(p)) return VQ_ERR_UNSUPPORTED;
+            if (a.N > max_n) max_n = a.N;
+            max_vwg = std::max(max_vwg, (uint32_t)(a.S * a.RB) / bpi);
+        }
+    // lanes: as many as fit side by side (a power of two; the largest problem decides)
+    PipeLanes lanes;
+    std::memset(&lanes, 0, sizeof(lanes));
+    uint32_t n_lanes = 1;
+    while (n_lanes < 8 && max_vwg * n_lanes * 2 <= (uint32_t)kPipeWgs && max_vwg * n_lanes * 2 / 8 * 8 == max_vwg * n_lanes * 2) n_lanes *= 2;
+    if (max_vwg % 8) n_lanes = 1;   // (the die bits of a workgroup number must be those of its number within the lane)
+    while ((1u << lanes.log2_lanes) < n_lanes) ++lanes.log2_lanes;
+    // the table, lane after lane; within a lane the problems keep their order
+    std::vector<PipeProblem> table;
+    table.reserve((size_t)n);
+    for (uint32_t l = 0; l < n_lanes; ++l) {
+        lanes.first[l] = (uint32_t)table.size();
+        uint32_t items = 0;
+        for (int q = (int)l; q < n; q += (int)n_lanes) {
+            PipeProblem p = probs[(size_t)q];
+            p.item_first = items;
+            items += (uint32_t)p.n_groups * bpi;
+            p.item_end = items;
+            table.push_back(p);
+        }
+        lanes.n[l] = (uint32_t)table.size() - lanes.first[l];
+        lanes.items[l] = items;
+    }
+    GemvPipeline *h = new (std::nothrow) GemvPipeline;
+    if (!h) return VQ_ERR_LAUNCH;
+    if (hipGetDevice(&h->device) != hipSuccess) { delete h; return VQ_ERR_LAUNCH; }
+    h->n = (uint32_t)n;
+    h->lanes = lanes;
+    h->max_n = max_n;
+    h->status = reinterpret_cast<uint32_t *>(base);
+    h->table = reinterpret_cast<PipeProblem *>(base + kPipeHeader);
+    if (hipMemsetAsync(h->status, 0, kPipeHeader, s) != hipSuccess ||
+        hipMemcpyAsync(h->table, table.data(), (size_t)n * sizeof(PipeProblem), hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess) {
+        delete h;
+        return VQ_ERR_LAUNCH;
+    }
+    *out = h;
+    return VQ_OK;
+}
+
+void gemv_pipeline_destroy(GemvPipeline *h) { delete h; }
+
+int launch_gemv_pipeline(const GemvPipeline *h, hipStream_t s) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != h->device) return VQ_ERR_LAUNCH;   // the table lives on another GPU
+    static KernelSetup setup;   // (the atoms hold absolute LDS addresses: no static LDS allowed)
+    if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_pipeline_kernel), kPipeLds, true, setup)) return st;
+    gemv_pipeline_kernel<<<kPipeWgs, (kPipeConsumers + 1 + kPipeProducers) * 64, kPipeLds, s>>>(h->table, h->lanes, h->status);
+    if (int st = launch_status()) return st;
+    gemv_pipeline_finalize_kernel<<<dim3((h->max_n + kFinalizeRows - 1) / kFinalizeRows, h->n), kFinalizeRows, 0, s>>>(h->table);
+    return launch_status();
+}
+
+int gemv_pipeline_status(const GemvPipeline *h, hipStream_t s, int *status) {
+    uint32_t v = 0;
+    if (hipMemcpyAsync(&v, h->status, sizeof(v), hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+        return VQ_ERR_LAUNCH;
+    *status = (int)v;
+    return VQ_OK;
 }
 
 }  // namespace vq

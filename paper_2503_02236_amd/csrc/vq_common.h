@@ -93,6 +93,14 @@ int launch_gemv_packed_batch(const vq_weight_t *const *w, const void *const *x, 
                              hipStream_t s);
 size_t gemv_packed_sequence_workspace(const vq_gemv_call_t *calls, int n_calls);
 int launch_gemv_packed_sequence(const vq_gemv_call_t *calls, int n_calls, void *ws, hipStream_t s);
+// The pipelined launch (one persistent kernel for all problems of a sequence).
+struct GemvPipeline;
+size_t gemv_pipeline_workspace(const vq_gemv_call_t *calls, int n_calls);
+bool gemv_pipeline_supports(const vq_weight_t *w);
+int gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, hipStream_t s, GemvPipeline **out);
+void gemv_pipeline_destroy(GemvPipeline *h);
+int launch_gemv_pipeline(const GemvPipeline *h, hipStream_t s);
+int gemv_pipeline_status(const GemvPipeline *h, hipStream_t s, int *status);
 int check_kv(const vq_kv_t *kv);
 
 // Kernel launchers (defined next to their kernels).

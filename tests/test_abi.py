@@ -287,6 +287,56 @@ def test_gemv_sequence_validation():
     assert f(arr, 1, None, 0, None, ctypes.byref(side)) == VQ_ERR_WORKSPACE         # n = 0: the one-stream call
 
 
+def test_gemv_pipeline_validation():
+    """Host-side checks of vq_gemv_pipeline_*: everything is validated before any GPU call; no handle on failure."""
+    from paper_2503_02236_amd import workloads as wl
+    from paper_2503_02236_amd.binding import vq_gemv_call_t
+    lib = vq.lib()
+    WP = ctypes.POINTER(vq_weight_t)
+    w = wl.make_weight(128, 512, 8, 16, 1, 65536, 0.02, seed=5)
+    buf, pack = vq.vq_gemv_prepack(w)
+    pack.data = P                                            # a (fake) aligned device address: nothing is launched here
+    packed = vq_weight_t(w.N, w.K, 8, 16, 1, 65536, None, P, None, ctypes.pointer(pack))
+    canonical = weight()
+
+    def call(ws_list, xs, ys):
+        n = len(ws_list)
+        c = vq_gemv_call_t()
+        c._keep = ((WP * n)(*[ctypes.pointer(x) for x in ws_list]), (ctypes.c_void_p * n)(*xs), (ctypes.c_void_p * n)(*ys))
+        c.w, c.x, c.y = (ctypes.cast(c._keep[0], ctypes.POINTER(WP)), ctypes.cast(c._keep[1], ctypes.POINTER(ctypes.c_void_p)),
+                         ctypes.cast(c._keep[2], ctypes.POINTER(ctypes.c_void_p)))
+        c.count = n
+        return c
+
+    def create(calls, ws=P, ws_bytes=1 << 30):                # (P is 256-byte aligned)
+        arr = (vq_gemv_call_t * len(calls))(*calls)
+        h = ctypes.c_void_p(1)
+        st = lib.vq_gemv_pipeline_create(arr, len(calls), ws, ws_bytes, None, ctypes.byref(h))
+        assert h.value is None                               # every failure leaves a null handle
+        return st, lib.vq_gemv_pipeline_workspace(arr, len(calls))
+
+    assert P % 256 == 0
+    good = call([packed, packed], [P, P], [P, P])
+    arr = (vq_gemv_call_t * 1)(good)
+    need = lib.vq_gemv_pipeline_workspace(arr, 1)
+    # status words (256 B), a table of 2 problems (rounded to 256 B), 32 x 1 partial sums for each of 128 rows, twice
+    assert need > 256 + 2 * 32 * 128 * 4 and need % 256 == 0
+    h = ctypes.c_void_p()
+    assert lib.vq_gemv_pipeline_create(arr, 1, P, 1 << 30, None, None) == VQ_ERR_NULL
+    assert lib.vq_gemv_pipeline_create(None, 1, P, 1 << 30, None, ctypes.byref(h)) == VQ_ERR_NULL
+    assert lib.vq_gemv_pipeline_create(arr, 0, P, 1 << 30, None, ctypes.byref(h)) == VQ_ERR_SHAPE
+    assert create([good], ws=None) == (VQ_ERR_WORKSPACE, need)
+    assert create([good], ws_bytes=need - 1) == (VQ_ERR_WORKSPACE, need)
+    assert create([good], ws=P + 16) == (VQ_ERR_ALIGN, need) # 16-byte aligned is not enough here
+    assert create([good, call([canonical], [P], [P])]) == (VQ_ERR_UNSUPPORTED, 0)
+    assert create([call([packed], [None], [P])]) == (VQ_ERR_NULL, 0)
+    assert create([call([packed], [P], [P + 2])]) == (VQ_ERR_ALIGN, 0)
+    assert lib.vq_gemv_pipeline_run(None, None) == VQ_ERR_NULL
+    st = ctypes.c_int(7)
+    assert lib.vq_gemv_pipeline_status(None, None, ctypes.byref(st)) == VQ_ERR_NULL
+    lib.vq_gemv_pipeline_destroy(None)                       # allowed
+
+
 def test_probe_argument_validation():
     lib = vq.lib()
     assert lib.vq_probe_copy(None, P, 16, None) == VQ_ERR_NULL

@@ -388,6 +388,58 @@ def test_gemv_sequence_on_several_streams_eager_and_graph(gpu_device, n_side):
         torch.cuda.synchronize()
 
 
+def _pipeline_case(gpu_device, specs, seed0, reps=2):
+    calls, ref = [], []
+    seed = seed0
+    for spec in specs:
+        call = []
+        for (N, K, E, sc) in spec:
+            seed += 1
+            w = wl.make_weight(N, K, 8, 16, 1, E, 0.02, seed=seed, with_scale=sc)
+            wd = vq.weight_to_device(w, gpu_device, prepack=True, keep_codes=False)
+            x = wl.make_activations(1, K, seed=seed + 500)
+            call.append((wd, dev_x(x, gpu_device), torch.full((1, N), 5.0, dtype=torch.float16, device=gpu_device)))
+            ref.append((w, x))
+        calls.append(call)
+    flat = [t for c in calls for t in c]
+    want = [vq.vq_gemv(wd, xd).clone() for (wd, xd, _) in flat]
+    torch.cuda.synchronize()
+    pipe = vq.GemvPipeline(calls)
+    for rep in range(reps):                                  # again: the second run re-uses table, workspace and LDS protocol
+        assert pipe.run() == 0
+        torch.cuda.synchronize()
+        assert pipe.status() == 0                            # no wavefront gave up a wait
+        for (wd, xd, y), w_, (w, x) in zip(flat, want, ref):
+            assert torch.equal(y, w_), (w.N, w.K, rep)       # the additions of vq_gemv in the order of vq_gemv
+            if rep == 0:
+                assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), f"pipeline member {w.N}x{w.K}")
+            y.fill_(3.0)
+    pipe.close()
+
+
+def test_gemv_pipeline_mixed_shapes(gpu_device):
+    """vq_gemv_pipeline: one persistent launch for all products.  One, two and many problems; problems with fewer
+    blocks than the launch has workgroups, with one row, without scale, with smaller codebooks (fewer slices), with
+    groups longer than one piece (K = 2048: about 11 steps in the longest group); bit-identical to vq_gemv."""
+    _pipeline_case(gpu_device, [[(512, 512, 65536, True)]], 9800)
+    _pipeline_case(gpu_device, [[(4096, 512, 65536, True)], [(1000, 1024, 65536, False)]], 9810)
+    _pipeline_case(gpu_device, [
+        [(4096, 512, 65536, True), (4096, 512, 65536, False), (1000, 512, 65536, True)],
+        [(300, 1024, 4096, True)],
+        [(2000, 256, 65536, True), (64, 256, 65536, True)],
+        [(11008, 512, 65536, True)],
+        [(4096, 1024, 8192, False), (4096, 2048, 65536, True)],
+        [(1, 64, 65536, True)]], 9820)
+
+
+def test_gemv_pipeline_llama_blocks_full_size(gpu_device):
+    """Two decoder blocks at full size, as bench.py issues them (four problem lanes, four row blocks per LDS image,
+    K = 11008 in two parts): bit-identical to vq_gemv, within tolerance of the oracle."""
+    block = [[(4096, 4096, 65536, True)] * 3, [(4096, 4096, 65536, True)], [(11008, 4096, 65536, True)] * 2,
+             [(4096, 11008, 65536, True)]]
+    _pipeline_case(gpu_device, block + block, 9850)
+
+
 def test_gemv_packed_padding_never_touches_a_codebook_entry(gpu_device):
     # entries that no code uses are set to infinity and NaN: padding atoms multiply a zero unit of x with an
     # entry that some code really uses, never with one of these, so every output stays what the oracle says (finite)
