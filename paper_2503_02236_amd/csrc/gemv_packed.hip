@@ -1012,7 +1012,7 @@ constexpr int kPipeConsumers = 13, kPipeProducers = 2;   // wavefronts 0 .. 12 a
 constexpr int kPipeScout = kPipeConsumers, kPipeFirstProducer = kPipeConsumers + 1;
 constexpr int kPipeOps = 12;                            // staging operations per producer and problem
 constexpr uint32_t kPipeImage = 65536;                  // LDS bytes from one image to the other
-constexpr uint32_t kPipeFlags = 2 * kPipeImage;         // staged[2], done[2]
+constexpr uint32_t kPipeFlags = 2 * kPipeImage;         // staged[2], done[2], next group to hand out
 constexpr uint32_t kPipeLds = kPipeFlags + 64;
 constexpr uint32_t kPipeSpinLimit = 1u << 20;
 
@@ -1025,10 +1025,10 @@ struct PipeProblem {
     half_t *y;
     int N, J, S, RB, rows_per_block, EB, P, Jp, n_groups;
     uint32_t wg_pitch;
-    uint32_t item_first;   // groups of all earlier problems: group g of this one is item item_first + g
-    uint32_t item_end;
+    uint32_t reserved[2];
     uint32_t bpi;          // row blocks per LDS image: a workgroup of the launch takes bpi consecutive row blocks of its slice
-    uint32_t pad[3];
+    uint32_t rbv;          // RB / bpi
+    uint32_t pad[2];
     // How producer w builds the LDS image, worked out on the host (the kernel's instruction issue is a scarce
     // resource: four wavefronts per SIMD): pairs (source byte offset, PipeOp word), the list ends at a zero word.
     uint32_t ops[kPipeProducers][kPipeOps][2];
@@ -1074,18 +1074,13 @@ __device__ __forceinline__ void pipe_signal(uint32_t addr, int lane) {
     if (lane == 0) __hip_atomic_fetch_add((lds_u32_t *)(uintptr_t)addr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-// A consumer's unit of work: up to PF consecutive steps of group g of problem i (of this workgroup's block), all
-// of them requested at once.  A group of more steps is taken in several pieces, one after the other by the
+// A consumer's unit of work: up to PF consecutive steps of one group of problem i (of this workgroup's blocks),
+// all of them requested at once.  A group of more steps is taken in several pieces, one after the other by the
 // same wavefront, the sums carried in registers.
 template <int PF>
 struct PipePiece {
     uint32_t i;          // problem (n: no more work)
-    uint32_t valid;      // the workgroup has a block of this problem
-    uint32_t first;      // first step of the piece in its group
-    uint32_t last;       // the group ends with this piece
-    uint32_t EB, P, Jp, rows_per_block;
-    uint32_t N, planes, plane0, row0;   // rows of the matrix; S * P; s * P; first row of the block
-    float *partial;
+    uint32_t meta;       // first step of the piece in its group | row block of the image << 8 | last piece << 16 | valid << 17
     uint32_t slot, steps_v;
     uint32_t q[PF][2];
 };
@@ -1093,53 +1088,108 @@ struct PipePiece {
 __host__ __device__ __forceinline__ size_t pipe_partial_index(uint32_t planes, uint32_t plane, uint32_t row) {
     return ((size_t)(row >> 6) * planes + plane) * 64 + (row & 63);
 }
-// What a consumer requests next: piece h of flat group t (groups of all problems numbered through), which lies in
-// problem i or a later one.
+// The groups of a lane's problems are numbered through ("items").  Consumers take them from an LDS counter as they
+// go (each wavefront when it has requests to issue, i.e. two pieces before it works on them): whoever gets
+// long groups takes fewer of them.  What a wavefront takes is ascending, so it still passes the problems in order.
 struct PipeCursor {
-    uint32_t t, i, h;
+    uint32_t t, h;       // the group being requested (number in the lane's list) and its next piece
+    uint32_t t_next_v;   // the group after it (taken ahead; in a vector register until needed: no wait for the counter)
+    // the group being requested, worked out when the group before it had been requested
+    uint32_t word;       // its entry of the problem's group table (prefix << 16 | common steps)
+    uint32_t wg, g, jb;  // block in the packed tables, group in the block, row block of the image
+    bool none;           // past the last group
+    bool advance;        // the piece last requested ended its group
 };
+// (take = 0 reads the counter without taking anything: the callers have no branch around this)
+__device__ __forceinline__ uint32_t pipe_grab(int lane, uint32_t take) {
+    uint32_t v = 0;
+    if (lane == 0)
+        v = __hip_atomic_fetch_add((lds_u32_t *)(uintptr_t)(kPipeFlags + 16u), take, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return v;
+}
+// What requesting needs of a problem: read once per problem and wavefront, kept in scalar registers.
+struct PipeHead {
+    uint32_t i;
+    int S, RB, ng, bpi;
+    uint32_t wg_pitch;
+    const unsigned char *atoms, *tasks, *steps;
+    int s, rbv;          // this workgroup's slice and first row block / bpi
+    bool in;             // the workgroup has blocks of this problem
+};
+__device__ __forceinline__ void pipe_head_load(PipeHead &h, cproblem_t *table, uint32_t i, int bid) {
+    cproblem_t &pr = table[i];
+    h.i = i;
+    h.S = pr.S; h.RB = pr.RB; h.ng = pr.n_groups; h.bpi = (int)pr.bpi;
+    h.wg_pitch = pr.wg_pitch;
+    h.atoms = pr.atoms; h.tasks = pr.tasks; h.steps = pr.steps;
+    const int RBv = (int)pr.rbv;
+    h.in = bid < h.S * RBv;
+    slice_and_block(h.in ? bid : 0, h.S, RBv, h.s, h.rbv);
+}
+
+// Moves the cursor behind the piece last requested: to the next piece of the group, or to the next group of this
+// wavefront, taken from the counter.  Straight-line code for both cases.  Where group t lies comes from a table
+// the host wrote (problem | row block of the image << 16 | group << 20).  Called BEFORE the wavefront works on an
+// earlier piece: the scalar loads here (the last one is left in flight) land while it does, instead of standing
+// in front of the next requests.  Not called between the requests and the end of the main loop: anything but
+// the requests themselves there makes the compiler lose count of the requests in flight at the loop's head (it
+// then waits for nearly all of them).
+__device__ __forceinline__ void pipe_next(PipeCursor &cu, PipeHead &hd, cproblem_t *table, cu32_t *items, uint32_t total_items, int bid,
+                                          int lane) {
+    const bool advance = cu.advance;
+    const uint32_t taken = __builtin_amdgcn_readfirstlane(cu.t_next_v);
+    const uint32_t fresh = pipe_grab(lane, advance ? 1u : 0u);
+    cu.t_next_v = advance ? fresh : cu.t_next_v;
+    cu.t = advance ? taken : cu.t;
+    cu.h = advance ? 0u : cu.h + 1u;
+    cu.none = cu.t >= total_items;
+    const uint32_t tt = cu.none ? total_items - 1 : cu.t;   // (past the end: the last group's loads once more, never used)
+    const uint32_t where = items[tt];
+    const uint32_t i = where & 0xFFFFu;
+    if (i != hd.i) pipe_head_load(hd, table, i, bid);
+    cu.jb = (where >> 16) & 15u;
+    cu.g = where >> 20;
+    cu.wg = (uint32_t)(hd.s * hd.RB + hd.rbv * hd.bpi) + cu.jb;
+    cu.word = table[i].group[cu.g];
+}
 
 template <int PF>
-__device__ __forceinline__ void pipe_fetch(PipePiece<PF> &it, PipeCursor &cu, cproblem_t *table, uint32_t n, uint32_t total_items,
-                                           int bid, int lane, uint32_t zero_v) {
-    const bool none = cu.t >= total_items;
-    const uint32_t tt = none ? total_items - 1 : cu.t;   // (past the end: the last group's loads once more, never used)
-    uint32_t i = cu.i;
-    while (tt >= table[i].item_end) ++i;
-    i = __builtin_amdgcn_readfirstlane(i);
-    cproblem_t &pr = table[i];
-    const int S = pr.S, RB = pr.RB, ng = pr.n_groups, bpi = (int)pr.bpi;
-    // item -> (row block of the image, group): the groups of the first row block, then those of the second, ...
-    uint32_t g = tt - pr.item_first;
-    int jb = 0;
-    while (g >= (uint32_t)ng) { g -= (uint32_t)ng; ++jb; }
-    const int RBv = RB / bpi;   // (bpi is 1, 2 or 4 and divides RB)
-    const bool in = bid < S * RBv;
-    int s, rb;
-    slice_and_block(in ? bid : 0, S, RBv, s, rb);
-    rb = rb * bpi + jb;
-    const uint32_t wg = (uint32_t)(s * RB + rb);
-    const uint32_t word = pr.group[g];
-    const uint32_t common = word & 0xFFFFu, first = cu.h * PF;
-    gbyte_t *gbase = (gbyte_t *)pr.atoms + ((size_t)wg * pr.wg_pitch + (word >> 16) + first) * kStepBytes + (uint32_t)lane * 8u;
+__device__ __forceinline__ void pipe_fetch(PipePiece<PF> &it, PipeCursor &cu, PipeHead &hd, cproblem_t *table, cu32_t *items,
+                                           uint32_t n, uint32_t total_items, int bid, int lane, uint32_t zero_v) {
+    const uint32_t common = cu.word & 0xFFFFu, first = cu.h * PF;
+    gbyte_t *gbase = (gbyte_t *)hd.atoms + ((size_t)cu.wg * hd.wg_pitch + (cu.word >> 16) + first) * kStepBytes + (uint32_t)lane * 8u;
     // (a vector load of one address: a scalar load would be waited for with the next LDS read.  The address is a
     // scalar base plus a register that holds 0 for the whole kernel, so that no register is written here that an
     // earlier request may still be writing to.)
-    it.steps_v = *(gu32_t *)((gbyte_t *)((gu32_t *)pr.steps + (wg * (uint32_t)ng + g)) + zero_v);
-    it.slot = ((gu16_t *)pr.tasks)[(size_t)(wg * (uint32_t)ng + g) * 64 + lane];
+    it.steps_v = *(gu32_t *)((gbyte_t *)((gu32_t *)hd.steps + (cu.wg * (uint32_t)hd.ng + cu.g)) + zero_v);
+    it.slot = ((gu16_t *)hd.tasks)[(size_t)(cu.wg * (uint32_t)hd.ng + cu.g) * 64 + lane];
 #pragma unroll
     for (int st = 0; st < PF; ++st) load_step(it.q[st], gbase, st);
-    it.i = none ? n : i;
-    it.valid = (in && !none) ? 1u : 0u;
-    it.first = first;
-    it.last = first + PF >= common ? 1u : 0u;
-    it.EB = (uint32_t)pr.EB; it.P = (uint32_t)pr.P; it.Jp = (uint32_t)pr.Jp; it.rows_per_block = (uint32_t)pr.rows_per_block;
-    it.N = (uint32_t)pr.N; it.planes = (uint32_t)(S * pr.P); it.plane0 = (uint32_t)(s * pr.P);
-    it.row0 = (uint32_t)(rb * pr.rows_per_block);
-    it.partial = pr.partial;
-    // what comes after this piece
-    cu.i = i;
-    if (it.last) { cu.t += kPipeConsumers; cu.h = 0; } else { ++cu.h; }
+    const uint32_t last = first + PF >= common ? 1u : 0u;
+    it.i = cu.none ? n : hd.i;
+    it.meta = first | (cu.jb << 8) | (last << 16) | ((hd.in && !cu.none) ? 1u << 17 : 0u);
+    cu.advance = last != 0u;
+}
+
+// What working on a piece needs of its problem: read when a wavefront enters the problem.
+struct PipeBody {
+    uint32_t i;
+    uint32_t EB, P, Jp, rows_per_block;
+    uint32_t N, planes, plane0, row_base;   // rows of the matrix; S * P; s * P; first row of this workgroup's first block
+    float *partial;
+};
+__device__ __forceinline__ void pipe_body_load(PipeBody &b, cproblem_t *table, uint32_t i, int bid) {
+    cproblem_t &pr = table[i];
+    b.i = i;
+    b.EB = (uint32_t)pr.EB; b.P = (uint32_t)pr.P; b.Jp = (uint32_t)pr.Jp; b.rows_per_block = (uint32_t)pr.rows_per_block;
+    b.N = (uint32_t)pr.N;
+    b.partial = pr.partial;
+    const int S = pr.S, RBv = (int)pr.rbv;
+    int s, rbv;
+    slice_and_block(bid < S * RBv ? bid : 0, S, RBv, s, rbv);
+    b.planes = (uint32_t)S * b.P;
+    b.plane0 = (uint32_t)s * b.P;
+    b.row_base = (uint32_t)rbv * pr.bpi * b.rows_per_block;
 }
 
 // Where a consumer stands: in problem `cur` (seen staged), all earlier ones left.
@@ -1160,24 +1210,28 @@ __device__ __forceinline__ void pipe_advance(PipeConsumer &c, uint32_t to, int l
 }
 
 template <int PF>
-__device__ __forceinline__ void pipe_consume(PipePiece<PF> &it, Acc3 &acc, PipeConsumer &c, int lane) {
+__device__ __forceinline__ void pipe_consume(PipePiece<PF> &it, Acc3 &acc, PipeConsumer &c, PipeBody &bd, cproblem_t *table, int bid,
+                                             int lane) {
     static_assert(PF % 2 == 0 && PF <= kPackTailBlocks, "steps in pairs; requests run up to PF - 1 blocks past the end of a group");
     pipe_advance(c, it.i, lane);
     if (it.i >= c.n) return;
-    const uint32_t own = it.valid ? __builtin_amdgcn_readfirstlane(it.steps_v) : 0u;
-    const uint32_t n_steps = own > it.first ? own - it.first : 0u;   // of this piece (those past PF belong to the next one)
-    const uint32_t slot = it.valid ? it.slot : 0xFFFFu;
+    if (bd.i != it.i) pipe_body_load(bd, table, it.i, bid);
+    const bool valid = (it.meta >> 17) & 1u;
+    const uint32_t first = it.meta & 0xFFu, jb = (it.meta >> 8) & 0xFFu;
+    const uint32_t own = valid ? __builtin_amdgcn_readfirstlane(it.steps_v) : 0u;
+    const uint32_t n_steps = own > first ? own - first : 0u;   // of this piece (those past PF belong to the next one)
+    const uint32_t slot = valid ? it.slot : 0xFFFFu;
     const uint32_t img = (it.i & 1u) * kPipeImage;
-    const uint32_t slice_bytes = 16u << it.EB, part_pitch = (it.Jp + kZeroUnits) * 16u;
+    const uint32_t slice_bytes = 16u << bd.EB, part_pitch = (bd.Jp + kZeroUnits) * 16u;
     uint32_t part = 0;
-    for (uint32_t p = 1; p < it.P; ++p) part += (slot != 0xFFFFu && slot >= p * it.rows_per_block) ? 1u : 0u;
+    for (uint32_t p = 1; p < bd.P; ++p) part += (slot != 0xFFFFu && slot >= p * bd.rows_per_block) ? 1u : 0u;
     AtomDecode dec;
-    dec.emask4 = ((1u << it.EB) - 1u) << 4;
-    dec.eb = it.EB;
-    dec.xb = (uint32_t)kAtomBits - it.EB;
+    dec.emask4 = ((1u << bd.EB) - 1u) << 4;
+    dec.eb = bd.EB;
+    dec.xb = (uint32_t)kAtomBits - bd.EB;
     dec.ebase = img;
     dec.xbase = img + slice_bytes + part * part_pitch;
-    if (it.first == 0) acc = {{0.f, 0.f, 0.f}};
+    if (first == 0) acc = {{0.f, 0.f, 0.f}};
 #pragma unroll
     for (int k = 0; k < PF; k += 2) {
         const uint32_t lo[2] = {it.q[k][0], it.q[k + 1][0]}, hi[2] = {it.q[k][1], it.q[k + 1][1]};
@@ -1188,10 +1242,10 @@ __device__ __forceinline__ void pipe_consume(PipePiece<PF> &it, Acc3 &acc, PipeC
             steps_dot<1>(lo1, hi1, dec, acc);
         }
     }
-    if (it.last && slot != 0xFFFFu) {
-        const uint32_t row = it.row0 + (slot - part * it.rows_per_block);
-        if (row < it.N)
-            ((__attribute__((address_space(1))) float *)it.partial)[pipe_partial_index(it.planes, it.plane0 + part, row)] =
+    if (((it.meta >> 16) & 1u) && slot != 0xFFFFu) {
+        const uint32_t row = bd.row_base + jb * bd.rows_per_block + (slot - part * bd.rows_per_block);
+        if (row < bd.N)
+            ((__attribute__((address_space(1))) float *)bd.partial)[pipe_partial_index(bd.planes, bd.plane0 + part, row)] =
                 (acc.a[0] + acc.a[1]) + acc.a[2];
     }
 }
@@ -1215,7 +1269,7 @@ struct PipeStage {
 __device__ __forceinline__ PipeStage pipe_stage_read(cproblem_t *table, uint32_t k, int bid, int pw) {
     cproblem_t &pr = table[k];
     PipeStage st;
-    const int S = pr.S, RB = pr.RB / (int)pr.bpi;
+    const int S = pr.S, RB = (int)pr.rbv;
     const bool mine = bid < S * RB;
     int s, rb;
     slice_and_block(mine ? bid : 0, S, RB, s, rb);
@@ -1263,7 +1317,7 @@ __device__ __forceinline__ void pipe_scout(cproblem_t *table, uint32_t n, int bi
         for (int l = 0; l < (int)(sizeof(PipeProblem) / 64); ++l) acc |= words[l * 16];   // (one word per 64-byte line)
         asm volatile("" ::"s"(acc));
         cproblem_t &pr = table[k];
-        const int S = pr.S, RB = pr.RB / (int)pr.bpi;
+        const int S = pr.S, RB = (int)pr.rbv;
         uint32_t warm = 0u;
         if (bid < S * RB) {
             int s, rb;
@@ -1285,10 +1339,12 @@ __device__ __forceinline__ void pipe_scout(cproblem_t *table, uint32_t n, int bi
 // workgroups, and a workgroup that stages one image for bpi blocks has bpi times the work between two image
 // changes -- more groups to spread over its consumers, and more time to stage the next image in.
 struct PipeLanes {
-    uint32_t first[8], n[8], items[8];   // per lane: where its problems start in the table, how many, their groups
+    uint32_t first[8], n[8];             // per lane: where its problems start in the table, how many
+    uint32_t item_first[8], items[8];    // where its groups start in the table of groups, how many
     uint32_t log2_lanes;
 };
-__global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *table_, PipeLanes lanes, uint32_t *status) {
+__global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *table_, const uint32_t *items_, PipeLanes lanes,
+                                                               uint32_t *status) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     // workgroup number = [index in the lane : lane : die] (the low three bits are the die the workgroup lands on;
@@ -1297,10 +1353,12 @@ __global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *
     const int bid = (int)((blockIdx.x & 7u) | ((blockIdx.x >> (3u + lanes.log2_lanes)) << 3));
     uint32_t n = lanes.n[my_lane], total_items = lanes.items[my_lane];
     table_ += lanes.first[my_lane];
-    pin_scalar(table_); pin_scalar(n); pin_scalar(total_items); pin_scalar(status);
+    items_ += lanes.item_first[my_lane];
+    pin_scalar(table_); pin_scalar(items_); pin_scalar(n); pin_scalar(total_items); pin_scalar(status);
     if (n == 0u) return;
     cproblem_t *table = (cproblem_t *)table_;
-    if (threadIdx.x < 4) reinterpret_cast<uint32_t *>(smem + kPipeFlags)[threadIdx.x] = 0u;
+    cu32_t *items = (cu32_t *)items_;
+    if (threadIdx.x < 5) reinterpret_cast<uint32_t *>(smem + kPipeFlags)[threadIdx.x] = threadIdx.x < 4 ? 0u : (uint32_t)kPipeConsumers;
     __syncthreads();
     PipeSync sy = {false};
     if (wave == kPipeScout) {
@@ -1329,26 +1387,38 @@ __global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *
     // three pieces in rotation: while one is worked on, the requests of the next two are in flight (a piece is
     // 4 - 8 steps, about a microsecond of this wavefront's time; a request that misses the caches takes two)
     PipePiece<PF> a, b, d;
-    PipeCursor cu = {(uint32_t)wave, 0u, 0u};
+    PipeCursor cu;
+    cu.t_next_v = (uint32_t)wave;   // the first group of wavefront w is group w (the counter starts behind these)
+    PipeHead hd;
+    pipe_head_load(hd, table, 0u, bid);
+    cu.t = 0u; cu.h = 0u; cu.advance = true;
+    PipeBody bd;
+    pipe_body_load(bd, table, 0u, bid);
     Acc3 acc = {{0.f, 0.f, 0.f}};
     uint32_t zero_v = 0u;
     asm volatile("" : "+v"(zero_v));
-    pipe_fetch(a, cu, table, n, total_items, bid, lane, zero_v);
-    pipe_fetch(b, cu, table, n, total_items, bid, lane, zero_v);
-    pipe_fetch(d, cu, table, n, total_items, bid, lane, zero_v);
+    pipe_next(cu, hd, table, items, total_items, bid, lane);
+    pipe_fetch(a, cu, hd, table, items, n, total_items, bid, lane, zero_v);
+    pipe_next(cu, hd, table, items, total_items, bid, lane);
+    pipe_fetch(b, cu, hd, table, items, n, total_items, bid, lane, zero_v);
+    pipe_next(cu, hd, table, items, total_items, bid, lane);
+    pipe_fetch(d, cu, hd, table, items, n, total_items, bid, lane, zero_v);
     for (;;) {
-        pipe_consume(a, acc, c, lane);
+        pipe_next(cu, hd, table, items, total_items, bid, lane);
+        pipe_consume(a, acc, c, bd, table, bid, lane);
         pipe_retire(a);
         if (b.i >= n) break;
-        pipe_fetch(a, cu, table, n, total_items, bid, lane, zero_v);
-        pipe_consume(b, acc, c, lane);
+        pipe_fetch(a, cu, hd, table, items, n, total_items, bid, lane, zero_v);
+        pipe_next(cu, hd, table, items, total_items, bid, lane);
+        pipe_consume(b, acc, c, bd, table, bid, lane);
         pipe_retire(b);
         if (d.i >= n) break;
-        pipe_fetch(b, cu, table, n, total_items, bid, lane, zero_v);
-        pipe_consume(d, acc, c, lane);
+        pipe_fetch(b, cu, hd, table, items, n, total_items, bid, lane, zero_v);
+        pipe_next(cu, hd, table, items, total_items, bid, lane);
+        pipe_consume(d, acc, c, bd, table, bid, lane);
         pipe_retire(d);
         if (a.i >= n) break;
-        pipe_fetch(d, cu, table, n, total_items, bid, lane, zero_v);
+        pipe_fetch(d, cu, hd, table, items, n, total_items, bid, lane, zero_v);
     }
     pipe_advance(c, n, lane);
     if (c.sy.broken && lane == 0) *status = 1u;
@@ -1600,6 +1670,16 @@ int launch_gemv_packed_sequence(const vq_gemv_call_t *calls, int n_calls, void *
 namespace {
 constexpr size_t kPipeHeader = 256;
 size_t pipe_table_bytes(int n) { return ((size_t)n * sizeof(PipeProblem) + 255) & ~(size_t)255; }
+// the table of groups: one word per (problem, row block of an image, group); at most 4 row blocks per image
+size_t pipe_items_bytes(const vq_gemv_call_t *calls, int n_calls) {
+    size_t groups = 0;
+    for (int c = 0; c < n_calls; ++c)
+        for (int i = 0; i < calls[c].count; ++i) {
+            const vq_gemv_pack_t *p = calls[c].w[i]->gemv_pack;
+            groups += 4 * (((size_t)p->rows_per_block * p->parts + 63) / 64);
+        }
+    return (groups * sizeof(uint32_t) + 255) & ~(size_t)255;
+}
 int pipe_problems(const vq_gemv_call_t *calls, int n_calls) {
     int n = 0;
     for (int c = 0; c < n_calls; ++c) n += calls[c].count;
@@ -1637,6 +1717,7 @@ struct GemvPipeline {
     PipeLanes lanes;
     int max_n;
     PipeProblem *table;    // device
+    uint32_t *items;       // device
     uint32_t *status;      // device
 };
 
@@ -1646,7 +1727,7 @@ static size_t pipe_partial_bytes(const vq_weight_t *w) {
     return (size_t)p->S * p->parts * (((size_t)w->N + 63) / 64) * 64 * sizeof(float);
 }
 size_t gemv_pipeline_workspace(const vq_gemv_call_t *calls, int n_calls) {
-    size_t total = kPipeHeader + pipe_table_bytes(pipe_problems(calls, n_calls));
+    size_t total = kPipeHeader + pipe_table_bytes(pipe_problems(calls, n_calls)) + pipe_items_bytes(calls, n_calls);
     for (int c = 0; c < n_calls; ++c)
         for (int i = 0; i < calls[c].count; ++i) total += pipe_partial_bytes(calls[c].w[i]);
     return total;
@@ -1666,8 +1747,10 @@ int gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, hip
     const int n = pipe_problems(calls, n_calls);
     std::vector<PipeProblem> probs((size_t)n);
     unsigned char *base = (unsigned char *)ws;
-    size_t off = kPipeHeader + pipe_table_bytes(n);
+    const size_t items_off = kPipeHeader + pipe_table_bytes(n);
+    size_t off = items_off + pipe_items_bytes(calls, n_calls);
     int k = 0, max_n = 0;
+    if (n > 0xFFFF) return VQ_ERR_UNSUPPORTED;   // (a problem number travels in 16 bits)
     uint32_t bpi = 4, max_vwg = 1;   // blocks per image: the largest of 4, 2, 1 that divides every problem's row blocks
     for (int c = 0; c < n_calls; ++c)
         for (int i = 0; i < calls[c].count; ++i)
@@ -1688,6 +1771,9 @@ int gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, hip
             p.EB = a.EB; p.P = a.P; p.Jp = a.Jp; p.n_groups = a.n_groups;
             p.wg_pitch = a.wg_pitch;
             p.bpi = bpi;
+            p.rbv = (uint32_t)a.RB / bpi;
+            for (int g = 0; g < a.n_groups; ++g)
+                if ((a.group[g] & 0xFFFFu) > 255u) return VQ_ERR_UNSUPPORTED;   // (the first step of a piece travels in 8 bits)
             std::memcpy(p.group, a.group, sizeof(p.group));
             if (!pipe_build_ops(p)) return VQ_ERR_UNSUPPORTED;
             if (a.N > max_n) max_n = a.N;
@@ -1702,19 +1788,20 @@ int gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, hip
     while ((1u << lanes.log2_lanes) < n_lanes) ++lanes.log2_lanes;
     // the table, lane after lane; within a lane the problems keep their order
     std::vector<PipeProblem> table;
+    std::vector<uint32_t> items;
     table.reserve((size_t)n);
     for (uint32_t l = 0; l < n_lanes; ++l) {
         lanes.first[l] = (uint32_t)table.size();
-        uint32_t items = 0;
+        lanes.item_first[l] = (uint32_t)items.size();
         for (int q = (int)l; q < n; q += (int)n_lanes) {
-            PipeProblem p = probs[(size_t)q];
-            p.item_first = items;
-            items += (uint32_t)p.n_groups * bpi;
-            p.item_end = items;
+            const PipeProblem &p = probs[(size_t)q];
+            const uint32_t i = (uint32_t)table.size() - lanes.first[l];   // its number within the lane
+            for (uint32_t jb = 0; jb < bpi; ++jb)
+                for (uint32_t g = 0; g < (uint32_t)p.n_groups; ++g) items.push_back(i | (jb << 16) | (g << 20));
             table.push_back(p);
         }
         lanes.n[l] = (uint32_t)table.size() - lanes.first[l];
-        lanes.items[l] = items;
+        lanes.items[l] = (uint32_t)items.size() - lanes.item_first[l];
     }
     GemvPipeline *h = new (std::nothrow) GemvPipeline;
     if (!h) return VQ_ERR_LAUNCH;
@@ -1724,8 +1811,10 @@ int gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, hip
     h->max_n = max_n;
     h->status = reinterpret_cast<uint32_t *>(base);
     h->table = reinterpret_cast<PipeProblem *>(base + kPipeHeader);
+    h->items = reinterpret_cast<uint32_t *>(base + items_off);
     if (hipMemsetAsync(h->status, 0, kPipeHeader, s) != hipSuccess ||
         hipMemcpyAsync(h->table, table.data(), (size_t)n * sizeof(PipeProblem), hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(h->items, items.data(), items.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) {
         delete h;
         return VQ_ERR_LAUNCH;
@@ -1741,7 +1830,7 @@ int launch_gemv_pipeline(const GemvPipeline *h, hipStream_t s) {
     if (hipGetDevice(&dev) != hipSuccess || dev != h->device) return VQ_ERR_LAUNCH;   // the table lives on another GPU
     static KernelSetup setup;   // (the atoms hold absolute LDS addresses: no static LDS allowed)
     if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_pipeline_kernel), kPipeLds, true, setup)) return st;
-    gemv_pipeline_kernel<<<kPipeWgs, (kPipeConsumers + 1 + kPipeProducers) * 64, kPipeLds, s>>>(h->table, h->lanes, h->status);
+    gemv_pipeline_kernel<<<kPipeWgs, (kPipeConsumers + 1 + kPipeProducers) * 64, kPipeLds, s>>>(h->table, h->items, h->lanes, h->status);
     if (int st = launch_status()) return st;
     gemv_pipeline_finalize_kernel<<<dim3((h->max_n + kFinalizeRows - 1) / kFinalizeRows, h->n), kFinalizeRows, 0, s>>>(h->table);
     return launch_status();
