@@ -155,11 +155,11 @@ def main():
         only = {"gemv"}
 
     # ------------------------------------------------------------------ measured ceilings of this chip
-    # (second reference beside the vendor peaks): a plain 128-bit streaming read of 1 GiB, cold, and a
+    # (second reference beside the vendor peaks): a plain 128-bit streaming read of 2 GiB, cold, and a
     # register-resident fp16 MFMA loop
     ceil_hbm = ceil_mfma = ceil_mfma_rand = ceil_mfma_lds = None
     if not args.pmc_probe:
-        big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
         big.fill_(1)
         sink = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
         ms = timed(lambda: vq.vq_probe_read(big, sink), 10, 2)

@@ -107,26 +107,29 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(uint4 *__restrict__ dst
     for (; i < n16; i += stride) dst[i] = src[i];
 }
 
+// A contiguous chunk per workgroup, eight independent non-temporal 16-byte loads in flight per thread: the
+// fastest plain read of a large buffer found on this chip (grid-stride order and ordinary loads are 10 - 15 %
+// slower).
 __global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict__ src, size_t n16,
                                                          uint4 *__restrict__ sink) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t stride = (size_t)gridDim.x * blockDim.x;
-    uint4 a = make_uint4(0, 0, 0, 0);
-    // four independent loads in flight per thread
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
-        a.x ^= v0.x ^ v1.x ^ v2.x ^ v3.x;
-        a.y ^= v0.y ^ v1.y ^ v2.y ^ v3.y;
-        a.z ^= v0.z ^ v1.z ^ v2.z ^ v3.z;
-        a.w ^= v0.w ^ v1.w ^ v2.w ^ v3.w;
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    constexpr int U = 8;
+    const size_t per_wg = (n16 + gridDim.x - 1) / gridDim.x;
+    const size_t begin = (size_t)blockIdx.x * per_wg, end = begin + per_wg < n16 ? begin + per_wg : n16;
+    const u32x4_t *p = reinterpret_cast<const u32x4_t *>(src);
+    u32x4_t a = {0, 0, 0, 0};
+    size_t i = begin + threadIdx.x;
+    for (; i + (U - 1) * 256 < end; i += U * 256) {
+        u32x4_t v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(p + i + u * 256);
+#pragma unroll
+        for (int u = 0; u < U; ++u) a ^= v[u];
     }
-    for (; i < n16; i += stride) {
-        uint4 v0 = src[i];
-        a.x ^= v0.x; a.y ^= v0.y; a.z ^= v0.z; a.w ^= v0.w;
-    }
+    for (; i < end; i += 256) a ^= __builtin_nontemporal_load(p + i);
     // fold the block into one value so the loads cannot be removed
     __shared__ uint4 red[256];
-    red[threadIdx.x] = a;
+    red[threadIdx.x] = make_uint4(a.x, a.y, a.z, a.w);
     __syncthreads();
     if (threadIdx.x == 0) {
         uint4 t = make_uint4(0, 0, 0, 0);
@@ -228,7 +231,7 @@ int launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
 
 int launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t s) {
     size_t n16 = bytes / 16;
-    int blocks = (int)((n16 + 1023) / 1024 < 4096 ? (n16 + 1023) / 1024 : 4096);
+    int blocks = (int)((n16 + 2047) / 2048 < 512 ? (n16 + 2047) / 2048 : 512);   // (the sink holds one value per block)
     if (blocks < 1) blocks = 1;
     probe_read_kernel<<<blocks, 256, 0, s>>>((const uint4 *)src, n16, (uint4 *)sink);
     return launch_status();

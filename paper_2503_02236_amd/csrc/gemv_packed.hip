@@ -1163,6 +1163,8 @@ __device__ __forceinline__ void pipe_fetch(PipePiece<PF> &it, PipeCursor &cu, Pi
     // earlier request may still be writing to.)
     it.steps_v = *(gu32_t *)((gbyte_t *)((gu32_t *)hd.steps + (cu.wg * (uint32_t)hd.ng + cu.g)) + zero_v);
     it.slot = ((gu16_t *)hd.tasks)[(size_t)(cu.wg * (uint32_t)hd.ng + cu.g) * 64 + lane];
+    // (ordinary loads: with a non-temporal hint the steps requested past the end of a short group -- the head of
+    // the next group, which another wavefront is about to request -- come from memory twice; measured 7 % slower)
 #pragma unroll
     for (int st = 0; st < PF; ++st) load_step(it.q[st], gbase, st);
     const uint32_t last = first + PF >= common ? 1u : 0u;
