@@ -56,7 +56,7 @@ def parse():
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter run (wrap in rocprofv3 --pmc FETCH_SIZE or WRITE_SIZE): three plain copies of "
                          "known size as calibration, then one eager pass over the headline gemv stack; no timing")
-    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "gemv_packed_c2_hbm_traffic.md"),
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "gemv_pipeline_c2_hbm_traffic.md"),
                     help="summary written by paper_2503_02236_amd.profile_summary traffic; its "
                          "'traffic_bytes_per_launch:' line fills roofline.traffic")
     return ap.parse_args()
@@ -177,6 +177,8 @@ def main():
                                        "mfma_fp16_register_loop_random_operands_TFLOPs": round(ceil_mfma_rand, 1),
                                        "mfma_fp16_lds_fed_random_operands_TFLOPs": round(ceil_mfma_lds, 1)}
         torch.cuda.empty_cache()
+
+    cpu_secondary = {}   # the oracle timed on bounded samples of the secondary workloads (context beside cpu_baseline)
 
     # ------------------------------------------------------------------ headline: C2 gemv stack
     if want("gemv"):
@@ -365,6 +367,18 @@ def main():
                                       "sample": "%d of the %d matrices (the first %d decoder blocks), mean of %d passes, "
                                                 "%.2f s per pass" % (len(host_block0), len(singles),
                                                                      len(host_block0) // 7, reps, dt)}
+            # the same oracle on ONE thread, on the first decoder block
+            n_threads = oracle.threads()
+            oracle.set_threads(1)
+            t0 = time.perf_counter()
+            for w in host_block0[:7]:
+                oracle.gemv(w.codes, w.codebooks, w.scale, xs[w.K])
+            dt1 = time.perf_counter() - t0
+            one_thread = oracle.threads()
+            oracle.set_threads(n_threads)
+            cpu_secondary["gemv_single_thread"] = {
+                "value": round(sum(w.effective_bytes(1) for w in host_block0[:7]) / dt1 / 1e9, 4), "unit": "GB/s",
+                "cores": one_thread, "kind": "oracle", "sample": "the 7 matrices of the first decoder block, one pass, %.2f s" % dt1}
         del calls, singles, per_shape, graph
         torch.cuda.empty_cache()
 
@@ -387,6 +401,18 @@ def main():
                                             "pct_measured_mfma_lds_fed_random_operands": round(100 * tf / ceil_mfma_lds, 2)}
                 del wd, Y, gws
         result["gemm_prefill_M2048_K4096"] = gemm
+        if not args.skip_cpu:
+            # the oracle on a bounded sample of the same product: 1024 evenly spaced output channels, all 2048 rows of X
+            import oracle
+            wh = wl.config4_layer(4096, 8)
+            rows = list(range(0, 4096, 4))
+            xh = X.cpu().numpy()
+            t0 = time.perf_counter()
+            oracle.gemm(wh.codes, wh.codebooks, wh.scale, xh, rows=rows)
+            dt = time.perf_counter() - t0
+            cpu_secondary["gemm_prefill_N4096_v8"] = {
+                "value": round(2.0 * 2048 * len(rows) * 4096 / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.threads(),
+                "kind": "oracle", "sample": "%d of 4096 output channels x 2048 rows, one pass, %.2f s" % (len(rows), dt)}
 
     # ------------------------------------------------------------------ secondary: C5 attention decode
     if want("attn") and not args.skip_secondary:
@@ -406,6 +432,16 @@ def main():
         result["attn_decode_B16_H32_T4096"] = {"us": round(ms * 1e3, 2), "GBps": round(b / ms / 1e6, 1),
                                                "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2),
                                                "pct_measured_stream_read": round(100 * b / ms / 1e6 / ceil_hbm, 2)}
+        if not args.skip_cpu:
+            # the oracle on the whole workload (16 sequences, all heads, all 4096 tokens): a few seconds
+            import oracle
+            nb = kv.B
+            t0 = time.perf_counter()
+            oracle.attn_decode(kv.k_codes[:nb], kv.v_codes[:nb], kv.k_codebooks, kv.v_codebooks, kv.q[:nb], float(sm))
+            dt = time.perf_counter() - t0
+            cpu_secondary["attn_decode_B16_H32_T4096"] = {
+                "value": round(b * nb / kv.B / dt / 1e9, 4), "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+                "sample": "%d of %d sequences, one pass, %.2f s" % (nb, kv.B, dt)}
         # on-the-fly quantization of new tokens into that cache: one decode step, and a 4096-token prefill
         kd = ring[0]
         k1 = torch.randn((kv.B, kv.H, 1, kv.D), device=dev).to(torch.float16)
@@ -532,6 +568,8 @@ def main():
         del variants
         torch.cuda.empty_cache()
 
+    if cpu_secondary:
+        result["cpu_baseline_secondary"] = cpu_secondary
     result["setup_plus_run_s"] = round(time.time() - t_setup, 1)
     print(json.dumps(result), flush=True)
 

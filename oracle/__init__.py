@@ -47,6 +47,8 @@ def _load():
         lib.vq_oracle_half_to_float_array.restype = None
         lib.vq_oracle_half_to_float_array.argtypes = [c_void, c_void, ctypes.c_size_t]
         lib.vq_oracle_threads.restype = c_int
+        lib.vq_oracle_set_threads.restype = None
+        lib.vq_oracle_set_threads.argtypes = [c_int]
         lib.vq_oracle_dequant.restype = None
         lib.vq_oracle_dequant.argtypes = [c_int] * 8 + [c_void] * 3
         lib.vq_oracle_unpack12.restype = None
@@ -62,6 +64,11 @@ def _load():
                                               + [c_void] * 3)
         _lib = lib
     return _lib
+
+
+def set_threads(n: int) -> None:
+    """Thread count of the following calls (for timing the oracle on one core); results do not depend on it."""
+    _load().vq_oracle_set_threads(int(n))
 
 
 def threads() -> int:

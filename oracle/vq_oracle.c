@@ -71,6 +71,16 @@ void vq_oracle_half_to_float_array(const uint16_t *h, float *out, size_t n)
     for (size_t i = 0; i < n; ++i) out[i] = vq_oracle_half_to_float(h[i]);
 }
 
+/* Thread count of the following calls (timing harnesses: the single-thread baseline); no effect on results. */
+void vq_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int vq_oracle_threads(void)
 {
 #ifdef _OPENMP

@@ -4,6 +4,12 @@
   python -m paper_2503_02236_amd.profile_summary traffic <fetch_counter_collection.csv> <write_counter_collection.csv>
          <out.md> --cmd "<command>" [--copy-bytes N]
 
+  python -m paper_2503_02236_amd.profile_summary counters <out.md> <counter_collection.csv>... --kernel <substring>...
+         --title "..." --cmd "<command>" [--note "..."]
+
+`counters` writes, for every kernel whose name contains one of the substrings, the average per dispatch of every counter
+found in the given files (one file per counter run).
+
 `traffic` expects two counter runs of `bench.py --pmc-probe` (one with FETCH_SIZE, one with
 WRITE_SIZE; both counters are in KiB per dispatch).  The probe run starts with plain copies of
 a known size; the ratio counter / known bytes of those copies is the calibration factor every
@@ -53,7 +59,7 @@ def traffic(args):
     copy_name = next(k for k in fetch if "probe_copy" in k)
     f_cal = sum(fetch[copy_name]) / len(fetch[copy_name]) / args.copy_bytes
     w_cal = sum(write[copy_name]) / len(write[copy_name]) / args.copy_bytes
-    kernels = sorted(k for k in fetch if "gemv_packed" in k)
+    kernels = sorted(k for k in fetch if "gemv_packed" in k or "gemv_pipeline" in k)
     mains = [k for k in kernels if "finalize" not in k]         # one dispatch of these per launch of the stack
     n = sum(len(fetch[k]) for k in mains)
     rd = sum(sum(fetch[k]) for k in kernels) / n / f_cal
@@ -67,10 +73,31 @@ def traffic(args):
         for k in kernels:
             f.write("| %s | %d | %.0f | %.0f |\n" % (k, len(fetch[k]), sum(fetch[k]) / len(fetch[k]) / f_cal,
                                                     sum(write[k]) / len(write[k]) / w_cal))
-        f.write("\nper launch (a vq_gemv or vq_gemv_batch call: main kernel + its reduction kernel), average over the "
-                "%d launches of one pass over the 32-block stack:\n\n" % n)
+        f.write("\nper launch (main kernel + its share of the reduction kernels: a vq_gemv / vq_gemv_batch call, or with "
+                "vq_gemv_pipeline the whole pass), average over the %d main-kernel launches of one pass over the "
+                "32-block stack:\n\n" % n)
         f.write("read_bytes_per_launch: %.0f\nwritten_bytes_per_launch: %.0f\ntraffic_bytes_per_launch: %.0f\n"
                 % (rd, wr, rd + wr))
+
+
+def counters(args):
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for path in args.src:
+        per = collections.defaultdict(lambda: collections.defaultdict(float))   # (kernel, dispatch) -> counter -> sum over units
+        for r in csv.DictReader(open(path)):
+            if any(k in r["Kernel_Name"] for k in args.kernel):
+                per[(_short(r["Kernel_Name"]), r["Dispatch_Id"])][r["Counter_Name"]] += float(r["Counter_Value"])
+        for (k, _), cs in per.items():
+            for c, v in cs.items():
+                agg[k][c].append(v)
+    with open(args.out, "w") as f:
+        f.write("# %s\n\ncommands (one run per counter set):\n`%s`\n\n%s\n\n" % (args.title, args.cmd, args.note))
+        for k in sorted(agg):
+            n = max(len(v) for v in agg[k].values())
+            f.write("## %s (%d dispatches; average per dispatch, summed over the chip)\n\n| counter | value |\n|---|---|\n" % (k, n))
+            for c in sorted(agg[k]):
+                f.write("| %s | %.0f |\n" % (c, sum(agg[k][c]) / len(agg[k][c])))
+            f.write("\n")
 
 
 def main():
@@ -89,6 +116,14 @@ def main():
     b.add_argument("--cmd", required=True)
     b.add_argument("--copy-bytes", type=int, default=256 << 20)
     b.set_defaults(fn=traffic)
+    c = sub.add_parser("counters")
+    c.add_argument("out")
+    c.add_argument("src", nargs="+")
+    c.add_argument("--kernel", required=True, nargs="+")
+    c.add_argument("--title", required=True)
+    c.add_argument("--cmd", required=True)
+    c.add_argument("--note", default="")
+    c.set_defaults(fn=counters)
     args = ap.parse_args()
     args.fn(args)
 
