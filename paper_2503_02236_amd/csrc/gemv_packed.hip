@@ -1008,8 +1008,8 @@ __global__ __launch_bounds__(kFinalizeRows) void gemv_packed_finalize_batch_kern
 // so the grid always drains.
 // The S partial sums per row of all problems are added by one reduction launch behind it.
 constexpr int kPipeWgs = 256;
-constexpr int kPipeConsumers = 13, kPipeProducers = 2;   // wavefronts 0 .. 12 and 14, 15; wavefront 13 is the scout
-constexpr int kPipeScout = kPipeConsumers, kPipeFirstProducer = kPipeConsumers + 1;
+constexpr int kPipeConsumers = 14, kPipeProducers = 2;   // wavefronts 0 .. 13 and 14, 15
+constexpr int kPipeFirstProducer = kPipeConsumers;
 constexpr int kPipeOps = 12;                            // staging operations per producer and problem
 constexpr uint32_t kPipeImage = 65536;                  // LDS bytes from one image to the other
 constexpr uint32_t kPipeFlags = 2 * kPipeImage;         // staged[2], done[2], next group to hand out
@@ -1305,35 +1305,40 @@ __device__ __forceinline__ void pipe_stage(const PipeStage &st, int lane, unsign
     }
 }
 
-// The scout runs ahead of everybody: it reads the descriptor of a coming problem through the scalar cache and
-// touches the lines of its codebook slice and of its x, so that the producers' and consumers' scalar loads hit
-// the scalar cache and the producers' transfers hit this die's L2.  A first touch of anything costs a trip to
-// memory, 1.5 - 2 us under this load: as long as a short problem's gathers.
-__device__ __forceinline__ void pipe_scout(cproblem_t *table, uint32_t n, int bid, int lane, PipeSync &sy) {
-    for (uint32_t k = 0; k < n; ++k) {
-        // not more than three problems ahead of the slowest consumer: what is touched must still be cached when used
-        if (k >= 3) pipe_wait(kPipeFlags + 8u + ((k - 3u) & 1u) * 4u, (uint32_t)kPipeConsumers * ((k - 3u) / 2u + 1u), sy);
-        cu32_t *words = (cu32_t *)&table[k];
-        uint32_t acc = 0;
+// Scouting: between two images a producer reads the descriptor of a coming problem through the scalar cache and
+// touches its share of the lines of that problem's codebook slice and x, so that the producers' and consumers'
+// scalar loads hit the scalar cache and the staging transfers hit this die's L2.  A first touch of anything costs
+// a trip to memory, 1.5 - 2 us under this load: as long as a short problem's gathers.  Returns a value that
+// depends on the touches: the caller declares it used after its next full wait (so the touches cost no wait of
+// their own).
+struct PipeWarm {
+    uint32_t w[4];
+};
+__device__ __forceinline__ PipeWarm pipe_scout(cproblem_t *table, uint32_t k, int bid, int pw, int lane) {
+    cu32_t *words = (cu32_t *)&table[k];
+    uint32_t acc = 0;
 #pragma unroll
-        for (int l = 0; l < (int)(sizeof(PipeProblem) / 64); ++l) acc |= words[l * 16];   // (one word per 64-byte line)
-        asm volatile("" ::"s"(acc));
-        cproblem_t &pr = table[k];
-        const int S = pr.S, RB = (int)pr.rbv;
-        uint32_t warm = 0u;
-        if (bid < S * RB) {
-            int s, rb;
-            slice_and_block(bid, S, RB, s, rb);
-            const uint32_t slice_bytes = 16u << pr.EB, x_bytes = (uint32_t)pr.J * 16u;
-            const gbyte_t *slice = (gbyte_t *)pr.cb + (size_t)s * slice_bytes;
-            const gbyte_t *x = (gbyte_t *)pr.x;
-            for (uint32_t line = (uint32_t)lane * 128u; line < slice_bytes; line += 64u * 128u)
-                warm |= *(const volatile gu32_t *)(slice + line);
-            for (uint32_t line = (uint32_t)lane * 128u; line < x_bytes; line += 64u * 128u)
-                warm |= *(const volatile gu32_t *)(x + line);
-        }
-        asm volatile("" ::"v"(warm));
-    }
+    for (int l = 0; l < (int)(sizeof(PipeProblem) / 64); ++l) acc |= words[l * 16];   // (one word per 64-byte line)
+    asm volatile("" ::"s"(acc));
+    cproblem_t &pr = table[k];
+    const int S = pr.S, RB = (int)pr.rbv;
+    int s, rb;
+    slice_and_block(bid < S * RB ? bid : 0, S, RB, s, rb);
+    const uint32_t slice_bytes = 16u << pr.EB, x_bytes = (uint32_t)pr.J * 16u;
+    const gbyte_t *slice = (gbyte_t *)pr.cb + (size_t)s * slice_bytes;
+    const gbyte_t *x = (gbyte_t *)pr.x;
+    // two lines of the slice and two of x per lane (a 32 KiB slice and up to 32 KiB of x with two producers); no
+    // conditions and no dependent arithmetic: a lane past the end touches the last line again
+    const uint32_t first = (uint32_t)(pw * 64 + lane) * 128u, stride = (uint32_t)kPipeProducers * 64u * 128u;
+    PipeWarm r;
+    r.w[0] = *(const volatile gu32_t *)(slice + min(first, slice_bytes - 128u));
+    r.w[1] = *(const volatile gu32_t *)(slice + min(first + stride, slice_bytes - 128u));
+    r.w[2] = *(const volatile gu32_t *)(x + min(first, x_bytes - 16u));
+    r.w[3] = *(const volatile gu32_t *)(x + min(first + stride, x_bytes - 16u));
+    return r;
+}
+__device__ __forceinline__ void pipe_warm_done(const PipeWarm &r) {
+    asm volatile("" ::"v"(r.w[0]), "v"(r.w[1]), "v"(r.w[2]), "v"(r.w[3]));
 }
 
 // The 256 workgroups form 1, 2, 4 or 8 independent lanes, each with a problem list of its own (problem k of the
@@ -1363,20 +1368,18 @@ __global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *
     if (threadIdx.x < 5) reinterpret_cast<uint32_t *>(smem + kPipeFlags)[threadIdx.x] = threadIdx.x < 4 ? 0u : (uint32_t)kPipeConsumers;
     __syncthreads();
     PipeSync sy = {false};
-    if (wave == kPipeScout) {
-        pipe_scout(table, n, bid, lane, sy);
-        if (sy.broken && lane == 0) *status = 1u;
-        return;
-    }
     if (wave >= kPipeFirstProducer) {
-        // ---- producer
+        // ---- producer (and scout, two problems ahead, in the slack between two images)
         const int pw = wave - kPipeFirstProducer;
+        PipeWarm warm = pipe_scout(table, n > 2u ? 2u : 0u, bid, pw, lane);
         for (uint32_t k = 0; k < n; ++k) {
             const PipeStage st = pipe_stage_read(table, k, bid, pw);
             if (k >= 2) pipe_wait(kPipeFlags + 8u + (k & 1u) * 4u, (uint32_t)kPipeConsumers * ((k - 2u) / 2u + 1u), sy);
             pipe_stage(st, lane, smem + (k & 1u) * kPipeImage);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the transfers of this wavefront
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the transfers of this wavefront (and the touches before them)
+            pipe_warm_done(warm);
             pipe_signal(kPipeFlags + (k & 1u) * 4u, lane);
+            warm = pipe_scout(table, k + 3u < n ? k + 3u : n - 1u, bid, pw, lane);
         }
         if (sy.broken && lane == 0) *status = 1u;
         return;
@@ -1832,7 +1835,7 @@ int launch_gemv_pipeline(const GemvPipeline *h, hipStream_t s) {
     if (hipGetDevice(&dev) != hipSuccess || dev != h->device) return VQ_ERR_LAUNCH;   // the table lives on another GPU
     static KernelSetup setup;   // (the atoms hold absolute LDS addresses: no static LDS allowed)
     if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_pipeline_kernel), kPipeLds, true, setup)) return st;
-    gemv_pipeline_kernel<<<kPipeWgs, (kPipeConsumers + 1 + kPipeProducers) * 64, kPipeLds, s>>>(h->table, h->items, h->lanes, h->status);
+    gemv_pipeline_kernel<<<kPipeWgs, (kPipeConsumers + kPipeProducers) * 64, kPipeLds, s>>>(h->table, h->items, h->lanes, h->status);
     if (int st = launch_status()) return st;
     gemv_pipeline_finalize_kernel<<<dim3((h->max_n + kFinalizeRows - 1) / kFinalizeRows, h->n), kFinalizeRows, 0, s>>>(h->table);
     return launch_status();

@@ -221,6 +221,7 @@ def config4_layer(N: int, v: int) -> VQWeight:
 
 
 def config5_kv(B: int = 16, H: int = 32, D: int = 128, T: int = 4096, G: int = 1,
-               ragged: bool = False) -> VQKVCache:
-    """VQ KV cache decode attention: v=4, 256-entry codebooks ~N(0,1) per (head, K|V)."""
-    return make_kv(B, H, D, T, 4, 256, G, seed_for(5, G), ragged=ragged)
+               ragged: bool = False, v: int = 4) -> VQKVCache:
+    """VQ KV cache decode attention: v=4, 256-entry codebooks ~N(0,1) per (head, K|V).
+    v=2 with G=64 is the paper's CQ-4 row of Tbl. III (one codebook per 2-channel sub-space, 4 bits per value)."""
+    return make_kv(B, H, D, T, v, 256, G, seed_for(5, G + (100 if v != 4 else 0)), ragged=ragged)

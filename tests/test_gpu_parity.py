@@ -636,6 +636,15 @@ def test_attn_config5_coupled_quantization_layout_full_size(gpu_device):
     assert_close(out, oracle_attn(kv, sm), "C5 G=32 full")
 
 
+def test_attn_config5_cq4_full_size(gpu_device):
+    # the paper's CQ-4 row (Tbl. III: VQ<2,8,1>): one codebook per 2-channel sub-space, 64 per head and side
+    # (64 KiB of K codebooks per head), 64 code bytes per token and side, at the full C5 shape
+    kv = wl.config5_kv(G=64, v=2)
+    sm = 1.0 / np.sqrt(128.0)
+    out = run_attn(kv, gpu_device, sm)
+    assert_close(out, oracle_attn(kv, sm), "C5 CQ-4 full")
+
+
 def test_attn_config5_full_size(gpu_device):
     kv = wl.config5_kv()
     sm = 1.0 / np.sqrt(128.0)
