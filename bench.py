@@ -467,6 +467,17 @@ def main():
         b = kv.effective_bytes()
         result["attn_decode_B16_H32_T4096_cq32"] = {"us": round(ms * 1e3, 2), "GBps": round(b / ms / 1e6, 1),
                                                     "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2)}
+        # the other side of the paper's trade-off for this layout: channel-parallel workgroups, partial inner products
+        # accumulated through global memory (three launches)
+        ws_cp = vq.new_workspace(kv.B * kv.H * (kv.D // 32 + 1) * kv.T * 4, dev)
+
+        def attn_loop_cp():
+            for kd in ring:
+                vq.vq_attn_decode_channel_parallel(kd, q, sm, out=out, ws=ws_cp)
+        ms = timed(attn_loop_cp, 10, 2) / len(ring)
+        result["attn_decode_B16_H32_T4096_cq32_channel_parallel"] = {
+            "us": round(ms * 1e3, 2), "GBps": round(b / ms / 1e6, 1), "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2)}
+        del ws_cp
         del ring
         torch.cuda.empty_cache()
         # CQ-4 (Tbl. III: VQ<2,8,1>): 64 codebooks per head and side, twice the code bytes per token

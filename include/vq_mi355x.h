@@ -331,6 +331,22 @@ typedef struct vq_kv_t {
  */
 int vq_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out,
                    void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The same product by the CHANNEL-PARALLEL, codebook-centric dataflow of Sec. VI-A for caches with one codebook
+ * per channel sub-space (coupled quantization, Sec. III-B / Tbl. IV): a workgroup owns 32 channels of a head and
+ * stages only their codebooks; the partial inner products of the D / 32 channel groups are accumulated through
+ * global memory (three launches: partial scores, sum + softmax over the tokens, values).  vq_attn_decode keeps
+ * all codebooks of a head in LDS and switches between them instead (token-parallel); this entry point exists so
+ * that the two sides of the paper's trade-off can be measured against each other.  Same arguments and results
+ * (within the tolerance of the fp32 reductions, whose order differs); repeated calls are bit-identical.
+ * Needs D % 32 == 0, cb_groups a multiple of D / 32 and at most 60 KiB of codebooks per channel group
+ * (VQ_ERR_UNSUPPORTED otherwise).  ws: vq_attn_decode_channel_parallel_workspace(kv) bytes
+ * (B H (D / 32 + 1) T floats), 16-byte aligned; the query returns 0 for an unsupported cache.
+ */
+int vq_attn_decode_channel_parallel(const vq_kv_t *kv, const void *q, float sm_scale, void *out,
+                                    void *ws, size_t ws_bytes, void *stream);
+size_t vq_attn_decode_channel_parallel_workspace(const vq_kv_t *kv);
 size_t vq_attn_decode_workspace(const vq_kv_t *kv);
 
 /*

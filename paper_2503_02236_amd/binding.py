@@ -96,6 +96,9 @@ SYMBOLS = {
     "vq_attn_decode": (ctypes.c_int, [ctypes.POINTER(vq_kv_t), ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "vq_attn_decode_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_kv_t)]),
+    "vq_attn_decode_channel_parallel": (ctypes.c_int, [ctypes.POINTER(vq_kv_t), ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
+                                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "vq_attn_decode_channel_parallel_workspace": (ctypes.c_size_t, [ctypes.POINTER(vq_kv_t)]),
     "vq_dequant": (ctypes.c_int, [ctypes.POINTER(vq_weight_t), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]),
     "vq_kv_dequant": (ctypes.c_int, [ctypes.POINTER(vq_kv_t), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]),
     "vq_kv_quantize": (ctypes.c_int, [ctypes.POINTER(vq_kv_t), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
@@ -460,6 +463,19 @@ def vq_attn_decode(kv: VQKVDev, q: torch.Tensor, sm_scale: float, out: Optional[
     ws_t, ws_p, ws_n = _workspace(int(lib().vq_attn_decode_workspace(ctypes.byref(d))), q.device, ws)
     _check(lib().vq_attn_decode(ctypes.byref(d), _dev(q, "q", torch.float16), float(sm_scale),
                                 _dev(out, "out", torch.float16), ws_p, ws_n, _stream()), "vq_attn_decode")
+    return out
+
+
+def vq_attn_decode_channel_parallel(kv: VQKVDev, q: torch.Tensor, sm_scale: float, out: Optional[torch.Tensor] = None,
+                                    ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The same product by the channel-parallel dataflow (caches with one codebook per channel sub-space)."""
+    if out is None:
+        out = torch.empty_like(q)
+    d = kv.desc()
+    ws_t, ws_p, ws_n = _workspace(int(lib().vq_attn_decode_channel_parallel_workspace(ctypes.byref(d))), q.device, ws)
+    _check(lib().vq_attn_decode_channel_parallel(ctypes.byref(d), _dev(q, "q", torch.float16), float(sm_scale),
+                                                 _dev(out, "out", torch.float16), ws_p, ws_n, _stream()),
+           "vq_attn_decode_channel_parallel")
     return out
 
 

@@ -380,6 +380,25 @@ int vq_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, 
     return launch_attn_decode(kv, q, sm_scale, out, ws, static_cast<hipStream_t>(stream));
 }
 
+size_t vq_attn_decode_channel_parallel_workspace(const vq_kv_t *kv) {
+    if (check_kv(kv) != VQ_OK || !attn_channel_supported(kv)) return 0;
+    return attn_channel_workspace(kv);
+}
+
+int vq_attn_decode_channel_parallel(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, size_t ws_bytes,
+                                    void *stream) {
+    int st = check_kv(kv);
+    if (st != VQ_OK) return st;
+    if (!attn_channel_supported(kv)) return VQ_ERR_UNSUPPORTED;
+    if (!q || !out) return VQ_ERR_NULL;
+    if (!aligned16(q) || !aligned16(out)) return VQ_ERR_ALIGN;
+    if (kv->B == 0 || kv->H == 0) return VQ_OK;
+    const size_t need = attn_channel_workspace(kv);
+    if (need && (!ws || ws_bytes < need)) return VQ_ERR_WORKSPACE;
+    if (ws && !aligned16(ws)) return VQ_ERR_ALIGN;
+    return launch_attn_channel(kv, q, sm_scale, out, ws, static_cast<hipStream_t>(stream));
+}
+
 int vq_kv_quantize(const vq_kv_t *kv, const void *k_new, const void *v_new, int n_new, int pos, void *stream) {
     int st = check_kv(kv);
     if (st != VQ_OK) return st;

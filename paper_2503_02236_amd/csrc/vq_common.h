@@ -117,6 +117,10 @@ size_t gemm_workspace(const vq_weight_t *w, int M);
 int launch_gemm_dense(const half_t *A, const half_t *B, const half_t *scale, half_t *C, int M, int N, int K,
                       hipStream_t s);
 int launch_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, hipStream_t s);
+// channel-parallel variant for caches with one codebook per channel sub-space (attn_channel.hip)
+bool attn_channel_supported(const vq_kv_t *kv);
+size_t attn_channel_workspace(const vq_kv_t *kv);
+int launch_attn_channel(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, hipStream_t s);
 size_t attn_decode_workspace(const vq_kv_t *kv);
 int launch_kv_quantize(const vq_kv_t *kv, const void *k_new, const void *v_new, int n_new, int pos, hipStream_t s);
 int launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s);

@@ -135,6 +135,23 @@ def test_attention_argument_validation():
     assert lib.vq_attn_decode(ctypes.byref(kvdesc(B=0)), P, 0.1, P, None, 0, None) == 0
 
 
+def test_attention_channel_parallel_argument_validation():
+    lib = vq.lib()
+    f, wsq = lib.vq_attn_decode_channel_parallel, lib.vq_attn_decode_channel_parallel_workspace
+    cq = kvdesc(cb_groups=32)                            # D = 128, v = 4: 4 channel groups of 8 codebooks
+    need = wsq(ctypes.byref(cq))
+    assert need == cq.B * cq.H * (128 // 32 + 1) * cq.T * 4
+    assert f(ctypes.byref(cq), None, 0.1, P, P, need, None) == VQ_ERR_NULL
+    assert f(ctypes.byref(cq), P, 0.1, P + 8, P, need, None) == VQ_ERR_ALIGN
+    assert f(ctypes.byref(cq), P, 0.1, P, None, 0, None) == VQ_ERR_WORKSPACE
+    assert f(ctypes.byref(cq), P, 0.1, P, P, need - 1, None) == VQ_ERR_WORKSPACE
+    assert f(ctypes.byref(cq), P, 0.1, P, P + 4, need, None) == VQ_ERR_ALIGN
+    one = kvdesc()                                       # one codebook per head: does not divide over 4 channel groups
+    assert wsq(ctypes.byref(one)) == 0
+    assert f(ctypes.byref(one), P, 0.1, P, P, 1 << 30, None) == VQ_ERR_UNSUPPORTED
+    assert f(ctypes.byref(kvdesc(cb_groups=32, B=0)), P, 0.1, P, None, 0, None) == 0
+
+
 def test_kv_quantize_argument_validation():
     lib = vq.lib()
     kv = kvdesc()

@@ -636,6 +636,44 @@ def test_attn_config5_coupled_quantization_layout_full_size(gpu_device):
     assert_close(out, oracle_attn(kv, sm), "C5 G=32 full")
 
 
+@pytest.mark.parametrize("B,H,T,v,G,ragged", [
+    (2, 3, 1, 4, 32, False),       # a single token
+    (2, 2, 300, 4, 32, False),     # one partial range of 256 tokens + a tail
+    (3, 2, 1000, 4, 32, True),     # ragged lengths (with a full-length sequence)
+    (2, 2, 513, 2, 64, False),     # CQ-4: 16 codes per channel group and token
+    (1, 2, 700, 8, 16, True),      # v = 8: 4 codes per channel group
+    (2, 2, 400, 4, 4, False),      # one codebook per channel group (the coarsest layout the variant takes)
+])
+def test_attn_channel_parallel(gpu_device, B, H, T, v, G, ragged):
+    """vq_attn_decode_channel_parallel (Sec. VI-A codebook-centric dataflow with global accumulation of the partial
+    inner products) against the oracle and against the token-parallel kernel; repeated calls bit-identical."""
+    kv = wl.make_kv(B, H, 128, T, v, 256, G, seed=8800 + T + G, ragged=ragged)
+    if ragged:
+        kv.seq_lens[-1] = 0                              # an empty sequence yields zeros
+    sm = 1.0 / np.sqrt(128.0)
+    kd = vq.kv_to_device(kv, gpu_device)
+    qd = dev_x(kv.q, gpu_device)
+    out = vq.vq_attn_decode_channel_parallel(kd, qd, sm)
+    torch.cuda.synchronize()
+    want = oracle_attn(kv, sm)
+    assert_close(out, want, "channel-parallel")
+    assert_close(vq.vq_attn_decode(kd, qd, sm), want, "token-parallel, same cache")
+    again = vq.vq_attn_decode_channel_parallel(kd, qd, sm)
+    torch.cuda.synchronize()
+    assert torch.equal(out, again)
+    if ragged:
+        assert float(out[-1].abs().max()) == 0.0
+
+
+def test_attn_channel_parallel_config5_cq_full_size(gpu_device):
+    kv = wl.config5_kv(G=32)
+    sm = 1.0 / np.sqrt(128.0)
+    kd = vq.kv_to_device(kv, gpu_device)
+    out = vq.vq_attn_decode_channel_parallel(kd, dev_x(kv.q, gpu_device), sm)
+    torch.cuda.synchronize()
+    assert_close(out, oracle_attn(kv, sm), "C5 G=32 full, channel-parallel")
+
+
 def test_attn_config5_cq4_full_size(gpu_device):
     # the paper's CQ-4 row (Tbl. III: VQ<2,8,1>): one codebook per 2-channel sub-space, 64 per head and side
     # (64 KiB of K codebooks per head), 64 code bytes per token and side, at the full C5 shape
