@@ -1093,12 +1093,17 @@ __host__ __device__ __forceinline__ size_t pipe_partial_index(uint32_t planes, u
 // long groups takes fewer of them.  What a wavefront takes is ascending, so it still passes the problems in order.
 struct PipeCursor {
     uint32_t t, h;       // the group being requested (number in the lane's list) and its next piece
-    uint32_t t_next_v;   // the group after it (taken ahead; in a vector register until needed: no wait for the counter)
-    // the group being requested, worked out when the group before it had been requested
+    // the group being requested, worked out before the piece before it is worked on
     uint32_t word;       // its entry of the problem's group table (prefix << 16 | common steps)
     uint32_t wg, g, jb;  // block in the packed tables, group in the block, row block of the image
     bool none;           // past the last group
     bool advance;        // the piece last requested ended its group
+    // two groups taken ahead, so that nothing here waits: the group after the current one with its entry of the
+    // table of groups already requested (a scalar load that lands while a piece is worked on), and the one after
+    // that still on its way back from the LDS counter (in a vector register until needed)
+    uint32_t where_a;
+    uint32_t t_b, where_b;
+    uint32_t t_c_v;
 };
 // (take = 0 reads the counter without taking anything: the callers have no branch around this)
 __device__ __forceinline__ uint32_t pipe_grab(int lane, uint32_t take) {
@@ -1137,14 +1142,18 @@ __device__ __forceinline__ void pipe_head_load(PipeHead &h, cproblem_t *table, u
 __device__ __forceinline__ void pipe_next(PipeCursor &cu, PipeHead &hd, cproblem_t *table, cu32_t *items, uint32_t total_items, int bid,
                                           int lane) {
     const bool advance = cu.advance;
-    const uint32_t taken = __builtin_amdgcn_readfirstlane(cu.t_next_v);
-    const uint32_t fresh = pipe_grab(lane, advance ? 1u : 0u);
-    cu.t_next_v = advance ? fresh : cu.t_next_v;
-    cu.t = advance ? taken : cu.t;
+    // current <- next (its table entry was requested one call ago), next <- the one after (taken from the counter
+    // one call ago; its table entry is requested now), and one more is taken from the counter
+    const uint32_t where = advance ? cu.where_b : cu.where_a;
+    cu.where_a = where;
+    cu.t = advance ? cu.t_b : cu.t;
     cu.h = advance ? 0u : cu.h + 1u;
+    const uint32_t t_c = __builtin_amdgcn_readfirstlane(cu.t_c_v);
+    cu.t_b = advance ? t_c : cu.t_b;
+    const uint32_t fresh = pipe_grab(lane, advance ? 1u : 0u);
+    cu.t_c_v = advance ? fresh : cu.t_c_v;
+    cu.where_b = items[cu.t_b < total_items ? cu.t_b : total_items - 1];   // (past the end: the last group once more, never used)
     cu.none = cu.t >= total_items;
-    const uint32_t tt = cu.none ? total_items - 1 : cu.t;   // (past the end: the last group's loads once more, never used)
-    const uint32_t where = items[tt];
     const uint32_t i = where & 0xFFFFu;
     if (i != hd.i) pipe_head_load(hd, table, i, bid);
     cu.jb = (where >> 16) & 15u;
@@ -1365,7 +1374,7 @@ __global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *
     if (n == 0u) return;
     cproblem_t *table = (cproblem_t *)table_;
     cu32_t *items = (cu32_t *)items_;
-    if (threadIdx.x < 5) reinterpret_cast<uint32_t *>(smem + kPipeFlags)[threadIdx.x] = threadIdx.x < 4 ? 0u : (uint32_t)kPipeConsumers;
+    if (threadIdx.x < 5) reinterpret_cast<uint32_t *>(smem + kPipeFlags)[threadIdx.x] = threadIdx.x < 4 ? 0u : 2u * (uint32_t)kPipeConsumers;
     __syncthreads();
     PipeSync sy = {false};
     if (wave >= kPipeFirstProducer) {
@@ -1392,11 +1401,14 @@ __global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *
     // three pieces in rotation: while one is worked on, the requests of the next two are in flight (a piece is
     // 4 - 8 steps, about a microsecond of this wavefront's time; a request that misses the caches takes two)
     PipePiece<PF> a, b, d;
+    // the first three groups of wavefront w are w, w + NC and w + 2 NC (the counter starts behind these)
     PipeCursor cu;
-    cu.t_next_v = (uint32_t)wave;   // the first group of wavefront w is group w (the counter starts behind these)
+    cu.t = 0u; cu.h = 0u; cu.advance = true; cu.where_a = 0u;
+    cu.t_b = (uint32_t)wave;
+    cu.where_b = items[cu.t_b < total_items ? cu.t_b : total_items - 1];
+    cu.t_c_v = (uint32_t)(wave + kPipeConsumers);
     PipeHead hd;
     pipe_head_load(hd, table, 0u, bid);
-    cu.t = 0u; cu.h = 0u; cu.advance = true;
     PipeBody bd;
     pipe_body_load(bd, table, 0u, bid);
     Acc3 acc = {{0.f, 0.f, 0.f}};
