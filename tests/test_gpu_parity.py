@@ -432,6 +432,48 @@ def test_gemv_pipeline_mixed_shapes(gpu_device):
         [(1, 64, 65536, True)]], 9820)
 
 
+def test_gemv_pipeline_as_replayed_graph(gpu_device):
+    """vq_gemv_pipeline_run captured into a HIP graph (as bench.py times it) and replayed several times with eager
+    work and synchronisations in between: every replay gives the bits of vq_gemv."""
+    calls, flat = [], []
+    for c in range(5):
+        call = []
+        for k in range(1 + c % 2):
+            N, K = [(4096, 512), (1000, 1024), (2500, 256)][(c + k) % 3]
+            w = wl.make_weight(N, K, 8, 16, 1, 65536, 0.02, seed=9900 + 10 * c + k)
+            wd = vq.weight_to_device(w, gpu_device, prepack=True, keep_codes=False)
+            xd = dev_x(wl.make_activations(1, K, seed=9950 + 10 * c + k), gpu_device)
+            call.append((wd, xd, torch.full((1, N), 7.0, dtype=torch.float16, device=gpu_device)))
+        calls.append(call)
+        flat += call
+    want = [vq.vq_gemv(wd, xd).clone() for (wd, xd, _) in flat]
+    torch.cuda.synchronize()
+    pipe = vq.GemvPipeline(calls)
+
+    def check(tag):
+        torch.cuda.synchronize()
+        assert pipe.status() == 0, tag
+        for (wd, xd, y), w_ in zip(flat, want):
+            assert torch.equal(y, w_), tag
+            y.fill_(7.0)
+        torch.cuda.synchronize()
+
+    assert pipe.run() == 0
+    check("eager")
+    g = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(g, stream=cap):
+            assert pipe.run() == 0
+    for rep in range(4):
+        g.replay()
+        check(f"replay {rep}")
+        vq.vq_gemv(flat[0][0], flat[0][1])               # eager work of the program between the replays
+        torch.cuda.synchronize()
+    del g
+    pipe.close()
+
+
 def test_gemv_pipeline_llama_blocks_full_size(gpu_device):
     """Two decoder blocks at full size, as bench.py issues them (four problem lanes, four row blocks per LDS image,
     K = 11008 in two parts): bit-identical to vq_gemv, within tolerance of the oracle."""
