@@ -1080,8 +1080,9 @@ __device__ __forceinline__ void pipe_signal(uint32_t addr, int lane) {
 template <int PF>
 struct PipePiece {
     uint32_t i;          // problem (n: no more work)
-    uint32_t meta;       // first step of the piece in its group | row block of the image << 8 | last piece << 16 | valid << 17
-    uint32_t slot, steps_v;
+    uint32_t meta;       // first step of the piece in its group | row block of the image << 8 | steps of the piece << 12 |
+                         // last piece << 16 | valid << 17
+    uint32_t slot;
     uint32_t q[PF][2];
 };
 // Partial sums of a pipelined problem: blocks of 64 rows, [block][slice * P + part][row % 64].
@@ -1095,6 +1096,7 @@ struct PipeCursor {
     uint32_t t, h;       // the group being requested (number in the lane's list) and its next piece
     // the group being requested, worked out before the piece before it is worked on
     uint32_t word;       // its entry of the problem's group table (prefix << 16 | common steps)
+    uint32_t own;        // steps that this workgroup's tasks of the group really have (<= common steps)
     uint32_t wg, g, jb;  // block in the packed tables, group in the block, row block of the image
     bool none;           // past the last group
     bool advance;        // the piece last requested ended its group
@@ -1160,25 +1162,32 @@ __device__ __forceinline__ void pipe_next(PipeCursor &cu, PipeHead &hd, cproblem
     cu.g = where >> 20;
     cu.wg = (uint32_t)(hd.s * hd.RB + hd.rbv * hd.bpi) + cu.jb;
     cu.word = table[i].group[cu.g];
+    cu.own = ((cu32_t *)hd.steps)[cu.wg * (uint32_t)hd.ng + cu.g];
 }
 
 template <int PF>
 __device__ __forceinline__ void pipe_fetch(PipePiece<PF> &it, PipeCursor &cu, PipeHead &hd, cproblem_t *table, cu32_t *items,
                                            uint32_t n, uint32_t total_items, int bid, int lane, uint32_t zero_v) {
-    const uint32_t common = cu.word & 0xFFFFu, first = cu.h * PF;
-    gbyte_t *gbase = (gbyte_t *)hd.atoms + ((size_t)cu.wg * hd.wg_pitch + (cu.word >> 16) + first) * kStepBytes + (uint32_t)lane * 8u;
-    // (a vector load of one address: a scalar load would be waited for with the next LDS read.  The address is a
-    // scalar base plus a register that holds 0 for the whole kernel, so that no register is written here that an
-    // earlier request may still be writing to.)
-    it.steps_v = *(gu32_t *)((gbyte_t *)((gu32_t *)hd.steps + (cu.wg * (uint32_t)hd.ng + cu.g)) + zero_v);
+    const uint32_t first = cu.h * PF;
+    const uint32_t left = cu.own > first ? cu.own - first : 0u;          // steps of the group from this piece on
+    const uint32_t n_piece = left < (uint32_t)PF ? left : (uint32_t)PF;
+    gbyte_t *gbase = (gbyte_t *)hd.atoms + ((size_t)cu.wg * hd.wg_pitch + (cu.word >> 16) + first) * kStepBytes;
     it.slot = ((gu16_t *)hd.tasks)[(size_t)(cu.wg * (uint32_t)hd.ng + cu.g) * 64 + lane];
-    // (ordinary loads: with a non-temporal hint the steps requested past the end of a short group -- the head of
-    // the next group, which another wavefront is about to request -- come from memory twice; measured 7 % slower)
+    // PF requests whatever the piece's length (no branch: the compiler must be able to count them), but those past
+    // the piece's last step name that step again: the blocks behind a short group's own steps are padding that
+    // nobody needs, or the next group's head, and neither should cross the memory system for this wavefront.
+    // (ordinary loads: with a non-temporal hint such repeats come from memory again; measured 7 % slower)
+    const uint32_t top = n_piece > 0u ? n_piece - 1u : 0u;
+    const uint32_t lane8 = (uint32_t)lane * 8u + zero_v;
 #pragma unroll
-    for (int st = 0; st < PF; ++st) load_step(it.q[st], gbase, st);
-    const uint32_t last = first + PF >= common ? 1u : 0u;
+    for (int st = 0; st < PF; ++st) {
+        const uint32_t idx = (uint32_t)st < top ? (uint32_t)st : top;
+        gu32_t *p = (gu32_t *)(gbase + (size_t)idx * kStepBytes + lane8);
+        it.q[st][0] = p[0]; it.q[st][1] = p[1];
+    }
+    const uint32_t last = left <= (uint32_t)PF ? 1u : 0u;
     it.i = cu.none ? n : hd.i;
-    it.meta = first | (cu.jb << 8) | (last << 16) | ((hd.in && !cu.none) ? 1u << 17 : 0u);
+    it.meta = first | (cu.jb << 8) | (n_piece << 12) | (last << 16) | ((hd.in && !cu.none) ? 1u << 17 : 0u);
     cu.advance = last != 0u;
 }
 
@@ -1228,9 +1237,8 @@ __device__ __forceinline__ void pipe_consume(PipePiece<PF> &it, Acc3 &acc, PipeC
     if (it.i >= c.n) return;
     if (bd.i != it.i) pipe_body_load(bd, table, it.i, bid);
     const bool valid = (it.meta >> 17) & 1u;
-    const uint32_t first = it.meta & 0xFFu, jb = (it.meta >> 8) & 0xFFu;
-    const uint32_t own = valid ? __builtin_amdgcn_readfirstlane(it.steps_v) : 0u;
-    const uint32_t n_steps = own > first ? own - first : 0u;   // of this piece (those past PF belong to the next one)
+    const uint32_t first = it.meta & 0xFFu, jb = (it.meta >> 8) & 0xFu;
+    const uint32_t n_steps = valid ? (it.meta >> 12) & 15u : 0u;   // of this piece
     const uint32_t slot = valid ? it.slot : 0xFFFFu;
     const uint32_t img = (it.i & 1u) * kPipeImage;
     const uint32_t slice_bytes = 16u << bd.EB, part_pitch = (bd.Jp + kZeroUnits) * 16u;
@@ -1268,7 +1276,7 @@ template <int PF>
 __device__ __forceinline__ void pipe_retire(const PipePiece<PF> &it) {
 #pragma unroll
     for (int k = 0; k < PF; ++k) asm volatile("" ::"v"(it.q[k][0]), "v"(it.q[k][1]));
-    asm volatile("" ::"v"(it.slot), "v"(it.steps_v));
+    asm volatile("" ::"v"(it.slot));
 }
 
 // Producer w's share of the image of problem k, from the list the host prepared: read (all of it, into scalar
