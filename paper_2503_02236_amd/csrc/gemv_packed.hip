@@ -1002,8 +1002,11 @@ __global__ __launch_bounds__(kFinalizeRows) void gemv_packed_finalize_batch_kern
 //   staged[k & 1]: +1 by each producer when its share of problem k has landed   (k staged: >= NP (k/2 + 1))
 //   done  [k & 1]: +1 by each consumer when it has left problem k               (k done:   >= NC (k/2 + 1))
 // A consumer enters problem k after seeing it staged; a producer stages k after seeing k - 2 done.  No wavefront
-// can be two problems ahead of another, so the counters of one parity are never ambiguous.  A consumer writes
-// the sum of a task straight to global memory: one partial sum per (row, slice, part of the row), S * P per row.  Every wait is bounded: after
+// can be two problems ahead of another, so the counters of one parity are never ambiguous.  A consumer leaves the
+// sum of a task in an LDS buffer of the image (by row); the producers write the buffer of problem k - 1 out in
+// row order, whole lines at a time, before they stage problem k + 1.  (Stores straight from the consumers'
+// registers -- 64 scattered 4-byte writes per group -- cost a quarter of the kernel's time: measured 0.74 ms with
+// them against 0.56 ms without, gathers switched off in both.)  Every wait is bounded: after
 // kPipeSpinLimit looks a wavefront gives up waiting for the rest of the launch and raises the status word,
 // so the grid always drains.
 // The S partial sums per row of all problems are added by one reduction launch behind it.
@@ -1012,8 +1015,13 @@ constexpr int kPipeConsumers = 14, kPipeProducers = 2;   // wavefronts 0 .. 13 a
 constexpr int kPipeFirstProducer = kPipeConsumers;
 constexpr int kPipeOps = 12;                            // staging operations per producer and problem
 constexpr uint32_t kPipeImage = 65536;                  // LDS bytes from one image to the other
-constexpr uint32_t kPipeFlags = 2 * kPipeImage;         // staged[2], done[2], next group to hand out
-constexpr uint32_t kPipeLds = kPipeFlags + 64;
+constexpr uint32_t kPipeFlags = kPipeImage - 64;        // in the tail of image 0: staged[2], done[2], next group to hand
+                                                        // out, finished groups per image and row block [2][4]
+constexpr uint32_t kPipeGroupsDone = kPipeFlags + 20u;
+constexpr uint32_t kPipeAcc = 2 * kPipeImage;           // two buffers (one per image) of one float per task ...
+constexpr uint32_t kPipeAccBytes = 16384;               // ... for problems with up to 4096 tasks per image; larger ones
+                                                        // keep theirs in the tail of their image
+constexpr uint32_t kPipeLds = kPipeAcc + 2 * kPipeAccBytes;   // 160 KiB: all of a compute unit's LDS
 constexpr uint32_t kPipeSpinLimit = 1u << 20;
 
 // One problem as the kernel reads it (a table in device memory, written once when the pipeline is created).
@@ -1028,7 +1036,8 @@ struct PipeProblem {
     uint32_t reserved[2];
     uint32_t bpi;          // row blocks per LDS image: a workgroup of the launch takes bpi consecutive row blocks of its slice
     uint32_t rbv;          // RB / bpi
-    uint32_t pad[2];
+    uint32_t acc_lds;      // LDS byte address of the problem's buffer of task sums: [row block of the image][part][row]
+    uint32_t groups_through;   // groups per row block of this and all earlier problems of the lane with the same parity
     // How producer w builds the LDS image, worked out on the host (the kernel's instruction issue is a scarce
     // resource: four wavefronts per SIMD): pairs (source byte offset, PipeOp word), the list ends at a zero word.
     uint32_t ops[kPipeProducers][kPipeOps][2];
@@ -1085,10 +1094,6 @@ struct PipePiece {
     uint32_t slot;
     uint32_t q[PF][2];
 };
-// Partial sums of a pipelined problem: blocks of 64 rows, [block][slice * P + part][row % 64].
-__host__ __device__ __forceinline__ size_t pipe_partial_index(uint32_t planes, uint32_t plane, uint32_t row) {
-    return ((size_t)(row >> 6) * planes + plane) * 64 + (row & 63);
-}
 // The groups of a lane's problems are numbered through ("items").  Consumers take them from an LDS counter as they
 // go (each wavefront when it has requests to issue, i.e. two pieces before it works on them): whoever gets
 // long groups takes fewer of them.  What a wavefront takes is ascending, so it still passes the problems in order.
@@ -1195,21 +1200,13 @@ __device__ __forceinline__ void pipe_fetch(PipePiece<PF> &it, PipeCursor &cu, Pi
 struct PipeBody {
     uint32_t i;
     uint32_t EB, P, Jp, rows_per_block;
-    uint32_t N, planes, plane0, row_base;   // rows of the matrix; S * P; s * P; first row of this workgroup's first block
-    float *partial;
+    uint32_t acc_lds;     // where the sums of the image's tasks go
 };
-__device__ __forceinline__ void pipe_body_load(PipeBody &b, cproblem_t *table, uint32_t i, int bid) {
+__device__ __forceinline__ void pipe_body_load(PipeBody &b, cproblem_t *table, uint32_t i) {
     cproblem_t &pr = table[i];
     b.i = i;
     b.EB = (uint32_t)pr.EB; b.P = (uint32_t)pr.P; b.Jp = (uint32_t)pr.Jp; b.rows_per_block = (uint32_t)pr.rows_per_block;
-    b.N = (uint32_t)pr.N;
-    b.partial = pr.partial;
-    const int S = pr.S, RBv = (int)pr.rbv;
-    int s, rbv;
-    slice_and_block(bid < S * RBv ? bid : 0, S, RBv, s, rbv);
-    b.planes = (uint32_t)S * b.P;
-    b.plane0 = (uint32_t)s * b.P;
-    b.row_base = (uint32_t)rbv * pr.bpi * b.rows_per_block;
+    b.acc_lds = pr.acc_lds;
 }
 
 // Where a consumer stands: in problem `cur` (seen staged), all earlier ones left.
@@ -1235,7 +1232,7 @@ __device__ __forceinline__ void pipe_consume(PipePiece<PF> &it, Acc3 &acc, PipeC
     static_assert(PF % 2 == 0 && PF <= kPackTailBlocks, "steps in pairs; requests run up to PF - 1 blocks past the end of a group");
     pipe_advance(c, it.i, lane);
     if (it.i >= c.n) return;
-    if (bd.i != it.i) pipe_body_load(bd, table, it.i, bid);
+    if (bd.i != it.i) pipe_body_load(bd, table, it.i);
     const bool valid = (it.meta >> 17) & 1u;
     const uint32_t first = it.meta & 0xFFu, jb = (it.meta >> 8) & 0xFu;
     const uint32_t n_steps = valid ? (it.meta >> 12) & 15u : 0u;   // of this piece
@@ -1261,11 +1258,13 @@ __device__ __forceinline__ void pipe_consume(PipePiece<PF> &it, Acc3 &acc, PipeC
             steps_dot<1>(lo1, hi1, dec, acc);
         }
     }
-    if (((it.meta >> 16) & 1u) && slot != 0xFFFFu) {
-        const uint32_t row = bd.row_base + jb * bd.rows_per_block + (slot - part * bd.rows_per_block);
-        if (row < bd.N)
-            ((__attribute__((address_space(1))) float *)bd.partial)[pipe_partial_index(bd.planes, bd.plane0 + part, row)] =
+    if ((it.meta >> 16) & 1u) {
+        if (slot != 0xFFFFu)   // (slot = part * rows_per_block + row inside the block)
+            *(__attribute__((address_space(3))) float *)(uintptr_t)(bd.acc_lds + (jb * bd.rows_per_block * bd.P + slot) * 4u) =
                 (acc.a[0] + acc.a[1]) + acc.a[2];
+        // one more group of this row block is finished: when all are, the producers write the block's rows out
+        // (counted also where the workgroup has no block of the problem: the counters run on over all problems)
+        pipe_signal(kPipeGroupsDone + ((it.i & 1u) * 4u + jb) * 4u, lane);
     }
 }
 // Declares every requested step of a piece used.  The steps past the end of a short group are never looked at, and
@@ -1318,6 +1317,34 @@ __device__ __forceinline__ void pipe_stage(const PipeStage &st, int lane, unsign
             if ((uint32_t)lane < ((w >> 19) & 127u)) dma_1k(st.x + (src >> 4) + lane, dst);
         } else {
             reinterpret_cast<uint32_t *>(dst)[lane] = 0u;
+        }
+    }
+}
+
+// The partial sums of problem k of this workgroup, LDS -> global: rows in natural order (whole 256-byte runs per
+// store instruction), the parts of a row added in part order -- the additions of the one-problem kernel.  Row
+// block by row block, each as soon as the consumers have finished its groups (so that only the last one's rows
+// stand between "problem done" and the staging of the next image); the rows are dealt to the producers 64 at a time.
+__device__ __forceinline__ void pipe_emit(cproblem_t *table, uint32_t k, int bid, int pw, int lane, PipeSync &sy) {
+    cproblem_t &pr = table[k];
+    const int S = pr.S, RBv = (int)pr.rbv, bpi = (int)pr.bpi, rpb = pr.rows_per_block, P = pr.P, N = pr.N;
+    const uint32_t through = pr.groups_through;
+    if (bid >= S * RBv) return;
+    int s, rbv;
+    slice_and_block(bid, S, RBv, s, rbv);
+    __attribute__((address_space(1))) float *out = (__attribute__((address_space(1))) float *)pr.partial;
+    const uint32_t acc_lds = pr.acc_lds;
+    for (int jb = 0; jb < bpi; ++jb) {
+        pipe_wait(kPipeGroupsDone + ((k & 1u) * 4u + (uint32_t)jb) * 4u, through, sy);
+        const uint32_t base = acc_lds + (uint32_t)(jb * rpb * P) * 4u;
+        const int row0 = (rbv * bpi + jb) * rpb;
+#pragma unroll 4
+        for (int r = pw * 64 + lane; r < rpb; r += kPipeProducers * 64) {
+            const int row = row0 + r;
+            float sum = *(const __attribute__((address_space(3))) float *)(uintptr_t)(base + (uint32_t)r * 4u);
+            for (int p = 1; p < P; ++p)
+                sum += *(const __attribute__((address_space(3))) float *)(uintptr_t)(base + (uint32_t)(p * rpb + r) * 4u);
+            if (row < N) out[partial_index(S, s, row)] = sum;
         }
     }
 }
@@ -1382,7 +1409,7 @@ __global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *
     if (n == 0u) return;
     cproblem_t *table = (cproblem_t *)table_;
     cu32_t *items = (cu32_t *)items_;
-    if (threadIdx.x < 5) reinterpret_cast<uint32_t *>(smem + kPipeFlags)[threadIdx.x] = threadIdx.x < 4 ? 0u : 2u * (uint32_t)kPipeConsumers;
+    if (threadIdx.x < 13) reinterpret_cast<uint32_t *>(smem + kPipeFlags)[threadIdx.x] = threadIdx.x == 4 ? 2u * (uint32_t)kPipeConsumers : 0u;
     __syncthreads();
     PipeSync sy = {false};
     if (wave >= kPipeFirstProducer) {
@@ -1397,7 +1424,11 @@ __global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *
             pipe_warm_done(warm);
             pipe_signal(kPipeFlags + (k & 1u) * 4u, lane);
             warm = pipe_scout(table, k + 3u < n ? k + 3u : n - 1u, bid, pw, lane);
+            // the sums of the problem before: its buffer is the one that problem k + 1's tasks will write
+            if (k >= 1) pipe_emit(table, k - 1u, bid, pw, lane, sy);
         }
+        pipe_warm_done(warm);
+        pipe_emit(table, n - 1u, bid, pw, lane, sy);
         if (sy.broken && lane == 0) *status = 1u;
         return;
     }
@@ -1418,7 +1449,7 @@ __global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *
     PipeHead hd;
     pipe_head_load(hd, table, 0u, bid);
     PipeBody bd;
-    pipe_body_load(bd, table, 0u, bid);
+    pipe_body_load(bd, table, 0u);
     Acc3 acc = {{0.f, 0.f, 0.f}};
     uint32_t zero_v = 0u;
     asm volatile("" : "+v"(zero_v));
@@ -1449,37 +1480,15 @@ __global__ __launch_bounds__(1024) void gemv_pipeline_kernel(const PipeProblem *
     if (c.sy.broken && lane == 0) *status = 1u;
 }
 
-// y of every problem of a pipeline: blockIdx.y picks the problem.  y[n] = scale[n] * sum_s (sum_p partial[s][p][n]):
-// the parts of a row added first, in part order, then the slices in ascending order -- the additions of the
-// one-problem kernels, in their order.
+// y of every problem of a pipeline: blockIdx.y picks the problem.
 __global__ __launch_bounds__(kFinalizeRows) void gemv_pipeline_finalize_kernel(const PipeProblem *table_) {
     cproblem_t &pr = ((cproblem_t *)table_)[blockIdx.y];
     const float *partial = pr.partial;
     const half_t *scale = pr.scale;
     half_t *y = pr.y;
-    int N = pr.N, S = pr.S, P = pr.P;
-    pin_scalar(partial); pin_scalar(scale); pin_scalar(y); pin_scalar(N); pin_scalar(S); pin_scalar(P);
-    const int n = blockIdx.x * kFinalizeRows + threadIdx.x;
-    if (n >= N) return;
-    const __attribute__((address_space(1))) float *gp = (const __attribute__((address_space(1))) float *)partial;
-    const __attribute__((address_space(1))) half_t *gs = (const __attribute__((address_space(1))) half_t *)scale;
-    __attribute__((address_space(1))) half_t *gy = (__attribute__((address_space(1))) half_t *)y;
-    const float sc = scale ? (float)gs[n] : 1.f;
-    float sum = 0.f;
-    if (P == 1) {
-        float v[kPackMaxSlices];
-#pragma unroll
-        for (int k = 0; k < kPackMaxSlices; ++k) v[k] = gp[pipe_partial_index((uint32_t)S, (uint32_t)(k < S ? k : S - 1), (uint32_t)n)];
-#pragma unroll
-        for (int k = 0; k < kPackMaxSlices; ++k) sum += k < S ? v[k] : 0.f;
-    } else {
-        for (int k = 0; k < S; ++k) {
-            float t = gp[pipe_partial_index((uint32_t)(S * P), (uint32_t)(k * P), (uint32_t)n)];
-            for (int p = 1; p < P; ++p) t += gp[pipe_partial_index((uint32_t)(S * P), (uint32_t)(k * P + p), (uint32_t)n)];
-            sum += t;
-        }
-    }
-    gy[n] = scaled_output(sum, sc);
+    int N = pr.N, S = pr.S;
+    pin_scalar(partial); pin_scalar(scale); pin_scalar(y); pin_scalar(N); pin_scalar(S);
+    gemv_packed_finalize_body<kPackMaxSlices>(partial, scale, y, N, S);
 }
 
 bool gemv_uses_pack(const vq_weight_t *w, int bs) {
@@ -1746,11 +1755,8 @@ struct GemvPipeline {
     uint32_t *status;      // device
 };
 
-// S * P partial sums per row in blocks of 64 rows (pipe_partial_index), 256-byte aligned.
-static size_t pipe_partial_bytes(const vq_weight_t *w) {
-    const vq_gemv_pack_t *p = w->gemv_pack;
-    return (size_t)p->S * p->parts * (((size_t)w->N + 63) / 64) * 64 * sizeof(float);
-}
+// S partial sums per row in blocks of 64 rows (partial_index), 256-byte aligned.
+static size_t pipe_partial_bytes(const vq_weight_t *w) { return (gemv_packed_workspace(w) + 255) & ~(size_t)255; }
 size_t gemv_pipeline_workspace(const vq_gemv_call_t *calls, int n_calls) {
     size_t total = kPipeHeader + pipe_table_bytes(pipe_problems(calls, n_calls)) + pipe_items_bytes(calls, n_calls);
     for (int c = 0; c < n_calls; ++c)
@@ -1764,7 +1770,7 @@ bool gemv_pipeline_supports(const vq_weight_t *w) {
     PackPlan plan;
     if (!pack_plan(w, &plan)) return false;
     const size_t image = ((size_t)plan.slice_entries + (size_t)plan.P * (plan.Jp + kZeroUnits)) * 16;
-    return plan.S * plan.RB <= (uint32_t)kPipeWgs && image <= kPipeImage;
+    return plan.S * plan.RB <= (uint32_t)kPipeWgs && image + 64 <= kPipeImage;   // (64 bytes of counters in the tail of image 0)
 }
 
 // Builds the problem table in the workspace (a synchronous copy: the calls' arrays need not outlive this).
@@ -1818,9 +1824,22 @@ int gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, hip
     for (uint32_t l = 0; l < n_lanes; ++l) {
         lanes.first[l] = (uint32_t)table.size();
         lanes.item_first[l] = (uint32_t)items.size();
+        uint32_t through[2] = {0u, 0u};
         for (int q = (int)l; q < n; q += (int)n_lanes) {
-            const PipeProblem &p = probs[(size_t)q];
+            PipeProblem p = probs[(size_t)q];
             const uint32_t i = (uint32_t)table.size() - lanes.first[l];   // its number within the lane
+            through[i & 1u] += (uint32_t)p.n_groups;
+            p.groups_through = through[i & 1u];
+            // where the sums of its tasks wait for the producers: the buffer of its image's parity, or (more than
+            // 4096 tasks per image) the tail of the image itself
+            const uint32_t acc_bytes = bpi * (uint32_t)p.rows_per_block * (uint32_t)p.P * 4u;
+            const uint32_t image = (((16u << p.EB) + (uint32_t)p.P * ((uint32_t)p.Jp + kZeroUnits) * 16u) + 15u) & ~15u;
+            if (acc_bytes <= kPipeAccBytes)
+                p.acc_lds = kPipeAcc + (i & 1u) * kPipeAccBytes;
+            else if (image + acc_bytes + 64u <= kPipeImage)
+                p.acc_lds = (i & 1u) * kPipeImage + image;
+            else
+                return VQ_ERR_UNSUPPORTED;
             for (uint32_t jb = 0; jb < bpi; ++jb)
                 for (uint32_t g = 0; g < (uint32_t)p.n_groups; ++g) items.push_back(i | (jb << 16) | (g << 20));
             table.push_back(p);
