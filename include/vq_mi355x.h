@@ -269,7 +269,8 @@ size_t vq_gemv_sequence_streams_workspace(const vq_gemv_call_t *calls, int n_cal
  *     ws: device, 256-byte aligned (VQ_ERR_ALIGN), vq_gemv_pipeline_workspace(calls, n_calls) bytes, owned by the
  *     caller and in use by the pipeline until it is destroyed.
  *     VQ_ERR_UNSUPPORTED: a weight without re-tiled codes, or one that does not fit the persistent launch
- *     (more than 256 row-block x slice workgroups, an LDS image above 64 KiB, x in more than about three parts).
+ *     (more than 256 row-block x slice workgroups, an LDS image above 64 KiB - 64 B, x in more than about three parts,
+ *     or more sums per image than its LDS buffer holds).
  *   vq_gemv_pipeline_run: two kernel launches on `stream`; no allocation, no synchronisation; capturable.  Runs of
  *     one pipeline must not overlap (they share ws).  VQ_ERR_LAUNCH when called with another GPU current.
  *   vq_gemv_pipeline_status: copies the device status word to *status (synchronises `stream`): 0, or 1 if a
