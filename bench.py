@@ -514,6 +514,20 @@ def main():
                 b = wds[0].codes.numel() + wds[0].codebooks.numel() * 2 + N * 2 + bs * (K + N) * 2
                 add["%dx%d_bs%d" % (N, K, bs)] = {"us": round(ms * 1e3, 2),
                                                    "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBPS, 2)}
+                if bs == 1:
+                    # the same matrices three to a launch (vq_gemv_batch: projections of a decoder block that share
+                    # their input, as query/key/value do); per-matrix time
+                    ys3 = [torch.empty((1, N), dtype=torch.float16, device=dev) for _ in range(3)]
+                    bcs = [vq.GemvBatch(wds[i:i + 3], [x] * 3, ys3) for i in range(0, len(wds) - 2, 3)]
+
+                    def bloop(bcs=bcs):
+                        for bc in bcs:
+                            st = bc.run(None, 0)
+                            if st != 0:
+                                raise vq.VQError(st, "vq_gemv_batch")
+                    msb = timed_replay(bloop, 3, 1) / (3 * len(bcs))
+                    add["%dx%d_bs1_batch_of_3" % (N, K)] = {"us": round(msb * 1e3, 2),
+                                                           "pct_hbm_peak": round(100 * b / msb / 1e6 / HBM_PEAK_GBPS, 2)}
             del wds
             torch.cuda.empty_cache()
         result["gemv_additive_2x256x8"] = add

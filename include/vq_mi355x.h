@@ -192,7 +192,11 @@ int vq_reorder_by_frequency(const vq_weight_t *w_host, void *codes_out_host, voi
  * the projections of a decoder block that do not depend on each other (query/key/value; gate/up).
  * When every W_i carries re-tiled codes (gemv_pack) the whole batch is ONE launch of the codebook-centric
  * kernel (Sec. VI-A) plus one launch of its global reduction, so the fixed latencies of a launch are paid
- * once; any other mix is run as `count` vq_gemv calls.  Results are bit-identical to separate vq_gemv calls.
+ * once, and the results are bit-identical to separate vq_gemv calls.  A batch of canonical-code weights of one
+ * kind (same code width, v and number of codebooks) whose codebooks fit LDS is one launch of the matrix-core
+ * gemv; it may split K over another number of wavefronts than a single call does, so its results equal those of
+ * vq_gemv up to the order of the fp32 additions (and are the same from call to call).  Any other mix is run as
+ * `count` vq_gemv calls.
  * w, x, y: HOST arrays of `count` pointers (x_i: device fp16 [K_i], y_i: device fp16 [N_i]; the x_i may
  * be the same buffer).  ws: vq_gemv_batch_workspace(w, count) bytes.
  * Errors: as vq_gemv; VQ_ERR_SHAPE for count outside 1..VQ_GEMV_BATCH_MAX.

@@ -187,6 +187,10 @@ int vq_gemv_batch(const vq_weight_t *const *w, const void *const *x, void *const
     if (ws && !aligned16(ws)) return VQ_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (batch_all_packed(w, count)) return launch_gemv_packed_batch(w, x, y, count, ws, s);
+    // canonical codes with whole codebooks in LDS, all of one kind: one launch of the matrix-core gemv
+    bool none_packed = true;
+    for (int i = 0; i < count; ++i) none_packed = none_packed && !gemv_uses_pack(w[i], 1);
+    if (none_packed && gemv_mfma_batch_supported(w, count)) return launch_gemv_mfma_batch(w, x, y, count, s);
     // any other mix: one launch per problem, each with its own slot of the workspace
     size_t off = 0;
     for (int i = 0; i < count; ++i) {

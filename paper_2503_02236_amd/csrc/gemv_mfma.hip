@@ -20,6 +20,8 @@
 // of x once -- bs * K * 2 bytes from L2 --, which at bs = 16 is what the kernel waits for (N = 11008,
 // K = 4096: 688 workgroups x 128 KiB = 88 MB through the L2s at ~11 TB/s, 8 of the 18 us); with two tiles per
 // workgroup it is half of that.  Used where enough workgroups remain to fill the chip.
+#include <algorithm>
+
 #include "vq_common.h"
 
 namespace vq {
@@ -69,7 +71,7 @@ __device__ __forceinline__ unsigned word_code<Code12>(const V16 &cd, int q) {
 // pays off when the entries have been reordered by frequency (vq_reorder_by_frequency), so that most
 // codes are small; with uniformly used entries nearly every lookup takes the L2 path.
 template <typename CodeT, int V, int R, bool HOT, int RT>
-__global__ __launch_bounds__(RT == 1 ? 1024 : 512) void gemv_mfma_kernel(GemvMfmaArgs a) {  // (two tiles: twice the operands in flight, up to 8 wavefronts)
+__device__ __forceinline__ void gemv_mfma_body(const GemvMfmaArgs &a, const int bx) {
     constexpr int LB = GemvMfmaShape<CodeT, R>::LB;     // bytes of codes per lane and iteration
     constexpr int CPL = GemvMfmaShape<CodeT, R>::CPL;   // sub-vector positions per code load
     constexpr int CPO = 8 / V;                          // codes per MFMA operand (8 consecutive k)
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(RT == 1 ? 1024 : 512) void gemv_mfma_kernel(GemvMfm
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nwaves = blockDim.x >> 6;
     const int r = lane & 15, g = lane >> 4;
-    const int n0 = blockIdx.x * 16 * RT;
+    const int n0 = bx * 16 * RT;
     // codes and x of this wavefront's first iteration are requested before the codebook is staged
     const unsigned char *crow[RT];
 #pragma unroll
@@ -297,6 +299,25 @@ __global__ __launch_bounds__(RT == 1 ? 1024 : 512) void gemv_mfma_kernel(GemvMfm
     }
 }
 
+template <typename CodeT, int V, int R, bool HOT, int RT>
+__global__ __launch_bounds__(RT == 1 ? 1024 : 512) void gemv_mfma_kernel(GemvMfmaArgs a) {  // (two tiles: twice the operands in flight, up to 8 wavefronts)
+    gemv_mfma_body<CodeT, V, R, HOT, RT>(a, blockIdx.x);
+}
+
+// Several independent problems of one kind in one launch (blockIdx.y picks the problem): the fixed costs of a
+// launch -- ramp-up, first touches, drain; about as long as the useful part of a bs = 1 product of this size --
+// are paid once, and workgroups of different problems share the compute units.
+constexpr int kGemvMfmaBatch = 4;
+struct GemvMfmaBatch {
+    GemvMfmaArgs a[kGemvMfmaBatch];
+    int n_wg[kGemvMfmaBatch];
+};
+template <typename CodeT, int V, int R>
+__global__ __launch_bounds__(1024) void gemv_mfma_batch_kernel(GemvMfmaBatch b) {
+    if ((int)blockIdx.x >= b.n_wg[blockIdx.y]) return;
+    gemv_mfma_body<CodeT, V, R, false, 1>(b.a[blockIdx.y], blockIdx.x);
+}
+
 namespace {
 
 constexpr size_t kGemvMfmaLdsCodebook = 128 * 1024;  // whole codebooks up to this size live in LDS
@@ -361,7 +382,88 @@ int by_r(const vq_weight_t *w, const half_t *x, int bs, half_t *y, hipStream_t s
     }
 }
 
+// One problem of a batched launch: the arguments of the plain one-tile build (whole codebooks in LDS).
+template <typename CodeT, int V, int R>
+GemvMfmaArgs batch_args(const vq_weight_t *w, const half_t *x, half_t *y) {
+    constexpr int CPL = GemvMfmaShape<CodeT, R>::CPL;
+    GemvMfmaArgs a;
+    a.codes = w->codes;
+    a.cb = (const half_t *)w->codebooks;
+    a.scale = (const half_t *)w->scale;
+    a.x = x;
+    a.y = y;
+    a.N = w->N;
+    a.K = w->K;
+    a.J = w->K / V;
+    a.E = w->n_entries;
+    a.bs = 1;
+    a.nit = (a.J + 4 * CPL - 1) / (4 * CPL);
+    a.tile_n = w->cb_tile_n;
+    a.tiles_k = w->cb_tile_n > 0 ? w->K / w->cb_tile_k : 1;
+    a.tile_j = w->cb_tile_n > 0 ? w->cb_tile_k / V : (1 << 30);
+    a.n_hot = a.E;
+    return a;
+}
+
+template <typename CodeT, int V, int R>
+int run_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, hipStream_t s) {
+    GemvMfmaBatch b;
+    int grid = 0, total = 0, min_nit = 1 << 30;
+    size_t cb_bytes = 0;
+    for (int i = 0; i < kGemvMfmaBatch; ++i) {
+        const int k = i < count ? i : 0;   // unused slots repeat problem 0 (never launched: grid.y = count)
+        b.a[i] = batch_args<CodeT, V, R>(w[k], (const half_t *)x[k], (half_t *)y[k]);
+        b.n_wg[i] = (w[k]->N + 15) / 16;
+        if (i < count) {
+            grid = std::max(grid, b.n_wg[i]);
+            total += b.n_wg[i];
+            min_nit = std::min(min_nit, b.a[i].nit);
+            cb_bytes = std::max(cb_bytes, (size_t)R * b.a[i].n_hot * V * 2 * b.a[i].tiles_k);
+        }
+    }
+    // wavefronts per workgroup as for one problem with all the workgroups of the batch
+    int waves = 16;
+    while (waves > 4 && total * waves > 4096) waves >>= 1;
+    if (waves > min_nit) waves = min_nit;
+    if (waves < 1) waves = 1;
+    const size_t lds = ((cb_bytes + 15) & ~(size_t)15) + (size_t)waves * 64 * sizeof(float4v_t);
+    static KernelSetup setup;
+    if (int st = kernel_setup(reinterpret_cast<const void *>(&gemv_mfma_batch_kernel<CodeT, V, R>), lds, false, setup)) return st;
+    gemv_mfma_batch_kernel<CodeT, V, R><<<dim3(grid, count), waves * 64, lds, s>>>(b);
+    return launch_status();
+}
+
 }  // namespace
+
+// Whether `count` bs = 1 problems can share one launch of the matrix-core gemv: all of one kind (code width, v,
+// number of codebooks), whole codebooks in LDS, none empty.
+bool gemv_mfma_batch_supported(const vq_weight_t *const *w, int count) {
+    if (count < 2 || count > kGemvMfmaBatch) return false;
+    for (int i = 0; i < count; ++i) {
+        if (!w[i] || w[i]->N <= 0 || w[i]->K <= 0 || !gemv_mfma_supported(w[i])) return false;
+        if (w[i]->code_bits != w[0]->code_bits || w[i]->v != w[0]->v || w[i]->n_codebooks != w[0]->n_codebooks) return false;
+        if (w[i]->cb_tile_n == 0 && (size_t)w[i]->n_codebooks * w[i]->n_entries * w[i]->v * 2 > kGemvMfmaLdsCodebook) return false;
+        if (w[i]->n_codebooks != 1 && w[i]->n_codebooks != 2 && w[i]->n_codebooks != 4) return false;
+    }
+    return true;
+}
+
+int launch_gemv_mfma_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, hipStream_t s) {
+#define VQ_MB(CodeT, V)                                                                   \
+    switch (w[0]->n_codebooks) {                                                          \
+        case 1: return run_batch<CodeT, V, 1>(w, x, y, count, s);                         \
+        case 2: return run_batch<CodeT, V, 2>(w, x, y, count, s);                         \
+        default: return run_batch<CodeT, V, 4>(w, x, y, count, s);                        \
+    }
+    if (w[0]->code_bits == 8) {
+        if (w[0]->v == 8) { VQ_MB(uint8_t, 8) } else { VQ_MB(uint8_t, 4) }
+    } else if (w[0]->code_bits == 12) {
+        if (w[0]->v == 8) { VQ_MB(Code12, 8) } else { VQ_MB(Code12, 4) }
+    } else {
+        if (w[0]->v == 8) { VQ_MB(uint16_t, 8) } else { VQ_MB(uint16_t, 4) }
+    }
+#undef VQ_MB
+}
 
 // Codebooks must fit LDS next to the reduction buffer (a single larger codebook is cached partly), and a
 // row of codes must be a whole number of code words made of whole sub-vector positions.

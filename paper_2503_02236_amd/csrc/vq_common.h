@@ -116,6 +116,8 @@ int launch_gemm(const vq_weight_t *w, const void *X, int M, void *Y, void *ws, h
 size_t gemm_workspace(const vq_weight_t *w, int M);
 int launch_gemm_dense(const half_t *A, const half_t *B, const half_t *scale, half_t *C, int M, int N, int K,
                       hipStream_t s);
+bool gemv_mfma_batch_supported(const vq_weight_t *const *w, int count);
+int launch_gemv_mfma_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, hipStream_t s);
 int launch_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, hipStream_t s);
 // channel-parallel variant for caches with one codebook per channel sub-space (attn_channel.hip)
 bool attn_channel_supported(const vq_kv_t *kv);

@@ -284,6 +284,46 @@ def test_gemv_batch_matches_single_calls_and_oracle(gpu_device):
         assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, xx), "mixed batch member")
 
 
+@pytest.mark.parametrize("bits,v,R,E,shapes", [
+    (8, 8, 2, 256, [(768, 1024), (768, 1024), (300, 1024)]),      # C3-like: two additive 256 x 8 codebooks, ragged last member
+    (8, 8, 2, 256, [(2000, 512), (50, 2048)]),                    # different K and very different N in one launch
+    (8, 4, 1, 256, [(512, 512), (512, 512), (512, 512), (40, 512)]),
+    (12, 8, 2, 4096, [(256, 1024), (512, 1024)]),                 # packed 12-bit codes, 128 KiB of codebooks
+    (16, 8, 1, 4096, [(300, 512), (700, 512)]),                   # uint16 codes, a codebook that fits LDS
+])
+def test_gemv_batch_of_lds_codebook_weights_is_one_launch_with_the_bits_of_single_calls(gpu_device, bits, v, R, E, shapes):
+    """vq_gemv_batch on canonical codes whose codebooks live in LDS (the matrix-core gemv): one launch for all
+    members; at these sizes K is split over the same number of wavefronts as in a single call, so the bits are
+    those of vq_gemv; within tolerance of the oracle."""
+    ws = [wl.make_weight(N, K, v, bits, R, E, 0.01, seed=7500 + 10 * bits + i, with_scale=(i % 2 == 0)) for i, (N, K) in enumerate(shapes)]
+    xs = [wl.make_activations(1, K, seed=7600 + i) for i, (N, K) in enumerate(shapes)]
+    wds = [vq.weight_to_device(w, gpu_device) for w in ws]
+    xds = [dev_x(x, gpu_device) for x in xs]
+    ys = vq.vq_gemv_batch(wds, xds)
+    torch.cuda.synchronize()
+    for w, wd, x, xd, y in zip(ws, wds, xs, xds, ys):
+        assert torch.equal(y, vq.vq_gemv(wd, xd)), (w.N, w.K)
+        codes = oracle.Packed12(w.codes, (w.N, w.K // w.v, w.R)) if bits == 12 else w.codes
+        assert_close(y, oracle.gemv(codes, w.codebooks, w.scale, x), f"LDS-codebook batch member {w.N}x{w.K}")
+
+
+def test_gemv_batch_config3_full_size(gpu_device):
+    # the additive configuration at Llama-7B shapes, as bench.py batches it: three 4096 x 4096, two 11008 x 4096
+    for shape_idx, count in ((0, 3), (1, 2)):
+        ws = [wl.config3_layer(shape_idx, layer=20 + i) for i in range(count)]
+        x = wl.make_activations(1, ws[0].K, wl.seed_for(3, 700 + shape_idx))
+        xd = dev_x(x, gpu_device)
+        wds = [vq.weight_to_device(w, gpu_device) for w in ws]
+        ys = vq.vq_gemv_batch(wds, [xd] * count)
+        again = vq.vq_gemv_batch(wds, [xd] * count)
+        torch.cuda.synchronize()
+        for i, (w, wd, y, y2) in enumerate(zip(ws, wds, ys, again)):
+            # (the batch may split K over another number of wavefronts than the single call: same products, another
+            # order of the fp32 additions; repeated batches are bit-identical)
+            assert torch.equal(y, y2)
+            assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), f"C3 batch[{shape_idx}][{i}]")
+
+
 def test_gemv_sequence_equals_separate_calls(gpu_device):
     """vq_gemv_sequence: the reduction of every launch rides along in the next one.  Mixed shapes (so that the
     pending rows per workgroup go from a few to more than one chunk of 64), single problems and batches, scales
