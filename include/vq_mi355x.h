@@ -281,6 +281,17 @@ size_t vq_gemv_sequence_streams_workspace(const vq_gemv_call_t *calls, int n_cal
  *     wavefront of some run gave up one of its bounded waits inside the kernel (the outputs of that run are then
  *     invalid; this takes a workgroup whose own wavefronts stop making progress for tens of milliseconds).
  *   vq_gemv_pipeline_destroy: frees the handle (not ws); NULL is allowed.
+ *
+ * Second kind of list: weights with SMALL codebooks in the canonical layout (no re-tiled codes; uint8 codes, v = 8,
+ * one or two additive codebooks of <= 256 entries, K a multiple of 64 in [512, 12288]; Sec. II-A residual
+ * quantization, Sec. III-C VQ-gemv).  All problems of the list must be of this kind and have the same number of
+ * codebooks (a mix: VQ_ERR_UNSUPPORTED).  One launch: a workgroup per compute unit holds 16 copies of every entry
+ * of the current problem's codebooks in LDS, one per bank column, so that the random entry reads of a wavefront never
+ * collide; groups of workgroups work on different problems at the same time and re-stage between problems while
+ * the next problem's codes are already in flight.  No partial sums, no second launch: ws holds only the problem
+ * table.  Outputs are within the gemv tolerance of the definition but not bit-identical to vq_gemv's (another
+ * summation order); repeated runs give identical bits.  vq_gemv_pipeline_status reports 0 (this kernel has no waits
+ * it could give up).
  */
 typedef struct vq_gemv_pipeline vq_gemv_pipeline_t;
 size_t vq_gemv_pipeline_workspace(const vq_gemv_call_t *calls, int n_calls);

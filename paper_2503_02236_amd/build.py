@@ -15,7 +15,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvqmi.so")
-SOURCES = ["api.hip", "dequant.hip", "gemv.hip", "gemv_packed.hip", "gemv_mfma.hip", "gemm.hip", "gemm_dense.hip", "attn.hip", "attn_channel.hip", "kv_quantize.hip", "reorder.hip"]
+SOURCES = ["api.hip", "dequant.hip", "gemv.hip", "gemv_packed.hip", "gemv_mfma.hip", "gemv_replica.hip", "gemm.hip", "gemm_dense.hip", "attn.hip", "attn_channel.hip", "kv_quantize.hip", "reorder.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are disabled for every kernel of this library

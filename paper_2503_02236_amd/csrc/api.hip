@@ -239,9 +239,41 @@ int vq_gemv_sequence(const vq_gemv_call_t *calls, int n_calls, void *ws, size_t 
     return launch_gemv_packed_sequence(calls, n_calls, ws, static_cast<hipStream_t>(stream));
 }
 
+// A pipeline is one of two kinds, after its weights: re-tiled codes of a large codebook (the persistent two-image
+// kernel), or canonical uint8 codes with small codebooks (the kernel that holds 16 LDS copies of every entry).
 struct vq_gemv_pipeline {
     GemvPipeline *impl;
+    GemvReplicaList *rep;
 };
+
+// 1 if every problem can run on the small-codebook kernel, 0 if none can (or some weight is re-tiled), < 0 on a
+// mix or an invalid argument.
+static int replica_calls(const vq_gemv_call_t *calls, int n_calls) {
+    if (!calls) return VQ_ERR_NULL;
+    if (n_calls < 1) return VQ_ERR_SHAPE;
+    int yes = 0, no = 0, R = 0;
+    for (int c = 0; c < n_calls; ++c) {
+        if (!calls[c].w || !calls[c].x || !calls[c].y) return VQ_ERR_NULL;
+        if (calls[c].count < 1 || calls[c].count > VQ_GEMV_BATCH_MAX) return VQ_ERR_SHAPE;
+        for (int i = 0; i < calls[c].count; ++i) {
+            const vq_weight_t *w = calls[c].w[i];
+            if (!w) return VQ_ERR_NULL;
+            if (w->gemv_pack || check_weight(w, true) != VQ_OK || !gemv_replica_supported(w)) { ++no; continue; }
+            if (R && w->n_codebooks != R) return VQ_ERR_UNSUPPORTED;
+            R = w->n_codebooks;
+            if (!calls[c].x[i] || !calls[c].y[i]) return VQ_ERR_NULL;
+            if (!aligned16(calls[c].x[i]) || !aligned16(calls[c].y[i])) return VQ_ERR_ALIGN;
+            ++yes;
+        }
+    }
+    if (yes && no) return VQ_ERR_UNSUPPORTED;
+    return yes ? 1 : 0;
+}
+static int count_problems(const vq_gemv_call_t *calls, int n_calls) {
+    int n = 0;
+    for (int c = 0; c < n_calls; ++c) n += calls[c].count;
+    return n;
+}
 
 static int check_pipeline_calls(const vq_gemv_call_t *calls, int n_calls) {
     if (!calls) return VQ_ERR_NULL;
@@ -255,7 +287,9 @@ static int check_pipeline_calls(const vq_gemv_call_t *calls, int n_calls) {
 }
 
 size_t vq_gemv_pipeline_workspace(const vq_gemv_call_t *calls, int n_calls) {
-    if (check_pipeline_calls(calls, n_calls) != VQ_OK) return 0;
+    const int rep = replica_calls(calls, n_calls);
+    if (rep == 1) return gemv_replica_list_workspace(count_problems(calls, n_calls));
+    if (rep < 0 || check_pipeline_calls(calls, n_calls) != VQ_OK) return 0;
     return gemv_pipeline_workspace(calls, n_calls);
 }
 
@@ -263,12 +297,20 @@ int vq_gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, 
                             vq_gemv_pipeline_t **out) {
     if (!out) return VQ_ERR_NULL;
     *out = nullptr;
-    if (int st = check_pipeline_calls(calls, n_calls)) return st;
-    if (!ws || ws_bytes < gemv_pipeline_workspace(calls, n_calls)) return VQ_ERR_WORKSPACE;
+    const int rep = replica_calls(calls, n_calls);
+    if (rep < 0) return rep;
+    if (rep == 0)
+        if (int st = check_pipeline_calls(calls, n_calls)) return st;
+    const size_t need = rep ? gemv_replica_list_workspace(count_problems(calls, n_calls)) : gemv_pipeline_workspace(calls, n_calls);
+    if (!ws || ws_bytes < need) return VQ_ERR_WORKSPACE;
     if (((uintptr_t)ws & 255) != 0) return VQ_ERR_ALIGN;
     vq_gemv_pipeline *h = new (std::nothrow) vq_gemv_pipeline;
     if (!h) return VQ_ERR_LAUNCH;
-    if (int st = gemv_pipeline_create(calls, n_calls, ws, static_cast<hipStream_t>(stream), &h->impl)) {
+    h->impl = nullptr;
+    h->rep = nullptr;
+    const int st = rep ? gemv_replica_list_create(calls, n_calls, ws, static_cast<hipStream_t>(stream), &h->rep)
+                       : gemv_pipeline_create(calls, n_calls, ws, static_cast<hipStream_t>(stream), &h->impl);
+    if (st != VQ_OK) {
         delete h;
         return st;
     }
@@ -277,18 +319,24 @@ int vq_gemv_pipeline_create(const vq_gemv_call_t *calls, int n_calls, void *ws, 
 }
 
 int vq_gemv_pipeline_run(const vq_gemv_pipeline_t *p, void *stream) {
-    if (!p || !p->impl) return VQ_ERR_NULL;
+    if (!p || (!p->impl && !p->rep)) return VQ_ERR_NULL;
+    if (p->rep) return launch_gemv_replica_list(p->rep, static_cast<hipStream_t>(stream));
     return launch_gemv_pipeline(p->impl, static_cast<hipStream_t>(stream));
 }
 
 int vq_gemv_pipeline_status(const vq_gemv_pipeline_t *p, void *stream, int *status) {
-    if (!p || !p->impl || !status) return VQ_ERR_NULL;
+    if (!p || (!p->impl && !p->rep) || !status) return VQ_ERR_NULL;
+    if (p->rep) {   // (that kernel has no waits it could give up)
+        *status = 0;
+        return hipStreamSynchronize(static_cast<hipStream_t>(stream)) == hipSuccess ? VQ_OK : VQ_ERR_LAUNCH;
+    }
     return gemv_pipeline_status(p->impl, static_cast<hipStream_t>(stream), status);
 }
 
 void vq_gemv_pipeline_destroy(vq_gemv_pipeline_t *p) {
     if (!p) return;
-    gemv_pipeline_destroy(p->impl);
+    if (p->impl) gemv_pipeline_destroy(p->impl);
+    if (p->rep) gemv_replica_list_destroy(p->rep);
     delete p;
 }
 

@@ -118,6 +118,13 @@ int launch_gemm_dense(const half_t *A, const half_t *B, const half_t *scale, hal
                       hipStream_t s);
 bool gemv_mfma_batch_supported(const vq_weight_t *const *w, int count);
 int launch_gemv_mfma_batch(const vq_weight_t *const *w, const void *const *x, void *const *y, int count, hipStream_t s);
+// bs = 1 with 16 LDS copies of every entry of a small codebook: a list of problems in one launch (gemv_replica.hip)
+struct GemvReplicaList;
+bool gemv_replica_supported(const vq_weight_t *w);
+size_t gemv_replica_list_workspace(int n);
+int gemv_replica_list_create(const vq_gemv_call_t *calls, int n_calls, void *ws, hipStream_t s, GemvReplicaList **out);
+void gemv_replica_list_destroy(GemvReplicaList *h);
+int launch_gemv_replica_list(const GemvReplicaList *h, hipStream_t s);
 int launch_attn_decode(const vq_kv_t *kv, const void *q, float sm_scale, void *out, void *ws, hipStream_t s);
 // channel-parallel variant for caches with one codebook per channel sub-space (attn_channel.hip)
 bool attn_channel_supported(const vq_kv_t *kv);

@@ -354,6 +354,52 @@ def test_gemv_pipeline_validation():
     lib.vq_gemv_pipeline_destroy(None)                       # allowed
 
 
+def test_gemv_pipeline_small_codebook_list_validation():
+    """vq_gemv_pipeline_* with canonical uint8 weights of small codebooks (the second kind of list): the workspace is
+    the problem table alone; lists that mix kinds or codebook counts are refused before any GPU call."""
+    from paper_2503_02236_amd import workloads as wl
+    from paper_2503_02236_amd.binding import vq_gemv_call_t
+    lib = vq.lib()
+    WP = ctypes.POINTER(vq_weight_t)
+
+    def call(ws_list, xs, ys):
+        n = len(ws_list)
+        c = vq_gemv_call_t()
+        c._keep = ((WP * n)(*[ctypes.pointer(x) for x in ws_list]), (ctypes.c_void_p * n)(*xs), (ctypes.c_void_p * n)(*ys))
+        c.w, c.x, c.y = (ctypes.cast(c._keep[0], ctypes.POINTER(WP)), ctypes.cast(c._keep[1], ctypes.POINTER(ctypes.c_void_p)),
+                         ctypes.cast(c._keep[2], ctypes.POINTER(ctypes.c_void_p)))
+        c.count = n
+        return c
+
+    def create(calls, ws=P, ws_bytes=1 << 20):
+        arr = (vq_gemv_call_t * len(calls))(*calls)
+        h = ctypes.c_void_p(1)
+        st = lib.vq_gemv_pipeline_create(arr, len(calls), ws, ws_bytes, None, ctypes.byref(h))
+        assert h.value is None
+        return st, lib.vq_gemv_pipeline_workspace(arr, len(calls))
+
+    two = weight(N=4096, K=4096, n_codebooks=2)
+    one = weight(N=300, K=1024, n_codebooks=1, n_entries=64)
+    odd_k = weight(N=300, K=1000, n_codebooks=2)              # K not a multiple of 64: not this kind (and not re-tiled)
+    wide = weight(N=300, K=16384, n_codebooks=2)              # x does not fit next to the codebook copies
+    w16 = wl.make_weight(128, 512, 8, 16, 1, 65536, 0.02, seed=5)
+    buf, pack = vq.vq_gemv_prepack(w16)
+    pack.data = P
+    packed = vq_weight_t(w16.N, w16.K, 8, 16, 1, 65536, None, P, None, ctypes.pointer(pack))
+    good = [call([two, two, two], [P, P, P], [P, P, P]), call([two], [P], [P])]
+    need = 256                                                # four table entries of 56 bytes, rounded up to 256
+    assert create(good, ws=None) == (VQ_ERR_WORKSPACE, need)
+    assert create(good, ws_bytes=need - 1) == (VQ_ERR_WORKSPACE, need)
+    assert create(good, ws=P + 16) == (VQ_ERR_ALIGN, need)
+    assert create([call([two], [P + 2], [P])]) == (VQ_ERR_ALIGN, 0)
+    assert create([call([two], [None], [P])]) == (VQ_ERR_NULL, 0)
+    assert create([call([two, one], [P, P], [P, P])]) == (VQ_ERR_UNSUPPORTED, 0)     # one and two codebooks in a list
+    assert create([call([two], [P], [P]), call([packed], [P], [P])]) == (VQ_ERR_UNSUPPORTED, 0)   # the two kinds mixed
+    assert create([call([two, odd_k], [P, P], [P, P])]) == (VQ_ERR_UNSUPPORTED, 0)
+    assert create([call([wide], [P], [P])]) == (VQ_ERR_UNSUPPORTED, 0)
+    assert create([call([one], [P], [P])], ws=None) == (VQ_ERR_WORKSPACE, 256)       # a single-codebook list is fine
+
+
 def test_probe_argument_validation():
     lib = vq.lib()
     assert lib.vq_probe_copy(None, P, 16, None) == VQ_ERR_NULL

@@ -457,6 +457,97 @@ def _pipeline_case(gpu_device, specs, seed0, reps=2):
     pipe.close()
 
 
+def _small_codebook_list(gpu_device, R, specs, seed0, subsets):
+    calls, ref = [], []
+    for i, (N, K, E, sc) in enumerate(specs):
+        w = wl.make_weight(N, K, 8, 8, R, E, 0.01, seed=seed0 + i, with_scale=sc)
+        x = wl.make_activations(1, K, seed=seed0 + 500 + i)
+        calls.append([(vq.weight_to_device(w, gpu_device), dev_x(x, gpu_device),
+                       torch.full((1, N), 5.0, dtype=torch.float16, device=gpu_device))])
+        ref.append((w, x))
+    first = {}
+    for sub in subsets:
+        pipe = vq.GemvPipeline([calls[i] for i in sub])
+        for rep in range(2):                                     # the second run re-uses the table and the LDS contents
+            assert pipe.run() == 0
+            torch.cuda.synchronize()
+            assert pipe.status() == 0
+            for i in sub:
+                w, x = ref[i]
+                y = calls[i][0][2]
+                assert_close(y, oracle.gemv(w.codes, w.codebooks, w.scale, x), f"list member {w.N}x{w.K} R={R} of {len(sub)}")
+                # the bits do not depend on the run, nor on what else is in the list (every order is fixed per problem)
+                assert torch.equal(y, first.setdefault(i, y.clone())), (w.N, w.K, rep, len(sub))
+                y.fill_(3.0)
+        pipe.close()
+
+
+def test_gemv_pipeline_small_codebook_lists(gpu_device):
+    """vq_gemv_pipeline with canonical uint8 weights of small codebooks: 16 LDS copies of every entry, a list of
+    problems in one launch.  Rows that end inside a chunk of 512 positions (K = 1024 + 64, 11008, 2112), three chunks
+    (K = 11008, 12288), one row, fewer rows than workgroups, codebooks of 16 / 64 / 128 entries, no scale; lists of 1,
+    3 and all problems (1, 2 and 8 groups of workgroups); one and two additive codebooks."""
+    _small_codebook_list(gpu_device, 2, [(4096, 4096, 256, True), (300, 1024, 256, False), (11008, 4096, 256, True),
+                                         (4096, 11008, 256, True), (1, 512, 256, True), (777, 2112, 64, True),
+                                         (513, 12288, 256, True), (2000, 576, 256, True), (64, 8192, 16, False)],
+                         9900, [range(9), [0], [0, 1, 2], [6, 4, 3, 8]])
+    _small_codebook_list(gpu_device, 1, [(4096, 4096, 256, True), (333, 1088, 256, True), (1000, 11008, 128, False)],
+                         9950, [range(3), [2]])
+
+
+def test_gemv_pipeline_small_codebook_nan_entries_unused(gpu_device):
+    """Entries that no code uses are never multiplied into a result: with NaN in them the outputs stay finite and
+    equal those with zeros there (a lane past the end of a ragged row computes with codes that are not its own;
+    that value is dropped, not multiplied by zero)."""
+    N, K, E = 600, 1088, 256
+    w = wl.make_weight(N, K, 8, 8, 2, E, 0.01, seed=9970, with_scale=True)
+    w.codes[...] = w.codes % 200                             # entries 200..255 of both codebooks are never used
+    x = wl.make_activations(1, K, seed=9971)
+    outs = []
+    for fill in (0.0, float("nan")):
+        w.codebooks[:, 200:, :] = np.float16(fill)
+        wd = vq.weight_to_device(w, gpu_device)
+        y = torch.full((1, N), 5.0, dtype=torch.float16, device=gpu_device)
+        pipe = vq.GemvPipeline([[(wd, dev_x(x, gpu_device), y)]])
+        assert pipe.run() == 0
+        torch.cuda.synchronize()
+        outs.append(y.clone())
+        pipe.close()
+    assert torch.isfinite(outs[1]).all()
+    assert torch.equal(outs[0], outs[1])
+    w.codebooks[:, 200:, :] = np.float16(0.0)
+    assert_close(outs[0], oracle.gemv(w.codes, w.codebooks, w.scale, x), "nan-entries case")
+
+
+def test_gemv_pipeline_config3_stack_full_size(gpu_device):
+    """Two decoder blocks of the additive 2 x 256 x 8 configuration at full size (4 + 2 + 1 matrices each) as one
+    list: sampled rows against the oracle, all rows finite, repeatable."""
+    calls, ref = [], []
+    for blk in range(2):
+        for si, cnt in ((0, 4), (1, 2), (2, 1)):
+            N, K = wl.LLAMA7B_SHAPES[si]
+            for j in range(cnt):
+                w = wl.config3_layer(si, blk * 4 + j)
+                x = wl.make_activations(1, K, seed=9990 + len(calls))
+                calls.append([(vq.weight_to_device(w, gpu_device), dev_x(x, gpu_device),
+                               torch.full((1, N), 5.0, dtype=torch.float16, device=gpu_device))])
+                ref.append((w, x))
+    pipe = vq.GemvPipeline(calls)
+    assert pipe.run() == 0
+    torch.cuda.synchronize()
+    first = [c[0][2].clone() for c in calls]
+    assert pipe.run() == 0
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(77)
+    for c, f, (w, x) in zip(calls, first, ref):
+        assert torch.equal(c[0][2], f)
+        assert torch.isfinite(f).all()
+        rows = np.unique(np.concatenate([rng.integers(0, w.N, 48), [0, w.N - 1]]))
+        want = oracle.gemv(w.codes, w.codebooks, w.scale, x, rows=rows)
+        assert_close(f[:, torch.from_numpy(rows).to(f.device)], want, f"stack member {w.N}x{w.K}")
+    pipe.close()
+
+
 def test_gemv_pipeline_mixed_shapes(gpu_device):
     """vq_gemv_pipeline: one persistent launch for all products.  One, two and many problems; problems with fewer
     blocks than the launch has workgroups, with one row, without scale, with smaller codebooks (fewer slices), with
