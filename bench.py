@@ -530,6 +530,41 @@ def main():
                                                            "pct_hbm_peak": round(100 * b / msb / 1e6 / HBM_PEAK_GBPS, 2)}
             del wds
             torch.cuda.empty_cache()
+        # the whole decoder stack of this configuration (32 blocks x (4 + 2 + 1) matrices, every weight its own
+        # codes and codebooks): one launch through vq_gemv_pipeline (16 LDS copies of every entry), against the
+        # same stack as one vq_gemv call per matrix; algorithmic bytes as in the headline figure
+        stack, nbytes = [], 0
+        for layer in range(args.layers):
+            for si, cnt in ((0, 4), (1, 2), (2, 1)):
+                N, K = wl.LLAMA7B_SHAPES[si]
+                for j in range(cnt):
+                    wd = vq.weight_to_device(wl.config3_layer(si, layer * 4 + j), dev)
+                    x = torch.from_numpy(wl.make_activations(1, K, wl.seed_for(3, 1))).to(dev)
+                    stack.append((wd, x, torch.empty((1, N), dtype=torch.float16, device=dev)))
+                    nbytes += N * K // 8 * 2 + 2 * 256 * 8 * 2 + K * 2 + N * 4
+        pipe = vq.GemvPipeline([[t] for t in stack])
+
+        def stack_pipeline():
+            st = pipe.run()
+            if st != 0:
+                raise vq.VQError(st, "vq_gemv_pipeline_run")
+        ms_p = timed_replay(stack_pipeline, 10, 2)
+        cs = [GemvCall(wd, x, y) for (wd, x, y) in stack]
+
+        def stack_calls():
+            for c in cs:
+                c()
+        ms_c = timed_replay(stack_calls, 5, 1)
+        add["stack_%d_matrices_bs1" % len(stack)] = {
+            "algorithmic_bytes": nbytes,
+            "vq_gemv_pipeline": {"ms": round(ms_p, 4), "GBps": round(nbytes / ms_p / 1e6, 1),
+                                 "pct_hbm_peak": round(100 * nbytes / ms_p / 1e6 / HBM_PEAK_GBPS, 2), "kernel_dispatches": 1},
+            "one_vq_gemv_per_matrix": {"ms": round(ms_c, 4), "GBps": round(nbytes / ms_c / 1e6, 1),
+                                       "pct_hbm_peak": round(100 * nbytes / ms_c / 1e6 / HBM_PEAK_GBPS, 2),
+                                       "kernel_dispatches": len(stack)}}
+        pipe.close()
+        del pipe, cs, stack
+        torch.cuda.empty_cache()
         result["gemv_additive_2x256x8"] = add
 
     # ------------------------------------------------------------------ secondary: per-tile codebooks (VQ<4,8,1>, 256 x 256 tiles)
