@@ -56,6 +56,9 @@ def parse():
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter run (wrap in rocprofv3 --pmc FETCH_SIZE or WRITE_SIZE): three plain copies of "
                          "known size as calibration, then one eager pass over the headline gemv stack; no timing")
+    ap.add_argument("--pmc-probe-additive", action="store_true",
+                    help="counter run like --pmc-probe, over the additive-codebook (2 x 256 x 8) decoder stack through "
+                         "vq_gemv_pipeline (one launch)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "gemv_pipeline_c2_hbm_traffic.md"),
                     help="summary written by paper_2503_02236_amd.profile_summary traffic; its "
                          "'traffic_bytes_per_launch:' line fills roofline.traffic")
@@ -143,6 +146,22 @@ def main():
     result = {}
     t_setup = time.time()
 
+    def additive_stack():
+        """The decoder stack of the additive 2 x 256 x 8 configuration: 32 blocks x (4 + 2 + 1) matrices, every weight
+        its own codes and codebooks; (weight, x, y) triples and the algorithmic bytes (as in the headline figure)."""
+        stack, nbytes = [], 0
+        for layer in range(args.layers):
+            for si, cnt in ((0, 4), (1, 2), (2, 1)):
+                N, K = wl.LLAMA7B_SHAPES[si]
+                for j in range(cnt):
+                    wd = vq.weight_to_device(wl.config3_layer(si, layer * 4 + j), dev)
+                    x = torch.from_numpy(wl.make_activations(1, K, wl.seed_for(3, 1))).to(dev)
+                    stack.append((wd, x, torch.empty((1, N), dtype=torch.float16, device=dev)))
+                    nbytes += N * K // 8 * 2 + 2 * 256 * 8 * 2 + K * 2 + N * 4
+        return stack, nbytes
+
+    if args.pmc_probe_additive:
+        args.pmc_probe = True
     if args.pmc_probe:
         nbytes = 256 << 20
         src = torch.full((nbytes,), 3, dtype=torch.uint8, device=dev)
@@ -153,6 +172,16 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         only = {"gemv"}
+        if args.pmc_probe_additive:
+            stack, eff = additive_stack()
+            pipe = vq.GemvPipeline([[t] for t in stack])
+            st = pipe.run()
+            if st != 0:
+                raise vq.VQError(st, "vq_gemv_pipeline_run")
+            torch.cuda.synchronize()
+            print(json.dumps({"pmc_probe": True, "probe_copy_bytes": 256 << 20, "probe_copies": 3,
+                              "gemv_launches": 1, "effective_bytes": eff}), flush=True)
+            return
 
     # ------------------------------------------------------------------ measured ceilings of this chip
     # (second reference beside the vendor peaks): a plain 128-bit streaming read of 2 GiB, cold, and a
@@ -533,15 +562,7 @@ def main():
         # the whole decoder stack of this configuration (32 blocks x (4 + 2 + 1) matrices, every weight its own
         # codes and codebooks): one launch through vq_gemv_pipeline (16 LDS copies of every entry), against the
         # same stack as one vq_gemv call per matrix; algorithmic bytes as in the headline figure
-        stack, nbytes = [], 0
-        for layer in range(args.layers):
-            for si, cnt in ((0, 4), (1, 2), (2, 1)):
-                N, K = wl.LLAMA7B_SHAPES[si]
-                for j in range(cnt):
-                    wd = vq.weight_to_device(wl.config3_layer(si, layer * 4 + j), dev)
-                    x = torch.from_numpy(wl.make_activations(1, K, wl.seed_for(3, 1))).to(dev)
-                    stack.append((wd, x, torch.empty((1, N), dtype=torch.float16, device=dev)))
-                    nbytes += N * K // 8 * 2 + 2 * 256 * 8 * 2 + K * 2 + N * 4
+        stack, nbytes = additive_stack()
         pipe = vq.GemvPipeline([[t] for t in stack])
 
         def stack_pipeline():
