@@ -111,3 +111,50 @@ def test_attention_kernels_have_no_static_lds(tmp_path):
     assert len(kernels) >= 6            # v = 2, 4, 8 x one / several codebooks (x one or two sequences)
     for name, body in kernels:
         assert re.search(r"\.amdhsa_group_segment_fixed_size 0\b", body), name
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
+def test_gemv_replica_gathers_form_one_block_and_nothing_lives_in_scratch(tmp_path):
+    """The small-codebook list kernel forms absolute LDS addresses (no static LDS allowed), reads its problem list
+    with scalar loads (a by-value list indexed with a register would move to scratch memory: none allowed), and issues
+    the gathers of an item as asm in front of one full LDS wait: between the first gather of an item and that wait
+    there is nothing but gathers and address permutes, 16 gathers with two codebooks and 8 with one."""
+    out = tmp_path / "gemv_replica.s"
+    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "--cuda-device-only", "-S",
+           os.path.join(CSRC, "gemv_replica.hip"), "-o", str(out)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    text = out.read_text()
+    checked = 0
+    for R in (1, 2):
+        name = r"_ZN2vq25gemv_replica_table_kernelILi%dEE\w*" % R
+        k = re.search(r"\.amdhsa_kernel (%s)\n(.*?)\.end_amdhsa_kernel" % name, text, re.S)
+        assert k, R
+        assert re.search(r"\.amdhsa_group_segment_fixed_size 0\b", k.group(2)), R
+        assert re.search(r"\.amdhsa_private_segment_fixed_size 0\b", k.group(2)), R
+        m = re.search(r"^(%s):[^\n]*\n(.*?)^\.Lfunc_end" % name, text, re.S | re.M)
+        assert m, R
+        lines = [l.strip() for l in m.group(2).splitlines()]
+        lines = [l for l in lines if l and not l.startswith(";")]
+        assert not any(l.startswith("scratch_") for l in lines), R
+        # every block of asm gathers: maximal runs of ds_read_b128 / v_perm_b32 that end in the full wait
+        items = 0
+        i = 0
+        while i < len(lines):
+            if lines[i].startswith("v_perm_b32"):
+                j, gathers = i, 0
+                while lines[j].startswith(("v_perm_b32", "ds_read_b128")):
+                    gathers += lines[j].startswith("ds_read_b128")
+                    j += 1
+                if gathers:
+                    assert gathers == 8 * R, (R, gathers, lines[i:j + 2])
+                    rest = [l for l in lines[j:j + 3] if not l.startswith("s_nop")]
+                    assert rest[0] == "s_waitcnt lgkmcnt(0)", (R, lines[j:j + 3])
+                    items += 1
+                i = j
+            i += 1
+        assert items >= 6, (R, items)                    # one block per item of a round
+        assert sum(l.startswith("v_mfma_f32_4x4x4") for l in lines) == items * 16 * R
+        checked += 1
+    assert checked == 2
