@@ -33,8 +33,10 @@ MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix-core peak, vendor figure
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps first; the default is long enough for the clocks to settle (a GPU that comes "
+                         "from idle runs its first few launches fast, the next dozen slow, and levels out after that)")
     ap.add_argument("--layers", type=int, default=32, help="decoder blocks in the gemv stack")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     ap.add_argument("--skip-secondary", action="store_true", help="only the headline gemv stack")
@@ -89,18 +91,28 @@ def main():
     def want(section):
         return not only or section in only
 
-    def timed(fn, iters, warm):
-        """Average ms per call of fn() over `iters` back-to-back calls, HIP events on the launch stream."""
-        for _ in range(warm):
-            fn()
-        torch.cuda.synchronize()
+    def timed_once(fn, iters):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(iters):
             fn()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        return e0.elapsed_time(e1)
+
+    def timed(fn, iters, warm):
+        """Average ms per call of fn() over back-to-back calls, HIP events on the launch stream: at least `iters`
+        calls, and as many as it takes to time about 60 ms of GPU work after as much untimed work (steady clocks:
+        a GPU that comes from idle runs its first launches fast and the next ones slow before it levels out)."""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        ms = timed_once(fn, iters)
+        if ms < 60.0 and not args.pmc_probe:
+            n = min(max(iters, int(iters * 60.0 / max(ms, 1e-3)) + 1), 5000)
+            timed_once(fn, n)
+            return timed_once(fn, n) / n
+        return ms / iters
 
     def timed_replay(fn, iters, warm):
         """Like timed(), with fn() captured once into a HIP graph and replayed (as the headline stack is timed):
@@ -304,6 +316,10 @@ def main():
         else:
             run_step = step
 
+        # the first 20 steps of a GPU that comes from idle, for the record (they are part of no other figure)
+        torch.cuda.synchronize()
+        time.sleep(0.2)
+        ms_from_idle = timed_once(run_step, 20) / 20
         for _ in range(args.warmup):
             run_step()
         torch.cuda.synchronize()
@@ -348,6 +364,7 @@ def main():
             "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
             "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "f16", "data": "synthetic",
+            "first_20_steps_from_idle_ms_per_step": round(ms_from_idle, 5),
             "config": {"workload": "C2: Llama-7B decode VQ-gemv bs=1, %d blocks x 7 matrices, VQ<8,16,1> uint16 codes, "
                                    "fp16 scale" % L,
                        "launches_per_step": n_launch, "matrices_per_step": len(singles),
