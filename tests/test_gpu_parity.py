@@ -1167,3 +1167,36 @@ def test_measurement_probes_run_and_copy_is_exact(gpu_device):
         vq.vq_probe_mfma(8, 4, sink, random_operands=mode)
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
+
+
+def test_gemv_pipeline_small_codebook_list_as_replayed_graph(gpu_device):
+    """The small-codebook kind of vq_gemv_pipeline captured into a HIP graph and replayed, with eager work and
+    synchronisations in between: every replay gives the bits of the eager run."""
+    calls, ref = [], []
+    for i, (N, K) in enumerate([(4096, 1024), (1000, 2112), (2500, 512), (300, 11008), (4096, 4096)]):
+        w = wl.make_weight(N, K, 8, 8, 2, 256, 0.01, seed=9700 + i)
+        xd = dev_x(wl.make_activations(1, K, seed=9750 + i), gpu_device)
+        calls.append([(vq.weight_to_device(w, gpu_device), xd, torch.full((1, N), 7.0, dtype=torch.float16, device=gpu_device))])
+        ref.append((w, xd))
+    pipe = vq.GemvPipeline(calls)
+    assert pipe.run() == 0
+    torch.cuda.synchronize()
+    want = [c[0][2].clone() for c in calls]
+    for c, (w, xd) in zip(calls, ref):
+        assert_close(c[0][2], oracle.gemv(w.codes, w.codebooks, w.scale, xd.cpu().numpy()), f"eager {w.N}x{w.K}")
+        c[0][2].fill_(7.0)
+    g = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(g, stream=cap):
+            assert pipe.run() == 0
+    for rep in range(4):
+        g.replay()
+        torch.cuda.synchronize()
+        for c, w_ in zip(calls, want):
+            assert torch.equal(c[0][2], w_), rep
+            c[0][2].fill_(7.0)
+        vq.vq_gemv(calls[0][0][0], calls[0][0][1])           # eager work of the program between the replays
+        torch.cuda.synchronize()
+    del g
+    pipe.close()
