@@ -320,7 +320,10 @@ def main():
         torch.cuda.synchronize()
         time.sleep(0.2)
         ms_from_idle = timed_once(run_step, 20) / 20
-        for _ in range(args.warmup):
+        # whatever --warmup says, the clocks get 50 more untimed steps to settle after that start from idle (the
+        # default --warmup 50 covers it; a caller's smaller value is topped up, and the JSON line says by how much)
+        settle = max(0, 50 - args.warmup)
+        for _ in range(settle + args.warmup):
             run_step()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -365,6 +368,7 @@ def main():
             "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "f16", "data": "synthetic",
             "first_20_steps_from_idle_ms_per_step": round(ms_from_idle, 5),
+            "settle_steps_before_warmup": settle,
             "config": {"workload": "C2: Llama-7B decode VQ-gemv bs=1, %d blocks x 7 matrices, VQ<8,16,1> uint16 codes, "
                                    "fp16 scale" % L,
                        "launches_per_step": n_launch, "matrices_per_step": len(singles),
