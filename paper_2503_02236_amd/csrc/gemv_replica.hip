@@ -13,7 +13,7 @@
 // lane % 16 = c, is collision free whatever the codes are: 2 x 64 KiB of the CU's 160 KiB for two codebooks.  The
 // address is one v_perm_b32: the code byte dropped into byte 1 of a per-lane constant.
 //
-// Mapping.  One persistent workgroup of 8 wavefronts per compute unit.  The workgroups form up to 16 groups; group g
+// Mapping.  One persistent workgroup of 12 wavefronts per compute unit.  The workgroups form up to 16 groups; group g
 // takes problems g, g + groups, ... of the list, and each of its workgroups a contiguous range of rows of every
 // such problem (the more rows per workgroup, the less the re-staging of codebooks between problems weighs).  A row's
 // codes are cut into chunks of 512 positions: lane l of a wavefront loads the 8 (x R) code bytes of positions
@@ -24,10 +24,10 @@
 // independent pairs of 4 x 4 matrices, row i of the first and column i of the second operand of a pair held by the
 // same lane, so diagonal element i of a product is that lane's own 4-term dot product, in accumulator register
 // lane % 4 (the other three registers collect cross terms and are never read).  An item's 64 lane sums are added by
-// DPP steps; chunk sums meet in LDS and thread t of the workgroup finishes rows t and t + 512 of its range:
+// DPP steps; chunk sums meet in LDS and thread t of the workgroup finishes rows t and t + 768 of its range:
 // y = fp16(scale * sum), chunks in ascending order.  Every order is fixed: repeated runs give the same bits.
 //
-// Between two problems the workgroup re-stages: each thread holds one entry of the next problem (and up to 48 bytes
+// Between two problems the workgroup re-stages: each thread holds one entry of the next problem (and up to 32 bytes
 // of its x, and the scales of its rows), requested a whole problem earlier, and writes the 16 copies -- lane l starts
 // at copy l % 16, so the writes of a pass fall into 16 different columns too.  The codes of a wavefront's next six
 // items are also requested one round ahead, across problem boundaries; the workgroup barriers wait for LDS traffic
@@ -44,7 +44,8 @@
 
 namespace vq {
 
-constexpr int kRepThreads = 512;   // (12 wavefronts with 4 items in flight each: 4 % faster, with register spills)
+constexpr int kRepThreads = 768;   // 12 wavefronts, three per SIMD: 170 registers each (8: 7 % slower; 16: registers spill)
+constexpr int kRepHalves = 2;      // an item's gathers are issued in this many blocks, each in front of its own arithmetic
 constexpr int kRepWaves = kRepThreads / kWave;
 constexpr int kRepCopies = 16;
 constexpr int kRepCbStride = 256 * kRepCopies * 16;     // 64 KiB: LDS bytes of one codebook
@@ -185,41 +186,44 @@ __device__ __forceinline__ RepCodes<R> rep_load(const uint8_t *codes, uint32_t r
 // One item: 8 positions of one row.  Returns the lane's sum over its 8 positions.
 template <int R>
 __device__ __forceinline__ float rep_item_sum(const RepCodes<R> &q, const V16 (&xr)[8], uint32_t k0, uint32_t k1, int lane) {
-    // All gathers of the item are issued before anything waits: as asm, because the compiler, left to order them,
-    // takes one entry at a time through one set of registers and waits out a full LDS round trip for each.  The
-    // wait is for everything (scalar loads count in the same counter and return out of order, so no partial count
+    // The gathers of an item go out in kRepHalves blocks, each block issued whole before anything waits: as asm,
+    // because the compiler, left to order them, takes one entry at a time through one set of registers and waits out
+    // a full LDS round trip for each.  (One block of 16 needs 64 registers for the entries; two of 8 leave room for a
+    // third wavefront per SIMD, which hides the second block's round trip.)  The wait is for everything (scalar loads count in the same counter and return out of order, so no partial count
     // is safe here) and names every destination, so nothing that reads one can move in front of it.
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-    u32x4_t ev[8 * R];
-#pragma unroll
-    for (int i = 0; i < 8 * R; ++i) {
-        // byte 0: copy column (lane constant), byte 1: the code, byte 2: codebook (lane constant), byte 3: 0
-        const uint32_t sel = 0x0C060004u | ((uint32_t)(i & 3) << 8);
-        const uint32_t addr = __builtin_amdgcn_perm((R == 2 && (i & 1)) ? k1 : k0, q.w[i >> 2], sel);
-        asm volatile("ds_read_b128 %0, %1" : "=v"(ev[i]) : "v"(addr));
-    }
-    if constexpr (R == 2) {
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(ev[0]), "+v"(ev[1]), "+v"(ev[2]), "+v"(ev[3]), "+v"(ev[4]), "+v"(ev[5]), "+v"(ev[6]), "+v"(ev[7]),
-                       "+v"(ev[8]), "+v"(ev[9]), "+v"(ev[10]), "+v"(ev[11]), "+v"(ev[12]), "+v"(ev[13]), "+v"(ev[14]), "+v"(ev[15]));
-    } else {
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(ev[0]), "+v"(ev[1]), "+v"(ev[2]), "+v"(ev[3]), "+v"(ev[4]), "+v"(ev[5]), "+v"(ev[6]), "+v"(ev[7]));
-    }
-    V16 e[8 * R];
-#pragma unroll
-    for (int i = 0; i < 8 * R; ++i) { e[i].w[0] = ev[i].x; e[i].w[1] = ev[i].y; e[i].w[2] = ev[i].z; e[i].w[3] = ev[i].w; }
+    constexpr int G = 8 * R / kRepHalves;   // gathers per block
     // four accumulators in turn: no matrix instruction waits for the one before it
     float4_t a[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const half4_t xl = rep_half4(xr[i].w[0], xr[i].w[1]), xh = rep_half4(xr[i].w[2], xr[i].w[3]);
+    for (int h = 0; h < kRepHalves; ++h) {
+        u32x4_t ev[G];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const V16 &en = e[i * R + r];
-            const int j = R == 2 ? 2 * r : 2 * (i & 1);
-            a[j] = __builtin_amdgcn_mfma_f32_4x4x4f16(rep_half4(en.w[0], en.w[1]), xl, a[j], 0, 0, 0);
-            a[j + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(rep_half4(en.w[2], en.w[3]), xh, a[j + 1], 0, 0, 0);
+        for (int g = 0; g < G; ++g) {
+            const int i = h * G + g;
+            // byte 0: copy column (lane constant), byte 1: the code, byte 2: codebook (lane constant), byte 3: 0
+            const uint32_t sel = 0x0C060004u | ((uint32_t)(i & 3) << 8);
+            const uint32_t addr = __builtin_amdgcn_perm((R == 2 && (i & 1)) ? k1 : k0, q.w[i >> 2], sel);
+            asm volatile("ds_read_b128 %0, %1" : "=v"(ev[g]) : "v"(addr));
+        }
+        if constexpr (G == 16) {
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(ev[0]), "+v"(ev[1]), "+v"(ev[2]), "+v"(ev[3]), "+v"(ev[4]), "+v"(ev[5]), "+v"(ev[6]), "+v"(ev[7]),
+                           "+v"(ev[8]), "+v"(ev[9]), "+v"(ev[10]), "+v"(ev[11]), "+v"(ev[12]), "+v"(ev[13]), "+v"(ev[14]), "+v"(ev[15]));
+        } else if constexpr (G == 8) {
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(ev[0]), "+v"(ev[1]), "+v"(ev[2]), "+v"(ev[3]), "+v"(ev[4]), "+v"(ev[5]), "+v"(ev[6]), "+v"(ev[7]));
+        } else {
+            static_assert(G == 4, "gathers per block");
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ev[0]), "+v"(ev[1]), "+v"(ev[2]), "+v"(ev[3]));
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int i = h * G + g, pos = i / R, r = i % R;
+            const half4_t xl = rep_half4(xr[pos].w[0], xr[pos].w[1]), xh = rep_half4(xr[pos].w[2], xr[pos].w[3]);
+            const int j = R == 2 ? 2 * r : 2 * (pos & 1);
+            a[j] = __builtin_amdgcn_mfma_f32_4x4x4f16(rep_half4(ev[g].x, ev[g].y), xl, a[j], 0, 0, 0);
+            a[j + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(rep_half4(ev[g].z, ev[g].w), xh, a[j + 1], 0, 0, 0);
         }
     }
     float4_t s = (a[0] + a[1]) + (a[2] + a[3]);
@@ -242,7 +246,7 @@ __device__ __forceinline__ void gemv_replica_body(const Table &table, const int 
     struct Staged {
         uint4 ent;
         uint4 x[kRepXPer];
-        float sc[2];   // scales of the rows that this thread finishes: tid and tid + 512 of the workgroup's share
+        float sc[2];   // scales of the rows that this thread finishes: tid and tid + 768 of the workgroup's share
     };
     auto request = [&](const RepProblem &p) {
         Staged st;
