@@ -50,10 +50,9 @@ constexpr int kRepWaves = kRepThreads / kWave;
 constexpr int kRepCopies = 16;
 constexpr int kRepCbStride = 256 * kRepCopies * 16;     // 64 KiB: LDS bytes of one codebook
 constexpr int kRepX = 2 * kRepCbStride;                 // x of the current problem (zeros past its end)
-constexpr int kRepMaxK = 12288;                         // 24 KiB of x: 48 bytes per thread
+constexpr int kRepMaxK = 12288;                         // 24 KiB of x in LDS
 constexpr int kRepXPer = (kRepMaxK / 8 + kRepThreads - 1) / kRepThreads;   // 16-byte units of x per thread
 constexpr int kRepPart = kRepX + kRepMaxK * 2;          // chunk sums [chunk][row of the workgroup], fp32
-constexpr int kRepMaxChunks = kRepMaxK / 8 / 512;       // 3
 constexpr int kRepPartFloats = 2048;                     // chunks x rows of one problem per workgroup
 constexpr int kRepLds = kRepPart + kRepPartFloats * 4;
 static_assert(kRepLds <= 160 * 1024, "one workgroup per CU, all of its LDS");
