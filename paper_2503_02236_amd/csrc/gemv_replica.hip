@@ -13,7 +13,7 @@
 // lane % 16 = c, is collision free whatever the codes are: 2 x 64 KiB of the CU's 160 KiB for two codebooks.  The
 // address is one v_perm_b32: the code byte dropped into byte 1 of a per-lane constant.
 //
-// Mapping.  One persistent workgroup of 12 wavefronts per compute unit.  The workgroups form up to 16 groups; group g
+// Mapping.  One persistent workgroup of 12 wavefronts per compute unit.  The workgroups form up to 32 groups; group g
 // takes problems g, g + groups, ... of the list, and each of its workgroups a contiguous range of rows of every
 // such problem (the more rows per workgroup, the less the re-staging of codebooks between problems weighs).  A row's
 // codes are cut into chunks of 512 positions: lane l of a wavefront loads the 8 (x R) code bytes of positions
@@ -56,7 +56,7 @@ constexpr int kRepPart = kRepX + kRepMaxK * 2;          // chunk sums [chunk][ro
 constexpr int kRepPartFloats = 2048;                     // chunks x rows of one problem per workgroup
 constexpr int kRepLds = kRepPart + kRepPartFloats * 4;
 static_assert(kRepLds <= 160 * 1024, "one workgroup per CU, all of its LDS");
-constexpr int kRepMaxGroups = 16;                       // groups of workgroups that work on different problems
+constexpr int kRepMaxGroups = 32;                       // groups of workgroups that work on different problems
 constexpr int kRepRound = 6;                            // items (16-byte code loads) a wavefront has in flight per round
 
 struct RepProblem {
@@ -433,7 +433,7 @@ int gemv_replica_list_create(const vq_gemv_call_t *calls, int n_calls, void *ws,
     }
     for (int c = 0; c < n_calls; ++c)
         for (int i = 0; i < calls[c].count; ++i) max_n = std::max(max_n, calls[c].w[i]->N);
-    // One workgroup per compute unit.  The problems are dealt to up to 8 groups of workgroups (a power of two that
+    // One workgroup per compute unit.  The problems are dealt to up to 32 groups of workgroups (a power of two that
     // divides the workgroups): the more rows of a problem a workgroup gets, the less its re-staging weighs.
     h->n = n;
     h->R = calls[0].w[0]->n_codebooks;

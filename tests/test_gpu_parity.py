@@ -486,13 +486,21 @@ def test_gemv_pipeline_small_codebook_lists(gpu_device):
     """vq_gemv_pipeline with canonical uint8 weights of small codebooks: 16 LDS copies of every entry, a list of
     problems in one launch.  Rows that end inside a chunk of 512 positions (K = 1024 + 64, 11008, 2112), three chunks
     (K = 11008, 12288), one row, fewer rows than workgroups, codebooks of 16 / 64 / 128 entries, no scale; lists of 1,
-    3 and all problems (1, 2 and 8 groups of workgroups); one and two additive codebooks."""
+    3, 4 and all problems (1, 2, 4 and 8 groups of workgroups); one and two additive codebooks."""
     _small_codebook_list(gpu_device, 2, [(4096, 4096, 256, True), (300, 1024, 256, False), (11008, 4096, 256, True),
                                          (4096, 11008, 256, True), (1, 512, 256, True), (777, 2112, 64, True),
                                          (513, 12288, 256, True), (2000, 576, 256, True), (64, 8192, 16, False)],
                          9900, [range(9), [0], [0, 1, 2], [6, 4, 3, 8]])
     _small_codebook_list(gpu_device, 1, [(4096, 4096, 256, True), (333, 1088, 256, True), (1000, 11008, 128, False)],
                          9950, [range(3), [2]])
+
+
+def test_gemv_pipeline_small_codebook_list_of_forty(gpu_device):
+    """Forty problems in one list: 32 groups of 8 workgroups (the launch shape of the decoder stack in bench.py), some
+    groups with two problems and some with one; shapes cycle through ragged and whole chunks."""
+    shapes = [(700, 1088), (512, 512), (1000, 2112), (96, 4096), (2049, 576)]
+    specs = [shapes[i % len(shapes)] + (256, i % 3 != 0) for i in range(40)]
+    _small_codebook_list(gpu_device, 2, specs, 9600, [range(40), range(33)])
 
 
 def test_gemv_pipeline_small_codebook_nan_entries_unused(gpu_device):
