@@ -192,8 +192,9 @@ __device__ __forceinline__ float rep_item_sum(const RepCodes<R> &q, const V16 (&
     // is safe here) and names every destination, so nothing that reads one can move in front of it.
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
     constexpr int G = 8 * R / kRepHalves;   // gathers per block
-    // four accumulators in turn: no matrix instruction waits for the one before it
-    float4_t a[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    // two accumulators in turn, one for each half of an entry (four, so that no matrix instruction waits for the one
+    // before it, cost more in the additions at the end than the waits do: 2 % slower)
+    float4_t a[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
     for (int h = 0; h < kRepHalves; ++h) {
         u32x4_t ev[G];
@@ -218,14 +219,13 @@ __device__ __forceinline__ float rep_item_sum(const RepCodes<R> &q, const V16 (&
         }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int i = h * G + g, pos = i / R, r = i % R;
+            const int pos = (h * G + g) / R;
             const half4_t xl = rep_half4(xr[pos].w[0], xr[pos].w[1]), xh = rep_half4(xr[pos].w[2], xr[pos].w[3]);
-            const int j = R == 2 ? 2 * r : 2 * (pos & 1);
-            a[j] = __builtin_amdgcn_mfma_f32_4x4x4f16(rep_half4(ev[g].x, ev[g].y), xl, a[j], 0, 0, 0);
-            a[j + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(rep_half4(ev[g].z, ev[g].w), xh, a[j + 1], 0, 0, 0);
+            a[0] = __builtin_amdgcn_mfma_f32_4x4x4f16(rep_half4(ev[g].x, ev[g].y), xl, a[0], 0, 0, 0);
+            a[1] = __builtin_amdgcn_mfma_f32_4x4x4f16(rep_half4(ev[g].z, ev[g].w), xh, a[1], 0, 0, 0);
         }
     }
-    float4_t s = (a[0] + a[1]) + (a[2] + a[3]);
+    float4_t s = a[0] + a[1];
     asm volatile("" : "+v"(s));   // (all four sums, then two selects: no branches)
     const float s01 = (lane & 1) ? s.y : s.x, s23 = (lane & 1) ? s.w : s.z;
     return (lane & 2) ? s23 : s01;
