@@ -13,7 +13,7 @@
 // lane % 16 = c, is collision free whatever the codes are: 2 x 64 KiB of the CU's 160 KiB for two codebooks.  The
 // address is one v_perm_b32: the code byte dropped into byte 1 of a per-lane constant.
 //
-// Mapping.  One persistent workgroup of 12 wavefronts per compute unit.  The workgroups form up to 32 groups; group g
+// Mapping.  One persistent workgroup of 16 wavefronts per compute unit.  The workgroups form up to 32 groups; group g
 // takes problems g, g + groups, ... of the list, and each of its workgroups a contiguous range of rows of every
 // such problem (the more rows per workgroup, the less the re-staging of codebooks between problems weighs).  A row's
 // codes are cut into chunks of 512 positions: lane l of a wavefront loads the 8 (x R) code bytes of positions
@@ -24,13 +24,14 @@
 // independent pairs of 4 x 4 matrices, row i of the first and column i of the second operand of a pair held by the
 // same lane, so diagonal element i of a product is that lane's own 4-term dot product, in accumulator register
 // lane % 4 (the other three registers collect cross terms and are never read).  An item's 64 lane sums are added by
-// DPP steps; chunk sums meet in LDS and thread t of the workgroup finishes rows t and t + 768 of its range:
+// DPP steps; chunk sums meet in LDS and thread t of the workgroup finishes rows t and t + 1024 of its range:
 // y = fp16(scale * sum), chunks in ascending order.  Every order is fixed: repeated runs give the same bits.
 //
 // Between two problems the workgroup re-stages: each thread holds one entry of the next problem (and up to 32 bytes
 // of its x, and the scales of its rows), requested a whole problem earlier, and writes the 16 copies -- lane l starts
-// at copy l % 16, so the writes of a pass fall into 16 different columns too.  The codes of a wavefront's next six
-// items are also requested one round ahead, across problem boundaries; the workgroup barriers wait for LDS traffic
+// at copy l % 16, so the writes of a pass fall into 16 different columns too.  The codes of a wavefront's next three
+// items are also in flight, across problem boundaries (a ring of three slots, each refilled as soon as its item has
+// been worked on); the workgroup barriers wait for LDS traffic
 // only, so these requests stay in flight across them.
 //
 // What bounds it: instruction issue.  An item (512 positions of a row, 1024 gathers with two codebooks) is about 150
@@ -44,7 +45,7 @@
 
 namespace vq {
 
-constexpr int kRepThreads = 768;   // 12 wavefronts, three per SIMD: 170 registers each (8: 7 % slower; 16: registers spill)
+constexpr int kRepThreads = 1024;  // 16 wavefronts, four per SIMD, 128 registers each (12 wavefronts: 4 % slower, 8: 11 %)
 constexpr int kRepHalves = 2;      // an item's gathers are issued in this many blocks, each in front of its own arithmetic
 constexpr int kRepWaves = kRepThreads / kWave;
 constexpr int kRepCopies = 16;
@@ -57,7 +58,7 @@ constexpr int kRepPartFloats = 2048;                     // chunks x rows of one
 constexpr int kRepLds = kRepPart + kRepPartFloats * 4;
 static_assert(kRepLds <= 160 * 1024, "one workgroup per CU, all of its LDS");
 constexpr int kRepMaxGroups = 32;                       // groups of workgroups that work on different problems
-constexpr int kRepRound = 6;                            // items (16-byte code loads) a wavefront has in flight per round
+constexpr int kRepRound = 3;                            // items (16-byte code loads) a wavefront has in flight per round
 
 struct RepProblem {
     const uint8_t *codes;   // [N][K/8][R]
@@ -187,8 +188,8 @@ template <int R>
 __device__ __forceinline__ float rep_item_sum(const RepCodes<R> &q, const V16 (&xr)[8], uint32_t k0, uint32_t k1, int lane) {
     // The gathers of an item go out in kRepHalves blocks, each block issued whole before anything waits: as asm,
     // because the compiler, left to order them, takes one entry at a time through one set of registers and waits out
-    // a full LDS round trip for each.  (One block of 16 needs 64 registers for the entries; two of 8 leave room for a
-    // third wavefront per SIMD, which hides the second block's round trip.)  The wait is for everything (scalar loads count in the same counter and return out of order, so no partial count
+    // a full LDS round trip for each.  (One block of 16 needs 64 registers for the entries; two of 8 leave room for more
+    // wavefronts per SIMD, which hide the second block's round trip.)  The wait is for everything (scalar loads count in the same counter and return out of order, so no partial count
     // is safe here) and names every destination, so nothing that reads one can move in front of it.
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
     constexpr int G = 8 * R / kRepHalves;   // gathers per block
@@ -245,7 +246,7 @@ __device__ __forceinline__ void gemv_replica_body(const Table &table, const int 
     struct Staged {
         uint4 ent;
         uint4 x[kRepXPer];
-        float sc[2];   // scales of the rows that this thread finishes: tid and tid + 768 of the workgroup's share
+        float sc[2];   // scales of the rows that this thread finishes: tid and tid + 1024 of the workgroup's share
     };
     auto request = [&](const RepProblem &p) {
         Staged st;
@@ -283,33 +284,36 @@ __device__ __forceinline__ void gemv_replica_body(const Table &table, const int 
             if (j * kRepThreads + tid < kRepMaxK / 8) rep_lds16_store(kRepX + (uint32_t)(j * kRepThreads + tid) * 16u, st.x[j]);
     };
 
-    // The codes of the wavefront's next round of items, requested one round ahead: `ahead` runs over the problems
-    // one round in front of the work.
+    // The codes of a wavefront's items are requested one round (kRepRound items) ahead: slot t of the ring holds item t
+    // of the current round until it has been worked on and is then refilled with item t of the next round -- of the
+    // same problem, or of the next problem in which the wavefront has items (every problem starts a round of its own:
+    // the slots past the end of a run hold its last item once more and are never used).  `ahead` runs over the
+    // problems one round in front of the work.
     int ahead_k = grp - groups;
+    bool ahead_none = false;
     RepRun ahead = {0, 0, 0, 0, 0};
     const uint8_t *ahead_codes = nullptr;
     uint32_t ahead_row_bytes = 0;
     int ahead_row0 = 0, ahead_lane_chunks = 0;
     RepCodes<R> qn[kRepRound];
-    auto request_round = [&]() {
-        while (ahead.u >= ahead.end) {   // on to the next problem in which the wavefront has items
-            ahead_k += groups;
-            if (ahead_k >= n) return;
-            const RepProblem p = table[ahead_k];
-            const RepShare s = rep_share(p, wave, wb);
-            ahead = rep_run(s);
-            ahead_codes = p.codes;
-            ahead_row_bytes = (uint32_t)(p.K >> 3) * R;
-            ahead_row0 = s.row0;
-            ahead_lane_chunks = s.lane_chunks;
+    auto request_slot = [&](int t) {
+        if (t == 0) {
+            if (ahead.u > ahead.end) ahead.u = ahead.end;
+            while (!ahead_none && ahead.u >= ahead.end) {   // on to the next problem in which the wavefront has items
+                ahead_k += groups;
+                if (ahead_k >= n) { ahead_none = true; break; }
+                const RepProblem p = table[ahead_k];
+                const RepShare s = rep_share(p, wave, wb);
+                ahead = rep_run(s);
+                ahead_codes = p.codes;
+                ahead_row_bytes = (uint32_t)(p.K >> 3) * R;
+                ahead_row0 = s.row0;
+                ahead_lane_chunks = s.lane_chunks;
+            }
         }
-#pragma unroll
-        for (int t = 0; t < kRepRound; ++t) {
-            // (past the end of the run: the last item again, never used)
-            qn[t] = rep_load<R>(ahead_codes, ahead_row_bytes, ahead_row0, ahead_lane_chunks, ahead, lane);
-            if (ahead.u + 1 < ahead.end || t == kRepRound - 1) rep_step(ahead);
-        }
-        if (ahead.u > ahead.end) ahead.u = ahead.end;
+        if (ahead_none) return;
+        qn[t] = rep_load<R>(ahead_codes, ahead_row_bytes, ahead_row0, ahead_lane_chunks, ahead, lane);
+        if (ahead.u + 1 < ahead.end || t == kRepRound - 1) rep_step(ahead);
     };
 
     // Row `tid` of the workgroup's share of a problem: y = fp16(scale * sum of the chunk sums, ascending).
@@ -328,7 +332,8 @@ __device__ __forceinline__ void gemv_replica_body(const Table &table, const int 
     };
     Staged st = request(table[grp]);
     float sc_done[2] = {1.f, 1.f};
-    request_round();
+#pragma unroll
+    for (int t = 0; t < kRepRound; ++t) request_slot(t);
     int k_last = grp;
     for (int k = grp; k < n; k += groups) {
         k_last = k;
@@ -348,12 +353,10 @@ __device__ __forceinline__ void gemv_replica_body(const Table &table, const int 
         bool active = true;
         V16 xr[8];
         while (run.u < run.end) {
-            RepCodes<R> q[kRepRound];
-#pragma unroll
-            for (int t = 0; t < kRepRound; ++t) q[t] = qn[t];
-            request_round();
 #pragma unroll
             for (int t = 0; t < kRepRound; ++t) {
+                const RepCodes<R> q = qn[t];
+                request_slot(t);
                 if (run.u < run.end) {
                     if (run.c != cur_c) {   // (uniform) the wavefront moves to another chunk index: its x from LDS
                         cur_c = run.c;
@@ -363,7 +366,7 @@ __device__ __forceinline__ void gemv_replica_body(const Table &table, const int 
                         for (int i = 0; i < 8; ++i) xr[i] = rep_lds16(kRepX + (uint32_t)(lc * 8 + i) * 16u);
                     }
                     // (a lane past the end of the row has computed with codes that are not its own: dropped here)
-                    const float item = rep_item_sum<R>(q[t], xr, k0, k1, lane);
+                    const float item = rep_item_sum<R>(q, xr, k0, k1, lane);
                     const float total = rep_wave_sum_to_63(active ? item : 0.f);
                     if (lane == 63)
                         *(__attribute__((address_space(3))) float *)(uintptr_t)(kRepPart + (uint32_t)(run.c * run.rows + run.row) * 4u) = total;
