@@ -34,9 +34,9 @@
 // been worked on); the workgroup barriers wait for LDS traffic
 // only, so these requests stay in flight across them.
 //
-// What bounds it: instruction issue.  An item (512 positions of a row, 1024 gathers with two codebooks) is about 150
+// What bounds it: instruction issue.  An item (512 positions of a row, 1024 gathers with two codebooks) is about 130
 // issue slots per wavefront -- 16 address permutes, 16 LDS reads, 32 matrix instructions of two slots each (the same
-// 64 slots as v_dot2 would take), ~40 for the sums and the bookkeeping -- against 77 clocks of LDS time.
+// 64 slots as v_dot2 would take), ~30 for the sums and the bookkeeping -- against 77 clocks of LDS time.
 #include <algorithm>
 #include <new>
 #include <vector>
